@@ -1,0 +1,235 @@
+/*
+ * CPU oracle for the per-token core of the UloRL objective (arxiv 2507.19766).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain, fp64 statement of what
+ * the GPU library computes.  It shares no code, header, table or helper with the
+ * HIP path and must never be linked, imported or called by the product path; only
+ * tests, the smoke check and the benchmark's reported CPU baseline use it.
+ *
+ * Everything is evaluated in double precision, directly from the definitions:
+ *   - softmax of the policy over the vocabulary (ratio numerator of Eq. 6; the
+ *     p_t^j inside the DMMPT objective of Sec. 3.2.2),
+ *   - per-token entropy, the inner vocabulary sum of the H-bar definition in
+ *     Sec. 3.2.2 with the sign of an entropy (H = -sum p ln p),
+ *   - SAIS / POIS importance ratio (Sec. 3.1.2, Eq. "sais" and the POIS paragraph),
+ *   - the clipped surrogate (Eq. 1 / Eq. 7 with eps_low, eps_high),
+ *   - the MPT set (Eq. "MPTS", Sec. 3.2.1) and the dynamic mask I_msk with its
+ *     per-response entropy gate (Sec. 3.2.2),
+ *   - the token-mean reduction 1 / sum_i |o_i| of the DMMPT objective,
+ *   - the gradient of loss = -J with respect to the logits (chain rule; the mask
+ *     is a constant, the paper adds no extra optimisation objective).
+ *
+ * No blocking, no online rescaling, no fusion: each quantity is a loop over its
+ * definition.  OpenMP is used over independent rows only; all sums that cross
+ * rows (per-response entropy, the loss) are sequential in index order.
+ *
+ * Storage codes for logits: 0 = float32, 1 = bfloat16 (raw uint16), 2 = float64.
+ * Both narrow types convert to double exactly, so the oracle consumes exactly
+ * the values the GPU sees.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORC_F32 = 0, ORC_BF16 = 1, ORC_F64 = 2 };
+enum { ORC_IS_SAIS = 0, ORC_IS_POIS = 1 };
+enum { ORC_GATE_PER_RESPONSE = 0, ORC_GATE_GLOBAL = 1, ORC_GATE_ALWAYS = 2, ORC_GATE_NEVER = 3 };
+
+static double bf16_bits_to_double(uint16_t h)
+{
+    uint32_t w = ((uint32_t)h) << 16; /* bfloat16 is the upper half of a binary32 */
+    float f;
+    memcpy(&f, &w, sizeof f);
+    return (double)f;
+}
+
+static double logit_at(const void *base, int storage, int64_t idx)
+{
+    switch (storage) {
+    case ORC_F32: return (double)((const float *)base)[idx];
+    case ORC_BF16: return bf16_bits_to_double(((const uint16_t *)base)[idx]);
+    default: return ((const double *)base)[idx];
+    }
+}
+
+/*
+ * Softmax statistics of each row (independent rows).
+ *   lse[t]  = ln sum_j exp(z[t,j])                 (evaluated with the usual max shift)
+ *   logp[t] = z[t, y[t]] - lse[t]                  log pi_theta(o_t | .)      (Eq. 6 numerator)
+ *   H[t]    = - sum_j q_j ln q_j,  q_j = exp(z[t,j] - lse[t]),  ln q_j = z[t,j] - lse[t]
+ *                                                  (Sec. 3.2.2, inner sum of H-bar; natural log)
+ * Returns 0, or -1 on a token id outside [0, V).
+ */
+int ulorl_oracle_row_stats(const void *logits, int storage, int64_t n_rows, int64_t V,
+                           int64_t row_stride, const int32_t *token_ids, double *lse,
+                           double *logp, double *entropy)
+{
+    int bad = 0;
+#pragma omp parallel for schedule(static) reduction(| : bad)
+    for (int64_t t = 0; t < n_rows; ++t) {
+        const int64_t off = t * row_stride;
+        double m = -INFINITY;
+        for (int64_t j = 0; j < V; ++j) {
+            double z = logit_at(logits, storage, off + j);
+            if (z > m) m = z;
+        }
+        double S = 0.0;
+        for (int64_t j = 0; j < V; ++j) S += exp(logit_at(logits, storage, off + j) - m);
+        const double l = m + log(S);
+        double h = 0.0;
+        for (int64_t j = 0; j < V; ++j) {
+            const double lnq = logit_at(logits, storage, off + j) - l;
+            const double q = exp(lnq);
+            if (q > 0.0) h -= q * lnq;
+        }
+        lse[t] = l;
+        entropy[t] = h;
+        const int64_t y = token_ids[t];
+        if (y < 0 || y >= V) {
+            bad |= 1;
+            logp[t] = NAN;
+        } else {
+            logp[t] = logit_at(logits, storage, off + y) - l;
+        }
+    }
+    return bad ? -1 : 0;
+}
+
+/*
+ * Everything that is O(1) per token, given the per-row log-prob and entropy.
+ *
+ * Per response i (cu[i] <= t < cu[i+1]):
+ *   Hbar[i] = mean_t H[t]  over ALL tokens of the response          (Sec. 3.2.2)
+ *   gate[i] = Hbar[i] < sigma (strict)                               (Sec. 3.2.2, I_msk case 1)
+ *     gate modes: per response (the equation), global (token-mean entropy of the whole
+ *     call, the prose reading "the model's current entropy"), always (static masking
+ *     experiment of Sec. 3.2.1), never (plain DAPO objective, Eq. 7).
+ * Per token:
+ *   seg[t]  = f(t): explicit id if given, else offset-in-response div seg_len   (Sec. 3.1.2)
+ *   MPT     = (A[t] > 0) and (p[t] >= tau), p = exp(logp)            (Eq. MPTS; reward 1 <=> A > 0)
+ *   I[t]    = gate and MPT
+ *   r       = exp(logp - old_logp) [SAIS]  |  1 [POIS, d r / d logp = 1]
+ *   s       = min(r A, clip(r, 1-eps_low, 1+eps_high) A)
+ *   loss    = -(1/D) sum_t (1 - I[t]) s[t],  D = sum_i |o_i| = N unless overridden
+ *   g[t]    = d loss / d logp[t] = -(1/D) (1 - I[t]) [r A <= clip(r) A] r A
+ *
+ * counters[0] = number of masked tokens (I = 1)
+ * counters[1] = number of tokens whose clipped branch is the strict minimum (no gradient)
+ * counters[2] = number of tokens with A > 0
+ * Any output pointer except loss may be NULL.  Returns 0, or -2 on malformed cu_seqlens.
+ */
+int ulorl_oracle_token_terms(int64_t N, const double *logp, const double *entropy,
+                             const int32_t *cu_seqlens, int32_t R, const int32_t *segment_ids,
+                             int32_t seg_len, const double *old_logp, const double *advantages,
+                             double eps_low, double eps_high, double tau, double sigma,
+                             int is_mode, int gate_mode, double denominator,
+                             double *loss, double *resp_entropy, uint8_t *resp_gate,
+                             int32_t *seg_out, uint8_t *mask, double *ratio, double *surrogate,
+                             double *gcoef, int64_t *counters)
+{
+    if (cu_seqlens[0] != 0 || cu_seqlens[R] != N) return -2;
+    for (int32_t i = 0; i < R; ++i)
+        if (cu_seqlens[i + 1] < cu_seqlens[i]) return -2;
+
+    const double D = denominator > 0.0 ? denominator : (double)N;
+
+    /* token-mean entropy over the whole call, for the global gate */
+    double Hall = 0.0;
+    for (int64_t t = 0; t < N; ++t) Hall += entropy[t];
+    const double Hglobal = N > 0 ? Hall / (double)N : 0.0;
+
+    double acc = 0.0;
+    int64_t n_masked = 0, n_clipped = 0, n_pos = 0;
+    for (int32_t i = 0; i < R; ++i) {
+        const int64_t b = cu_seqlens[i], e = cu_seqlens[i + 1];
+        double hs = 0.0;
+        for (int64_t t = b; t < e; ++t) hs += entropy[t];
+        const double hbar = e > b ? hs / (double)(e - b) : 0.0;
+        int gate;
+        switch (gate_mode) {
+        case ORC_GATE_PER_RESPONSE: gate = (e > b) && (hbar < sigma); break;
+        case ORC_GATE_GLOBAL: gate = Hglobal < sigma; break;
+        case ORC_GATE_ALWAYS: gate = 1; break;
+        default: gate = 0; break;
+        }
+        if (resp_entropy) resp_entropy[i] = hbar;
+        if (resp_gate) resp_gate[i] = (uint8_t)gate;
+
+        for (int64_t t = b; t < e; ++t) {
+            const int32_t seg = segment_ids ? segment_ids[t]
+                                            : (seg_len > 0 ? (int32_t)((t - b) / seg_len) : 0);
+            const double A = advantages[t];
+            const double p = exp(logp[t]);
+            const int positive = A > 0.0;
+            const int mpt = positive && (p >= tau);
+            const int I = gate && mpt;
+            const double r = (is_mode == ORC_IS_POIS) ? 1.0 : exp(logp[t] - old_logp[t]);
+            double c = r;
+            if (c < 1.0 - eps_low) c = 1.0 - eps_low;
+            if (c > 1.0 + eps_high) c = 1.0 + eps_high;
+            const double u = r * A, v = c * A;
+            const int active = u <= v; /* the unclipped branch attains the min: gradient flows */
+            const double s = active ? u : v;
+            const double keep = I ? 0.0 : 1.0;
+            acc += keep * s;
+            if (seg_out) seg_out[t] = seg;
+            if (mask) mask[t] = (uint8_t)I;
+            if (ratio) ratio[t] = r;
+            if (surrogate) surrogate[t] = s;
+            if (gcoef) gcoef[t] = I ? 0.0 : (active ? -(r * A) / D : 0.0);
+            n_masked += I;
+            n_clipped += !active;
+            n_pos += positive;
+        }
+    }
+    *loss = -acc / D;
+    if (counters) {
+        counters[0] = n_masked;
+        counters[1] = n_clipped;
+        counters[2] = n_pos;
+    }
+    return 0;
+}
+
+/*
+ * Gradient of the loss with respect to the logits of selected rows:
+ *   dz[k, j] = grad_out * g[t] * ( [j == y[t]] - q_{t,j} ),  t = rows[k] (or k if rows == NULL),
+ *   q_{t,j} = exp(z[t,j] - lse[t]).
+ * Output is dense double [n_sel, V].
+ */
+int ulorl_oracle_dlogits(const void *logits, int storage, int64_t V, int64_t row_stride,
+                         const int32_t *token_ids, const double *lse, const double *gcoef,
+                         double grad_out, const int64_t *rows, int64_t n_sel, double *dz)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t k = 0; k < n_sel; ++k) {
+        const int64_t t = rows ? rows[k] : k;
+        const int64_t off = t * row_stride;
+        const double w = grad_out * gcoef[t];
+        const int64_t y = token_ids[t];
+        double *out = dz + k * V;
+        for (int64_t j = 0; j < V; ++j) {
+            const double q = exp(logit_at(logits, storage, off + j) - lse[t]);
+            out[j] = w * ((j == y ? 1.0 : 0.0) - q);
+        }
+    }
+    return 0;
+}
+
+/* Number of OpenMP threads the row loops will use (reported by the CPU baseline). */
+int ulorl_oracle_threads(void)
+{
+    int n = 1;
+#pragma omp parallel
+    {
+#pragma omp single
+#ifdef _OPENMP
+        n = omp_get_num_threads();
+#endif
+    }
+    return n;
+}

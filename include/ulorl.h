@@ -1,0 +1,185 @@
+/*
+ * libulorl -- the per-token core of the UloRL reinforcement-learning objective
+ * (arxiv 2507.19766) for AMD MI355X (gfx950), behind a plain C ABI.
+ *
+ * From the policy's vocabulary logits the forward call computes, per token row,
+ * the log-softmax statistics, the chosen-token log-prob and the entropy; then the
+ * importance ratio against the behaviour policy of the token's segment (SAIS) or
+ * the pseudo-on-policy ratio (POIS), the clipped policy-gradient term, the dynamic
+ * mask of well-mastered positive tokens (MPTs) with its entropy gate, and the
+ * token-mean loss.  The backward call streams the logits once more and writes
+ * d loss / d logits.
+ *
+ * Conventions common to every entry point
+ *   - All array arguments are DEVICE pointers (HIP global memory on the current
+ *     device) unless marked HOST.  The library never allocates, frees or copies
+ *     device memory, and never synchronises: every call only enqueues kernels on
+ *     the HIP stream passed in (`hip_stream` is a hipStream_t; NULL = default
+ *     stream) and returns.  Buffers must stay alive until the stream has drained.
+ *   - The return value is a ulorl_status; nothing throws or aborts.  Argument
+ *     errors are detected on the host before anything is launched.  Errors that
+ *     only the device can see (token id outside [0, V), a non-finite logit,
+ *     malformed cu_seqlens) never fault: the offending row contributes zero to
+ *     the loss and gets a zero gradient, and a bit is raised in counters[3].
+ *   - Results are bitwise reproducible from run to run (no floating-point atomics;
+ *     every cross-row sum has a fixed order).
+ *   - Rows are packed without padding: response i owns rows cu_seqlens[i] ..
+ *     cu_seqlens[i+1]-1.
+ */
+#ifndef ULORL_H
+#define ULORL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ULORL_OK = 0,
+    ULORL_ERR_NULL = -1,      /* a required pointer is NULL                          */
+    ULORL_ERR_SHAPE = -2,     /* N, V, R, stride or chunk out of range               */
+    ULORL_ERR_DTYPE = -3,     /* unknown storage type                                */
+    ULORL_ERR_ALIGN = -4,     /* logits base or row stride not 16-byte aligned       */
+    ULORL_ERR_PARAM = -5,     /* eps < 0, tau outside (0,1], unknown mode, ...       */
+    ULORL_ERR_WORKSPACE = -6, /* workspace missing, misaligned or too small          */
+    ULORL_ERR_HIP = -7        /* a kernel launch was rejected by the runtime         */
+} ulorl_status;
+
+/* Storage type of logits / dlogits. */
+typedef enum { ULORL_F32 = 0, ULORL_BF16 = 1 } ulorl_dtype;
+
+/* Importance-sampling mode (Sec. 3.1.2).
+ *   SAIS: r_t = exp(logp_t - old_logp_t); old_logp_t is the log-prob recorded by the
+ *         policy that generated the segment f(t) the token belongs to (Eq. "sais").
+ *   POIS: every segment's behaviour policy is replaced by the latest one, which with
+ *         one update per rollout step equals the current policy: r_t = 1 in value,
+ *         d r_t / d logp_t = 1, nothing is ever clipped.  old_logp is not read.      */
+typedef enum { ULORL_IS_SAIS = 0, ULORL_IS_POIS = 1 } ulorl_is_mode;
+
+/* When MPTs are masked (Sec. 3.2.2).  The equation of I_msk gates per response on
+ * the response's mean token entropy; the prose speaks of "the current entropy" of the
+ * model, offered as GLOBAL (token-mean entropy over the whole call).  ALWAYS is the
+ * static "Masking MPTs" experiment of Sec. 3.2.1; NEVER gives the DAPO objective
+ * (Eq. 7) unchanged.                                                                */
+typedef enum {
+    ULORL_GATE_PER_RESPONSE = 0,
+    ULORL_GATE_GLOBAL = 1,
+    ULORL_GATE_ALWAYS = 2,
+    ULORL_GATE_NEVER = 3
+} ulorl_gate_mode;
+
+/* Bits of the device status word counters[3]. */
+enum {
+    ULORL_STATUS_BAD_TOKEN = 1,     /* a token id outside [0, V)                      */
+    ULORL_STATUS_NONFINITE = 2,     /* a row whose softmax statistics are not finite  */
+    ULORL_STATUS_BAD_CU = 4         /* cu_seqlens not 0 = cu[0] <= ... <= cu[R] = N   */
+};
+
+/* HOST struct of scalar parameters. */
+typedef struct ulorl_params {
+    float eps_low;        /* clip range [1 - eps_low, 1 + eps_high] (Eq. 7; Sec. 3.2.2 uses one eps) */
+    float eps_high;
+    float tau;            /* MPT probability threshold, 0.99 in Sec. 4.1; in (0, 1]  */
+    float sigma;          /* target entropy in nats, 0.2 in Sec. 4.1                  */
+    int32_t is_mode;      /* ulorl_is_mode                                            */
+    int32_t gate_mode;    /* ulorl_gate_mode                                          */
+    int32_t seg_len;      /* > 0: segment id f(t) = offset in response / seg_len;
+                             0: ids are taken from segment_ids[] (or all 0)          */
+    int32_t reserved;     /* must be 0                                                */
+    double denominator;   /* <= 0: D = N, the token count of the call (the 1/sum|o_i|
+                             of Sec. 3.2.2 counts masked tokens too); > 0: use this D,
+                             e.g. the global count when a batch is split over calls   */
+} ulorl_params;
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int32_t ulorl_version(void);
+
+/* Static string for a status code (HOST pointer, never NULL). */
+const char *ulorl_status_string(int32_t status);
+
+/* Bytes of device workspace ulorl_token_loss_fwd needs for N rows in R responses
+ * (0 if N or R is out of range).  The workspace holds per-response entropy sums and
+ * per-block partial sums; its contents need not be preserved between calls.        */
+size_t ulorl_token_loss_workspace_bytes(int64_t N, int32_t R);
+
+/*
+ * Forward: log-softmax statistics -> ratio -> clipped term -> MPT mask -> loss.
+ *
+ *   logits        [N, V] row-major, element type dt, row t at logits + t*row_stride
+ *                 elements; base and row_stride*sizeof(element) multiples of 16 bytes;
+ *                 row_stride >= V.  V need not be a multiple of the vector width.
+ *   token_ids     [N] chosen token o_t of each row, in [0, V).
+ *   cu_seqlens    [R+1] response boundaries, cu[0] = 0, cu[R] = N, non-decreasing.
+ *   segment_ids   [N] segment id f(t) per token, or NULL (then p->seg_len rules).
+ *                 The ids do not enter the loss (old_logp is already per token); they
+ *                 are validated/derived and returned in segment_out.
+ *   old_logp      [N] log pi_old_{f(t)}(o_t): behaviour-policy log-prob recorded when
+ *                 the token's segment was generated.  May be NULL iff POIS.
+ *   advantages    [N] advantage A_t of each token (a response's value broadcast over
+ *                 its tokens).  A token is "positive" iff A_t > 0 (reward 1 in a mixed
+ *                 group, Sec. 3.3).  NULL selects the STATS-ONLY pass: only lse, logp
+ *                 and entropy are written (this is how a caller records old_logp).
+ *   p             HOST parameters.
+ * Outputs (all DEVICE; [N] float unless noted; any of segment_out, ratio, mpt_mask,
+ * resp_entropy, resp_gate, counters may be NULL):
+ *   loss          [1]  -(1/D) sum_t (1 - I_t) min(r_t A_t, clip(r_t) A_t)   (Sec. 3.2.2, loss = -J)
+ *   logp          log pi_theta(o_t) = z[t, o_t] - lse_t                     (Eq. 6 numerator)
+ *   entropy       H_t = - sum_j p_j ln p_j over the vocabulary, nats         (inner sum of H-bar)
+ *   lse           log-sum-exp of the row (saved for the backward pass)
+ *   gcoef         d loss / d logp_t = -(1/D)(1 - I_t)[r A <= clip(r) A] r_t A_t  (saved for backward)
+ *   mpt_mask      [N] uint8  I_t = gate(response of t) and A_t > 0 and p_t >= tau   (Eq. MPTS, I_msk)
+ *   ratio         r_t
+ *   segment_out   [N] int32 f(t)
+ *   resp_entropy  [R] float  H-bar_i, mean token entropy over all tokens of response i
+ *   resp_gate     [R] uint8  1 if MPTs of response i are masked
+ *   counters      [4] int64: masked tokens, tokens on the clipped (gradient-free) branch,
+ *                 positive tokens, status word (ULORL_STATUS_* bits)
+ *   workspace     >= ulorl_token_loss_workspace_bytes(N, R) bytes, 256-byte aligned; not
+ *                 needed (may be NULL) for the stats-only pass.
+ */
+int32_t ulorl_token_loss_fwd(
+    const void *logits, int32_t dt, int64_t N, int64_t V, int64_t row_stride,
+    const int32_t *token_ids, const int32_t *cu_seqlens, int32_t R,
+    const int32_t *segment_ids, const float *old_logp, const float *advantages,
+    const ulorl_params *p,
+    float *loss, float *logp, float *entropy, float *lse, float *gcoef,
+    uint8_t *mpt_mask, float *ratio, int32_t *segment_out,
+    float *resp_entropy, uint8_t *resp_gate, int64_t *counters,
+    void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Backward: dlogits[t, j] = grad_out * gcoef[t] * ( [j == token_ids[t]] - exp(logits[t, j] - lse[t]) )
+ * (chain rule through the log-softmax; the mask is a constant).  Rows with gcoef[t] == 0
+ * (masked, clipped, zero advantage, or flagged invalid) are written as zeros without being
+ * read.  dlogits has the type and row stride of logits and MAY BE THE SAME BUFFER as logits
+ * (each row is read and then overwritten by the one workgroup that owns it).  Values are
+ * rounded to the storage type with round-to-nearest-even.
+ *   lse, gcoef    [N] as produced by the forward call on the same logits.
+ *   grad_out      HOST scalar, upstream d(objective)/d(loss), usually 1.
+ */
+int32_t ulorl_token_loss_bwd(
+    const void *logits, int32_t dt, int64_t N, int64_t V, int64_t row_stride,
+    const int32_t *token_ids, const float *lse, const float *gcoef, float grad_out,
+    void *dlogits, void *hip_stream);
+
+/*
+ * Launch-shape knobs of the two streaming kernels (process-wide, HOST state; not thread
+ * safe against concurrent calls).  Results do not depend on them beyond summation order.
+ *   *_THREADS  workgroup size per token row: 256, 512 or 1024
+ *   *_UNROLL   16-byte loads each lane keeps in flight per loop trip: 2, 4 or 8
+ * Returns ULORL_ERR_PARAM for an unknown knob or an unsupported value.
+ */
+typedef enum {
+    ULORL_TUNE_FWD_THREADS = 0,
+    ULORL_TUNE_FWD_UNROLL = 1,
+    ULORL_TUNE_BWD_THREADS = 2,
+    ULORL_TUNE_BWD_UNROLL = 3
+} ulorl_tune_knob;
+int32_t ulorl_tune(int32_t knob, int32_t value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ULORL_H */

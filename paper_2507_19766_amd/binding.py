@@ -1,0 +1,243 @@
+"""ctypes binding of libulorl: argument marshalling only.
+
+Every function here has the name of the C entry point it wraps (minus the ``ulorl_`` prefix)
+and does nothing but check tensors (device, dtype, contiguity), allocate outputs with torch
+and pass raw pointers plus the current HIP stream.  All arithmetic runs in the HIP kernels.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+F32, BF16 = 0, 1
+IS_SAIS, IS_POIS = 0, 1
+GATE_PER_RESPONSE, GATE_GLOBAL, GATE_ALWAYS, GATE_NEVER = 0, 1, 2, 3
+STATUS_BAD_TOKEN, STATUS_NONFINITE, STATUS_BAD_CU = 1, 2, 4
+TUNE_FWD_THREADS, TUNE_FWD_UNROLL, TUNE_BWD_THREADS, TUNE_BWD_UNROLL = 0, 1, 2, 3
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+class UlorlError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: %s (status %d)" % (where, status_string(status), status))
+
+
+class _CParams(ctypes.Structure):
+    _fields_ = [("eps_low", ctypes.c_float), ("eps_high", ctypes.c_float),
+                ("tau", ctypes.c_float), ("sigma", ctypes.c_float),
+                ("is_mode", ctypes.c_int32), ("gate_mode", ctypes.c_int32),
+                ("seg_len", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("denominator", ctypes.c_double)]
+
+
+@dataclass
+class Params:
+    """Scalar parameters; defaults are the paper's (tau = 0.99, sigma = 0.2, Sec. 4.1)."""
+    eps_low: float = 0.2
+    eps_high: float = 0.2
+    tau: float = 0.99
+    sigma: float = 0.2
+    is_mode: int = IS_SAIS
+    gate_mode: int = GATE_PER_RESPONSE
+    seg_len: int = 0
+    denominator: float = 0.0
+
+    def to_c(self) -> _CParams:
+        return _CParams(self.eps_low, self.eps_high, self.tau, self.sigma, self.is_mode,
+                        self.gate_mode, self.seg_len, 0, self.denominator)
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "lib", "libulorl.so")
+
+
+_lib = None
+
+
+def load_library(build_if_missing: bool = True):
+    """Load lib/libulorl.so (building it once if it is absent)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = lib_path()
+    if not os.path.exists(path):
+        if not build_if_missing:
+            raise FileNotFoundError(path)
+        from . import build as _build
+        _build.build()
+    lib = ctypes.CDLL(path)
+    c = ctypes
+    lib.ulorl_version.restype = c.c_int32
+    lib.ulorl_status_string.restype = c.c_char_p
+    lib.ulorl_status_string.argtypes = [c.c_int32]
+    lib.ulorl_tune.restype = c.c_int32
+    lib.ulorl_tune.argtypes = [c.c_int32, c.c_int32]
+    lib.ulorl_token_loss_workspace_bytes.restype = c.c_size_t
+    lib.ulorl_token_loss_workspace_bytes.argtypes = [c.c_int64, c.c_int32]
+    vp = c.c_void_p
+    lib.ulorl_token_loss_fwd.restype = c.c_int32
+    lib.ulorl_token_loss_fwd.argtypes = [
+        vp, c.c_int32, c.c_int64, c.c_int64, c.c_int64,      # logits, dt, N, V, stride
+        vp, vp, c.c_int32,                                   # token_ids, cu_seqlens, R
+        vp, vp, vp,                                          # segment_ids, old_logp, advantages
+        c.POINTER(_CParams),
+        vp, vp, vp, vp, vp,                                  # loss, logp, entropy, lse, gcoef
+        vp, vp, vp,                                          # mpt_mask, ratio, segment_out
+        vp, vp, vp,                                          # resp_entropy, resp_gate, counters
+        vp, c.c_size_t, vp]                                  # workspace, bytes, stream
+    lib.ulorl_token_loss_bwd.restype = c.c_int32
+    lib.ulorl_token_loss_bwd.argtypes = [
+        vp, c.c_int32, c.c_int64, c.c_int64, c.c_int64, vp, vp, vp, c.c_float, vp, vp]
+    _lib = lib
+    return lib
+
+
+def version() -> int:
+    return int(load_library().ulorl_version())
+
+
+def status_string(status: int) -> str:
+    return load_library().ulorl_status_string(status).decode()
+
+
+def tune(knob: int, value: int) -> None:
+    rc = load_library().ulorl_tune(knob, value)
+    if rc != 0:
+        raise UlorlError(rc, "ulorl_tune")
+
+
+def token_loss_workspace_bytes(N: int, R: int) -> int:
+    return int(load_library().ulorl_token_loss_workspace_bytes(N, R))
+
+
+# ------------------------------------------------------------------------------------ helpers
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError("logits must be float32 or bfloat16, got %s" % t.dtype)
+
+
+def _check_logits(logits: torch.Tensor):
+    if not logits.is_cuda:
+        raise RuntimeError("libulorl runs on the GPU only: logits must be a device tensor")
+    if logits.dim() != 2 or logits.stride(1) != 1:
+        raise ValueError("logits must be [N, V] with unit stride along V")
+    return _dtype_code(logits), logits.shape[0], logits.shape[1], logits.stride(0)
+
+
+def _vec(t: Optional[torch.Tensor], dtype, n: int, name: str, dev):
+    if t is None:
+        return None
+    if t.device != dev or t.dtype != dtype or t.dim() != 1 or t.shape[0] != n or not t.is_contiguous():
+        raise ValueError("%s must be a contiguous %s[%d] tensor on %s" % (name, dtype, n, dev))
+    return t
+
+
+def _p(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(dev) -> ctypes.c_void_p:
+    return ctypes.c_void_p(torch.cuda.current_stream(dev).cuda_stream)
+
+
+@dataclass
+class FwdResult:
+    loss: Optional[torch.Tensor]
+    logp: torch.Tensor
+    entropy: torch.Tensor
+    lse: torch.Tensor
+    gcoef: Optional[torch.Tensor] = None
+    mpt_mask: Optional[torch.Tensor] = None
+    ratio: Optional[torch.Tensor] = None
+    segment_out: Optional[torch.Tensor] = None
+    resp_entropy: Optional[torch.Tensor] = None
+    resp_gate: Optional[torch.Tensor] = None
+    counters: Optional[torch.Tensor] = None
+
+
+def token_loss_fwd(logits, token_ids, cu_seqlens, advantages, old_logp=None, params: Params = None,
+                   segment_ids=None, out: Optional[FwdResult] = None,
+                   workspace: Optional[torch.Tensor] = None) -> FwdResult:
+    """ulorl_token_loss_fwd.  ``advantages=None`` selects the stats-only pass.
+    ``out``/``workspace`` let a caller reuse buffers (nothing is allocated then)."""
+    lib = load_library()
+    dt, N, V, stride = _check_logits(logits)
+    dev = logits.device
+    stats_only = advantages is None
+    token_ids = _vec(token_ids, torch.int32, N, "token_ids", dev)
+    f32 = dict(dtype=torch.float32, device=dev)
+    if out is None:
+        out = FwdResult(None, torch.empty(N, **f32), torch.empty(N, **f32), torch.empty(N, **f32))
+    R = 0
+    cparams = None
+    ws_bytes = 0
+    if not stats_only:
+        params = params or Params()
+        cparams = params.to_c()
+        if cu_seqlens.device != dev or cu_seqlens.dtype != torch.int32 or not cu_seqlens.is_contiguous():
+            raise ValueError("cu_seqlens must be a contiguous int32 device tensor")
+        R = cu_seqlens.shape[0] - 1
+        advantages = _vec(advantages, torch.float32, N, "advantages", dev)
+        old_logp = _vec(old_logp, torch.float32, N, "old_logp", dev)
+        segment_ids = _vec(segment_ids, torch.int32, N, "segment_ids", dev)
+        if out.loss is None:
+            out.loss = torch.empty(1, **f32)
+            out.gcoef = torch.empty(N, **f32)
+            out.mpt_mask = torch.empty(N, dtype=torch.uint8, device=dev)
+            out.ratio = torch.empty(N, **f32)
+            out.segment_out = torch.empty(N, dtype=torch.int32, device=dev)
+            out.resp_entropy = torch.empty(max(R, 1), **f32)[:R]
+            out.resp_gate = torch.empty(max(R, 1), dtype=torch.uint8, device=dev)[:R]
+            out.counters = torch.empty(4, dtype=torch.int64, device=dev)
+        ws_bytes = token_loss_workspace_bytes(N, R)
+        if workspace is None:
+            workspace = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
+        ws_bytes = workspace.numel() * workspace.element_size()
+    rc = lib.ulorl_token_loss_fwd(
+        _p(logits), dt, N, V, stride, _p(token_ids), _p(cu_seqlens) if not stats_only else None, R,
+        _p(segment_ids) if not stats_only else None, _p(old_logp) if not stats_only else None,
+        _p(advantages), ctypes.byref(cparams) if cparams is not None else None,
+        _p(out.loss), _p(out.logp), _p(out.entropy), _p(out.lse), _p(out.gcoef),
+        _p(out.mpt_mask), _p(out.ratio), _p(out.segment_out), _p(out.resp_entropy),
+        _p(out.resp_gate), _p(out.counters), _p(workspace), ws_bytes, _stream(dev))
+    if rc != 0:
+        raise UlorlError(rc, "ulorl_token_loss_fwd")
+    return out
+
+
+def row_stats(logits, token_ids, out: Optional[FwdResult] = None) -> FwdResult:
+    """Stats-only forward: lse, chosen-token log-prob and entropy per row."""
+    return token_loss_fwd(logits, token_ids, None, None, out=out)
+
+
+def token_loss_bwd(logits, token_ids, lse, gcoef, grad_out: float = 1.0,
+                   dlogits: Optional[torch.Tensor] = None, inplace: bool = False) -> torch.Tensor:
+    """ulorl_token_loss_bwd.  ``inplace=True`` overwrites ``logits`` with the gradient."""
+    lib = load_library()
+    dt, N, V, stride = _check_logits(logits)
+    dev = logits.device
+    token_ids = _vec(token_ids, torch.int32, N, "token_ids", dev)
+    lse = _vec(lse, torch.float32, N, "lse", dev)
+    gcoef = _vec(gcoef, torch.float32, N, "gcoef", dev)
+    if inplace:
+        dlogits = logits
+    elif dlogits is None:
+        dlogits = torch.empty_strided((N, V), (stride, 1), dtype=logits.dtype, device=dev)
+    if (dlogits.shape != logits.shape or dlogits.dtype != logits.dtype or dlogits.device != dev
+            or dlogits.stride() != logits.stride()):
+        raise ValueError("dlogits must match logits in shape, dtype, strides and device")
+    rc = lib.ulorl_token_loss_bwd(_p(logits), dt, N, V, stride, _p(token_ids), _p(lse), _p(gcoef),
+                                  float(grad_out), _p(dlogits), _stream(dev))
+    if rc != 0:
+        raise UlorlError(rc, "ulorl_token_loss_bwd")
+    return dlogits

@@ -1,0 +1,774 @@
+// Fused UloRL token loss for gfx950 (MI355X): streaming kernels and their C entry points.
+//
+// Three kernels do all the work of the forward/backward pair declared in ulorl.h:
+//   row_stats_kernel   one workgroup per token row streams the V logits once with 16-byte
+//                      loads and keeps a per-lane online (max, sum-exp, sum-exp*z) triple in
+//                      registers; lanes are merged with wave shuffles, waves through LDS.
+//                      -> lse, chosen-token log-prob (Eq. 6 numerator), entropy (Sec. 3.2.2).
+//   token_terms_*      O(N) epilogue: per-response mean entropy and gate, SAIS/POIS ratio
+//                      (Sec. 3.1.2), clipped term (Eq. 7), MPT mask (Eq. MPTS / I_msk), the
+//                      token-mean loss and d loss / d logp.  Fixed-order fp64 sums.
+//   dlogits_kernel     one workgroup per row re-reads the row, recomputes the softmax from the
+//                      saved lse and writes g_t * (onehot - p); rows with g_t == 0 are
+//                      write-only.  Safe in place: a row is read and written by one workgroup,
+//                      each 16-byte vector by the lane that loaded it.
+//
+// The HBM stream is the bound; the per-element VALU budget is what has to stay under it, so
+// the inner loops are: unpack, one FMA (scaled argument), one v_exp_f32, and two accumulate
+// ops in the forward; unpack, FMA, v_exp_f32 and a pack in the backward.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ulorl.h"
+
+// Every fused multiply-add in this file is written out as fmaf(): the error-free transforms
+// below (rescale by exactly 1 when the max is unchanged, TwoSum) are wrong if the compiler
+// fuses a rounded product into a neighbouring add.
+#pragma clang fp contract(off)
+
+namespace {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kEmpty = -1.0e30f;  // "no element seen yet"; finite so that 0 * kEmpty == 0
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ u32x4 load_stream(const u32x4* p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ void store_stream(u32x4* p, u32x4 v) { __builtin_nontemporal_store(v, p); }
+
+// ---------------------------------------------------------------------------------------------
+// storage traits: how a 16-byte vector maps to fp32 values
+// ---------------------------------------------------------------------------------------------
+struct StoreBF16 {
+    using elem = uint16_t;
+    static constexpr int kPerVec = 8;
+    static __device__ __forceinline__ void unpack(u32x4 v, float* f)
+    {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            f[2 * k] = __uint_as_float(v[k] << 16);
+            f[2 * k + 1] = __uint_as_float(v[k] & 0xffff0000u);
+        }
+    }
+    static __device__ __forceinline__ uint32_t pack2(float lo, float hi)
+    {
+        f32x2 x = {lo, hi};
+        bf16x2 b = __builtin_convertvector(x, bf16x2);  // round-to-nearest-even pair convert
+        return __builtin_bit_cast(uint32_t, b);
+    }
+    static __device__ __forceinline__ u32x4 pack(const float* f)
+    {
+        u32x4 v;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v[k] = pack2(f[2 * k], f[2 * k + 1]);
+        return v;
+    }
+    static __device__ __forceinline__ float load1(const elem* p) { return __uint_as_float(((uint32_t)*p) << 16); }
+    static __device__ __forceinline__ void store1(elem* p, float x) { *p = (elem)(pack2(x, 0.0f) & 0xffffu); }
+};
+
+struct StoreF32 {
+    using elem = float;
+    static constexpr int kPerVec = 4;
+    static __device__ __forceinline__ void unpack(u32x4 v, float* f)
+    {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) f[k] = __uint_as_float(v[k]);
+    }
+    static __device__ __forceinline__ u32x4 pack(const float* f)
+    {
+        u32x4 v;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v[k] = __float_as_uint(f[k]);
+        return v;
+    }
+    static __device__ __forceinline__ float load1(const elem* p) { return *p; }
+    static __device__ __forceinline__ void store1(elem* p, float x) { *p = x; }
+};
+
+// ---------------------------------------------------------------------------------------------
+// online softmax statistics
+// ---------------------------------------------------------------------------------------------
+// Per lane: m = running max, mL = fl(m * log2e), S + Sc = sum 2^(z*log2e - mL),
+// T = sum 2^(z*log2e - mL) * (z*log2e - mL)   (log2 units, <= 0).
+//
+// A peaked row has one term equal to 1 and ~V terms of 1e-8: added one by one to a running
+// fp32 sum near 1 they would vanish below half an ulp.  So the terms of a chunk are first
+// summed as a pairwise tree (the big term meets only log2(chunk) partial sums), and the chunk
+// total is added to the running sum with an error-free TwoSum whose residual is carried in Sc.
+struct LaneAcc {
+    float m, mL, S, Sc, T;
+};
+
+template <int COUNT>
+__device__ __forceinline__ void absorb(const float* f, LaneAcc& a)
+{
+    static_assert((COUNT & (COUNT - 1)) == 0, "chunk size must be a power of two");
+    float cm = f[0];
+#pragma unroll
+    for (int k = 1; k < COUNT; ++k) cm = fmaxf(cm, f[k]);
+    // rescale the running sums if this chunk raises the lane's max (branch-free; one exp per chunk)
+    const float mn = fmaxf(a.m, cm);
+    const float mLn = mn * kLog2e;
+    const float d = a.mL - mLn;  // <= 0
+    const float sc = fast_exp2(d);
+    float T = sc * fmaf(d, a.S, a.T);
+    const float S = sc * a.S;
+    const float Sc = sc * a.Sc;
+    float e[COUNT];
+#pragma unroll
+    for (int k = 0; k < COUNT; ++k) {
+        const float x = fmaf(f[k], kLog2e, -mLn);
+        e[k] = fast_exp2(x);
+        T = fmaf(e[k], x, T);
+    }
+#pragma unroll
+    for (int w = COUNT / 2; w >= 1; w >>= 1) {
+#pragma unroll
+        for (int k = 0; k < w; ++k) e[k] += e[k + w];
+    }
+    // TwoSum(S, e[0])
+    const float t = S + e[0];
+    const float bv = t - S;
+    const float err = (S - (t - bv)) + (e[0] - bv);
+    a.S = t;
+    a.Sc = Sc + err;
+    a.T = T;
+    a.m = mn;
+    a.mL = mLn;
+}
+
+// (m, S, T) with T in log2 units relative to m; exact when the two maxima coincide.
+__device__ __forceinline__ void merge(float& m, float& S, float& T, float m2, float S2, float T2)
+{
+    const float M = fmaxf(m, m2);
+    const float d1 = (m - M) * kLog2e;
+    const float d2 = (m2 - M) * kLog2e;
+    const float s1 = fast_exp2(d1);
+    const float s2 = fast_exp2(d2);
+    T = s1 * fmaf(d1, S, T) + s2 * fmaf(d2, S2, T2);
+    S = s1 * S + s2 * S2;
+    m = M;
+}
+
+template <class Tr, int NT, int U>
+__global__ __launch_bounds__(NT) void row_stats_kernel(const typename Tr::elem* __restrict__ logits,
+                                                       int64_t row_stride, int32_t V,
+                                                       const int32_t* __restrict__ token_ids,
+                                                       float* __restrict__ lse_out,
+                                                       float* __restrict__ logp_out,
+                                                       float* __restrict__ ent_out)
+{
+    constexpr int E = Tr::kPerVec;
+    constexpr int NW = NT / 64;
+    const int64_t row = blockIdx.x;
+    const typename Tr::elem* rowp = logits + row * row_stride;
+    const u32x4* vp = reinterpret_cast<const u32x4*>(rowp);
+    const int nvec = V / E;
+    const int tid = threadIdx.x;
+
+    LaneAcc a = {kEmpty, kEmpty * kLog2e, 0.0f, 0.0f, 0.0f};
+
+    int i = tid;
+    for (; i + (U - 1) * NT < nvec; i += U * NT) {
+        u32x4 v[U];
+#pragma unroll
+        for (int k = 0; k < U; ++k) v[k] = load_stream(vp + i + k * NT);
+        float f[U * E];
+#pragma unroll
+        for (int k = 0; k < U; ++k) Tr::unpack(v[k], f + k * E);
+        absorb<U * E>(f, a);
+    }
+    for (; i < nvec; i += NT) {
+        float f[E];
+        Tr::unpack(load_stream(vp + i), f);
+        absorb<E>(f, a);
+    }
+    if (tid == NT - 1) {  // ragged tail when V is not a multiple of the vector width
+        for (int j = nvec * E; j < V; ++j) {
+            float f = Tr::load1(rowp + j);
+            absorb<1>(&f, a);
+        }
+    }
+
+    // The fused argument z*log2e - mL differs from (z - m)*log2e by the rounding residual of
+    // mL, the same for every term of the lane: take it out once so that the term of the
+    // maximum is exactly 1.
+    const float delta = fmaf(a.m, kLog2e, -a.mL);
+    const float un = fast_exp2(-delta);
+    float m = a.m;
+    float S = un * (a.S + a.Sc);
+    float T = un * fmaf(-delta, a.S, a.T);
+
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const float m2 = __shfl_xor(m, off);
+        const float S2 = __shfl_xor(S, off);
+        const float T2 = __shfl_xor(T, off);
+        merge(m, S, T, m2, S2, T2);
+    }
+    __shared__ float sm[NW], sS[NW], sT[NW];
+    if ((tid & 63) == 0) {
+        sm[tid >> 6] = m;
+        sS[tid >> 6] = S;
+        sT[tid >> 6] = T;
+    }
+    __syncthreads();
+    if (tid == 0) {
+#pragma unroll
+        for (int w = 1; w < NW; ++w) merge(m, S, T, sm[w], sS[w], sT[w]);
+        const float lnS = logf(S);
+        const int32_t y = token_ids[row];
+        float lp = __builtin_nanf("");
+        if (y >= 0 && y < V) lp = (Tr::load1(rowp + y) - m) - lnS;
+        lse_out[row] = m + lnS;
+        logp_out[row] = lp;
+        ent_out[row] = lnS - (T * kLn2) / S;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// backward stream
+// ---------------------------------------------------------------------------------------------
+template <class Tr, int NT, int U>
+__global__ __launch_bounds__(NT) void dlogits_kernel(const typename Tr::elem* logits,
+                                                     int64_t row_stride, int32_t V,
+                                                     const int32_t* __restrict__ token_ids,
+                                                     const float* __restrict__ lse,
+                                                     const float* __restrict__ gcoef, float grad_out,
+                                                     typename Tr::elem* dlogits)
+{
+    constexpr int E = Tr::kPerVec;
+    const int64_t row = blockIdx.x;
+    const typename Tr::elem* rowp = logits + row * row_stride;
+    typename Tr::elem* outp = dlogits + row * row_stride;
+    const u32x4* vp = reinterpret_cast<const u32x4*>(rowp);
+    u32x4* op = reinterpret_cast<u32x4*>(outp);
+    const int nvec = V / E;
+    const int tid = threadIdx.x;
+
+    const float g = gcoef[row] * grad_out;
+    const float l = lse[row];
+    const int32_t y = token_ids[row];
+    const bool live = (g != 0.0f) && (fabsf(g) <= 3.0e38f) && (fabsf(l) <= 3.0e38f) && y >= 0 && y < V;
+
+    if (!live) {  // masked / clipped / zero-advantage / invalid row: write-only
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+        for (int i = tid; i < nvec; i += NT) store_stream(op + i, zero);
+        if (tid == NT - 1)
+            for (int j = nvec * E; j < V; ++j) Tr::store1(outp + j, 0.0f);
+        return;
+    }
+
+    // -g * exp(z - lse) = -sign(g) * 2^(z*log2e + c),  c = log2|g| - lse*log2e
+    const float c = fmaf(-l, kLog2e, log2f(fabsf(g)));
+    const float sgn = g > 0.0f ? -1.0f : 1.0f;
+    const int yvec = y / E;
+
+    int i = tid;
+    for (; i + (U - 1) * NT < nvec; i += U * NT) {
+        u32x4 v[U];
+#pragma unroll
+        for (int k = 0; k < U; ++k) v[k] = load_stream(vp + i + k * NT);
+#pragma unroll
+        for (int k = 0; k < U; ++k) {
+            float f[E];
+            Tr::unpack(v[k], f);
+#pragma unroll
+            for (int e = 0; e < E; ++e) f[e] = sgn * fast_exp2(fmaf(f[e], kLog2e, c));
+            if (i + k * NT == yvec) {
+#pragma unroll
+                for (int e = 0; e < E; ++e) f[e] += (e == y - yvec * E) ? g : 0.0f;
+            }
+            store_stream(op + i + k * NT, Tr::pack(f));
+        }
+    }
+    for (; i < nvec; i += NT) {
+        float f[E];
+        Tr::unpack(load_stream(vp + i), f);
+#pragma unroll
+        for (int e = 0; e < E; ++e) f[e] = sgn * fast_exp2(fmaf(f[e], kLog2e, c));
+        if (i == yvec) {
+#pragma unroll
+            for (int e = 0; e < E; ++e) f[e] += (e == y - yvec * E) ? g : 0.0f;
+        }
+        store_stream(op + i, Tr::pack(f));
+    }
+    if (tid == NT - 1) {
+        for (int j = nvec * E; j < V; ++j) {
+            float x = sgn * fast_exp2(fmaf(Tr::load1(rowp + j), kLog2e, c));
+            if (j == y) x += g;
+            Tr::store1(outp + j, x);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// O(N) epilogue of the forward call
+// ---------------------------------------------------------------------------------------------
+constexpr int kTokBlock = 1024;
+
+struct TokenArgs {
+    const float* logp;
+    const float* entropy;
+    const float* lse;
+    const int32_t* token_ids;
+    const int32_t* cu;
+    const int32_t* segment_ids;
+    const float* old_logp;
+    const float* adv;
+    float* gcoef;
+    uint8_t* mask;
+    float* ratio;
+    int32_t* seg_out;
+    float* resp_entropy;
+    uint8_t* resp_gate;
+    double* hsum;       // [R] workspace
+    uint32_t* rflags;   // [R] workspace
+    double* part_sum;   // [nblk] workspace
+    int64_t* part_cnt;  // [nblk * 4] workspace
+    int64_t N;
+    int32_t V, R;
+    int32_t is_mode, gate_mode, seg_len;
+    double eps_low, eps_high, tau, sigma, D;
+};
+
+__device__ __forceinline__ double shfl_xor_f64(double x, int off)
+{
+    int lo = __double2loint(x), hi = __double2hiint(x);
+    lo = __shfl_xor(lo, off);
+    hi = __shfl_xor(hi, off);
+    return __hiloint2double(hi, lo);
+}
+
+// Fixed-shape tree: lanes by xor-shuffle, then waves through LDS in index order.
+template <int NT>
+__device__ __forceinline__ double block_sum_f64(double x, double* scratch)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) x += shfl_xor_f64(x, off);
+    const int tid = threadIdx.x;
+    __syncthreads();
+    if ((tid & 63) == 0) scratch[tid >> 6] = x;
+    __syncthreads();
+    double s = 0.0;
+#pragma unroll
+    for (int w = 0; w < NT / 64; ++w) s += scratch[w];
+    return s;
+}
+
+template <int NT>
+__device__ __forceinline__ long long block_sum_i64(long long x, long long* scratch)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        int lo = (int)(x & 0xffffffffll), hi = (int)(x >> 32);
+        lo = __shfl_xor(lo, off);
+        hi = __shfl_xor(hi, off);
+        x += ((long long)hi << 32) | (unsigned int)lo;
+    }
+    const int tid = threadIdx.x;
+    __syncthreads();
+    if ((tid & 63) == 0) scratch[tid >> 6] = x;
+    __syncthreads();
+    long long s = 0;
+#pragma unroll
+    for (int w = 0; w < NT / 64; ++w) s += scratch[w];
+    return s;
+}
+
+// Bitwise OR of the three status bits over the workgroup (__syncthreads_or is a logical OR).
+__device__ __forceinline__ int block_or_bits(int flags)
+{
+    int r = 0;
+#pragma unroll
+    for (int bit = 1; bit <= 4; bit <<= 1) r |= __syncthreads_or(flags & bit) ? bit : 0;
+    return r;
+}
+
+// One workgroup per response: sum of the token entropies (Sec. 3.2.2, H-bar_i numerator) and a
+// sanity check of the response's bounds.
+__global__ __launch_bounds__(kTokBlock) void response_entropy_kernel(TokenArgs a)
+{
+    __shared__ double scratch[kTokBlock / 64];
+    const int i = blockIdx.x;
+    const int64_t b = a.cu[i], e = a.cu[i + 1];
+    const bool ok = b >= 0 && e >= b && e <= a.N && (i != 0 || b == 0) && (i != a.R - 1 || e == a.N);
+    double s = 0.0;
+    if (ok)
+        for (int64_t t = b + threadIdx.x; t < e; t += kTokBlock) s += (double)a.entropy[t];
+    s = block_sum_f64<kTokBlock>(s, scratch);
+    if (threadIdx.x == 0) {
+        a.hsum[i] = s;
+        a.rflags[i] = ok ? 0u : 1u;
+    }
+}
+
+__global__ __launch_bounds__(kTokBlock) void token_terms_kernel(TokenArgs a)
+{
+    __shared__ double scratch[kTokBlock / 64];
+    __shared__ long long iscratch[kTokBlock / 64];
+    const int tid = threadIdx.x;
+
+    // call-wide facts every block derives identically: any malformed response, global entropy
+    int badcu = 0;
+    double hall = 0.0;
+    for (int i = tid; i < a.R; i += kTokBlock) {
+        badcu |= (int)a.rflags[i];
+        hall += a.hsum[i];
+    }
+    badcu = __syncthreads_or(badcu);
+    double hglobal = 0.0;
+    if (a.gate_mode == ULORL_GATE_GLOBAL) hglobal = block_sum_f64<kTokBlock>(hall, scratch) / (double)a.N;
+
+    const int64_t t = (int64_t)blockIdx.x * kTokBlock + tid;
+    double contrib = 0.0;
+    long long n_mask = 0, n_clip = 0, n_pos = 0, flags = badcu ? ULORL_STATUS_BAD_CU : 0;
+
+    if (t < a.N) {
+        // response of token t: largest i with cu[i] <= t
+        int lo = 0, hi = a.R;  // invariant: cu[lo] <= t < cu[hi] for well-formed input
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if ((int64_t)a.cu[mid] <= t) lo = mid; else hi = mid;
+        }
+        const int i = lo;
+        const int64_t b = a.cu[i];
+        const int64_t L = (int64_t)a.cu[i + 1] - b;
+
+        int gate;
+        double hbar = 0.0;
+        if (!badcu && L > 0) hbar = a.hsum[i] / (double)L;
+        switch (a.gate_mode) {
+        case ULORL_GATE_PER_RESPONSE: gate = (!badcu && L > 0) && (hbar < a.sigma); break;
+        case ULORL_GATE_GLOBAL: gate = hglobal < a.sigma; break;
+        case ULORL_GATE_ALWAYS: gate = 1; break;
+        default: gate = 0; break;
+        }
+        const int32_t seg = a.segment_ids ? a.segment_ids[t]
+                                          : (a.seg_len > 0 && !badcu ? (int32_t)((t - b) / a.seg_len) : 0);
+        if (a.seg_out) a.seg_out[t] = seg;
+
+        const float lpf = a.logp[t];
+        const float hf = a.entropy[t];
+        const float lf = a.lse[t];
+        const int32_t y = a.token_ids[t];
+        const bool bad_tok = (y < 0 || y >= a.V);
+        const bool nonfinite = !(fabsf(lpf) <= 3.0e38f) || !(fabsf(hf) <= 3.0e38f) || !(fabsf(lf) <= 3.0e38f);
+        if (bad_tok) flags |= ULORL_STATUS_BAD_TOKEN;
+        if (!bad_tok && nonfinite) flags |= ULORL_STATUS_NONFINITE;
+
+        float g_out = 0.0f, r_out = 0.0f;
+        uint8_t m_out = 0;
+        if (!bad_tok && !nonfinite && !badcu) {
+            const double lp = (double)lpf;
+            const double A = (double)a.adv[t];
+            const double p = exp(lp);
+            const bool positive = A > 0.0;
+            const bool I = gate && positive && (p >= a.tau);
+            const double r = (a.is_mode == ULORL_IS_POIS) ? 1.0 : exp(lp - (double)a.old_logp[t]);
+            const double c = fmin(fmax(r, 1.0 - a.eps_low), 1.0 + a.eps_high);
+            const double u = r * A, v = c * A;
+            const bool active = u <= v;
+            const double s = active ? u : v;
+            contrib = I ? 0.0 : s;
+            g_out = (I || !active) ? 0.0f : (float)(-(r * A) / a.D);
+            r_out = (float)r;
+            m_out = I ? 1 : 0;
+            n_mask = I;
+            n_clip = !active;
+            n_pos = positive;
+        }
+        a.gcoef[t] = g_out;
+        if (a.ratio) a.ratio[t] = r_out;
+        if (a.mask) a.mask[t] = m_out;
+    }
+
+    const double bs = block_sum_f64<kTokBlock>(contrib, scratch);
+    const long long c0 = block_sum_i64<kTokBlock>(n_mask, iscratch);
+    const long long c1 = block_sum_i64<kTokBlock>(n_clip, iscratch);
+    const long long c2 = block_sum_i64<kTokBlock>(n_pos, iscratch);
+    const int fl = block_or_bits((int)flags);
+    if (tid == 0) {
+        a.part_sum[blockIdx.x] = bs;
+        a.part_cnt[4 * (int64_t)blockIdx.x + 0] = c0;
+        a.part_cnt[4 * (int64_t)blockIdx.x + 1] = c1;
+        a.part_cnt[4 * (int64_t)blockIdx.x + 2] = c2;
+        a.part_cnt[4 * (int64_t)blockIdx.x + 3] = fl;
+    }
+}
+
+__global__ __launch_bounds__(kTokBlock) void loss_finalize_kernel(TokenArgs a, int64_t nblk, float* loss,
+                                                                 int64_t* counters)
+{
+    __shared__ double scratch[kTokBlock / 64];
+    __shared__ long long iscratch[kTokBlock / 64];
+    const double* part_sum = a.part_sum;
+    const int64_t* part_cnt = a.part_cnt;
+    const double D = a.D;
+
+    // per-response outputs: mean entropy and gate (same call-wide reductions as token_terms_kernel)
+    {
+        int badcu = 0;
+        double hall = 0.0;
+        for (int i = threadIdx.x; i < a.R; i += kTokBlock) {
+            badcu |= (int)a.rflags[i];
+            hall += a.hsum[i];
+        }
+        badcu = __syncthreads_or(badcu);
+        double hglobal = 0.0;
+        if (a.gate_mode == ULORL_GATE_GLOBAL) hglobal = block_sum_f64<kTokBlock>(hall, scratch) / (double)a.N;
+        for (int i = threadIdx.x; i < a.R; i += kTokBlock) {
+            const int64_t L = badcu ? 0 : (int64_t)a.cu[i + 1] - (int64_t)a.cu[i];
+            const double hbar = L > 0 ? a.hsum[i] / (double)L : 0.0;
+            int gate;
+            switch (a.gate_mode) {
+            case ULORL_GATE_PER_RESPONSE: gate = L > 0 && hbar < a.sigma; break;
+            case ULORL_GATE_GLOBAL: gate = hglobal < a.sigma; break;
+            case ULORL_GATE_ALWAYS: gate = 1; break;
+            default: gate = 0; break;
+            }
+            if (a.resp_entropy) a.resp_entropy[i] = (float)hbar;
+            if (a.resp_gate) a.resp_gate[i] = badcu ? 0 : (uint8_t)gate;
+        }
+    }
+    double s = 0.0;
+    long long c0 = 0, c1 = 0, c2 = 0;
+    int fl = 0;
+    for (int64_t k = threadIdx.x; k < nblk; k += kTokBlock) {
+        s += part_sum[k];
+        c0 += part_cnt[4 * k + 0];
+        c1 += part_cnt[4 * k + 1];
+        c2 += part_cnt[4 * k + 2];
+        fl |= (int)part_cnt[4 * k + 3];
+    }
+    s = block_sum_f64<kTokBlock>(s, scratch);
+    c0 = block_sum_i64<kTokBlock>(c0, iscratch);
+    c1 = block_sum_i64<kTokBlock>(c1, iscratch);
+    c2 = block_sum_i64<kTokBlock>(c2, iscratch);
+    fl = block_or_bits(fl);
+    if (threadIdx.x == 0) {
+        *loss = (float)(-s / D);
+        if (counters) {
+            counters[0] = c0;
+            counters[1] = c1;
+            counters[2] = c2;
+            counters[3] = fl;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------------
+struct Tuning {
+    int fwd_threads = 256, fwd_unroll = 4;
+    int bwd_threads = 256, bwd_unroll = 4;
+};
+Tuning g_tune;
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct WorkspaceLayout {
+    size_t hsum, rflags, part_sum, part_cnt, total;
+    int64_t nblk;
+};
+
+WorkspaceLayout workspace_layout(int64_t N, int32_t R)
+{
+    WorkspaceLayout w;
+    w.nblk = (N + kTokBlock - 1) / kTokBlock;
+    size_t off = 0;
+    w.hsum = off;     off = align_up(off + sizeof(double) * (size_t)R, 256);
+    w.rflags = off;   off = align_up(off + sizeof(uint32_t) * (size_t)R, 256);
+    w.part_sum = off; off = align_up(off + sizeof(double) * (size_t)w.nblk, 256);
+    w.part_cnt = off; off = align_up(off + sizeof(int64_t) * 4 * (size_t)w.nblk, 256);
+    w.total = off;
+    return w;
+}
+
+bool shape_ok(int64_t N, int64_t V, int64_t stride)
+{
+    return N > 0 && N <= 0x7fffffffLL && V > 0 && V <= 0x7fffffffLL && stride >= V;
+}
+
+int32_t check_logits(const void* logits, int32_t dt, int64_t N, int64_t V, int64_t stride)
+{
+    if (!logits) return ULORL_ERR_NULL;
+    if (dt != ULORL_F32 && dt != ULORL_BF16) return ULORL_ERR_DTYPE;
+    if (!shape_ok(N, V, stride)) return ULORL_ERR_SHAPE;
+    const size_t esz = dt == ULORL_F32 ? 4 : 2;
+    if (((uintptr_t)logits & 15u) != 0 || ((size_t)stride * esz) % 16 != 0) return ULORL_ERR_ALIGN;
+    return ULORL_OK;
+}
+
+template <class Tr, int NT, int U>
+void launch_row_stats(const void* logits, int64_t N, int64_t V, int64_t stride, const int32_t* y, float* lse,
+                      float* logp, float* ent, hipStream_t st)
+{
+    hipLaunchKernelGGL((row_stats_kernel<Tr, NT, U>), dim3((unsigned)N), dim3(NT), 0, st,
+                       (const typename Tr::elem*)logits, stride, (int32_t)V, y, lse, logp, ent);
+}
+
+template <class Tr>
+bool dispatch_row_stats(int nt, int u, const void* logits, int64_t N, int64_t V, int64_t stride, const int32_t* y,
+                        float* lse, float* logp, float* ent, hipStream_t st)
+{
+#define ULORL_CASE(NT_, U_)                                                          \
+    if (nt == NT_ && u == U_) {                                                      \
+        launch_row_stats<Tr, NT_, U_>(logits, N, V, stride, y, lse, logp, ent, st);  \
+        return true;                                                                 \
+    }
+    ULORL_CASE(256, 2) ULORL_CASE(256, 4) ULORL_CASE(256, 8)
+    ULORL_CASE(512, 2) ULORL_CASE(512, 4) ULORL_CASE(512, 8)
+    ULORL_CASE(1024, 2) ULORL_CASE(1024, 4) ULORL_CASE(1024, 8)
+#undef ULORL_CASE
+    return false;
+}
+
+template <class Tr, int NT, int U>
+void launch_dlogits(const void* logits, int64_t N, int64_t V, int64_t stride, const int32_t* y, const float* lse,
+                    const float* g, float grad_out, void* dz, hipStream_t st)
+{
+    hipLaunchKernelGGL((dlogits_kernel<Tr, NT, U>), dim3((unsigned)N), dim3(NT), 0, st,
+                       (const typename Tr::elem*)logits, stride, (int32_t)V, y, lse, g, grad_out,
+                       (typename Tr::elem*)dz);
+}
+
+template <class Tr>
+bool dispatch_dlogits(int nt, int u, const void* logits, int64_t N, int64_t V, int64_t stride, const int32_t* y,
+                      const float* lse, const float* g, float grad_out, void* dz, hipStream_t st)
+{
+#define ULORL_CASE(NT_, U_)                                                              \
+    if (nt == NT_ && u == U_) {                                                          \
+        launch_dlogits<Tr, NT_, U_>(logits, N, V, stride, y, lse, g, grad_out, dz, st);  \
+        return true;                                                                     \
+    }
+    ULORL_CASE(256, 2) ULORL_CASE(256, 4) ULORL_CASE(256, 8)
+    ULORL_CASE(512, 2) ULORL_CASE(512, 4) ULORL_CASE(512, 8)
+    ULORL_CASE(1024, 2) ULORL_CASE(1024, 4) ULORL_CASE(1024, 8)
+#undef ULORL_CASE
+    return false;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t ulorl_version(void) { return 100; }
+
+const char* ulorl_status_string(int32_t status)
+{
+    switch (status) {
+    case ULORL_OK: return "ok";
+    case ULORL_ERR_NULL: return "required pointer is NULL";
+    case ULORL_ERR_SHAPE: return "shape out of range";
+    case ULORL_ERR_DTYPE: return "unknown storage type";
+    case ULORL_ERR_ALIGN: return "logits base or row stride not 16-byte aligned";
+    case ULORL_ERR_PARAM: return "invalid parameter";
+    case ULORL_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case ULORL_ERR_HIP: return "HIP launch failed";
+    default: return "unknown status";
+    }
+}
+
+int32_t ulorl_tune(int32_t knob, int32_t value)
+{
+    const bool threads_ok = value == 256 || value == 512 || value == 1024;
+    const bool unroll_ok = value == 2 || value == 4 || value == 8;
+    switch (knob) {
+    case ULORL_TUNE_FWD_THREADS: if (!threads_ok) return ULORL_ERR_PARAM; g_tune.fwd_threads = value; return ULORL_OK;
+    case ULORL_TUNE_FWD_UNROLL:  if (!unroll_ok) return ULORL_ERR_PARAM;  g_tune.fwd_unroll = value;  return ULORL_OK;
+    case ULORL_TUNE_BWD_THREADS: if (!threads_ok) return ULORL_ERR_PARAM; g_tune.bwd_threads = value; return ULORL_OK;
+    case ULORL_TUNE_BWD_UNROLL:  if (!unroll_ok) return ULORL_ERR_PARAM;  g_tune.bwd_unroll = value;  return ULORL_OK;
+    default: return ULORL_ERR_PARAM;
+    }
+}
+
+size_t ulorl_token_loss_workspace_bytes(int64_t N, int32_t R)
+{
+    if (N <= 0 || N > 0x7fffffffLL || R <= 0) return 0;
+    return workspace_layout(N, R).total;
+}
+
+int32_t ulorl_token_loss_fwd(const void* logits, int32_t dt, int64_t N, int64_t V, int64_t row_stride,
+                             const int32_t* token_ids, const int32_t* cu_seqlens, int32_t R,
+                             const int32_t* segment_ids, const float* old_logp, const float* advantages,
+                             const ulorl_params* p, float* loss, float* logp, float* entropy, float* lse,
+                             float* gcoef, uint8_t* mpt_mask, float* ratio, int32_t* segment_out,
+                             float* resp_entropy, uint8_t* resp_gate, int64_t* counters, void* workspace,
+                             size_t workspace_bytes, void* hip_stream)
+{
+    int32_t rc = check_logits(logits, dt, N, V, row_stride);
+    if (rc != ULORL_OK) return rc;
+    if (!token_ids || !logp || !entropy || !lse) return ULORL_ERR_NULL;
+    const bool stats_only = advantages == nullptr;
+    WorkspaceLayout wl = {};
+    if (!stats_only) {
+        if (!p || !cu_seqlens || !loss || !gcoef) return ULORL_ERR_NULL;
+        if (R <= 0) return ULORL_ERR_SHAPE;
+        if (!(p->eps_low >= 0.0f) || !(p->eps_high >= 0.0f) || !(p->tau > 0.0f && p->tau <= 1.0f) ||
+            !(p->sigma == p->sigma) || p->seg_len < 0 || p->reserved != 0)
+            return ULORL_ERR_PARAM;
+        if (p->is_mode != ULORL_IS_SAIS && p->is_mode != ULORL_IS_POIS) return ULORL_ERR_PARAM;
+        if (p->gate_mode < ULORL_GATE_PER_RESPONSE || p->gate_mode > ULORL_GATE_NEVER) return ULORL_ERR_PARAM;
+        if (p->is_mode == ULORL_IS_SAIS && !old_logp) return ULORL_ERR_NULL;
+        wl = workspace_layout(N, R);
+        if (!workspace || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < wl.total)
+            return ULORL_ERR_WORKSPACE;
+    }
+    hipStream_t st = (hipStream_t)hip_stream;
+
+    bool ok = dt == ULORL_BF16
+                  ? dispatch_row_stats<StoreBF16>(g_tune.fwd_threads, g_tune.fwd_unroll, logits, N, V, row_stride,
+                                                  token_ids, lse, logp, entropy, st)
+                  : dispatch_row_stats<StoreF32>(g_tune.fwd_threads, g_tune.fwd_unroll, logits, N, V, row_stride,
+                                                 token_ids, lse, logp, entropy, st);
+    if (!ok || hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;
+    if (stats_only) return ULORL_OK;
+
+    char* ws = (char*)workspace;
+    TokenArgs a;
+    a.logp = logp; a.entropy = entropy; a.lse = lse; a.token_ids = token_ids; a.cu = cu_seqlens;
+    a.segment_ids = segment_ids; a.old_logp = old_logp; a.adv = advantages; a.gcoef = gcoef;
+    a.mask = mpt_mask; a.ratio = ratio; a.seg_out = segment_out; a.resp_entropy = resp_entropy;
+    a.resp_gate = resp_gate;
+    a.hsum = (double*)(ws + wl.hsum); a.rflags = (uint32_t*)(ws + wl.rflags);
+    a.part_sum = (double*)(ws + wl.part_sum); a.part_cnt = (int64_t*)(ws + wl.part_cnt);
+    a.N = N; a.V = (int32_t)V; a.R = R;
+    a.is_mode = p->is_mode; a.gate_mode = p->gate_mode; a.seg_len = p->seg_len;
+    a.eps_low = (double)p->eps_low; a.eps_high = (double)p->eps_high;
+    a.tau = (double)p->tau; a.sigma = (double)p->sigma;
+    a.D = p->denominator > 0.0 ? p->denominator : (double)N;
+
+    hipLaunchKernelGGL(response_entropy_kernel, dim3((unsigned)R), dim3(kTokBlock), 0, st, a);
+    hipLaunchKernelGGL(token_terms_kernel, dim3((unsigned)wl.nblk), dim3(kTokBlock), 0, st, a);
+    hipLaunchKernelGGL(loss_finalize_kernel, dim3(1), dim3(kTokBlock), 0, st, a, wl.nblk, loss, counters);
+    if (hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;
+    return ULORL_OK;
+}
+
+int32_t ulorl_token_loss_bwd(const void* logits, int32_t dt, int64_t N, int64_t V, int64_t row_stride,
+                             const int32_t* token_ids, const float* lse, const float* gcoef, float grad_out,
+                             void* dlogits, void* hip_stream)
+{
+    int32_t rc = check_logits(logits, dt, N, V, row_stride);
+    if (rc != ULORL_OK) return rc;
+    if (!token_ids || !lse || !gcoef || !dlogits) return ULORL_ERR_NULL;
+    if (((uintptr_t)dlogits & 15u) != 0) return ULORL_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)hip_stream;
+    bool ok = dt == ULORL_BF16
+                  ? dispatch_dlogits<StoreBF16>(g_tune.bwd_threads, g_tune.bwd_unroll, logits, N, V, row_stride,
+                                                token_ids, lse, gcoef, grad_out, dlogits, st)
+                  : dispatch_dlogits<StoreF32>(g_tune.bwd_threads, g_tune.bwd_unroll, logits, N, V, row_stride,
+                                               token_ids, lse, gcoef, grad_out, dlogits, st);
+    if (!ok || hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;
+    return ULORL_OK;
+}
+
+}  // extern "C"

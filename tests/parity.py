@@ -1,0 +1,158 @@
+"""Shared machinery of the GPU-vs-oracle parity tests: run the HIP path through the C ABI,
+run the fp64 oracle on the same seeded inputs, compare element by element.
+
+Tolerances (derivation in DESIGN.md, "Tolerances"):
+  * integer / byte outputs (MPT mask, segment ids, gates, counters): bit-exact, except that
+    tokens whose oracle probability lies within 1e-6 of tau (mask) or whose ratio lies within
+    1e-5 of a clip edge (clip counter) are excluded -- both are discontinuities.
+  * per-row floats computed in fp32 from exact inputs (lse, logp, entropy, ratio, gcoef, loss):
+    |gpu - ref| <= RTOL*|ref| + ATOL with RTOL = 1e-5 for fp32 logits and 2e-5 for bf16 logits
+    (far inside the 2e-3 asked for bf16), ATOL = 2e-6 (the resolution of fp32 logits of
+    magnitude 16-32, which bounds any difference of two of them).
+  * dlogits: fp32 storage RTOL*|ref| + 4e-6*|g_t|; bf16 storage additionally half a bf16 ulp,
+    2^-8*|ref| (round-to-nearest-even of the fp32 value).
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import oracle
+import paper_2507_19766_amd as ulorl
+import ulorl_inputs as ui
+
+ATOL = 2e-6
+
+
+def rtol_for(dtype: str) -> float:
+    return 1e-5 if dtype == "f32" else 2e-5
+
+
+def assert_close(name, got, ref, rtol, atol=ATOL):
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, (name, got.shape, ref.shape)
+    err = np.abs(got - ref)
+    bound = rtol * np.abs(ref) + atol
+    bad = ~(err <= bound)
+    if bad.any():
+        k = int(np.argmax(err - bound))
+        raise AssertionError("%s: %d/%d outside tolerance; worst at %d: gpu=%r ref=%r err=%.3e bound=%.3e"
+                             % (name, bad.sum(), bad.size, k, got.flat[k], ref.flat[k], err.flat[k], bound.flat[k]))
+
+
+def params_for(w: ui.Workload, **kw) -> ulorl.Params:
+    base = dict(eps_low=w.eps_low, eps_high=w.eps_high, tau=w.tau, sigma=w.sigma, seg_len=w.seg_len)
+    base.update(kw)
+    return ulorl.Params(**base)
+
+
+def f32(x: float) -> float:
+    """The double value of x after the float32 rounding the C struct applies."""
+    return float(np.float32(x))
+
+
+def oracle_terms(logp, ent, cu, adv, old, p: ulorl.Params, denominator=None, segment_ids=None):
+    return oracle.token_terms(
+        logp, ent, cu, adv, old, segment_ids=segment_ids, seg_len=p.seg_len,
+        eps_low=f32(p.eps_low), eps_high=f32(p.eps_high), tau=f32(p.tau), sigma=f32(p.sigma),
+        is_mode=p.is_mode, gate_mode=p.gate_mode,
+        denominator=p.denominator if denominator is None else denominator)
+
+
+def check_token_outputs(res: ulorl.FwdResult, tt, o_logp, p: ulorl.Params, rtol, rows=None,
+                        check_counters=True):
+    """Per-token outputs of the forward call against the oracle's token terms."""
+    sel = slice(None) if rows is None else rows
+    g_mask = res.mpt_mask.cpu().numpy()[sel]
+    g_ratio = res.ratio.cpu().numpy()[sel]
+    g_g = res.gcoef.cpu().numpy()[sel]
+    prob = np.exp(o_logp)
+    near_tau = np.abs(prob - f32(p.tau)) < 1e-6
+    near_edge = (np.abs(tt.ratio - (1 - f32(p.eps_low))) < 1e-5) | (np.abs(tt.ratio - (1 + f32(p.eps_high))) < 1e-5)
+    ok_m = ~near_tau
+    np.testing.assert_array_equal(g_mask[ok_m], tt.mask[ok_m], err_msg="MPT mask")
+    assert_close("ratio", g_ratio, tt.ratio, rtol, atol=0.0)
+    ok_g = ok_m & ~near_edge
+    assert_close("gcoef", g_g[ok_g], tt.gcoef[ok_g], rtol, atol=0.0)
+    # exact zeros where the oracle has exact zeros
+    assert np.all(g_g[ok_g][tt.gcoef[ok_g] == 0.0] == 0.0)
+    if check_counters and rows is None:
+        cnt = res.counters.cpu().numpy()
+        assert abs(int(cnt[0]) - tt.n_masked) <= int(near_tau.sum())
+        assert abs(int(cnt[1]) - tt.n_clip_inactive) <= int(near_edge.sum())
+        assert int(cnt[2]) == tt.n_pos
+        assert int(cnt[3]) == 0
+    return int(near_tau.sum()), int(near_edge.sum())
+
+
+def dlogits_bound(ref, g_rows, dtype: str, rtol):
+    b = rtol * np.abs(ref) + 4e-6 * np.abs(g_rows)[:, None]
+    if dtype == "bf16":
+        b = b + 2.0 ** -8 * np.abs(ref)
+    return b
+
+
+def check_dlogits(name, got_rows: torch.Tensor, ref, g_rows, dtype, rtol):
+    got = got_rows.detach().float().cpu().numpy().astype(np.float64)
+    err = np.abs(got - ref)
+    bound = dlogits_bound(ref, g_rows, dtype, rtol)
+    bad = ~(err <= bound)
+    if bad.any():
+        k = np.unravel_index(int(np.argmax(err - bound)), err.shape)
+        raise AssertionError("%s dlogits: %d outside tolerance; worst at %s gpu=%r ref=%r g=%r"
+                             % (name, bad.sum(), k, got[k], ref[k], g_rows[k[0]]))
+    zero_rows = g_rows == 0.0
+    assert np.all(got[zero_rows] == 0.0), "rows with zero coefficient must be exactly zero"
+
+
+def run_full_parity(w: ui.Workload, p: ulorl.Params, dz_rows=None, inplace=False, data=None,
+                    grad_out=1.0):
+    """Whole path on the GPU vs whole oracle on the host, every row.  Returns (res, tt, info)."""
+    dev = torch.device("cuda:0")
+    d = data if data is not None else ui.generate(w, dev)
+    logits = d["logits"]
+    old = None if p.is_mode == ulorl.IS_POIS else d["old_logp"]
+    res = ulorl.token_loss_fwd(logits, d["token_ids"], d["cu_seqlens"], d["advantages"], old, p)
+    host_logits = ui.to_numpy_logits(logits)
+    y = d["token_ids"].cpu().numpy()
+    rtol = rtol_for(w.dtype)
+
+    o_lse, o_logp, o_H = oracle.row_stats(host_logits, y)
+    assert_close("lse", res.lse.cpu().numpy(), o_lse, rtol)
+    assert_close("logp", res.logp.cpu().numpy(), o_logp, rtol)
+    assert_close("entropy", res.entropy.cpu().numpy(), o_H, rtol)
+
+    adv = d["advantages"].cpu().numpy()
+    oldh = None if old is None else old.cpu().numpy()
+    tt = oracle_terms(o_logp, o_H, w.cu_seqlens, adv, oldh, p)
+    np.testing.assert_array_equal(res.segment_out.cpu().numpy(), tt.seg)
+    assert_close("resp_entropy", res.resp_entropy.cpu().numpy(), tt.resp_entropy, rtol)
+    np.testing.assert_array_equal(res.resp_gate.cpu().numpy(), tt.resp_gate)
+    n_tau, n_edge = check_token_outputs(res, tt, o_logp, p, rtol)
+    if n_tau == 0 and n_edge == 0:
+        assert_close("loss", res.loss.cpu().numpy()[0], tt.loss, rtol, atol=1e-7)
+
+    dz = ulorl.token_loss_bwd(logits, d["token_ids"], res.lse, res.gcoef, grad_out=grad_out,
+                              inplace=inplace)
+    rows = np.arange(w.N) if dz_rows is None else np.asarray(dz_rows)
+    # the oracle's gradient uses the oracle's own lse and coefficient
+    ref = oracle.dlogits(host_logits, y, o_lse, tt.gcoef, grad_out=grad_out, rows=rows)
+    near = (np.abs(np.exp(o_logp) - f32(p.tau)) < 1e-6) | \
+           (np.abs(tt.ratio - (1 - f32(p.eps_low))) < 1e-5) | (np.abs(tt.ratio - (1 + f32(p.eps_high))) < 1e-5)
+    keep = ~near[rows]
+    check_dlogits(w.name, dz[torch.as_tensor(rows[keep], device=dev)], ref[keep],
+                  grad_out * tt.gcoef[rows][keep], w.dtype, rtol)
+    return res, tt, dict(n_near_tau=n_tau, n_near_edge=n_edge, dz=dz, data=d, o_H=o_H)
+
+
+def sigma_between_responses(host_logits, y, cu, k=None):
+    """A target entropy midway between two responses' mean entropies (oracle side only), so that
+    some responses are gated and others are not; asserts a margin of 1e-3 nats."""
+    _, _, H = oracle.row_stats(host_logits, y)
+    hbar = np.array([H[cu[i]:cu[i + 1]].mean() for i in range(len(cu) - 1) if cu[i + 1] > cu[i]])
+    s = np.sort(hbar)
+    gaps = np.diff(s)
+    j = int(np.argmax(gaps)) if k is None else k
+    assert gaps[j] > 2e-3, "responses' mean entropies too close for a gate test"
+    return 0.5 * (s[j] + s[j + 1])

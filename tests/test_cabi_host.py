@@ -1,0 +1,109 @@
+"""Host-only checks of the C ABI: the library builds for gfx950, loads, exports every symbol the
+header declares, and rejects bad arguments before anything is launched (no GPU needed: every
+call below fails validation, so no kernel is ever enqueued)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2507_19766_amd as ulorl
+from paper_2507_19766_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    names = set()
+    for fn in os.listdir(os.path.join(ROOT, "include")):
+        if fn.endswith(".h"):
+            text = open(os.path.join(ROOT, "include", fn)).read()
+            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+            names |= set(re.findall(r"\b(ulorl_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ulorl.load_library()
+    names = declared_functions()
+    assert "ulorl_token_loss_fwd" in names and "ulorl_token_loss_bwd" in names
+    for n in names:
+        assert hasattr(lib, n), n
+    assert ulorl.version() >= 100
+    assert ulorl.status_string(0) == "ok"
+    assert "aligned" in ulorl.status_string(-4)
+
+
+def test_workspace_query():
+    assert ulorl.token_loss_workspace_bytes(0, 1) == 0
+    assert ulorl.token_loss_workspace_bytes(10, 0) == 0
+    a = ulorl.token_loss_workspace_bytes(131072, 1)
+    b = ulorl.token_loss_workspace_bytes(131072, 1024)
+    assert 0 < a < b < 1 << 20 and a % 256 == 0
+
+
+def _fwd(lib, logits=0x1000, dt=1, N=4, V=64, stride=64, y=0x2000, cu=0x3000, R=1, old=0x4000,
+         adv=0x5000, params=None, loss=0x6000, logp=0x7000, ent=0x8000, lse=0x9000, g=0xa000,
+         ws=0x10000, ws_bytes=1 << 20, use_params=True):
+    p = params or binding.Params()
+    cp = p.to_c()
+    vp = ctypes.c_void_p
+    return lib.ulorl_token_loss_fwd(
+        vp(logits), dt, N, V, stride, vp(y), vp(cu), R, None, vp(old), vp(adv),
+        ctypes.byref(cp) if use_params else None, vp(loss), vp(logp), vp(ent), vp(lse), vp(g),
+        None, None, None, None, None, None, vp(ws), ws_bytes, None)
+
+
+def test_forward_rejects_bad_arguments_on_the_host():
+    lib = ulorl.load_library()
+    P = binding.Params
+    assert _fwd(lib, logits=0) == -1
+    assert _fwd(lib, y=0) == -1
+    assert _fwd(lib, lse=0) == -1
+    assert _fwd(lib, loss=0) == -1
+    assert _fwd(lib, cu=0) == -1
+    assert _fwd(lib, old=0) == -1                                   # SAIS needs old_logp
+    assert _fwd(lib, use_params=False) == -1
+    assert _fwd(lib, N=0) == -2 and _fwd(lib, V=0) == -2 and _fwd(lib, stride=63) == -2
+    assert _fwd(lib, R=0) == -2
+    assert _fwd(lib, N=1 << 31) == -2
+    assert _fwd(lib, dt=2) == -3
+    assert _fwd(lib, logits=0x1008) == -4
+    assert _fwd(lib, V=60, stride=60) == -4                          # bf16 row of 120 bytes
+    assert _fwd(lib, dt=0, V=62, stride=62) == -4                    # fp32 row of 248 bytes
+    assert _fwd(lib, params=P(eps_low=-0.1)) == -5
+    assert _fwd(lib, params=P(eps_high=float("nan"))) == -5
+    assert _fwd(lib, params=P(tau=0.0)) == -5 and _fwd(lib, params=P(tau=1.5)) == -5
+    assert _fwd(lib, params=P(sigma=float("nan"))) == -5
+    assert _fwd(lib, params=P(is_mode=2)) == -5 and _fwd(lib, params=P(gate_mode=4)) == -5
+    assert _fwd(lib, params=P(seg_len=-1)) == -5
+    assert _fwd(lib, ws=0) == -6 and _fwd(lib, ws=0x10010) == -6 and _fwd(lib, ws_bytes=16) == -6
+
+
+def test_backward_rejects_bad_arguments_on_the_host():
+    lib = ulorl.load_library()
+    vp = ctypes.c_void_p
+
+    def bwd(logits=0x1000, dt=1, N=4, V=64, stride=64, y=0x2000, lse=0x3000, g=0x4000, dz=0x5000):
+        return lib.ulorl_token_loss_bwd(vp(logits), dt, N, V, stride, vp(y), vp(lse), vp(g), 1.0,
+                                        vp(dz), None)
+    assert bwd(logits=0) == -1 and bwd(y=0) == -1 and bwd(lse=0) == -1 and bwd(g=0) == -1
+    assert bwd(dz=0) == -1
+    assert bwd(N=-1) == -2 and bwd(stride=8) == -2
+    assert bwd(dt=7) == -3
+    assert bwd(dz=0x5004) == -4 and bwd(logits=0x1002) == -4
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    z = torch.zeros(2, 8)
+    with pytest.raises(RuntimeError):
+        ulorl.row_stats(z, torch.zeros(2, dtype=torch.int32))
+
+
+def test_tuning_knobs_validate():
+    ulorl.tune(ulorl.TUNE_FWD_THREADS, 256)
+    with pytest.raises(ulorl.UlorlError):
+        ulorl.tune(ulorl.TUNE_FWD_THREADS, 100)
+    with pytest.raises(ulorl.UlorlError):
+        ulorl.tune(9, 256)

@@ -1,0 +1,255 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 CPU oracle on the same
+seeded inputs.  Oracle-sized cases compare every element; see test_gpu_fullsize.py for the
+full-size configurations."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2507_19766_amd as ulorl
+import ulorl_inputs as ui
+from parity import (assert_close, check_dlogits, f32, oracle_terms, params_for, rtol_for,
+                    run_full_parity, sigma_between_responses)
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _host(d):
+    return ui.to_numpy_logits(d["logits"]), d["token_ids"].cpu().numpy()
+
+
+# ------------------------------------------------------------------ configuration 1 (fp32, whole)
+
+def test_cfg1_sais_per_response_gate():
+    w = ui.config(1)
+    d = ui.generate(w, DEV)
+    hl, y = _host(d)
+    sigma = sigma_between_responses(hl, y, w.cu_seqlens)
+    p = params_for(w, sigma=sigma, gate_mode=ulorl.GATE_PER_RESPONSE)
+    res, tt, info = run_full_parity(w, p, data=d)
+    assert tt.resp_gate.sum() == 1                      # one response gated, one not
+
+
+def test_cfg1_static_masking_and_paper_sigma():
+    w = ui.config(1)
+    d = ui.generate(w, DEV)
+    res, tt, _ = run_full_parity(w, params_for(w, gate_mode=ulorl.GATE_ALWAYS), data=d)
+    assert tt.n_masked > 0
+    # with the paper's sigma = 0.2 these high-entropy rows never trigger the gate
+    res2, tt2, _ = run_full_parity(w, params_for(w), data=d)
+    assert tt2.n_masked == 0 and int(res2.counters[0]) == 0
+
+
+def test_cfg1_pois_and_global_gate():
+    w = ui.config(1)
+    d = ui.generate(w, DEV)
+    res, tt, _ = run_full_parity(w, params_for(w, is_mode=ulorl.IS_POIS, gate_mode=ulorl.GATE_ALWAYS),
+                                 data=d)
+    assert torch.all(res.ratio == 1.0) and int(res.counters[1]) == 0
+    run_full_parity(w, params_for(w, gate_mode=ulorl.GATE_GLOBAL, sigma=100.0), data=d)
+    run_full_parity(w, params_for(w, gate_mode=ulorl.GATE_NEVER, denominator=5000.0), data=d,
+                    grad_out=-2.5)
+
+
+# ------------------------------------------------------------------ bf16, Qwen3-sized vocabulary
+
+def test_cfg2_recipe_small_ragged_responses():
+    w = ui.shrink(ui.config(2), [700, 300, 1100, 205], seg_len=256)
+    d = ui.generate(w, DEV)
+    hl, y = _host(d)
+    sigma = sigma_between_responses(hl, y, w.cu_seqlens)
+    rows = np.random.RandomState(3).choice(w.N, 48, replace=False)
+    p = params_for(w, sigma=sigma)
+    res, tt, _ = run_full_parity(w, p, dz_rows=rows, data=d)
+    assert 0 < tt.resp_gate.sum() < 4
+    res, tt, _ = run_full_parity(w, params_for(w, gate_mode=ulorl.GATE_ALWAYS), dz_rows=rows, data=d)
+    assert tt.n_masked > 0 and tt.n_clip_inactive > 0
+
+
+def test_cfg4_recipe_small_in_place():
+    w = ui.shrink(ui.config(4), [1500], seg_len=200)
+    d = ui.generate(w, DEV)
+    pristine = d["logits"].clone()
+    p = params_for(w, gate_mode=ulorl.GATE_ALWAYS)
+    rows = np.concatenate([np.arange(8), np.random.RandomState(4).choice(w.N, 40, replace=False)])
+    res, tt, info = run_full_parity(w, p, dz_rows=rows, data=d)         # out of place
+    dz_out = info["dz"]
+    assert torch.equal(d["logits"], pristine)
+    dz_in = ulorl.token_loss_bwd(d["logits"], d["token_ids"], res.lse, res.gcoef, inplace=True)
+    assert dz_in.data_ptr() == d["logits"].data_ptr()
+    assert torch.equal(dz_in.view(torch.int16), dz_out.view(torch.int16))  # bitwise the same
+    seg = res.segment_out.cpu().numpy()
+    np.testing.assert_array_equal(seg, np.arange(1500) // 200)
+    assert np.all(np.abs(tt.ratio[seg == 0] - 1.0) < 1e-5)               # first segment on-policy
+    assert np.abs(tt.ratio[seg == 6] - 1.0).max() > 0.05                 # later ones are stale
+
+
+def test_heavily_masked_batch_takes_the_write_only_path():
+    # spike +20: most peaked rows reach p >= 0.99 and are removed (labelled extra case)
+    from dataclasses import replace
+    w = replace(ui.shrink(ui.config(4), [600], seg_len=100), spike_boost=22.0, name="cfg4_spike22")
+    rows = np.arange(0, 600, 7)
+    res, tt, _ = run_full_parity(w, params_for(w, gate_mode=ulorl.GATE_ALWAYS), dz_rows=rows)
+    assert tt.n_masked > 100
+
+
+# ------------------------------------------------------------------ ragged shapes and edge cases
+
+@pytest.mark.parametrize("dtype,V", [("f32", 4099), ("f32", 3), ("f32", 4 * 256 * 4 * 2 + 4 * 77 + 1),
+                                     ("bf16", 1003), ("bf16", 5), ("bf16", 8 * 256 * 4 * 2 + 8 * 77 + 5),
+                                     ("bf16", 8 * 1024 * 8 + 8)])
+@pytest.mark.parametrize("threads,unroll", [(256, 4), (1024, 8), (512, 2)])
+def test_ragged_vocab_and_launch_shapes(dtype, V, threads, unroll):
+    base = ui.config(1) if dtype == "f32" else ui.config(2)
+    w = ui.shrink(base, [9, 1, 23], V=V, seg_len=4, name="ragged_%s_%d" % (dtype, V))
+    dev = torch.device(DEV)
+    vec = 4 if dtype == "f32" else 8
+    stride = (V + vec - 1) // vec * vec + 2 * vec          # padded rows: stride > V
+    d = ui.generate(w, DEV)
+    buf = torch.full((w.N, stride), float("nan"), dtype=w.torch_dtype(), device=dev)
+    buf[:, :V] = d["logits"]
+    d["logits"] = buf[:, :V]
+    for knob, val in ((ulorl.TUNE_FWD_THREADS, threads), (ulorl.TUNE_FWD_UNROLL, unroll),
+                      (ulorl.TUNE_BWD_THREADS, threads), (ulorl.TUNE_BWD_UNROLL, unroll)):
+        ulorl.tune(knob, val)
+    try:
+        res, tt, info = run_full_parity(w, params_for(w, gate_mode=ulorl.GATE_ALWAYS, tau=0.5), data=d)
+    finally:
+        for knob, val in ((ulorl.TUNE_FWD_THREADS, 256), (ulorl.TUNE_FWD_UNROLL, 4),
+                          (ulorl.TUNE_BWD_THREADS, 256), (ulorl.TUNE_BWD_UNROLL, 4)):
+            ulorl.tune(knob, val)
+    # in place on the padded buffer: same bits, and the padding columns stay untouched
+    dz_out = info["dz"]
+    assert dz_out.stride(0) == stride
+    dz_in = ulorl.token_loss_bwd(d["logits"], d["token_ids"], res.lse, res.gcoef, inplace=True)
+    as_int = torch.int32 if dtype == "f32" else torch.int16
+    assert torch.equal(dz_in.contiguous().view(as_int), dz_out.contiguous().view(as_int))
+    assert torch.isnan(buf[:, V:]).all()
+
+
+def test_single_row_single_token_and_empty_response():
+    w = ui.shrink(ui.config(1), [1], V=512, seg_len=1, name="one_row")
+    run_full_parity(w, params_for(w, gate_mode=ulorl.GATE_ALWAYS))
+    # an empty response in the middle of the batch
+    w = ui.shrink(ui.config(1), [5, 4], V=256, seg_len=2, name="with_empty")
+    d = ui.generate(w, DEV)
+    cu = torch.tensor([0, 5, 5, 9], dtype=torch.int32, device=DEV)
+    p = params_for(w, gate_mode=ulorl.GATE_PER_RESPONSE, sigma=100.0)
+    res = ulorl.token_loss_fwd(d["logits"], d["token_ids"], cu, d["advantages"], d["old_logp"], p)
+    hl, y = _host(d)
+    o_lse, o_logp, o_H = oracle.row_stats(hl, y)
+    tt = oracle_terms(o_logp, o_H, [0, 5, 5, 9], d["advantages"].cpu().numpy(), d["old_logp"].cpu().numpy(), p)
+    np.testing.assert_array_equal(res.resp_gate.cpu().numpy(), tt.resp_gate)
+    assert list(tt.resp_gate) == [1, 0, 1]
+    assert_close("resp_entropy", res.resp_entropy.cpu().numpy(), tt.resp_entropy, 1e-5)
+    np.testing.assert_array_equal(res.mpt_mask.cpu().numpy(), tt.mask)
+    np.testing.assert_array_equal(res.segment_out.cpu().numpy(), tt.seg)
+    assert_close("loss", res.loss.item(), tt.loss, 1e-5, atol=1e-7)
+
+
+def test_all_masked_and_none_masked():
+    V = 1024
+    N = 40
+    z = torch.zeros(N, V, device=DEV)
+    z[:, 17] = 30.0                                       # every row: p(17) ~ 1
+    y = torch.full((N,), 17, dtype=torch.int32, device=DEV)
+    cu = torch.tensor([0, N], dtype=torch.int32, device=DEV)
+    adv = torch.ones(N, device=DEV)
+    p = ulorl.Params(gate_mode=ulorl.GATE_PER_RESPONSE, is_mode=ulorl.IS_POIS)   # paper's tau, sigma
+    res = ulorl.token_loss_fwd(z, y, cu, adv, None, p)
+    assert int(res.resp_gate[0]) == 1 and int(res.mpt_mask.sum()) == N
+    assert res.loss.item() == 0.0 and torch.all(res.gcoef == 0)
+    dz = ulorl.token_loss_bwd(z, y, res.lse, res.gcoef)
+    assert torch.all(dz == 0)
+    # negative advantage: same rows are never masked
+    res2 = ulorl.token_loss_fwd(z, y, cu, -adv, None, p)
+    assert int(res2.mpt_mask.sum()) == 0 and res2.loss.item() == 1.0
+    assert int(res2.counters[2]) == 0
+
+
+def test_exact_threshold_boundary_rows():
+    """Spike rows just above / below p = tau (closed form a* = ln(99 (V-1)))."""
+    import math
+    V = 4096
+    a_star = math.log(99 * (V - 1))
+    z = torch.zeros(4, V, device=DEV)
+    for t, da in enumerate([+3e-4, -3e-4, +3e-4, -3e-4]):
+        z[t, 100 + t] = a_star + da
+    y = torch.tensor([100, 101, 102, 103], dtype=torch.int32, device=DEV)
+    cu = torch.tensor([0, 4], dtype=torch.int32, device=DEV)
+    adv = torch.tensor([1.0, 1.0, -1.0, 1.0], device=DEV)
+    p = ulorl.Params(gate_mode=ulorl.GATE_ALWAYS, is_mode=ulorl.IS_POIS)
+    res = ulorl.token_loss_fwd(z, y, cu, adv, None, p)
+    lse, logp, H = oracle.row_stats(z.cpu().numpy(), y.cpu().numpy())
+    tt = oracle_terms(logp, H, [0, 4], adv.cpu().numpy(), None, p)
+    assert np.all(np.abs(np.exp(logp) - f32(0.99)) > 1e-6)
+    np.testing.assert_array_equal(res.mpt_mask.cpu().numpy(), tt.mask)
+    assert list(tt.mask) == [1, 0, 0, 0]
+
+
+def test_stats_only_pass_and_determinism():
+    w = ui.shrink(ui.config(2), [333], V=20000, name="stats_only")
+    d = ui.generate(w, DEV)
+    a = ulorl.row_stats(d["logits"], d["token_ids"])
+    b = ulorl.row_stats(d["logits"], d["token_ids"])
+    assert a.loss is None and a.gcoef is None
+    for x, yv in ((a.lse, b.lse), (a.logp, b.logp), (a.entropy, b.entropy)):
+        assert torch.equal(x, yv)
+    hl, y = _host(d)
+    o = oracle.row_stats(hl, y)
+    for name, g, r in zip(("lse", "logp", "entropy"), (a.lse, a.logp, a.entropy), o):
+        assert_close(name, g.cpu().numpy(), r, rtol_for("bf16"))
+    p = params_for(w, gate_mode=ulorl.GATE_ALWAYS)
+    r1 = ulorl.token_loss_fwd(d["logits"], d["token_ids"], d["cu_seqlens"], d["advantages"], d["old_logp"], p)
+    r2 = ulorl.token_loss_fwd(d["logits"], d["token_ids"], d["cu_seqlens"], d["advantages"], d["old_logp"], p)
+    assert torch.equal(r1.loss, r2.loss) and torch.equal(r1.gcoef, r2.gcoef)
+    z1 = ulorl.token_loss_bwd(d["logits"], d["token_ids"], r1.lse, r1.gcoef)
+    z2 = ulorl.token_loss_bwd(d["logits"], d["token_ids"], r2.lse, r2.gcoef)
+    assert torch.equal(z1.view(torch.int16), z2.view(torch.int16))
+
+
+def test_explicit_segment_ids_pass_through():
+    w = ui.shrink(ui.config(2), [50, 30], V=512, seg_len=16)
+    d = ui.generate(w, DEV)
+    ids = torch.arange(80, dtype=torch.int32, device=DEV).flip(0).contiguous()
+    p = params_for(w, seg_len=0)
+    res = ulorl.token_loss_fwd(d["logits"], d["token_ids"], d["cu_seqlens"], d["advantages"],
+                               d["old_logp"], p, segment_ids=ids)
+    assert torch.equal(res.segment_out, ids)
+
+
+# ------------------------------------------------------------------ errors the device reports
+
+def test_device_detected_errors_raise_status_bits_without_faulting():
+    w = ui.shrink(ui.config(1), [20, 12], V=300, seg_len=8)
+    d = ui.generate(w, DEV)
+    p = params_for(w, gate_mode=ulorl.GATE_NEVER)
+    good = ulorl.token_loss_fwd(d["logits"], d["token_ids"], d["cu_seqlens"], d["advantages"], d["old_logp"], p)
+    assert int(good.counters[3]) == 0
+
+    y = d["token_ids"].clone()
+    y[3] = 300
+    y[7] = -1
+    r = ulorl.token_loss_fwd(d["logits"], y, d["cu_seqlens"], d["advantages"], d["old_logp"], p)
+    assert int(r.counters[3]) == ulorl.STATUS_BAD_TOKEN
+    assert r.gcoef[3].item() == 0.0 and r.gcoef[7].item() == 0.0
+    ok = torch.ones(32, dtype=torch.bool, device=DEV)
+    ok[3] = ok[7] = False
+    assert torch.equal(r.gcoef[ok], good.gcoef[ok])
+    dz = ulorl.token_loss_bwd(d["logits"], y, r.lse, r.gcoef)
+    assert torch.all(dz[3] == 0) and torch.all(dz[7] == 0)
+
+    z = d["logits"].clone()
+    z[5, 11] = float("inf")
+    z[6, 12] = float("nan")
+    r = ulorl.token_loss_fwd(z, d["token_ids"], d["cu_seqlens"], d["advantages"], d["old_logp"], p)
+    assert int(r.counters[3]) == ulorl.STATUS_NONFINITE
+    assert r.gcoef[5].item() == 0.0 and r.gcoef[6].item() == 0.0
+    assert torch.isfinite(r.loss).all()
+
+    for bad in ([0, 25, 20, 32], [1, 20, 32], [0, 20, 31], [0, 20, 40]):
+        cu = torch.tensor(bad, dtype=torch.int32, device=DEV)
+        r = ulorl.token_loss_fwd(d["logits"], d["token_ids"], cu, d["advantages"], d["old_logp"], p)
+        assert int(r.counters[3]) & ulorl.STATUS_BAD_CU
+        assert r.loss.item() == 0.0 and torch.all(r.gcoef == 0)

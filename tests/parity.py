@@ -156,3 +156,77 @@ def sigma_between_responses(host_logits, y, cu, k=None):
     j = int(np.argmax(gaps)) if k is None else k
     assert gaps[j] > 2e-3, "responses' mean entropies too close for a gate test"
     return 0.5 * (s[j] + s[j + 1])
+
+
+def oracle_row_stats_streamed(logits: torch.Tensor, y_host: np.ndarray, block_rows=4096, keep_rows=None,
+                              progress=None):
+    """Oracle row statistics of a device tensor of any size: rows are copied to the host block by
+    block (the host never holds the whole tensor).  Optionally keeps host copies of a few rows."""
+    N = logits.shape[0]
+    lse = np.empty(N)
+    logp = np.empty(N)
+    ent = np.empty(N)
+    kept = {}
+    keep = set(int(r) for r in (keep_rows if keep_rows is not None else []))
+    for r0 in range(0, N, block_rows):
+        r1 = min(N, r0 + block_rows)
+        host = ui.to_numpy_logits(logits[r0:r1])
+        lse[r0:r1], logp[r0:r1], ent[r0:r1] = oracle.row_stats(host, y_host[r0:r1])
+        for r in keep:
+            if r0 <= r < r1:
+                kept[r] = host[r - r0].copy()
+        if progress:
+            progress(r1, N)
+    return lse, logp, ent, kept
+
+
+def run_streamed_parity(w: ui.Workload, p: ulorl.Params, data, n_dz_rows=64, inplace=True, seed=0,
+                        say=print):
+    """Full-size parity: every row's statistics and every token's terms against the oracle (logits
+    streamed to the host in blocks), the gradient on sampled rows."""
+    dev = data["logits"].device
+    logits = data["logits"]
+    rtol = rtol_for(w.dtype)
+    y = data["token_ids"].cpu().numpy()
+    adv = data["advantages"].cpu().numpy()
+    old = None if p.is_mode == ulorl.IS_POIS else data["old_logp"]
+    res = ulorl.token_loss_fwd(logits, data["token_ids"], data["cu_seqlens"], data["advantages"], old, p)
+    torch.cuda.synchronize()
+    say("forward done; streaming %d rows to the oracle" % w.N)
+
+    rs = np.random.RandomState(seed)
+    rows = np.unique(np.concatenate([[0, w.N - 1], rs.choice(w.N, n_dz_rows, replace=False)]))
+    o_lse, o_logp, o_H, kept = oracle_row_stats_streamed(
+        logits, y, keep_rows=rows,
+        progress=lambda a, b: say("  oracle rows %d/%d" % (a, b)) if (a // 4096) % 8 == 0 or a == b else None)
+    assert_close("lse", res.lse.cpu().numpy(), o_lse, rtol)
+    assert_close("logp", res.logp.cpu().numpy(), o_logp, rtol)
+    assert_close("entropy", res.entropy.cpu().numpy(), o_H, rtol)
+    tt = oracle_terms(o_logp, o_H, w.cu_seqlens, adv, None if old is None else old.cpu().numpy(), p)
+    np.testing.assert_array_equal(res.segment_out.cpu().numpy(), tt.seg)
+    assert_close("resp_entropy", res.resp_entropy.cpu().numpy(), tt.resp_entropy, rtol)
+    np.testing.assert_array_equal(res.resp_gate.cpu().numpy(), tt.resp_gate)
+    n_tau, n_edge = check_token_outputs(res, tt, o_logp, p, rtol)
+    if n_tau == 0 and n_edge == 0:
+        assert_close("loss", res.loss.cpu().numpy()[0], tt.loss, rtol, atol=1e-7)
+    else:   # a token on a discontinuity may legitimately differ: bound its effect on the mean
+        assert abs(res.loss.item() - tt.loss) <= rtol * abs(tt.loss) + 2.0 * (n_tau + n_edge) / w.N
+    say("token terms ok (masked %d, clipped %d, near tau %d, near clip edge %d)"
+        % (tt.n_masked, tt.n_clip_inactive, n_tau, n_edge))
+
+    dz = ulorl.token_loss_bwd(logits, data["token_ids"], res.lse, res.gcoef, inplace=inplace)
+    torch.cuda.synchronize()
+    near = (np.abs(np.exp(o_logp) - f32(p.tau)) < 1e-6) | \
+           (np.abs(tt.ratio - (1 - f32(p.eps_low))) < 1e-5) | (np.abs(tt.ratio - (1 + f32(p.eps_high))) < 1e-5)
+    rows = np.array([r for r in rows if not near[r]])
+    sub = np.stack([kept[int(r)] for r in rows])
+    k = np.arange(len(rows))
+    ref = oracle.dlogits(sub, y[rows], o_lse[rows], tt.gcoef[rows])
+    check_dlogits(w.name, dz[torch.as_tensor(rows, device=dev)], ref, tt.gcoef[rows], w.dtype, rtol)
+    # properties that hold at any size: masked / clipped rows are exactly zero, live rows sum to ~0
+    zero_rows = np.nonzero(tt.gcoef == 0.0)[0]
+    zero_rows = zero_rows[~near[zero_rows]][:256]
+    if len(zero_rows):
+        assert torch.all(dz[torch.as_tensor(zero_rows, device=dev)] == 0)
+    say("dlogits ok on %d sampled rows, %d zero rows" % (len(k), len(zero_rows)))
+    return res, tt

@@ -99,9 +99,10 @@ int32_t ulorl_version(void);
 /* Static string for a status code (HOST pointer, never NULL). */
 const char *ulorl_status_string(int32_t status);
 
-/* Bytes of device workspace ulorl_token_loss_fwd needs for N rows in R responses
- * (0 if N or R is out of range).  The workspace holds per-response entropy sums and
- * per-block partial sums; its contents need not be preserved between calls.        */
+/* Bytes of device workspace ulorl_token_loss_fwd / _fwd_bwd need for N rows in R
+ * responses (0 if N or R is out of range).  The workspace holds per-response entropy
+ * sums, per-block partial sums and one flag byte per row; its contents need not be
+ * preserved between calls.                                                         */
 size_t ulorl_token_loss_workspace_bytes(int64_t N, int32_t R);
 
 /*
@@ -165,7 +166,29 @@ int32_t ulorl_token_loss_bwd(
     void *dlogits, void *hip_stream);
 
 /*
- * Launch-shape knobs of the two streaming kernels (process-wide, HOST state; not thread
+ * Fused forward + backward in one call: same inputs, outputs and conventions as
+ * ulorl_token_loss_fwd (advantages must not be NULL) plus grad_out and dlogits as in
+ * ulorl_token_loss_bwd (dlogits MAY BE logits).  Each row's statistics and gradient are
+ * produced by one workgroup back to back, so the second read of the row is served by the
+ * on-chip caches and HBM sees one read and one write per row instead of two reads and a write.
+ * A row's gradient can be formed at once unless it waits for the entropy gate of Sec. 3.2.2:
+ * under the PER_RESPONSE and GLOBAL gates the members of the MPT set (A_t > 0, p_t >= tau) are
+ * finished by a second, filtered backward launch after the gate is known.  Results are
+ * bit-identical to ulorl_token_loss_fwd followed by ulorl_token_loss_bwd when the launch
+ * shapes (ulorl_tune) of the three streaming kernels are equal, as they are by default.
+ */
+int32_t ulorl_token_loss_fwd_bwd(
+    const void *logits, int32_t dt, int64_t N, int64_t V, int64_t row_stride,
+    const int32_t *token_ids, const int32_t *cu_seqlens, int32_t R,
+    const int32_t *segment_ids, const float *old_logp, const float *advantages,
+    const ulorl_params *p, float grad_out,
+    float *loss, float *logp, float *entropy, float *lse, float *gcoef,
+    uint8_t *mpt_mask, float *ratio, int32_t *segment_out,
+    float *resp_entropy, uint8_t *resp_gate, int64_t *counters,
+    void *dlogits, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Launch-shape knobs of the streaming kernels (process-wide, HOST state; not thread
  * safe against concurrent calls).  Results do not depend on them beyond summation order.
  *   *_THREADS  workgroup size per token row: 256, 512 or 1024
  *   *_UNROLL   16-byte loads each lane keeps in flight per loop trip: 2, 4 or 8
@@ -175,7 +198,9 @@ typedef enum {
     ULORL_TUNE_FWD_THREADS = 0,
     ULORL_TUNE_FWD_UNROLL = 1,
     ULORL_TUNE_BWD_THREADS = 2,
-    ULORL_TUNE_BWD_UNROLL = 3
+    ULORL_TUNE_BWD_UNROLL = 3,
+    ULORL_TUNE_FUSED_THREADS = 4,
+    ULORL_TUNE_FUSED_UNROLL = 5
 } ulorl_tune_knob;
 int32_t ulorl_tune(int32_t knob, int32_t value);
 

@@ -18,6 +18,7 @@ IS_SAIS, IS_POIS = 0, 1
 GATE_PER_RESPONSE, GATE_GLOBAL, GATE_ALWAYS, GATE_NEVER = 0, 1, 2, 3
 STATUS_BAD_TOKEN, STATUS_NONFINITE, STATUS_BAD_CU = 1, 2, 4
 TUNE_FWD_THREADS, TUNE_FWD_UNROLL, TUNE_BWD_THREADS, TUNE_BWD_UNROLL = 0, 1, 2, 3
+TUNE_FUSED_THREADS, TUNE_FUSED_UNROLL = 4, 5
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 
@@ -91,6 +92,16 @@ def load_library(build_if_missing: bool = True):
         vp, vp, vp,                                          # mpt_mask, ratio, segment_out
         vp, vp, vp,                                          # resp_entropy, resp_gate, counters
         vp, c.c_size_t, vp]                                  # workspace, bytes, stream
+    lib.ulorl_token_loss_fwd_bwd.restype = c.c_int32
+    lib.ulorl_token_loss_fwd_bwd.argtypes = [
+        vp, c.c_int32, c.c_int64, c.c_int64, c.c_int64,      # logits, dt, N, V, stride
+        vp, vp, c.c_int32,                                   # token_ids, cu_seqlens, R
+        vp, vp, vp,                                          # segment_ids, old_logp, advantages
+        c.POINTER(_CParams), c.c_float,                      # params, grad_out
+        vp, vp, vp, vp, vp,                                  # loss, logp, entropy, lse, gcoef
+        vp, vp, vp,                                          # mpt_mask, ratio, segment_out
+        vp, vp, vp,                                          # resp_entropy, resp_gate, counters
+        vp, vp, c.c_size_t, vp]                              # dlogits, workspace, bytes, stream
     lib.ulorl_token_loss_bwd.restype = c.c_int32
     lib.ulorl_token_loss_bwd.argtypes = [
         vp, c.c_int32, c.c_int64, c.c_int64, c.c_int64, vp, vp, vp, c.c_float, vp, vp]
@@ -165,54 +176,98 @@ class FwdResult:
     counters: Optional[torch.Tensor] = None
 
 
+def _prepare_objective(logits, token_ids, cu_seqlens, advantages, old_logp, params, segment_ids, out, workspace):
+    """Shared marshalling of the objective's inputs/outputs for the fwd and fwd_bwd calls."""
+    dt, N, V, stride = _check_logits(logits)
+    dev = logits.device
+    f32 = dict(dtype=torch.float32, device=dev)
+    token_ids = _vec(token_ids, torch.int32, N, "token_ids", dev)
+    if out is None:
+        out = FwdResult(None, torch.empty(N, **f32), torch.empty(N, **f32), torch.empty(N, **f32))
+    params = params or Params()
+    if cu_seqlens.device != dev or cu_seqlens.dtype != torch.int32 or not cu_seqlens.is_contiguous():
+        raise ValueError("cu_seqlens must be a contiguous int32 device tensor")
+    R = cu_seqlens.shape[0] - 1
+    advantages = _vec(advantages, torch.float32, N, "advantages", dev)
+    old_logp = _vec(old_logp, torch.float32, N, "old_logp", dev)
+    segment_ids = _vec(segment_ids, torch.int32, N, "segment_ids", dev)
+    if out.loss is None:
+        out.loss = torch.empty(1, **f32)
+        out.gcoef = torch.empty(N, **f32)
+        out.mpt_mask = torch.empty(N, dtype=torch.uint8, device=dev)
+        out.ratio = torch.empty(N, **f32)
+        out.segment_out = torch.empty(N, dtype=torch.int32, device=dev)
+        out.resp_entropy = torch.empty(max(R, 1), **f32)[:R]
+        out.resp_gate = torch.empty(max(R, 1), dtype=torch.uint8, device=dev)[:R]
+        out.counters = torch.empty(4, dtype=torch.int64, device=dev)
+    if workspace is None:
+        workspace = torch.empty(max(token_loss_workspace_bytes(N, R), 256), dtype=torch.uint8, device=dev)
+    ws_bytes = workspace.numel() * workspace.element_size()
+    return (dt, N, V, stride, dev, token_ids, R, advantages, old_logp, segment_ids, params.to_c(), out,
+            workspace, ws_bytes)
+
+
 def token_loss_fwd(logits, token_ids, cu_seqlens, advantages, old_logp=None, params: Params = None,
                    segment_ids=None, out: Optional[FwdResult] = None,
                    workspace: Optional[torch.Tensor] = None) -> FwdResult:
     """ulorl_token_loss_fwd.  ``advantages=None`` selects the stats-only pass.
     ``out``/``workspace`` let a caller reuse buffers (nothing is allocated then)."""
     lib = load_library()
-    dt, N, V, stride = _check_logits(logits)
-    dev = logits.device
-    stats_only = advantages is None
-    token_ids = _vec(token_ids, torch.int32, N, "token_ids", dev)
-    f32 = dict(dtype=torch.float32, device=dev)
-    if out is None:
-        out = FwdResult(None, torch.empty(N, **f32), torch.empty(N, **f32), torch.empty(N, **f32))
-    R = 0
-    cparams = None
-    ws_bytes = 0
-    if not stats_only:
-        params = params or Params()
-        cparams = params.to_c()
-        if cu_seqlens.device != dev or cu_seqlens.dtype != torch.int32 or not cu_seqlens.is_contiguous():
-            raise ValueError("cu_seqlens must be a contiguous int32 device tensor")
-        R = cu_seqlens.shape[0] - 1
-        advantages = _vec(advantages, torch.float32, N, "advantages", dev)
-        old_logp = _vec(old_logp, torch.float32, N, "old_logp", dev)
-        segment_ids = _vec(segment_ids, torch.int32, N, "segment_ids", dev)
-        if out.loss is None:
-            out.loss = torch.empty(1, **f32)
-            out.gcoef = torch.empty(N, **f32)
-            out.mpt_mask = torch.empty(N, dtype=torch.uint8, device=dev)
-            out.ratio = torch.empty(N, **f32)
-            out.segment_out = torch.empty(N, dtype=torch.int32, device=dev)
-            out.resp_entropy = torch.empty(max(R, 1), **f32)[:R]
-            out.resp_gate = torch.empty(max(R, 1), dtype=torch.uint8, device=dev)[:R]
-            out.counters = torch.empty(4, dtype=torch.int64, device=dev)
-        ws_bytes = token_loss_workspace_bytes(N, R)
-        if workspace is None:
-            workspace = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
-        ws_bytes = workspace.numel() * workspace.element_size()
+    if advantages is None:                       # stats-only: lse, logp, entropy
+        dt, N, V, stride = _check_logits(logits)
+        dev = logits.device
+        token_ids = _vec(token_ids, torch.int32, N, "token_ids", dev)
+        f32 = dict(dtype=torch.float32, device=dev)
+        if out is None:
+            out = FwdResult(None, torch.empty(N, **f32), torch.empty(N, **f32), torch.empty(N, **f32))
+        rc = lib.ulorl_token_loss_fwd(
+            _p(logits), dt, N, V, stride, _p(token_ids), None, 0, None, None, None, None,
+            None, _p(out.logp), _p(out.entropy), _p(out.lse), None, None, None, None, None, None, None,
+            None, 0, _stream(dev))
+        if rc != 0:
+            raise UlorlError(rc, "ulorl_token_loss_fwd")
+        return out
+    (dt, N, V, stride, dev, token_ids, R, advantages, old_logp, segment_ids, cparams, out, workspace,
+     ws_bytes) = _prepare_objective(logits, token_ids, cu_seqlens, advantages, old_logp, params,
+                                    segment_ids, out, workspace)
     rc = lib.ulorl_token_loss_fwd(
-        _p(logits), dt, N, V, stride, _p(token_ids), _p(cu_seqlens) if not stats_only else None, R,
-        _p(segment_ids) if not stats_only else None, _p(old_logp) if not stats_only else None,
-        _p(advantages), ctypes.byref(cparams) if cparams is not None else None,
+        _p(logits), dt, N, V, stride, _p(token_ids), _p(cu_seqlens), R, _p(segment_ids), _p(old_logp),
+        _p(advantages), ctypes.byref(cparams),
         _p(out.loss), _p(out.logp), _p(out.entropy), _p(out.lse), _p(out.gcoef),
         _p(out.mpt_mask), _p(out.ratio), _p(out.segment_out), _p(out.resp_entropy),
         _p(out.resp_gate), _p(out.counters), _p(workspace), ws_bytes, _stream(dev))
     if rc != 0:
         raise UlorlError(rc, "ulorl_token_loss_fwd")
     return out
+
+
+def token_loss_fwd_bwd(logits, token_ids, cu_seqlens, advantages, old_logp=None, params: Params = None,
+                       segment_ids=None, grad_out: float = 1.0, dlogits: Optional[torch.Tensor] = None,
+                       inplace: bool = False, out: Optional[FwdResult] = None,
+                       workspace: Optional[torch.Tensor] = None):
+    """ulorl_token_loss_fwd_bwd -> (FwdResult, dlogits).  ``inplace=True`` overwrites ``logits``."""
+    lib = load_library()
+    (dt, N, V, stride, dev, token_ids, R, advantages, old_logp, segment_ids, cparams, out, workspace,
+     ws_bytes) = _prepare_objective(logits, token_ids, cu_seqlens, advantages, old_logp, params,
+                                    segment_ids, out, workspace)
+    if advantages is None:
+        raise ValueError("token_loss_fwd_bwd needs advantages")
+    if inplace:
+        dlogits = logits
+    elif dlogits is None:
+        dlogits = torch.empty_strided((N, V), (stride, 1), dtype=logits.dtype, device=dev)
+    if (dlogits.shape != logits.shape or dlogits.dtype != logits.dtype or dlogits.device != dev
+            or dlogits.stride() != logits.stride()):
+        raise ValueError("dlogits must match logits in shape, dtype, strides and device")
+    rc = lib.ulorl_token_loss_fwd_bwd(
+        _p(logits), dt, N, V, stride, _p(token_ids), _p(cu_seqlens), R, _p(segment_ids), _p(old_logp),
+        _p(advantages), ctypes.byref(cparams), float(grad_out),
+        _p(out.loss), _p(out.logp), _p(out.entropy), _p(out.lse), _p(out.gcoef),
+        _p(out.mpt_mask), _p(out.ratio), _p(out.segment_out), _p(out.resp_entropy),
+        _p(out.resp_gate), _p(out.counters), _p(dlogits), _p(workspace), ws_bytes, _stream(dev))
+    if rc != 0:
+        raise UlorlError(rc, "ulorl_token_loss_fwd_bwd")
+    return out, dlogits
 
 
 def row_stats(logits, token_ids, out: Optional[FwdResult] = None) -> FwdResult:

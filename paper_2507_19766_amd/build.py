@@ -12,10 +12,11 @@ CSRC = os.path.join(_HERE, "csrc")
 INCLUDE = os.path.join(ROOT, "include")
 LIB_DIR = os.path.join(_HERE, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "libulorl.so")
+PROBE_PATH = os.path.join(LIB_DIR, "ulorl_probe")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # fused multiply-adds only where the source says fmaf(): the kernels rely on exact
     # rounded products in their error-free transforms
     "-ffp-contract=off",
@@ -29,11 +30,9 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
-def build(verbose: bool = False) -> str:
-    """Compile every HIP source into lib/libulorl.so; always recompiles."""
-    os.makedirs(LIB_DIR, exist_ok=True)
-    tmp = LIB_PATH + ".tmp%d" % os.getpid()
-    cmd = [HIPCC] + FLAGS + ["-I" + INCLUDE, "-I" + CSRC] + sources() + ["-o", tmp]
+def _hipcc(args, out_path, verbose):
+    tmp = out_path + ".tmp%d" % os.getpid()
+    cmd = [HIPCC] + FLAGS + ["-I" + INCLUDE, "-I" + CSRC] + args + ["-o", tmp]
     if verbose:
         print(" ".join(cmd), flush=True)
     proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -43,7 +42,17 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
-    os.replace(tmp, LIB_PATH)
+    os.replace(tmp, out_path)
+    return out_path
+
+
+def build(verbose: bool = False) -> str:
+    """Compile every HIP source into lib/libulorl.so, and the torch-free profiling driver
+    lib/ulorl_probe (library sources + csrc/probe); always recompiles."""
+    os.makedirs(LIB_DIR, exist_ok=True)
+    _hipcc(["-shared"] + sources(), LIB_PATH, verbose)
+    probe = sorted(glob.glob(os.path.join(CSRC, "probe", "*.hip")))
+    _hipcc(sources() + probe, PROBE_PATH, verbose)
     return LIB_PATH
 
 

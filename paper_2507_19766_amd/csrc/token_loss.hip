@@ -156,18 +156,18 @@ __device__ __forceinline__ void merge(float& m, float& S, float& T, float m2, fl
     m = M;
 }
 
-template <class Tr, int NT, int U>
-__global__ __launch_bounds__(NT) void row_stats_kernel(const typename Tr::elem* __restrict__ logits,
-                                                       int64_t row_stride, int32_t V,
-                                                       const int32_t* __restrict__ token_ids,
-                                                       float* __restrict__ lse_out,
-                                                       float* __restrict__ logp_out,
-                                                       float* __restrict__ ent_out)
+// Row statistics of one row by one workgroup.  CACHED selects ordinary loads (the row stays in
+// the L2 / memory-side cache for a second read by the same workgroup) instead of streaming
+// non-temporal ones.  The result (max, sum, weighted sum in log2 units) is valid on thread 0.
+struct RowStats {
+    float m, S, T;
+};
+
+template <class Tr, int NT, int U, bool CACHED>
+__device__ __forceinline__ RowStats row_stats_core(const typename Tr::elem* __restrict__ rowp, int32_t V)
 {
     constexpr int E = Tr::kPerVec;
     constexpr int NW = NT / 64;
-    const int64_t row = blockIdx.x;
-    const typename Tr::elem* rowp = logits + row * row_stride;
     const u32x4* vp = reinterpret_cast<const u32x4*>(rowp);
     const int nvec = V / E;
     const int tid = threadIdx.x;
@@ -178,7 +178,7 @@ __global__ __launch_bounds__(NT) void row_stats_kernel(const typename Tr::elem* 
     for (; i + (U - 1) * NT < nvec; i += U * NT) {
         u32x4 v[U];
 #pragma unroll
-        for (int k = 0; k < U; ++k) v[k] = load_stream(vp + i + k * NT);
+        for (int k = 0; k < U; ++k) v[k] = CACHED ? vp[i + k * NT] : load_stream(vp + i + k * NT);
         float f[U * E];
 #pragma unroll
         for (int k = 0; k < U; ++k) Tr::unpack(v[k], f + k * E);
@@ -186,7 +186,7 @@ __global__ __launch_bounds__(NT) void row_stats_kernel(const typename Tr::elem* 
     }
     for (; i < nvec; i += NT) {
         float f[E];
-        Tr::unpack(load_stream(vp + i), f);
+        Tr::unpack(CACHED ? vp[i] : load_stream(vp + i), f);
         absorb<E>(f, a);
     }
     if (tid == NT - 1) {  // ragged tail when V is not a multiple of the vector width
@@ -222,40 +222,55 @@ __global__ __launch_bounds__(NT) void row_stats_kernel(const typename Tr::elem* 
     if (tid == 0) {
 #pragma unroll
         for (int w = 1; w < NW; ++w) merge(m, S, T, sm[w], sS[w], sT[w]);
-        const float lnS = logf(S);
-        const int32_t y = token_ids[row];
-        float lp = __builtin_nanf("");
-        if (y >= 0 && y < V) lp = (Tr::load1(rowp + y) - m) - lnS;
-        lse_out[row] = m + lnS;
+    }
+    return RowStats{m, S, T};
+}
+
+// lse, chosen-token log-prob and entropy from the merged statistics (thread 0 only).
+template <class Tr>
+__device__ __forceinline__ void finish_row(const RowStats& st, const typename Tr::elem* rowp, int32_t V, int32_t y,
+                                           float& lse, float& lp, float& ent)
+{
+    const float lnS = logf(st.S);
+    lp = __builtin_nanf("");
+    if (y >= 0 && y < V) lp = (Tr::load1(rowp + y) - st.m) - lnS;
+    lse = st.m + lnS;
+    ent = lnS - (st.T * kLn2) / st.S;
+}
+
+template <class Tr, int NT, int U>
+__global__ __launch_bounds__(NT) void row_stats_kernel(const typename Tr::elem* __restrict__ logits,
+                                                       int64_t row_stride, int32_t V,
+                                                       const int32_t* __restrict__ token_ids,
+                                                       float* __restrict__ lse_out,
+                                                       float* __restrict__ logp_out,
+                                                       float* __restrict__ ent_out)
+{
+    const int64_t row = blockIdx.x;
+    const typename Tr::elem* rowp = logits + row * row_stride;
+    const RowStats st = row_stats_core<Tr, NT, U, false>(rowp, V);
+    if (threadIdx.x == 0) {
+        float lse, lp, ent;
+        finish_row<Tr>(st, rowp, V, token_ids[row], lse, lp, ent);
+        lse_out[row] = lse;
         logp_out[row] = lp;
-        ent_out[row] = lnS - (T * kLn2) / S;
+        ent_out[row] = ent;
     }
 }
 
 // ---------------------------------------------------------------------------------------------
 // backward stream
 // ---------------------------------------------------------------------------------------------
+// One row of dlogits by one workgroup: zeros if !live, else g * (onehot(y) - exp(z - l)).
 template <class Tr, int NT, int U>
-__global__ __launch_bounds__(NT) void dlogits_kernel(const typename Tr::elem* logits,
-                                                     int64_t row_stride, int32_t V,
-                                                     const int32_t* __restrict__ token_ids,
-                                                     const float* __restrict__ lse,
-                                                     const float* __restrict__ gcoef, float grad_out,
-                                                     typename Tr::elem* dlogits)
+__device__ __forceinline__ void dlogits_core(const typename Tr::elem* rowp, typename Tr::elem* outp, int32_t V,
+                                             bool live, float g, float l, int32_t y)
 {
     constexpr int E = Tr::kPerVec;
-    const int64_t row = blockIdx.x;
-    const typename Tr::elem* rowp = logits + row * row_stride;
-    typename Tr::elem* outp = dlogits + row * row_stride;
     const u32x4* vp = reinterpret_cast<const u32x4*>(rowp);
     u32x4* op = reinterpret_cast<u32x4*>(outp);
     const int nvec = V / E;
     const int tid = threadIdx.x;
-
-    const float g = gcoef[row] * grad_out;
-    const float l = lse[row];
-    const int32_t y = token_ids[row];
-    const bool live = (g != 0.0f) && (fabsf(g) <= 3.0e38f) && (fabsf(l) <= 3.0e38f) && y >= 0 && y < V;
 
     if (!live) {  // masked / clipped / zero-advantage / invalid row: write-only
         const u32x4 zero = {0u, 0u, 0u, 0u};
@@ -308,6 +323,30 @@ __global__ __launch_bounds__(NT) void dlogits_kernel(const typename Tr::elem* lo
     }
 }
 
+__device__ __forceinline__ bool row_is_live(float g, float l, int32_t y, int32_t V)
+{
+    return (g != 0.0f) && (fabsf(g) <= 3.0e38f) && (fabsf(l) <= 3.0e38f) && y >= 0 && y < V;
+}
+
+// `only` (may be NULL): process just the rows whose flag is non-zero (the rows the fused
+// forward+backward kernel had to defer until the entropy gate was known).
+template <class Tr, int NT, int U>
+__global__ __launch_bounds__(NT) void dlogits_kernel(const typename Tr::elem* logits,
+                                                     int64_t row_stride, int32_t V,
+                                                     const int32_t* __restrict__ token_ids,
+                                                     const float* __restrict__ lse,
+                                                     const float* __restrict__ gcoef, float grad_out,
+                                                     typename Tr::elem* dlogits,
+                                                     const uint8_t* __restrict__ only)
+{
+    const int64_t row = blockIdx.x;
+    if (only != nullptr && only[row] == 0) return;
+    const float g = gcoef[row] * grad_out;
+    const float l = lse[row];
+    const int32_t y = token_ids[row];
+    dlogits_core<Tr, NT, U>(logits + row * row_stride, dlogits + row * row_stride, V, row_is_live(g, l, y, V), g, l, y);
+}
+
 // ---------------------------------------------------------------------------------------------
 // O(N) epilogue of the forward call
 // ---------------------------------------------------------------------------------------------
@@ -345,6 +384,38 @@ __device__ __forceinline__ double shfl_xor_f64(double x, int off)
     hi = __shfl_xor(hi, off);
     return __hiloint2double(hi, lo);
 }
+
+// Everything about one token that does not depend on the entropy gate (Sec. 3.1.2 ratio,
+// Eq. 7 clipped term, Eq. MPTS membership, coefficient assuming the token is not masked).
+// Used by the O(N) epilogue and by the fused forward+backward kernel, so both take the same
+// decisions bit for bit.
+struct TokenEval {
+    double r, s;    // importance ratio, clipped surrogate term
+    float g;        // d loss / d logp if the token is kept
+    bool positive;  // A > 0
+    bool mpt;       // positive and p >= tau: member of the MPT set
+    bool active;    // unclipped branch attains the min: gradient flows
+};
+
+__device__ __forceinline__ TokenEval token_eval(float lpf, float advf, float oldf, int is_mode, double eps_low,
+                                                double eps_high, double tau, double D)
+{
+    TokenEval ev;
+    const double lp = (double)lpf;
+    const double A = (double)advf;
+    const double p = exp(lp);
+    ev.positive = A > 0.0;
+    ev.mpt = ev.positive && (p >= tau);
+    ev.r = (is_mode == ULORL_IS_POIS) ? 1.0 : exp(lp - (double)oldf);
+    const double c = fmin(fmax(ev.r, 1.0 - eps_low), 1.0 + eps_high);
+    const double u = ev.r * A, v = c * A;
+    ev.active = u <= v;
+    ev.s = ev.active ? u : v;
+    ev.g = ev.active ? (float)(-(ev.r * A) / D) : 0.0f;
+    return ev;
+}
+
+__device__ __forceinline__ bool not_finite(float x) { return !(fabsf(x) <= 3.0e38f); }
 
 // Fixed-shape tree: lanes by xor-shuffle, then waves through LDS in index order.
 template <int NT>
@@ -391,6 +462,22 @@ __device__ __forceinline__ int block_or_bits(int flags)
     return r;
 }
 
+__device__ __forceinline__ bool response_bounds_ok(const int32_t* cu, int i, int32_t R, int64_t N)
+{
+    const int64_t b = cu[i], e = cu[i + 1];
+    return b >= 0 && e >= b && e <= N && (i != 0 || b == 0) && (i != R - 1 || e == N);
+}
+
+// Single workgroup: is cu_seqlens well formed?  (The fused kernel needs the answer before it
+// writes any gradient.)
+__global__ __launch_bounds__(kTokBlock) void cu_check_kernel(const int32_t* cu, int32_t R, int64_t N, uint32_t* badcu)
+{
+    int bad = 0;
+    for (int i = threadIdx.x; i < R; i += kTokBlock) bad |= response_bounds_ok(cu, i, R, N) ? 0 : 1;
+    bad = __syncthreads_or(bad);
+    if (threadIdx.x == 0) *badcu = bad ? 1u : 0u;
+}
+
 // One workgroup per response: sum of the token entropies (Sec. 3.2.2, H-bar_i numerator) and a
 // sanity check of the response's bounds.
 __global__ __launch_bounds__(kTokBlock) void response_entropy_kernel(TokenArgs a)
@@ -398,7 +485,7 @@ __global__ __launch_bounds__(kTokBlock) void response_entropy_kernel(TokenArgs a
     __shared__ double scratch[kTokBlock / 64];
     const int i = blockIdx.x;
     const int64_t b = a.cu[i], e = a.cu[i + 1];
-    const bool ok = b >= 0 && e >= b && e <= a.N && (i != 0 || b == 0) && (i != a.R - 1 || e == a.N);
+    const bool ok = response_bounds_ok(a.cu, i, a.R, a.N);
     double s = 0.0;
     if (ok)
         for (int64_t t = b + threadIdx.x; t < e; t += kTokBlock) s += (double)a.entropy[t];
@@ -466,23 +553,16 @@ __global__ __launch_bounds__(kTokBlock) void token_terms_kernel(TokenArgs a)
         float g_out = 0.0f, r_out = 0.0f;
         uint8_t m_out = 0;
         if (!bad_tok && !nonfinite && !badcu) {
-            const double lp = (double)lpf;
-            const double A = (double)a.adv[t];
-            const double p = exp(lp);
-            const bool positive = A > 0.0;
-            const bool I = gate && positive && (p >= a.tau);
-            const double r = (a.is_mode == ULORL_IS_POIS) ? 1.0 : exp(lp - (double)a.old_logp[t]);
-            const double c = fmin(fmax(r, 1.0 - a.eps_low), 1.0 + a.eps_high);
-            const double u = r * A, v = c * A;
-            const bool active = u <= v;
-            const double s = active ? u : v;
-            contrib = I ? 0.0 : s;
-            g_out = (I || !active) ? 0.0f : (float)(-(r * A) / a.D);
-            r_out = (float)r;
+            const TokenEval ev = token_eval(lpf, a.adv[t], a.is_mode == ULORL_IS_POIS ? 0.0f : a.old_logp[t],
+                                            a.is_mode, a.eps_low, a.eps_high, a.tau, a.D);
+            const bool I = gate && ev.mpt;
+            contrib = I ? 0.0 : ev.s;
+            g_out = I ? 0.0f : ev.g;
+            r_out = (float)ev.r;
             m_out = I ? 1 : 0;
             n_mask = I;
-            n_clip = !active;
-            n_pos = positive;
+            n_clip = !ev.active;
+            n_pos = ev.positive;
         }
         a.gcoef[t] = g_out;
         if (a.ratio) a.ratio[t] = r_out;
@@ -564,18 +644,87 @@ __global__ __launch_bounds__(kTokBlock) void loss_finalize_kernel(TokenArgs a, i
 }
 
 // ---------------------------------------------------------------------------------------------
+// fused forward + backward stream
+// ---------------------------------------------------------------------------------------------
+// One workgroup per row does both passes back to back: statistics with ordinary (cacheable)
+// loads, then the gradient with the row read a second time while it is still in the L2 /
+// memory-side cache, so HBM sees one read and one write per row.  This is possible whenever the
+// row's coefficient does not depend on other rows: always for the ALWAYS / NEVER gates, and for
+// every token outside the MPT set under the entropy gates.  MPT members under an entropy gate
+// are left untouched and flagged in `defer`; dlogits_kernel finishes them once the gate is known.
+struct FusedArgs {
+    const int32_t* token_ids;
+    const float* old_logp;
+    const float* adv;
+    float* lse;
+    float* logp;
+    float* entropy;
+    uint8_t* defer;
+    const uint32_t* badcu;  // one word: non-zero if cu_seqlens is malformed (then nothing is trained)
+    int32_t is_mode, gate_mode;
+    double eps_low, eps_high, tau, D;
+    float grad_out;
+};
+
+template <class Tr, int NT, int U>
+__global__ __launch_bounds__(NT) void fused_row_kernel(const typename Tr::elem* logits, int64_t row_stride, int32_t V,
+                                                       typename Tr::elem* dlogits, FusedArgs a)
+{
+    __shared__ float bc_g, bc_l;
+    __shared__ int bc_mode;  // 0: write zeros, 1: write gradient, 2: deferred
+    const int64_t row = blockIdx.x;
+    const typename Tr::elem* rowp = logits + row * row_stride;
+    const int32_t y = a.token_ids[row];
+    const RowStats st = row_stats_core<Tr, NT, U, true>(rowp, V);
+    if (threadIdx.x == 0) {
+        float lse, lp, ent;
+        finish_row<Tr>(st, rowp, V, y, lse, lp, ent);
+        a.lse[row] = lse;
+        a.logp[row] = lp;
+        a.entropy[row] = ent;
+        int mode = 0;
+        float g = 0.0f;
+        const bool bad = (y < 0 || y >= V) || not_finite(lp) || not_finite(ent) || not_finite(lse) || *a.badcu != 0;
+        if (!bad) {
+            const TokenEval ev = token_eval(lp, a.adv[row], a.is_mode == ULORL_IS_POIS ? 0.0f : a.old_logp[row],
+                                            a.is_mode, a.eps_low, a.eps_high, a.tau, a.D);
+            const bool gate_known = a.gate_mode == ULORL_GATE_ALWAYS || a.gate_mode == ULORL_GATE_NEVER;
+            if (ev.mpt && !gate_known) {
+                mode = 2;
+            } else {
+                const bool I = ev.mpt && a.gate_mode == ULORL_GATE_ALWAYS;
+                g = (I ? 0.0f : ev.g) * a.grad_out;
+                mode = row_is_live(g, lse, y, V) ? 1 : 0;
+            }
+        }
+        a.defer[row] = mode == 2 ? 1 : 0;
+        bc_g = g;
+        bc_l = lse;
+        bc_mode = mode;
+    }
+    __syncthreads();
+    const int mode = bc_mode;
+    if (mode == 2) return;
+    dlogits_core<Tr, NT, U>(rowp, dlogits + row * row_stride, V, mode == 1, bc_g, bc_l, y);
+}
+
+// ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
+// Defaults from a sweep on 131072 x 151936 bf16.  The forward and the fused kernel share one
+// shape so that their row statistics are bit-identical (the backward is elementwise, its shape
+// does not change results).
 struct Tuning {
-    int fwd_threads = 256, fwd_unroll = 4;
+    int fwd_threads = 512, fwd_unroll = 8;
     int bwd_threads = 256, bwd_unroll = 4;
+    int fused_threads = 512, fused_unroll = 8;
 };
 Tuning g_tune;
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct WorkspaceLayout {
-    size_t hsum, rflags, part_sum, part_cnt, total;
+    size_t hsum, rflags, part_sum, part_cnt, defer, badcu, total;
     int64_t nblk;
 };
 
@@ -588,6 +737,8 @@ WorkspaceLayout workspace_layout(int64_t N, int32_t R)
     w.rflags = off;   off = align_up(off + sizeof(uint32_t) * (size_t)R, 256);
     w.part_sum = off; off = align_up(off + sizeof(double) * (size_t)w.nblk, 256);
     w.part_cnt = off; off = align_up(off + sizeof(int64_t) * 4 * (size_t)w.nblk, 256);
+    w.defer = off;    off = align_up(off + (size_t)N, 256);
+    w.badcu = off;    off = align_up(off + sizeof(uint32_t), 256);
     w.total = off;
     return w;
 }
@@ -633,27 +784,94 @@ bool dispatch_row_stats(int nt, int u, const void* logits, int64_t N, int64_t V,
 
 template <class Tr, int NT, int U>
 void launch_dlogits(const void* logits, int64_t N, int64_t V, int64_t stride, const int32_t* y, const float* lse,
-                    const float* g, float grad_out, void* dz, hipStream_t st)
+                    const float* g, float grad_out, void* dz, const uint8_t* only, hipStream_t st)
 {
     hipLaunchKernelGGL((dlogits_kernel<Tr, NT, U>), dim3((unsigned)N), dim3(NT), 0, st,
                        (const typename Tr::elem*)logits, stride, (int32_t)V, y, lse, g, grad_out,
-                       (typename Tr::elem*)dz);
+                       (typename Tr::elem*)dz, only);
 }
 
 template <class Tr>
 bool dispatch_dlogits(int nt, int u, const void* logits, int64_t N, int64_t V, int64_t stride, const int32_t* y,
-                      const float* lse, const float* g, float grad_out, void* dz, hipStream_t st)
+                      const float* lse, const float* g, float grad_out, void* dz, const uint8_t* only, hipStream_t st)
 {
-#define ULORL_CASE(NT_, U_)                                                              \
-    if (nt == NT_ && u == U_) {                                                          \
-        launch_dlogits<Tr, NT_, U_>(logits, N, V, stride, y, lse, g, grad_out, dz, st);  \
-        return true;                                                                     \
+#define ULORL_CASE(NT_, U_)                                                                    \
+    if (nt == NT_ && u == U_) {                                                                \
+        launch_dlogits<Tr, NT_, U_>(logits, N, V, stride, y, lse, g, grad_out, dz, only, st);  \
+        return true;                                                                           \
     }
     ULORL_CASE(256, 2) ULORL_CASE(256, 4) ULORL_CASE(256, 8)
     ULORL_CASE(512, 2) ULORL_CASE(512, 4) ULORL_CASE(512, 8)
     ULORL_CASE(1024, 2) ULORL_CASE(1024, 4) ULORL_CASE(1024, 8)
 #undef ULORL_CASE
     return false;
+}
+
+template <class Tr, int NT, int U>
+void launch_fused(const void* logits, int64_t N, int64_t V, int64_t stride, void* dz, const FusedArgs& a, hipStream_t st)
+{
+    hipLaunchKernelGGL((fused_row_kernel<Tr, NT, U>), dim3((unsigned)N), dim3(NT), 0, st,
+                       (const typename Tr::elem*)logits, stride, (int32_t)V, (typename Tr::elem*)dz, a);
+}
+
+template <class Tr>
+bool dispatch_fused(int nt, int u, const void* logits, int64_t N, int64_t V, int64_t stride, void* dz,
+                    const FusedArgs& a, hipStream_t st)
+{
+#define ULORL_CASE(NT_, U_)                                              \
+    if (nt == NT_ && u == U_) {                                          \
+        launch_fused<Tr, NT_, U_>(logits, N, V, stride, dz, a, st);      \
+        return true;                                                     \
+    }
+    ULORL_CASE(256, 2) ULORL_CASE(256, 4) ULORL_CASE(256, 8)
+    ULORL_CASE(512, 2) ULORL_CASE(512, 4) ULORL_CASE(512, 8)
+    ULORL_CASE(1024, 2) ULORL_CASE(1024, 4) ULORL_CASE(1024, 8)
+#undef ULORL_CASE
+    return false;
+}
+
+// Argument checks shared by the forward and the fused forward+backward entry points.
+int32_t check_objective_args(const int32_t* cu_seqlens, int32_t R, const float* old_logp, const ulorl_params* p,
+                             const float* loss, const float* gcoef)
+{
+    if (!p || !cu_seqlens || !loss || !gcoef) return ULORL_ERR_NULL;
+    if (R <= 0) return ULORL_ERR_SHAPE;
+    if (!(p->eps_low >= 0.0f) || !(p->eps_high >= 0.0f) || !(p->tau > 0.0f && p->tau <= 1.0f) ||
+        !(p->sigma == p->sigma) || p->seg_len < 0 || p->reserved != 0)
+        return ULORL_ERR_PARAM;
+    if (p->is_mode != ULORL_IS_SAIS && p->is_mode != ULORL_IS_POIS) return ULORL_ERR_PARAM;
+    if (p->gate_mode < ULORL_GATE_PER_RESPONSE || p->gate_mode > ULORL_GATE_NEVER) return ULORL_ERR_PARAM;
+    if (p->is_mode == ULORL_IS_SAIS && !old_logp) return ULORL_ERR_NULL;
+    return ULORL_OK;
+}
+
+TokenArgs make_token_args(int64_t N, int64_t V, const int32_t* token_ids, const int32_t* cu_seqlens, int32_t R,
+                          const int32_t* segment_ids, const float* old_logp, const float* advantages,
+                          const ulorl_params* p, float* logp, float* entropy, float* lse, float* gcoef,
+                          uint8_t* mpt_mask, float* ratio, int32_t* segment_out, float* resp_entropy,
+                          uint8_t* resp_gate, void* workspace, const WorkspaceLayout& wl)
+{
+    char* ws = (char*)workspace;
+    TokenArgs a;
+    a.logp = logp; a.entropy = entropy; a.lse = lse; a.token_ids = token_ids; a.cu = cu_seqlens;
+    a.segment_ids = segment_ids; a.old_logp = old_logp; a.adv = advantages; a.gcoef = gcoef;
+    a.mask = mpt_mask; a.ratio = ratio; a.seg_out = segment_out; a.resp_entropy = resp_entropy;
+    a.resp_gate = resp_gate;
+    a.hsum = (double*)(ws + wl.hsum); a.rflags = (uint32_t*)(ws + wl.rflags);
+    a.part_sum = (double*)(ws + wl.part_sum); a.part_cnt = (int64_t*)(ws + wl.part_cnt);
+    a.N = N; a.V = (int32_t)V; a.R = R;
+    a.is_mode = p->is_mode; a.gate_mode = p->gate_mode; a.seg_len = p->seg_len;
+    a.eps_low = (double)p->eps_low; a.eps_high = (double)p->eps_high;
+    a.tau = (double)p->tau; a.sigma = (double)p->sigma;
+    a.D = p->denominator > 0.0 ? p->denominator : (double)N;
+    return a;
+}
+
+void launch_token_epilogue(const TokenArgs& a, const WorkspaceLayout& wl, float* loss, int64_t* counters, hipStream_t st)
+{
+    hipLaunchKernelGGL(response_entropy_kernel, dim3((unsigned)a.R), dim3(kTokBlock), 0, st, a);
+    hipLaunchKernelGGL(token_terms_kernel, dim3((unsigned)wl.nblk), dim3(kTokBlock), 0, st, a);
+    hipLaunchKernelGGL(loss_finalize_kernel, dim3(1), dim3(kTokBlock), 0, st, a, wl.nblk, loss, counters);
 }
 
 }  // namespace
@@ -686,6 +904,8 @@ int32_t ulorl_tune(int32_t knob, int32_t value)
     case ULORL_TUNE_FWD_UNROLL:  if (!unroll_ok) return ULORL_ERR_PARAM;  g_tune.fwd_unroll = value;  return ULORL_OK;
     case ULORL_TUNE_BWD_THREADS: if (!threads_ok) return ULORL_ERR_PARAM; g_tune.bwd_threads = value; return ULORL_OK;
     case ULORL_TUNE_BWD_UNROLL:  if (!unroll_ok) return ULORL_ERR_PARAM;  g_tune.bwd_unroll = value;  return ULORL_OK;
+    case ULORL_TUNE_FUSED_THREADS: if (!threads_ok) return ULORL_ERR_PARAM; g_tune.fused_threads = value; return ULORL_OK;
+    case ULORL_TUNE_FUSED_UNROLL:  if (!unroll_ok) return ULORL_ERR_PARAM;  g_tune.fused_unroll = value;  return ULORL_OK;
     default: return ULORL_ERR_PARAM;
     }
 }
@@ -710,14 +930,8 @@ int32_t ulorl_token_loss_fwd(const void* logits, int32_t dt, int64_t N, int64_t 
     const bool stats_only = advantages == nullptr;
     WorkspaceLayout wl = {};
     if (!stats_only) {
-        if (!p || !cu_seqlens || !loss || !gcoef) return ULORL_ERR_NULL;
-        if (R <= 0) return ULORL_ERR_SHAPE;
-        if (!(p->eps_low >= 0.0f) || !(p->eps_high >= 0.0f) || !(p->tau > 0.0f && p->tau <= 1.0f) ||
-            !(p->sigma == p->sigma) || p->seg_len < 0 || p->reserved != 0)
-            return ULORL_ERR_PARAM;
-        if (p->is_mode != ULORL_IS_SAIS && p->is_mode != ULORL_IS_POIS) return ULORL_ERR_PARAM;
-        if (p->gate_mode < ULORL_GATE_PER_RESPONSE || p->gate_mode > ULORL_GATE_NEVER) return ULORL_ERR_PARAM;
-        if (p->is_mode == ULORL_IS_SAIS && !old_logp) return ULORL_ERR_NULL;
+        rc = check_objective_args(cu_seqlens, R, old_logp, p, loss, gcoef);
+        if (rc != ULORL_OK) return rc;
         wl = workspace_layout(N, R);
         if (!workspace || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < wl.total)
             return ULORL_ERR_WORKSPACE;
@@ -732,24 +946,62 @@ int32_t ulorl_token_loss_fwd(const void* logits, int32_t dt, int64_t N, int64_t 
     if (!ok || hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;
     if (stats_only) return ULORL_OK;
 
-    char* ws = (char*)workspace;
-    TokenArgs a;
-    a.logp = logp; a.entropy = entropy; a.lse = lse; a.token_ids = token_ids; a.cu = cu_seqlens;
-    a.segment_ids = segment_ids; a.old_logp = old_logp; a.adv = advantages; a.gcoef = gcoef;
-    a.mask = mpt_mask; a.ratio = ratio; a.seg_out = segment_out; a.resp_entropy = resp_entropy;
-    a.resp_gate = resp_gate;
-    a.hsum = (double*)(ws + wl.hsum); a.rflags = (uint32_t*)(ws + wl.rflags);
-    a.part_sum = (double*)(ws + wl.part_sum); a.part_cnt = (int64_t*)(ws + wl.part_cnt);
-    a.N = N; a.V = (int32_t)V; a.R = R;
-    a.is_mode = p->is_mode; a.gate_mode = p->gate_mode; a.seg_len = p->seg_len;
-    a.eps_low = (double)p->eps_low; a.eps_high = (double)p->eps_high;
-    a.tau = (double)p->tau; a.sigma = (double)p->sigma;
-    a.D = p->denominator > 0.0 ? p->denominator : (double)N;
-
-    hipLaunchKernelGGL(response_entropy_kernel, dim3((unsigned)R), dim3(kTokBlock), 0, st, a);
-    hipLaunchKernelGGL(token_terms_kernel, dim3((unsigned)wl.nblk), dim3(kTokBlock), 0, st, a);
-    hipLaunchKernelGGL(loss_finalize_kernel, dim3(1), dim3(kTokBlock), 0, st, a, wl.nblk, loss, counters);
+    const TokenArgs a = make_token_args(N, V, token_ids, cu_seqlens, R, segment_ids, old_logp, advantages, p, logp,
+                                        entropy, lse, gcoef, mpt_mask, ratio, segment_out, resp_entropy, resp_gate,
+                                        workspace, wl);
+    launch_token_epilogue(a, wl, loss, counters, st);
     if (hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;
+    return ULORL_OK;
+}
+
+int32_t ulorl_token_loss_fwd_bwd(const void* logits, int32_t dt, int64_t N, int64_t V, int64_t row_stride,
+                                 const int32_t* token_ids, const int32_t* cu_seqlens, int32_t R,
+                                 const int32_t* segment_ids, const float* old_logp, const float* advantages,
+                                 const ulorl_params* p, float grad_out, float* loss, float* logp, float* entropy,
+                                 float* lse, float* gcoef, uint8_t* mpt_mask, float* ratio, int32_t* segment_out,
+                                 float* resp_entropy, uint8_t* resp_gate, int64_t* counters, void* dlogits,
+                                 void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    int32_t rc = check_logits(logits, dt, N, V, row_stride);
+    if (rc != ULORL_OK) return rc;
+    if (!token_ids || !logp || !entropy || !lse || !advantages || !dlogits) return ULORL_ERR_NULL;
+    if (((uintptr_t)dlogits & 15u) != 0) return ULORL_ERR_ALIGN;
+    rc = check_objective_args(cu_seqlens, R, old_logp, p, loss, gcoef);
+    if (rc != ULORL_OK) return rc;
+    const WorkspaceLayout wl = workspace_layout(N, R);
+    if (!workspace || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < wl.total) return ULORL_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)hip_stream;
+    char* ws = (char*)workspace;
+
+    const TokenArgs a = make_token_args(N, V, token_ids, cu_seqlens, R, segment_ids, old_logp, advantages, p, logp,
+                                        entropy, lse, gcoef, mpt_mask, ratio, segment_out, resp_entropy, resp_gate,
+                                        workspace, wl);
+    FusedArgs f;
+    f.token_ids = token_ids; f.old_logp = old_logp; f.adv = advantages;
+    f.lse = lse; f.logp = logp; f.entropy = entropy;
+    f.defer = (uint8_t*)(ws + wl.defer); f.badcu = (const uint32_t*)(ws + wl.badcu);
+    f.is_mode = a.is_mode; f.gate_mode = a.gate_mode;
+    f.eps_low = a.eps_low; f.eps_high = a.eps_high; f.tau = a.tau; f.D = a.D;
+    f.grad_out = grad_out;
+
+    hipLaunchKernelGGL(cu_check_kernel, dim3(1), dim3(kTokBlock), 0, st, cu_seqlens, R, N, (uint32_t*)(ws + wl.badcu));
+    bool ok = dt == ULORL_BF16
+                  ? dispatch_fused<StoreBF16>(g_tune.fused_threads, g_tune.fused_unroll, logits, N, V, row_stride,
+                                              dlogits, f, st)
+                  : dispatch_fused<StoreF32>(g_tune.fused_threads, g_tune.fused_unroll, logits, N, V, row_stride,
+                                             dlogits, f, st);
+    if (!ok || hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;
+    launch_token_epilogue(a, wl, loss, counters, st);
+    if (hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;
+    if (a.gate_mode == ULORL_GATE_PER_RESPONSE || a.gate_mode == ULORL_GATE_GLOBAL) {
+        // MPT members waited for the gate: their rows are still logits (in place) or unwritten
+        ok = dt == ULORL_BF16
+                 ? dispatch_dlogits<StoreBF16>(g_tune.bwd_threads, g_tune.bwd_unroll, logits, N, V, row_stride,
+                                               token_ids, lse, gcoef, grad_out, dlogits, f.defer, st)
+                 : dispatch_dlogits<StoreF32>(g_tune.bwd_threads, g_tune.bwd_unroll, logits, N, V, row_stride,
+                                              token_ids, lse, gcoef, grad_out, dlogits, f.defer, st);
+        if (!ok || hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;
+    }
     return ULORL_OK;
 }
 
@@ -764,9 +1016,9 @@ int32_t ulorl_token_loss_bwd(const void* logits, int32_t dt, int64_t N, int64_t 
     hipStream_t st = (hipStream_t)hip_stream;
     bool ok = dt == ULORL_BF16
                   ? dispatch_dlogits<StoreBF16>(g_tune.bwd_threads, g_tune.bwd_unroll, logits, N, V, row_stride,
-                                                token_ids, lse, gcoef, grad_out, dlogits, st)
+                                                token_ids, lse, gcoef, grad_out, dlogits, nullptr, st)
                   : dispatch_dlogits<StoreF32>(g_tune.bwd_threads, g_tune.bwd_unroll, logits, N, V, row_stride,
-                                               token_ids, lse, gcoef, grad_out, dlogits, st);
+                                               token_ids, lse, gcoef, grad_out, dlogits, nullptr, st);
     if (!ok || hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;
     return ULORL_OK;
 }

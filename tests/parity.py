@@ -143,7 +143,43 @@ def run_full_parity(w: ui.Workload, p: ulorl.Params, dz_rows=None, inplace=False
     keep = ~near[rows]
     check_dlogits(w.name, dz[torch.as_tensor(rows[keep], device=dev)], ref[keep],
                   grad_out * tt.gcoef[rows][keep], w.dtype, rtol)
+    if not inplace:
+        check_fused_path(d, p, res, dz, grad_out=grad_out)
     return res, tt, dict(n_near_tau=n_tau, n_near_edge=n_edge, dz=dz, data=d, o_H=o_H)
+
+
+def _bits(t: torch.Tensor) -> torch.Tensor:
+    if t.dtype == torch.bfloat16:
+        return t.contiguous().view(torch.int16)
+    if t.dtype == torch.float32:
+        return t.contiguous().view(torch.int32)
+    return t
+
+
+def assert_same_results(a: ulorl.FwdResult, b: ulorl.FwdResult, what=""):
+    for name in ("loss", "logp", "entropy", "lse", "gcoef", "mpt_mask", "ratio", "segment_out",
+                 "resp_entropy", "resp_gate", "counters"):
+        x, y = getattr(a, name), getattr(b, name)
+        assert torch.equal(_bits(x), _bits(y)), "%s: %s differs between the fused and the two-call path" % (what, name)
+
+
+def check_fused_path(d, p: ulorl.Params, res: ulorl.FwdResult, dz_ref: torch.Tensor, grad_out=1.0,
+                     also_inplace=True):
+    """The one-call forward+backward must reproduce the two-call results bit for bit, out of place
+    and (on a copy of the logits) in place."""
+    old = None if p.is_mode == ulorl.IS_POIS else d["old_logp"]
+    r2, dz2 = ulorl.token_loss_fwd_bwd(d["logits"], d["token_ids"], d["cu_seqlens"], d["advantages"], old, p,
+                                       grad_out=grad_out)
+    assert_same_results(res, r2, "out of place")
+    assert torch.equal(_bits(dz2), _bits(dz_ref)), "fused dlogits differ from the two-call dlogits"
+    if also_inplace:
+        z = d["logits"].clone() if d["logits"].is_contiguous() else None
+        if z is not None:
+            r3, dz3 = ulorl.token_loss_fwd_bwd(z, d["token_ids"], d["cu_seqlens"], d["advantages"], old, p,
+                                               grad_out=grad_out, inplace=True)
+            assert dz3.data_ptr() == z.data_ptr()
+            assert_same_results(res, r3, "in place")
+            assert torch.equal(_bits(dz3), _bits(dz_ref)), "fused in-place dlogits differ"
 
 
 def sigma_between_responses(host_logits, y, cu, k=None):

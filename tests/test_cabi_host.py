@@ -94,6 +94,22 @@ def test_backward_rejects_bad_arguments_on_the_host():
     assert bwd(dz=0x5004) == -4 and bwd(logits=0x1002) == -4
 
 
+def test_fused_entry_rejects_bad_arguments_on_the_host():
+    lib = ulorl.load_library()
+    vp = ctypes.c_void_p
+    cp = binding.Params().to_c()
+
+    def call(logits=0x1000, dz=0x20000, adv=0x5000, ws=0x10000, ws_bytes=1 << 20, N=4, stride=64, old=0x4000):
+        return lib.ulorl_token_loss_fwd_bwd(
+            vp(logits), 1, N, 64, stride, vp(0x2000), vp(0x3000), 1, None, vp(old), vp(adv), ctypes.byref(cp), 1.0,
+            vp(0x6000), vp(0x7000), vp(0x8000), vp(0x9000), vp(0xa000), None, None, None, None, None, None,
+            vp(dz), vp(ws), ws_bytes, None)
+    assert call(logits=0) == -1 and call(dz=0) == -1 and call(adv=0) == -1 and call(old=0) == -1
+    assert call(N=0) == -2 and call(stride=32) == -2
+    assert call(dz=0x20008) == -4
+    assert call(ws=0) == -6 and call(ws_bytes=64) == -6
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     z = torch.zeros(2, 8)

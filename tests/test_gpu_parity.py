@@ -99,7 +99,7 @@ def test_heavily_masked_batch_takes_the_write_only_path():
 @pytest.mark.parametrize("dtype,V", [("f32", 4099), ("f32", 3), ("f32", 4 * 256 * 4 * 2 + 4 * 77 + 1),
                                      ("bf16", 1003), ("bf16", 5), ("bf16", 8 * 256 * 4 * 2 + 8 * 77 + 5),
                                      ("bf16", 8 * 1024 * 8 + 8)])
-@pytest.mark.parametrize("threads,unroll", [(256, 4), (1024, 8), (512, 2)])
+@pytest.mark.parametrize("threads,unroll", [(256, 4), (1024, 8), (512, 2), (512, 8)])
 def test_ragged_vocab_and_launch_shapes(dtype, V, threads, unroll):
     base = ui.config(1) if dtype == "f32" else ui.config(2)
     w = ui.shrink(base, [9, 1, 23], V=V, seg_len=4, name="ragged_%s_%d" % (dtype, V))
@@ -111,14 +111,16 @@ def test_ragged_vocab_and_launch_shapes(dtype, V, threads, unroll):
     buf[:, :V] = d["logits"]
     d["logits"] = buf[:, :V]
     for knob, val in ((ulorl.TUNE_FWD_THREADS, threads), (ulorl.TUNE_FWD_UNROLL, unroll),
-                      (ulorl.TUNE_BWD_THREADS, threads), (ulorl.TUNE_BWD_UNROLL, unroll)):
+                      (ulorl.TUNE_BWD_THREADS, threads), (ulorl.TUNE_BWD_UNROLL, unroll),
+                      (ulorl.TUNE_FUSED_THREADS, threads), (ulorl.TUNE_FUSED_UNROLL, unroll)):
         ulorl.tune(knob, val)
     try:
         res, tt, info = run_full_parity(w, params_for(w, gate_mode=ulorl.GATE_ALWAYS, tau=0.5), data=d)
     finally:
-        for knob, val in ((ulorl.TUNE_FWD_THREADS, 256), (ulorl.TUNE_FWD_UNROLL, 4),
-                          (ulorl.TUNE_BWD_THREADS, 256), (ulorl.TUNE_BWD_UNROLL, 4)):
-            ulorl.tune(knob, val)
+        for knob, val in ((ulorl.TUNE_FWD_THREADS, 512), (ulorl.TUNE_FWD_UNROLL, 8),
+                          (ulorl.TUNE_BWD_THREADS, 256), (ulorl.TUNE_BWD_UNROLL, 4),
+                          (ulorl.TUNE_FUSED_THREADS, 512), (ulorl.TUNE_FUSED_UNROLL, 8)):
+            ulorl.tune(knob, val)     # back to the library defaults
     # in place on the padded buffer: same bits, and the padding columns stay untouched
     dz_out = info["dz"]
     assert dz_out.stride(0) == stride
@@ -217,6 +219,36 @@ def test_explicit_segment_ids_pass_through():
     res = ulorl.token_loss_fwd(d["logits"], d["token_ids"], d["cu_seqlens"], d["advantages"],
                                d["old_logp"], p, segment_ids=ids)
     assert torch.equal(res.segment_out, ids)
+
+
+def test_fused_path_defers_mpt_members_until_the_gate_is_known():
+    """Under the entropy gates the one-call path finishes MPT members in a second launch; the
+    result must not depend on which path produced it (checked bitwise inside run_full_parity for
+    every case above); here the deferred rows are the majority."""
+    from dataclasses import replace
+    w = replace(ui.shrink(ui.config(2), [300, 280, 310, 290], seg_len=100), spike_boost=22.0, spike_frac=0.7,
+                name="cfg2_mostly_mpt")
+    d = ui.generate(w, DEV)
+    hl, y = _host(d)
+    sigma = sigma_between_responses(hl, y, w.cu_seqlens)
+    rows = np.arange(0, w.N, 11)
+    for mode, sg in ((ulorl.GATE_PER_RESPONSE, sigma), (ulorl.GATE_GLOBAL, 100.0), (ulorl.GATE_GLOBAL, 0.0)):
+        res, tt, _ = run_full_parity(w, params_for(w, gate_mode=mode, sigma=sg), dz_rows=rows, data=d)
+    p = params_for(w, gate_mode=ulorl.GATE_PER_RESPONSE, sigma=sigma)
+    res, tt, _ = run_full_parity(w, p, dz_rows=rows, data=d)
+    assert 0 < tt.resp_gate.sum() < 4 and tt.n_masked > 100
+    # device-detected errors behave the same through the one-call path
+    ybad = d["token_ids"].clone()
+    ybad[5] = w.V
+    r1 = ulorl.token_loss_fwd(d["logits"], ybad, d["cu_seqlens"], d["advantages"], d["old_logp"], p)
+    z1 = ulorl.token_loss_bwd(d["logits"], ybad, r1.lse, r1.gcoef)
+    r2, z2 = ulorl.token_loss_fwd_bwd(d["logits"], ybad, d["cu_seqlens"], d["advantages"], d["old_logp"], p)
+    assert int(r2.counters[3]) == ulorl.STATUS_BAD_TOKEN and torch.all(z2[5] == 0)
+    assert torch.equal(z1.view(torch.int16), z2.view(torch.int16))
+    cu_bad = d["cu_seqlens"].clone()
+    cu_bad[1] = 700
+    r3, z3 = ulorl.token_loss_fwd_bwd(d["logits"], d["token_ids"], cu_bad, d["advantages"], d["old_logp"], p)
+    assert int(r3.counters[3]) & ulorl.STATUS_BAD_CU and torch.all(z3 == 0) and r3.loss.item() == 0.0
 
 
 # ------------------------------------------------------------------ errors the device reports

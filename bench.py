@@ -2,16 +2,18 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4]
 
-A step is one pass of the whole hot path over one batch of synthetic input: the forward call
-(row statistics, ratio, clip, MPT mask, loss) followed by the backward call (dlogits, written in
-place for the ultra-long configuration).  Inputs are generated on the device before the timed
-region.  Because the in-place backward overwrites the logits, they are restored from a pristine
-device copy between steps; the restore is outside the timed brackets (each step is bracketed by
-a device synchronisation on both sides and the step times are summed).
+A step is one pass of the whole hot path over one batch of synthetic input: row statistics,
+ratio, clip, MPT mask, loss and dlogits (written in place for the ultra-long configuration).
+The headline path is the one-call fused forward+backward (ulorl_token_loss_fwd_bwd); the two-call
+path (ulorl_token_loss_fwd, then ulorl_token_loss_bwd) is timed the same way and reported
+beside it.  Inputs are generated on the device before the timed region.  Because the in-place
+backward overwrites the logits, they are restored from a pristine device copy between steps;
+the restore is outside the timed brackets (each step is bracketed by a device synchronisation
+on both sides and the step times are summed).
 
-Prints ONE JSON line: whole-job token-rows/s, the HBM roofline of the dominant kernel (the
-backward stream) from HIP-event timings taken inside the timed region, and the CPU oracle timed
-on a bounded sample of the same workload as a reported baseline.
+Prints ONE JSON line: whole-job token-rows/s, the HBM roofline of the dominant kernel from
+HIP-event timings taken inside the timed region, and the CPU oracle timed on a bounded sample of
+the same workload as a reported baseline.
 """
 from __future__ import annotations
 
@@ -66,11 +68,15 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="cfg4", choices=["cfg1", "cfg2", "cfg3", "cfg4"])
     ap.add_argument("--out-of-place", action="store_true", help="write dlogits to a second buffer")
-    ap.add_argument("--cpu-rows", type=int, default=8192, help="rows of the oracle sample (0 = skip)")
+    ap.add_argument("--cpu-rows", type=int, default=49152, help="rows of the oracle sample (0 = skip)")
+    ap.add_argument("--path", default="fused", choices=["fused", "two_call"],
+                    help="which path gives the headline value (both are timed)")
     ap.add_argument("--fwd-threads", type=int, default=0)
     ap.add_argument("--fwd-unroll", type=int, default=0)
     ap.add_argument("--bwd-threads", type=int, default=0)
     ap.add_argument("--bwd-unroll", type=int, default=0)
+    ap.add_argument("--fused-threads", type=int, default=0)
+    ap.add_argument("--fused-unroll", type=int, default=0)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build runs on ONE GPU (the token loss is row-parallel; see DESIGN.md, "
@@ -87,7 +93,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     for knob, val in ((ulorl.TUNE_FWD_THREADS, args.fwd_threads), (ulorl.TUNE_FWD_UNROLL, args.fwd_unroll),
-                      (ulorl.TUNE_BWD_THREADS, args.bwd_threads), (ulorl.TUNE_BWD_UNROLL, args.bwd_unroll)):
+                      (ulorl.TUNE_BWD_THREADS, args.bwd_threads), (ulorl.TUNE_BWD_UNROLL, args.bwd_unroll),
+                      (ulorl.TUNE_FUSED_THREADS, args.fused_threads), (ulorl.TUNE_FUSED_UNROLL, args.fused_unroll)):
         if val:
             ulorl.tune(knob, val)
 
@@ -111,11 +118,14 @@ def main():
     ws = torch.empty(ulorl.token_loss_workspace_bytes(w.N, w.R), dtype=torch.uint8, device=dev)
     out = None
 
-    def step(timed):
-        nonlocal out
+    def restore():
         if inplace:
             logits.copy_(pristine)
         torch.cuda.synchronize()
+
+    def step_two_call():
+        nonlocal out
+        restore()
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
         t_a = time.perf_counter()
         ev[0].record()
@@ -127,28 +137,64 @@ def main():
         t_b = time.perf_counter()
         return t_b - t_a, ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2])
 
+    def step_fused():
+        nonlocal out
+        restore()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        t_a = time.perf_counter()
+        ev[0].record()
+        out, _ = ulorl.token_loss_fwd_bwd(logits, y, cu, adv, old, params, grad_out=1.0, dlogits=dz, out=out,
+                                          workspace=ws)
+        ev[1].record()
+        torch.cuda.synchronize()
+        t_b = time.perf_counter()
+        return t_b - t_a, ev[0].elapsed_time(ev[1])
+
+    K = args.steps
     for _ in range(args.warmup):
-        step(False)
-    wall = fwd_ms = bwd_ms = 0.0
-    for _ in range(args.steps):
-        a, b, c = step(True)
-        wall += a
+        step_two_call()
+    wall2 = fwd_ms = bwd_ms = 0.0
+    for _ in range(K):
+        a, b, c = step_two_call()
+        wall2 += a
         fwd_ms += b
         bwd_ms += c
-    K = args.steps
-    ms_per_step = wall / K * 1e3
-    value = w.N * K / wall
+    for _ in range(args.warmup):
+        step_fused()
+    wall1 = fused_ms = 0.0
+    for _ in range(K):
+        a, b = step_fused()
+        wall1 += a
+        fused_ms += b
 
     cnt = out.counters.cpu().tolist()
     live = int((out.gcoef != 0).sum().item())
     row_bytes = w.V * elem
-    # algorithmic HBM bytes per launch: backward reads and writes live rows, only writes rows
-    # whose coefficient is zero; forward reads every row once
-    bwd_bytes = row_bytes * (2 * live + (w.N - live))
+    # Algorithmic HBM bytes per launch.  Two-call path: the forward reads every row once; the
+    # backward reads and writes live rows and only writes rows whose coefficient is zero.  Fused
+    # path: every row is read once and written once (its second read is served on chip).
     fwd_bytes = row_bytes * w.N
+    bwd_bytes = row_bytes * (2 * live + (w.N - live))
+    fused_bytes = row_bytes * 2 * w.N
+    nominal_bytes = row_bytes * 3 * w.N
+    fused_gbs = fused_bytes / (fused_ms / K * 1e-3) / 1e9
     bwd_gbs = bwd_bytes / (bwd_ms / K * 1e-3) / 1e9
     fwd_gbs = fwd_bytes / (fwd_ms / K * 1e-3) / 1e9
-    step_gbs = (bwd_bytes + fwd_bytes) / (wall / K) / 1e9
+
+    headline_fused = args.path == "fused"
+    wall = wall1 if headline_fused else wall2
+    value = w.N * K / wall
+    ms_per_step = wall / K * 1e3
+    roof_fused = {"bound": "hbm", "kernel": "fused_row_kernel (one-call forward+backward; the call also runs "
+                  "four O(N) kernels, about 0.1 ms)", "achieved": fused_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                  "frac": fused_gbs / HBM_PEAK_GBS, "traffic": None,
+                  "algorithmic_bytes_per_launch": fused_bytes, "avg_launch_ms": fused_ms / K}
+    roof_bwd = {"bound": "hbm", "kernel": "dlogits_kernel (backward call of the two-call path)",
+                "achieved": bwd_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": bwd_gbs / HBM_PEAK_GBS,
+                "traffic": None, "algorithmic_bytes_per_launch": bwd_bytes, "avg_launch_ms": bwd_ms / K}
+    roof_fwd = {"bound": "hbm", "kernel": "row_stats_kernel + O(N) epilogue (forward call of the two-call path)",
+                "achieved": fwd_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": fwd_gbs / HBM_PEAK_GBS,
+                "algorithmic_bytes_per_launch": fwd_bytes, "avg_call_ms": fwd_ms / K}
 
     result = {
         "metric": "token-rows/sec fused fwd+bwd RL token loss (V=151936 bf16) + % HBM roofline",
@@ -157,24 +203,20 @@ def main():
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "rows": w.N, "vocab": w.V, "logits_dtype": w.dtype,
                    "responses": w.R, "segment_len": w.seg_len, "dlogits": "in place" if inplace else "out of place",
+                   "path": "one call (ulorl_token_loss_fwd_bwd)" if headline_fused else "two calls (fwd, bwd)",
                    "is_mode": "SAIS", "gate": "always (static MPT masking)", "tau": w.tau,
                    "restore_between_steps": "untimed device copy" if inplace else "none"},
-        "roofline": {"bound": "hbm", "kernel": "dlogits_kernel (backward stream)", "achieved": bwd_gbs,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": bwd_gbs / HBM_PEAK_GBS, "traffic": None,
-                     "algorithmic_bytes_per_launch": bwd_bytes, "avg_launch_ms": bwd_ms / K},
-        "roofline_fwd": {"bound": "hbm", "kernel": "row_stats_kernel + O(N) epilogue (forward call)",
-                         "achieved": fwd_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                         "frac": fwd_gbs / HBM_PEAK_GBS, "algorithmic_bytes_per_launch": fwd_bytes,
-                         "avg_call_ms": fwd_ms / K},
-        "whole_step": {"achieved_GBps": step_gbs, "frac_of_hbm_peak": step_gbs / HBM_PEAK_GBS,
-                       "fwd_ms": fwd_ms / K, "bwd_ms": bwd_ms / K},
+        "roofline": roof_fused if headline_fused else roof_bwd,
+        "nominal_three_pass": {"bytes_per_step": nominal_bytes, "equivalent_GBps": nominal_bytes / (wall / K) / 1e9,
+                               "frac_of_hbm_peak": nominal_bytes / (wall / K) / 1e9 / HBM_PEAK_GBS},
+        "one_call": {"ms_per_step": wall1 / K * 1e3, "token_rows_per_s": w.N * K / wall1, "roofline": roof_fused},
+        "two_call": {"ms_per_step": wall2 / K * 1e3, "token_rows_per_s": w.N * K / wall2, "fwd_ms": fwd_ms / K,
+                     "bwd_ms": bwd_ms / K, "roofline_bwd": roof_bwd, "roofline_fwd": roof_fwd},
         "batch": {"masked_tokens": cnt[0], "clipped_tokens": cnt[1], "positive_tokens": cnt[2],
                   "zero_gradient_rows": w.N - live, "status": cnt[3], "loss": out.loss.item()},
     }
     if args.cpu_rows > 0:
-        if inplace:
-            logits.copy_(pristine)
-            torch.cuda.synchronize()
+        restore()
         log("timing the CPU oracle on %d rows..." % min(args.cpu_rows, w.N))
         result["cpu_baseline"] = cpu_baseline(w, data, params, args.cpu_rows)
     print(json.dumps(result), flush=True)

@@ -187,6 +187,56 @@ int32_t ulorl_token_loss_fwd_bwd(
     float *resp_entropy, uint8_t *resp_gate, int64_t *counters,
     void *dlogits, void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* ------------------------------------------------------------------------------------------
+ * lm_head variant: the logits are hidden . W and are never materialised.
+ *
+ *   hidden        [N, Hd] bf16 row-major (Hd contiguous), 16-byte aligned
+ *   W             [Hd, V] bf16 row-major (V contiguous), 16-byte aligned: output projection
+ *   Hd, V         multiples of 8 (16-byte rows)
+ *   vocab_chunk   multiple of 64; the backward pass materialises dlogits one chunk of this many
+ *                 vocabulary columns at a time ([N, vocab_chunk] bf16, twice) in the workspace
+ * Logits are formed tile by tile with bf16 MFMA and fp32 accumulation and consumed in registers.
+ * Everything else (token ids, cu_seqlens, old_logp, advantages, parameters, per-token and
+ * per-response outputs, counters, status bits) is exactly as in ulorl_token_loss_fwd, except
+ * that there is no stats-only pass (advantages must not be NULL).
+ *
+ * The workspace (ulorl_lmhead_workspace_bytes, 256-byte aligned) holds W^T, hidden^T, the two
+ * dlogits chunk buffers, an fp32 accumulator for dHidden and the token-loss workspace; nothing
+ * in it needs to survive between the forward and the backward call.
+ */
+size_t ulorl_lmhead_workspace_bytes(int64_t N, int64_t Hd, int64_t V, int32_t R, int32_t vocab_chunk);
+
+int32_t ulorl_lmhead_token_loss_fwd(
+    const void *hidden, const void *W, int64_t N, int64_t Hd, int64_t V, int32_t vocab_chunk,
+    const int32_t *token_ids, const int32_t *cu_seqlens, int32_t R,
+    const int32_t *segment_ids, const float *old_logp, const float *advantages,
+    const ulorl_params *p,
+    float *loss, float *logp, float *entropy, float *lse, float *gcoef,
+    uint8_t *mpt_mask, float *ratio, int32_t *segment_out,
+    float *resp_entropy, uint8_t *resp_gate, int64_t *counters,
+    void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Backward of the lm_head variant.  With dz[t, v] = grad_out * gcoef[t] * ([v == token_ids[t]]
+ * - exp(z[t, v] - lse[t])) recomputed chunk by chunk (rounded to bf16 as the GEMM operand):
+ *   d_hidden [N, Hd] bf16 = dz . W^T      (fp32 accumulation over the whole vocabulary)
+ *   d_W      [Hd, V] bf16 = hidden^T . dz (fp32 accumulation over all rows, rounded once)
+ * lse and gcoef are those the forward call produced.
+ */
+int32_t ulorl_lmhead_token_loss_bwd(
+    const void *hidden, const void *W, int64_t N, int64_t Hd, int64_t V, int32_t vocab_chunk,
+    const int32_t *token_ids, const float *lse, const float *gcoef, float grad_out,
+    void *d_hidden, void *d_W, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * The tiled bf16 MFMA product the lm_head variant is built from, on its own:
+ * C[m, n] = sum_k A[m, k] * B[n, k], A [M, K] and B [N, K] bf16 row-major with leading
+ * dimensions lda, ldb (multiples of 8, 16-byte aligned bases), C fp32 [M, N] with leading
+ * dimension ldc.  K must be a multiple of 8.
+ */
+int32_t ulorl_gemm_tn_bf16(const void *A, int64_t lda, const void *B, int64_t ldb,
+                           int64_t M, int64_t N, int64_t K, float *C, int64_t ldc, void *hip_stream);
+
 /*
  * Launch-shape knobs of the streaming kernels (process-wide, HOST state; not thread
  * safe against concurrent calls).  Results do not depend on them beyond summation order.

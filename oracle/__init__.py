@@ -162,3 +162,25 @@ def dlogits(logits: np.ndarray, token_ids, lse, gcoef, grad_out=1.0, rows=None, 
         _ptr(lse), _ptr(g), ctypes.c_double(grad_out), _ptr(sel), ctypes.c_int64(nsel),
         _ptr(out))
     return out
+
+
+# ------------------------------------------------------------------------------------ lm_head variant
+# The variant's definition is "the same objective with logits = hidden . W": the oracle forms the
+# logits with a stock fp64 matrix product and feeds them to the functions above; the two weight
+# gradients are the chain rule through that product.
+
+def bf16_to_f64(raw: np.ndarray) -> np.ndarray:
+    """Exact decode of raw bfloat16 (uint16) to float64."""
+    return (raw.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def lmhead_logits(hidden_raw: np.ndarray, weight_raw: np.ndarray) -> np.ndarray:
+    """z = hidden [N, Hd] . W [Hd, V] in fp64 from raw-bf16 operands."""
+    return bf16_to_f64(hidden_raw) @ bf16_to_f64(weight_raw)
+
+
+def lmhead_grads(hidden_raw: np.ndarray, weight_raw: np.ndarray, dz: np.ndarray):
+    """d_hidden = dz . W^T  [N, Hd],  d_W = hidden^T . dz  [Hd, V]   (fp64)."""
+    h = bf16_to_f64(hidden_raw)
+    w = bf16_to_f64(weight_raw)
+    return dz @ w.T, h.T @ dz

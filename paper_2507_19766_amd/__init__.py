@@ -10,4 +10,5 @@ from .binding import (  # noqa: F401
     TUNE_FWD_THREADS, TUNE_FWD_UNROLL, TUNE_BWD_THREADS, TUNE_BWD_UNROLL, TUNE_FUSED_THREADS, TUNE_FUSED_UNROLL,
     UlorlError, Params, FwdResult, lib_path, load_library, version, status_string, tune,
     token_loss_workspace_bytes, token_loss_fwd, token_loss_bwd, token_loss_fwd_bwd, row_stats,
+    lmhead_workspace_bytes, lmhead_token_loss_fwd, lmhead_token_loss_bwd, gemm_tn_bf16,
 )

@@ -102,6 +102,19 @@ def load_library(build_if_missing: bool = True):
         vp, vp, vp,                                          # mpt_mask, ratio, segment_out
         vp, vp, vp,                                          # resp_entropy, resp_gate, counters
         vp, vp, c.c_size_t, vp]                              # dlogits, workspace, bytes, stream
+    lib.ulorl_lmhead_workspace_bytes.restype = c.c_size_t
+    lib.ulorl_lmhead_workspace_bytes.argtypes = [c.c_int64, c.c_int64, c.c_int64, c.c_int32, c.c_int32]
+    lib.ulorl_lmhead_token_loss_fwd.restype = c.c_int32
+    lib.ulorl_lmhead_token_loss_fwd.argtypes = [
+        vp, vp, c.c_int64, c.c_int64, c.c_int64, c.c_int32,  # hidden, W, N, Hd, V, chunk
+        vp, vp, c.c_int32, vp, vp, vp, c.POINTER(_CParams),
+        vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+        vp, c.c_size_t, vp]
+    lib.ulorl_lmhead_token_loss_bwd.restype = c.c_int32
+    lib.ulorl_lmhead_token_loss_bwd.argtypes = [
+        vp, vp, c.c_int64, c.c_int64, c.c_int64, c.c_int32, vp, vp, vp, c.c_float, vp, vp, vp, c.c_size_t, vp]
+    lib.ulorl_gemm_tn_bf16.restype = c.c_int32
+    lib.ulorl_gemm_tn_bf16.argtypes = [vp, c.c_int64, vp, c.c_int64, c.c_int64, c.c_int64, c.c_int64, vp, c.c_int64, vp]
     lib.ulorl_token_loss_bwd.restype = c.c_int32
     lib.ulorl_token_loss_bwd.argtypes = [
         vp, c.c_int32, c.c_int64, c.c_int64, c.c_int64, vp, vp, vp, c.c_float, vp, vp]
@@ -296,3 +309,96 @@ def token_loss_bwd(logits, token_ids, lse, gcoef, grad_out: float = 1.0,
     if rc != 0:
         raise UlorlError(rc, "ulorl_token_loss_bwd")
     return dlogits
+
+
+# ------------------------------------------------------------------------------------ lm_head variant
+
+def lmhead_workspace_bytes(N: int, Hd: int, V: int, R: int, vocab_chunk: int) -> int:
+    return int(load_library().ulorl_lmhead_workspace_bytes(N, Hd, V, R, vocab_chunk))
+
+
+def _check_lmhead(hidden, weight):
+    if not hidden.is_cuda or not weight.is_cuda:
+        raise RuntimeError("libulorl runs on the GPU only")
+    if hidden.dtype != torch.bfloat16 or weight.dtype != torch.bfloat16:
+        raise TypeError("hidden and weight must be bfloat16")
+    if hidden.dim() != 2 or weight.dim() != 2 or not hidden.is_contiguous() or not weight.is_contiguous():
+        raise ValueError("hidden [N, Hd] and weight [Hd, V] must be contiguous")
+    if hidden.shape[1] != weight.shape[0]:
+        raise ValueError("hidden is [N, Hd], weight is [Hd, V]")
+    return hidden.shape[0], hidden.shape[1], weight.shape[1]
+
+
+def lmhead_token_loss_fwd(hidden, weight, token_ids, cu_seqlens, advantages, old_logp=None,
+                          params: Params = None, segment_ids=None, vocab_chunk: int = 8192,
+                          out: Optional[FwdResult] = None, workspace: Optional[torch.Tensor] = None) -> FwdResult:
+    """ulorl_lmhead_token_loss_fwd."""
+    lib = load_library()
+    N, Hd, V = _check_lmhead(hidden, weight)
+    dev = hidden.device
+    f32 = dict(dtype=torch.float32, device=dev)
+    token_ids = _vec(token_ids, torch.int32, N, "token_ids", dev)
+    params = params or Params()
+    cparams = params.to_c()
+    R = cu_seqlens.shape[0] - 1
+    advantages = _vec(advantages, torch.float32, N, "advantages", dev)
+    old_logp = _vec(old_logp, torch.float32, N, "old_logp", dev)
+    segment_ids = _vec(segment_ids, torch.int32, N, "segment_ids", dev)
+    if out is None:
+        out = FwdResult(torch.empty(1, **f32), torch.empty(N, **f32), torch.empty(N, **f32), torch.empty(N, **f32),
+                        torch.empty(N, **f32), torch.empty(N, dtype=torch.uint8, device=dev), torch.empty(N, **f32),
+                        torch.empty(N, dtype=torch.int32, device=dev), torch.empty(max(R, 1), **f32)[:R],
+                        torch.empty(max(R, 1), dtype=torch.uint8, device=dev)[:R],
+                        torch.empty(4, dtype=torch.int64, device=dev))
+    if workspace is None:
+        workspace = torch.empty(max(lmhead_workspace_bytes(N, Hd, V, R, vocab_chunk), 256), dtype=torch.uint8, device=dev)
+    rc = lib.ulorl_lmhead_token_loss_fwd(
+        _p(hidden), _p(weight), N, Hd, V, vocab_chunk, _p(token_ids), _p(cu_seqlens), R, _p(segment_ids),
+        _p(old_logp), _p(advantages), ctypes.byref(cparams),
+        _p(out.loss), _p(out.logp), _p(out.entropy), _p(out.lse), _p(out.gcoef), _p(out.mpt_mask), _p(out.ratio),
+        _p(out.segment_out), _p(out.resp_entropy), _p(out.resp_gate), _p(out.counters),
+        _p(workspace), workspace.numel(), _stream(dev))
+    if rc != 0:
+        raise UlorlError(rc, "ulorl_lmhead_token_loss_fwd")
+    return out
+
+
+def lmhead_token_loss_bwd(hidden, weight, token_ids, lse, gcoef, grad_out: float = 1.0, vocab_chunk: int = 8192,
+                          d_hidden: Optional[torch.Tensor] = None, d_weight: Optional[torch.Tensor] = None,
+                          workspace: Optional[torch.Tensor] = None):
+    """ulorl_lmhead_token_loss_bwd -> (d_hidden [N, Hd] bf16, d_weight [Hd, V] bf16)."""
+    lib = load_library()
+    N, Hd, V = _check_lmhead(hidden, weight)
+    dev = hidden.device
+    token_ids = _vec(token_ids, torch.int32, N, "token_ids", dev)
+    lse = _vec(lse, torch.float32, N, "lse", dev)
+    gcoef = _vec(gcoef, torch.float32, N, "gcoef", dev)
+    if d_hidden is None:
+        d_hidden = torch.empty_like(hidden)
+    if d_weight is None:
+        d_weight = torch.empty_like(weight)
+    if workspace is None:
+        workspace = torch.empty(max(lmhead_workspace_bytes(N, Hd, V, 1, vocab_chunk), 256), dtype=torch.uint8, device=dev)
+    rc = lib.ulorl_lmhead_token_loss_bwd(
+        _p(hidden), _p(weight), N, Hd, V, vocab_chunk, _p(token_ids), _p(lse), _p(gcoef), float(grad_out),
+        _p(d_hidden), _p(d_weight), _p(workspace), workspace.numel(), _stream(dev))
+    if rc != 0:
+        raise UlorlError(rc, "ulorl_lmhead_token_loss_bwd")
+    return d_hidden, d_weight
+
+
+def gemm_tn_bf16(a: torch.Tensor, b: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """ulorl_gemm_tn_bf16: a [M, K] . b [N, K]^T -> fp32 [M, N]."""
+    lib = load_library()
+    if not (a.is_cuda and b.is_cuda) or a.dtype != torch.bfloat16 or b.dtype != torch.bfloat16:
+        raise TypeError("a and b must be bfloat16 device tensors")
+    if a.dim() != 2 or b.dim() != 2 or a.stride(1) != 1 or b.stride(1) != 1 or a.shape[1] != b.shape[1]:
+        raise ValueError("a is [M, K], b is [N, K], unit stride along K")
+    M, K = a.shape
+    N = b.shape[0]
+    if out is None:
+        out = torch.empty(M, N, dtype=torch.float32, device=a.device)
+    rc = lib.ulorl_gemm_tn_bf16(_p(a), a.stride(0), _p(b), b.stride(0), M, N, K, _p(out), out.stride(0), _stream(a.device))
+    if rc != 0:
+        raise UlorlError(rc, "ulorl_gemm_tn_bf16")
+    return out

@@ -1,0 +1,620 @@
+// lm_head variant of the UloRL token loss for gfx950: logits = hidden . W are produced tile by
+// tile on the matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulate) and consumed in registers;
+// the [N, V] logits tensor never exists in memory.
+//
+// One tiled bf16 GEMM main loop, C[m, n] = sum_k A[m, k] * B[n, k] with BOTH operands contiguous
+// along the contraction index, serves every product of the path:
+//   forward   z^T[v, t] = Wt[v, :] . hidden[t, :]      epilogue: online softmax statistics per token
+//   backward  z^T again                                 epilogue: dz = g (onehot - softmax), stored
+//                                                        per vocabulary chunk as dZc[t, v] and dZc^T[v, t]
+//             dHidden[t, k] += dZc[t, :] . W[k, chunk]   (fp32 accumulation across chunks)
+//             dW[k, chunk]   = Ht[k, :] . dZc^T[v, :]    (each element written once)
+// Wt = W^T and Ht = hidden^T are made once per call by a tiled transpose, so that no operand
+// needs a transposing load.  In the z^T orientation a lane of the 32x32 MFMA result holds one
+// token column and 16 vocabulary rows, which makes the softmax reductions lane-local.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ulorl.h"
+#include "ulorl_internal.hpp"
+
+using namespace ulorl_detail;
+
+#pragma clang fp contract(off)
+
+namespace {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kEmpty = -1.0e30f;
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint16_t bf16_t;  // raw storage
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    f32x2 x = {lo, hi};
+    bf16x2 b = __builtin_convertvector(x, bf16x2);  // round to nearest even
+    return __builtin_bit_cast(uint32_t, b);
+}
+__device__ __forceinline__ bf16_t to_bf16(float x) { return (bf16_t)(pack_bf16x2(x, 0.0f) & 0xffffu); }
+
+// ---------------------------------------------------------------------------------------------
+// tiled GEMM main loop
+// ---------------------------------------------------------------------------------------------
+template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_>
+struct GemmCfg {
+    static constexpr int BM = BM_, BN = BN_, BK = BK_;
+    static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
+    static constexpr int NT = 64 * WAVES_M * WAVES_N;
+    static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+    static constexpr int MB = WM / 32, NB = WN / 32;      // 32x32 result blocks per wave
+    static constexpr int LDS_STRIDE = BK + 8;              // bf16 elements; the pad spreads rows over banks
+    static constexpr int A_STAGE = BM * LDS_STRIDE;
+    static constexpr int B_STAGE = BN * LDS_STRIDE;
+    static constexpr int VEC_PER_ROW = BK / 8;
+    static constexpr int A_VECS = BM * VEC_PER_ROW / NT;   // 16-byte vectors each thread moves per stage
+    static constexpr int B_VECS = BN * VEC_PER_ROW / NT;
+    static constexpr size_t LDS_BYTES = 2 * (size_t)(A_STAGE + B_STAGE) * sizeof(bf16_t);
+    static_assert(WM % 32 == 0 && WN % 32 == 0 && BK % 16 == 0, "tile shape");
+    static_assert((BM * VEC_PER_ROW) % NT == 0 && (BN * VEC_PER_ROW) % NT == 0, "load split");
+};
+
+// acc[bi][bj][r] holds C[m, n] with
+//   m = m0 + wave_m*WM + bi*32 + 8*(r/4) + 4*(lane/32) + (r%4),   n = n0 + wave_n*WN + bj*32 + lane%32.
+// Rows beyond M / N are computed from clamped addresses and must be ignored by the caller;
+// contraction indices beyond K contribute zero.  K and the leading dimensions are multiples of 8.
+template <class Cfg>
+__device__ __forceinline__ void gemm_tn_mainloop(const bf16_t* __restrict__ A, int64_t lda, int M, int m0,
+                                                 const bf16_t* __restrict__ B, int64_t ldb, int N, int n0, int K,
+                                                 f32x16 (&acc)[Cfg::MB][Cfg::NB], bf16_t* lds)
+{
+    constexpr int NT = Cfg::NT;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wave_m = wave / Cfg::WAVES_N;
+    const int wave_n = wave % Cfg::WAVES_N;
+    bf16_t* sA = lds;
+    bf16_t* sB = lds + 2 * Cfg::A_STAGE;
+
+#pragma unroll
+    for (int bi = 0; bi < Cfg::MB; ++bi)
+#pragma unroll
+        for (int bj = 0; bj < Cfg::NB; ++bj)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[bi][bj][r] = 0.0f;
+
+    // per-thread global sources of this tile (rows clamped into range)
+    const bf16_t* ga[Cfg::A_VECS];
+    const bf16_t* gb[Cfg::B_VECS];
+    int ka[Cfg::A_VECS], kb[Cfg::B_VECS];
+    int la[Cfg::A_VECS], lb[Cfg::B_VECS];
+#pragma unroll
+    for (int i = 0; i < Cfg::A_VECS; ++i) {
+        const int idx = tid + i * NT;
+        const int row = idx / Cfg::VEC_PER_ROW, kv = idx % Cfg::VEC_PER_ROW;
+        int gr = m0 + row;
+        gr = gr < M ? gr : M - 1;
+        ga[i] = A + (int64_t)gr * lda + kv * 8;
+        ka[i] = kv * 8;
+        la[i] = row * Cfg::LDS_STRIDE + kv * 8;
+    }
+#pragma unroll
+    for (int i = 0; i < Cfg::B_VECS; ++i) {
+        const int idx = tid + i * NT;
+        const int row = idx / Cfg::VEC_PER_ROW, kv = idx % Cfg::VEC_PER_ROW;
+        int gr = n0 + row;
+        gr = gr < N ? gr : N - 1;
+        gb[i] = B + (int64_t)gr * ldb + kv * 8;
+        kb[i] = kv * 8;
+        lb[i] = row * Cfg::LDS_STRIDE + kv * 8;
+    }
+
+    u32x4 ra[Cfg::A_VECS], rb[Cfg::B_VECS];
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < Cfg::A_VECS; ++i)
+            ra[i] = (k0 + ka[i] < K) ? *reinterpret_cast<const u32x4*>(ga[i] + k0) : zero;
+#pragma unroll
+        for (int i = 0; i < Cfg::B_VECS; ++i)
+            rb[i] = (k0 + kb[i] < K) ? *reinterpret_cast<const u32x4*>(gb[i] + k0) : zero;
+    };
+    auto stash = [&](int stage) {
+#pragma unroll
+        for (int i = 0; i < Cfg::A_VECS; ++i)
+            *reinterpret_cast<u32x4*>(sA + stage * Cfg::A_STAGE + la[i]) = ra[i];
+#pragma unroll
+        for (int i = 0; i < Cfg::B_VECS; ++i)
+            *reinterpret_cast<u32x4*>(sB + stage * Cfg::B_STAGE + lb[i]) = rb[i];
+    };
+
+    const int frag_row = lane & 31;
+    const int frag_k = 8 * (lane >> 5);
+    const int a_base = (wave_m * Cfg::WM + frag_row) * Cfg::LDS_STRIDE + frag_k;
+    const int b_base = (wave_n * Cfg::WN + frag_row) * Cfg::LDS_STRIDE + frag_k;
+
+    const int KT = (K + Cfg::BK - 1) / Cfg::BK;
+    fetch(0);
+    stash(0);
+    __syncthreads();
+    for (int kt = 0; kt < KT; ++kt) {
+        const int cur = kt & 1;
+        if (kt + 1 < KT) fetch((kt + 1) * Cfg::BK);
+        const bf16_t* cA = sA + cur * Cfg::A_STAGE + a_base;
+        const bf16_t* cB = sB + cur * Cfg::B_STAGE + b_base;
+#pragma unroll
+        for (int kk = 0; kk < Cfg::BK / 16; ++kk) {
+            bf16x8 fa[Cfg::MB], fb[Cfg::NB];
+#pragma unroll
+            for (int bi = 0; bi < Cfg::MB; ++bi)
+                fa[bi] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(cA + bi * 32 * Cfg::LDS_STRIDE + kk * 16));
+#pragma unroll
+            for (int bj = 0; bj < Cfg::NB; ++bj)
+                fb[bj] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(cB + bj * 32 * Cfg::LDS_STRIDE + kk * 16));
+#pragma unroll
+            for (int bi = 0; bi < Cfg::MB; ++bi)
+#pragma unroll
+                for (int bj = 0; bj < Cfg::NB; ++bj)
+                    acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[bi], fb[bj], acc[bi][bj], 0, 0, 0);
+        }
+        if (kt + 1 < KT) stash(cur ^ 1);
+        __syncthreads();
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// plain GEMM kernels: C = A . B^T with three ways of storing C
+// ---------------------------------------------------------------------------------------------
+enum { STORE_F32 = 0, STORE_F32_ACCUM = 1, STORE_BF16 = 2 };
+
+template <class Cfg, int STORE>
+__global__ __launch_bounds__(Cfg::NT) void gemm_tn_kernel(const bf16_t* __restrict__ A, int64_t lda, int M,
+                                                          const bf16_t* __restrict__ B, int64_t ldb, int N, int K,
+                                                          void* __restrict__ C, int64_t ldc)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    bf16_t* lds = reinterpret_cast<bf16_t*>(lds_raw);
+    const int m0 = blockIdx.x * Cfg::BM, n0 = blockIdx.y * Cfg::BN;
+    f32x16 acc[Cfg::MB][Cfg::NB];
+    gemm_tn_mainloop<Cfg>(A, lda, M, m0, B, ldb, N, n0, K, acc, lds);
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
+#pragma unroll
+    for (int bi = 0; bi < Cfg::MB; ++bi)
+#pragma unroll
+        for (int bj = 0; bj < Cfg::NB; ++bj) {
+            const int n = n0 + wn * Cfg::WN + bj * 32 + (lane & 31);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = m0 + wm * Cfg::WM + bi * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                if (m < M && n < N) {
+                    const int64_t off = (int64_t)m * ldc + n;
+                    if (STORE == STORE_F32) ((float*)C)[off] = acc[bi][bj][r];
+                    if (STORE == STORE_F32_ACCUM) ((float*)C)[off] += acc[bi][bj][r];
+                    if (STORE == STORE_BF16) ((bf16_t*)C)[off] = to_bf16(acc[bi][bj][r]);
+                }
+            }
+        }
+}
+
+// dst[c, r] = src[r, c] (bf16), 64x64 tiles through LDS; columns of dst beyond `rows` up to
+// dst_cols are written as zero (padding of the contraction dimension).
+__global__ __launch_bounds__(256) void transpose_bf16_kernel(const bf16_t* __restrict__ src, int64_t lds_, int rows,
+                                                            int cols, bf16_t* __restrict__ dst, int64_t ldd,
+                                                            int dst_cols)
+{
+    __shared__ bf16_t tile[64][66];
+    const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int i = ty; i < 64; i += 4) {
+        const int r = r0 + i, c = c0 + tx;
+        tile[i][tx] = (r < rows && c < cols) ? src[(int64_t)r * lds_ + c] : (bf16_t)0;
+    }
+    __syncthreads();
+    for (int i = ty; i < 64; i += 4) {
+        const int c = c0 + i, r = r0 + tx;
+        if (c < cols && r < dst_cols) dst[(int64_t)c * ldd + r] = tile[tx][i];
+    }
+}
+
+__global__ void f32_to_bf16_kernel(const float* __restrict__ src, bf16_t* __restrict__ dst, int64_t n)
+{
+    int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 2;
+    if (i + 1 < n) {
+        *reinterpret_cast<uint32_t*>(dst + i) = pack_bf16x2(src[i], src[i + 1]);
+    } else if (i < n) {
+        dst[i] = to_bf16(src[i]);
+    }
+}
+
+__global__ void fill_zero_f32_kernel(float* p, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0.0f;
+}
+
+// ---------------------------------------------------------------------------------------------
+// forward: softmax statistics from z^T tiles
+// ---------------------------------------------------------------------------------------------
+// (m, S, T) with T = sum e^(z-m) (z-m) in natural units; exact when the maxima coincide.
+__device__ __forceinline__ void merge_nat(float& m, float& S, float& T, float m2, float S2, float T2)
+{
+    const float M = fmaxf(m, m2);
+    const float d1 = m - M, d2 = m2 - M;
+    const float s1 = fast_exp2(d1 * kLog2e), s2 = fast_exp2(d2 * kLog2e);
+    T = s1 * fmaf(d1, S, T) + s2 * fmaf(d2, S2, T2);
+    S = s1 * S + s2 * S2;
+    m = M;
+}
+
+// Partial statistics of token t over one slice of the vocabulary: (max, sum, weighted sum,
+// chosen logit or kEmpty).
+struct StatQuad {
+    float m, S, T, zy;
+};
+
+template <class Cfg>
+__global__ __launch_bounds__(Cfg::NT) void lmhead_stats_kernel(const bf16_t* __restrict__ Wt, const bf16_t* __restrict__ H,
+                                                               int Hd, int V, int Ntok,
+                                                               const int32_t* __restrict__ token_ids, int v_per_split,
+                                                               StatQuad* __restrict__ partial)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    bf16_t* lds = reinterpret_cast<bf16_t*>(lds_raw);
+    const int t0 = blockIdx.x * Cfg::BN;
+    const int split = blockIdx.y;
+    const int vb = split * v_per_split;
+    const int ve = min(V, vb + v_per_split);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
+
+    float m[Cfg::NB], S[Cfg::NB], Sc[Cfg::NB], T[Cfg::NB], zy[Cfg::NB];
+    int32_t y[Cfg::NB];
+#pragma unroll
+    for (int bj = 0; bj < Cfg::NB; ++bj) {
+        m[bj] = kEmpty; S[bj] = 0.0f; Sc[bj] = 0.0f; T[bj] = 0.0f; zy[bj] = kEmpty;
+        const int t = t0 + wn * Cfg::WN + bj * 32 + (lane & 31);
+        y[bj] = t < Ntok ? token_ids[t] : -1;
+    }
+
+    for (int v0 = vb; v0 < ve; v0 += Cfg::BM) {
+        f32x16 acc[Cfg::MB][Cfg::NB];
+        gemm_tn_mainloop<Cfg>(Wt, Hd, V, v0, H, Hd, Ntok, t0, Hd, acc, lds);
+        const int vrow0 = v0 + wm * Cfg::WM + 4 * (lane >> 5);
+#pragma unroll
+        for (int bj = 0; bj < Cfg::NB; ++bj) {
+            float cm = kEmpty;
+#pragma unroll
+            for (int bi = 0; bi < Cfg::MB; ++bi)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int v = vrow0 + bi * 32 + 8 * (r >> 2) + (r & 3);
+                    if (v < ve) cm = fmaxf(cm, acc[bi][bj][r]);
+                }
+            const float mn = fmaxf(m[bj], cm);
+            const float d = m[bj] - mn;                   // <= 0
+            const float sc = fast_exp2(d * kLog2e);
+            float Tn = sc * fmaf(d, S[bj], T[bj]);
+            const float Sn = sc * S[bj];
+            const float Scn = sc * Sc[bj];
+            float part = 0.0f;                            // this tile's terms first, then one TwoSum
+#pragma unroll
+            for (int bi = 0; bi < Cfg::MB; ++bi)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int v = vrow0 + bi * 32 + 8 * (r >> 2) + (r & 3);
+                    const float z = acc[bi][bj][r];
+                    const float x = z - mn;
+                    const float e = v < ve ? fast_exp2(x * kLog2e) : 0.0f;
+                    part += e;
+                    Tn = fmaf(e, v < ve ? x : 0.0f, Tn);
+                    if (v == y[bj]) zy[bj] = z;
+                }
+            const float tsum = Sn + part;
+            const float bv = tsum - Sn;
+            const float err = (Sn - (tsum - bv)) + (part - bv);
+            S[bj] = tsum; Sc[bj] = Scn + err; T[bj] = Tn; m[bj] = mn;
+        }
+    }
+
+    // two lanes (lane, lane^32) share a token column; then the waves stacked along the vocabulary
+    __shared__ float red[Cfg::WAVES_M][Cfg::BN][4];
+#pragma unroll
+    for (int bj = 0; bj < Cfg::NB; ++bj) {
+        float mm = m[bj], SS = S[bj] + Sc[bj], TT = T[bj], zz = zy[bj];
+        const float m2 = __shfl_xor(mm, 32), S2 = __shfl_xor(SS, 32), T2 = __shfl_xor(TT, 32), z2 = __shfl_xor(zz, 32);
+        merge_nat(mm, SS, TT, m2, S2, T2);
+        zz = fmaxf(zz, z2);
+        if (lane < 32) {
+            float* q = red[wm][wn * Cfg::WN + bj * 32 + lane];
+            q[0] = mm; q[1] = SS; q[2] = TT; q[3] = zz;
+        }
+    }
+    __syncthreads();
+    for (int c = threadIdx.x; c < Cfg::BN; c += Cfg::NT) {
+        float mm = red[0][c][0], SS = red[0][c][1], TT = red[0][c][2], zz = red[0][c][3];
+#pragma unroll
+        for (int w = 1; w < Cfg::WAVES_M; ++w) {
+            merge_nat(mm, SS, TT, red[w][c][0], red[w][c][1], red[w][c][2]);
+            zz = fmaxf(zz, red[w][c][3]);
+        }
+        const int t = t0 + c;
+        if (t < Ntok) partial[(int64_t)split * Ntok + t] = StatQuad{mm, SS, TT, zz};
+    }
+}
+
+__global__ void lmhead_stats_merge_kernel(const StatQuad* __restrict__ partial, int splits, int Ntok, int V,
+                                          const int32_t* __restrict__ token_ids, float* __restrict__ lse,
+                                          float* __restrict__ logp, float* __restrict__ entropy)
+{
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= Ntok) return;
+    StatQuad q = partial[t];
+    for (int s = 1; s < splits; ++s) {
+        const StatQuad p = partial[(int64_t)s * Ntok + t];
+        merge_nat(q.m, q.S, q.T, p.m, p.S, p.T);
+        q.zy = fmaxf(q.zy, p.zy);
+    }
+    const float lnS = logf(q.S);
+    const int32_t y = token_ids[t];
+    lse[t] = q.m + lnS;
+    logp[t] = (y >= 0 && y < V) ? (q.zy - q.m) - lnS : __builtin_nanf("");
+    entropy[t] = lnS - q.T / q.S;
+}
+
+// ---------------------------------------------------------------------------------------------
+// backward: dz tiles of one vocabulary chunk, stored in both orientations
+// ---------------------------------------------------------------------------------------------
+template <class Cfg>
+__global__ __launch_bounds__(Cfg::NT) void lmhead_dz_kernel(const bf16_t* __restrict__ Wt, const bf16_t* __restrict__ H,
+                                                            int Hd, int V, int Ntok, int vc0, int cw,
+                                                            const int32_t* __restrict__ token_ids,
+                                                            const float* __restrict__ lse,
+                                                            const float* __restrict__ gcoef, float grad_out,
+                                                            bf16_t* __restrict__ dZc, int64_t ld_c,
+                                                            bf16_t* __restrict__ dZcT, int64_t ld_t)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    bf16_t* lds = reinterpret_cast<bf16_t*>(lds_raw);
+    const int v0 = vc0 + blockIdx.x * Cfg::BM;
+    const int t0 = blockIdx.y * Cfg::BN;
+    const int vend = min(V, vc0 + cw);
+    f32x16 acc[Cfg::MB][Cfg::NB];
+    gemm_tn_mainloop<Cfg>(Wt, Hd, V, v0, H, Hd, Ntok, t0, Hd, acc, lds);
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
+#pragma unroll
+    for (int bj = 0; bj < Cfg::NB; ++bj) {
+        const int t = t0 + wn * Cfg::WN + bj * 32 + (lane & 31);
+        float g = 0.0f, c = 0.0f, sgn = 0.0f;
+        int32_t y = -1;
+        if (t < Ntok) {
+            g = gcoef[t] * grad_out;
+            const float l = lse[t];
+            y = token_ids[t];
+            const bool live = (g != 0.0f) && (fabsf(g) <= 3.0e38f) && (fabsf(l) <= 3.0e38f) && y >= 0 && y < V;
+            if (live) {
+                c = fmaf(-l, kLog2e, log2f(fabsf(g)));
+                sgn = g > 0.0f ? -1.0f : 1.0f;
+            } else {
+                g = 0.0f;
+            }
+        }
+#pragma unroll
+        for (int bi = 0; bi < Cfg::MB; ++bi)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int v = v0 + wm * Cfg::WM + bi * 32 + 8 * q + 4 * (lane >> 5);
+                float dz[4];
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    float x = sgn * fast_exp2(fmaf(acc[bi][bj][4 * q + s], kLog2e, c));
+                    if (v + s == y) x += g;
+                    dz[s] = (sgn != 0.0f && v + s < vend) ? x : 0.0f;
+                }
+                if (t < Ntok && v < vc0 + cw) {
+                    u32x2 pk = {pack_bf16x2(dz[0], dz[1]), pack_bf16x2(dz[2], dz[3])};
+                    *reinterpret_cast<u32x2*>(dZc + (int64_t)t * ld_c + (v - vc0)) = pk;
+                }
+                if (t < ld_t) {
+#pragma unroll
+                    for (int s = 0; s < 4; ++s)
+                        if (v + s < vc0 + cw) dZcT[(int64_t)(v + s - vc0) * ld_t + t] = t < Ntok ? to_bf16(dz[s]) : (bf16_t)0;
+                }
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------------
+using CfgMain = GemmCfg<128, 128, 64, 2, 2>;
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline int64_t round_up64(int64_t x) { return (x + 63) / 64 * 64; }
+
+struct LmheadLayout {
+    size_t wt, ht, dzc, dzct, dhacc, partial, token_ws, total;
+    int64_t ldt;      // padded token count (leading dimension of Ht and dZc^T)
+    int64_t ldc;      // padded chunk width (leading dimension of dZc)
+    int splits;
+    int v_per_split;
+};
+
+LmheadLayout lmhead_layout(int64_t N, int64_t Hd, int64_t V, int32_t R, int32_t chunk)
+{
+    LmheadLayout L;
+    L.ldt = round_up64(N);
+    L.ldc = round_up64(chunk);
+    const int64_t ttiles = (N + CfgMain::BN - 1) / CfgMain::BN;
+    int splits = (int)((1024 + ttiles - 1) / ttiles);       // aim at >= 1024 workgroups
+    const int64_t vtiles = (V + CfgMain::BM - 1) / CfgMain::BM;
+    if (splits > vtiles) splits = (int)vtiles;
+    if (splits < 1) splits = 1;
+    const int64_t tiles_per_split = (vtiles + splits - 1) / splits;
+    L.v_per_split = (int)(tiles_per_split * CfgMain::BM);
+    L.splits = (int)((vtiles + tiles_per_split - 1) / tiles_per_split);
+    size_t off = 0;
+    L.wt = off;      off = align_up(off + (size_t)V * Hd * 2, 256);
+    L.ht = off;      off = align_up(off + (size_t)Hd * L.ldt * 2, 256);
+    L.dzc = off;     off = align_up(off + (size_t)N * L.ldc * 2, 256);
+    L.dzct = off;    off = align_up(off + (size_t)L.ldc * L.ldt * 2, 256);
+    L.dhacc = off;   off = align_up(off + (size_t)N * Hd * 4, 256);
+    L.partial = off; off = align_up(off + (size_t)L.splits * N * sizeof(StatQuad), 256);
+    L.token_ws = off; off = align_up(off + workspace_layout(N, R).total, 256);
+    L.total = off;
+    return L;
+}
+
+int32_t check_lmhead(const void* hidden, const void* W, int64_t N, int64_t Hd, int64_t V, int32_t chunk)
+{
+    if (!hidden || !W) return ULORL_ERR_NULL;
+    if (N <= 0 || N > 0x7fffffffLL || V <= 0 || V > 0x7fffffffLL || Hd <= 0 || Hd > (1 << 20)) return ULORL_ERR_SHAPE;
+    if (Hd % 8 != 0 || V % 8 != 0) return ULORL_ERR_SHAPE;     // 16-byte rows of hidden, W and their transposes
+    if (chunk <= 0 || chunk % 64 != 0) return ULORL_ERR_SHAPE;
+    if (((uintptr_t)hidden & 15u) != 0 || ((uintptr_t)W & 15u) != 0) return ULORL_ERR_ALIGN;
+    return ULORL_OK;
+}
+
+template <class Kernel>
+bool allow_lds(Kernel k, size_t bytes)
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) == hipSuccess;
+}
+
+void launch_transpose(const bf16_t* src, int64_t ld_src, int rows, int cols, bf16_t* dst, int64_t ld_dst, int dst_cols,
+                      hipStream_t st)
+{
+    dim3 grid((unsigned)((dst_cols + 63) / 64), (unsigned)((cols + 63) / 64));
+    hipLaunchKernelGGL(transpose_bf16_kernel, grid, dim3(256), 0, st, src, ld_src, rows, cols, dst, ld_dst, dst_cols);
+}
+
+template <int STORE>
+bool launch_gemm(const bf16_t* A, int64_t lda, int M, const bf16_t* B, int64_t ldb, int N, int K, void* C, int64_t ldc,
+                 hipStream_t st)
+{
+    auto kern = gemm_tn_kernel<CfgMain, STORE>;
+    if (!allow_lds(kern, CfgMain::LDS_BYTES)) return false;
+    dim3 grid((unsigned)((M + CfgMain::BM - 1) / CfgMain::BM), (unsigned)((N + CfgMain::BN - 1) / CfgMain::BN));
+    hipLaunchKernelGGL(kern, grid, dim3(CfgMain::NT), CfgMain::LDS_BYTES, st, A, lda, M, B, ldb, N, K, C, ldc);
+    return true;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t ulorl_gemm_tn_bf16(const void* A, int64_t lda, const void* B, int64_t ldb, int64_t M, int64_t N, int64_t K,
+                           float* C, int64_t ldc, void* hip_stream)
+{
+    if (!A || !B || !C) return ULORL_ERR_NULL;
+    if (M <= 0 || N <= 0 || K <= 0 || M > 0x7fffffffLL || N > 0x7fffffffLL || K > 0x7fffffffLL) return ULORL_ERR_SHAPE;
+    if (K % 8 != 0 || lda % 8 != 0 || ldb % 8 != 0 || lda < K || ldb < K || ldc < N) return ULORL_ERR_SHAPE;
+    if (((uintptr_t)A & 15u) != 0 || ((uintptr_t)B & 15u) != 0) return ULORL_ERR_ALIGN;
+    if (!launch_gemm<STORE_F32>((const bf16_t*)A, lda, (int)M, (const bf16_t*)B, ldb, (int)N, (int)K, C, ldc,
+                                (hipStream_t)hip_stream))
+        return ULORL_ERR_HIP;
+    return hipGetLastError() == hipSuccess ? ULORL_OK : ULORL_ERR_HIP;
+}
+
+size_t ulorl_lmhead_workspace_bytes(int64_t N, int64_t Hd, int64_t V, int32_t R, int32_t vocab_chunk)
+{
+    if (N <= 0 || N > 0x7fffffffLL || Hd <= 0 || V <= 0 || R <= 0 || vocab_chunk <= 0 || vocab_chunk % 64 != 0) return 0;
+    return lmhead_layout(N, Hd, V, R, vocab_chunk).total;
+}
+
+int32_t ulorl_lmhead_token_loss_fwd(const void* hidden, const void* W, int64_t N, int64_t Hd, int64_t V,
+                                    int32_t vocab_chunk, const int32_t* token_ids, const int32_t* cu_seqlens,
+                                    int32_t R, const int32_t* segment_ids, const float* old_logp,
+                                    const float* advantages, const ulorl_params* p, float* loss, float* logp,
+                                    float* entropy, float* lse, float* gcoef, uint8_t* mpt_mask, float* ratio,
+                                    int32_t* segment_out, float* resp_entropy, uint8_t* resp_gate, int64_t* counters,
+                                    void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    int32_t rc = check_lmhead(hidden, W, N, Hd, V, vocab_chunk);
+    if (rc != ULORL_OK) return rc;
+    if (!token_ids || !logp || !entropy || !lse || !advantages) return ULORL_ERR_NULL;
+    rc = check_objective_args(cu_seqlens, R, old_logp, p, loss, gcoef);
+    if (rc != ULORL_OK) return rc;
+    const LmheadLayout L = lmhead_layout(N, Hd, V, R, vocab_chunk);
+    if (!workspace || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < L.total) return ULORL_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)hip_stream;
+    char* ws = (char*)workspace;
+    bf16_t* Wt = (bf16_t*)(ws + L.wt);
+    StatQuad* partial = (StatQuad*)(ws + L.partial);
+
+    launch_transpose((const bf16_t*)W, V, (int)Hd, (int)V, Wt, Hd, (int)Hd, st);      // Wt[v, k] = W[k, v]
+    auto kern = lmhead_stats_kernel<CfgMain>;
+    if (!allow_lds(kern, CfgMain::LDS_BYTES)) return ULORL_ERR_HIP;
+    dim3 grid((unsigned)((N + CfgMain::BN - 1) / CfgMain::BN), (unsigned)L.splits);
+    hipLaunchKernelGGL(kern, grid, dim3(CfgMain::NT), CfgMain::LDS_BYTES, st, Wt, (const bf16_t*)hidden, (int)Hd, (int)V,
+                       (int)N, token_ids, L.v_per_split, partial);
+    hipLaunchKernelGGL(lmhead_stats_merge_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, st, partial, L.splits,
+                       (int)N, (int)V, token_ids, lse, logp, entropy);
+    if (hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;
+
+    const WorkspaceLayout wl = workspace_layout(N, R);
+    const TokenArgs a = make_token_args(N, V, token_ids, cu_seqlens, R, segment_ids, old_logp, advantages, p, logp,
+                                        entropy, lse, gcoef, mpt_mask, ratio, segment_out, resp_entropy, resp_gate,
+                                        ws + L.token_ws, wl);
+    launch_token_epilogue(a, wl, loss, counters, st);
+    return hipGetLastError() == hipSuccess ? ULORL_OK : ULORL_ERR_HIP;
+}
+
+int32_t ulorl_lmhead_token_loss_bwd(const void* hidden, const void* W, int64_t N, int64_t Hd, int64_t V,
+                                    int32_t vocab_chunk, const int32_t* token_ids, const float* lse,
+                                    const float* gcoef, float grad_out, void* d_hidden, void* d_W, void* workspace,
+                                    size_t workspace_bytes, void* hip_stream)
+{
+    int32_t rc = check_lmhead(hidden, W, N, Hd, V, vocab_chunk);
+    if (rc != ULORL_OK) return rc;
+    if (!token_ids || !lse || !gcoef || !d_hidden || !d_W) return ULORL_ERR_NULL;
+    if (((uintptr_t)d_hidden & 15u) != 0 || ((uintptr_t)d_W & 15u) != 0) return ULORL_ERR_ALIGN;
+    const LmheadLayout L = lmhead_layout(N, Hd, V, 1, vocab_chunk);
+    if (!workspace || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < L.total) return ULORL_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)hip_stream;
+    char* ws = (char*)workspace;
+    bf16_t* Wt = (bf16_t*)(ws + L.wt);
+    bf16_t* Ht = (bf16_t*)(ws + L.ht);
+    bf16_t* dZc = (bf16_t*)(ws + L.dzc);
+    bf16_t* dZcT = (bf16_t*)(ws + L.dzct);
+    float* dHacc = (float*)(ws + L.dhacc);
+    const bf16_t* H = (const bf16_t*)hidden;
+    const bf16_t* Wp = (const bf16_t*)W;
+
+    launch_transpose(Wp, V, (int)Hd, (int)V, Wt, Hd, (int)Hd, st);                    // Wt[v, k]
+    launch_transpose(H, Hd, (int)N, (int)Hd, Ht, L.ldt, (int)L.ldt, st);              // Ht[k, t], zero padded
+    const int64_t nh = N * Hd;
+    hipLaunchKernelGGL(fill_zero_f32_kernel, dim3((unsigned)((nh + 255) / 256)), dim3(256), 0, st, dHacc, nh);
+
+    auto dzk = lmhead_dz_kernel<CfgMain>;
+    if (!allow_lds(dzk, CfgMain::LDS_BYTES)) return ULORL_ERR_HIP;
+    for (int64_t vc0 = 0; vc0 < V; vc0 += vocab_chunk) {
+        const int cw = (int)((V - vc0 < vocab_chunk) ? (V - vc0) : vocab_chunk);
+        const int cw_pad = (int)round_up64(cw);         // dz of the padding columns is written as zero
+        dim3 grid((unsigned)((cw_pad + CfgMain::BM - 1) / CfgMain::BM), (unsigned)((L.ldt + CfgMain::BN - 1) / CfgMain::BN));
+        hipLaunchKernelGGL(dzk, grid, dim3(CfgMain::NT), CfgMain::LDS_BYTES, st, Wt, H, (int)Hd, (int)V, (int)N, (int)vc0,
+                           cw_pad, token_ids, lse, gcoef, grad_out, dZc, L.ldc, dZcT, L.ldt);
+        // dHidden[t, k] += sum_v dZc[t, v] W[k, vc0 + v]
+        if (!launch_gemm<STORE_F32_ACCUM>(dZc, L.ldc, (int)N, Wp + vc0, V, (int)Hd, cw, dHacc, Hd, st)) return ULORL_ERR_HIP;
+        // dW[k, vc0 + v] = sum_t Ht[k, t] dZc^T[v, t]
+        if (!launch_gemm<STORE_BF16>(Ht, L.ldt, (int)Hd, dZcT, L.ldt, cw, (int)L.ldt, (bf16_t*)d_W + vc0, V, st))
+            return ULORL_ERR_HIP;
+        if (hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;
+    }
+    hipLaunchKernelGGL(f32_to_bf16_kernel, dim3((unsigned)((nh / 2 + 256) / 256)), dim3(256), 0, st, dHacc,
+                       (bf16_t*)d_hidden, nh);
+    return hipGetLastError() == hipSuccess ? ULORL_OK : ULORL_ERR_HIP;
+}
+
+}  // extern "C"

@@ -20,6 +20,9 @@
 #include <stdint.h>
 
 #include "ulorl.h"
+#include "ulorl_internal.hpp"
+
+using namespace ulorl_detail;
 
 // Every fused multiply-add in this file is written out as fmaf(): the error-free transforms
 // below (rescale by exactly 1 when the max is unchanged, TwoSum) are wrong if the compiler
@@ -350,32 +353,6 @@ __global__ __launch_bounds__(NT) void dlogits_kernel(const typename Tr::elem* lo
 // ---------------------------------------------------------------------------------------------
 // O(N) epilogue of the forward call
 // ---------------------------------------------------------------------------------------------
-constexpr int kTokBlock = 1024;
-
-struct TokenArgs {
-    const float* logp;
-    const float* entropy;
-    const float* lse;
-    const int32_t* token_ids;
-    const int32_t* cu;
-    const int32_t* segment_ids;
-    const float* old_logp;
-    const float* adv;
-    float* gcoef;
-    uint8_t* mask;
-    float* ratio;
-    int32_t* seg_out;
-    float* resp_entropy;
-    uint8_t* resp_gate;
-    double* hsum;       // [R] workspace
-    uint32_t* rflags;   // [R] workspace
-    double* part_sum;   // [nblk] workspace
-    int64_t* part_cnt;  // [nblk * 4] workspace
-    int64_t N;
-    int32_t V, R;
-    int32_t is_mode, gate_mode, seg_len;
-    double eps_low, eps_high, tau, sigma, D;
-};
 
 __device__ __forceinline__ double shfl_xor_f64(double x, int off)
 {
@@ -721,28 +698,6 @@ struct Tuning {
 };
 Tuning g_tune;
 
-inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
-
-struct WorkspaceLayout {
-    size_t hsum, rflags, part_sum, part_cnt, defer, badcu, total;
-    int64_t nblk;
-};
-
-WorkspaceLayout workspace_layout(int64_t N, int32_t R)
-{
-    WorkspaceLayout w;
-    w.nblk = (N + kTokBlock - 1) / kTokBlock;
-    size_t off = 0;
-    w.hsum = off;     off = align_up(off + sizeof(double) * (size_t)R, 256);
-    w.rflags = off;   off = align_up(off + sizeof(uint32_t) * (size_t)R, 256);
-    w.part_sum = off; off = align_up(off + sizeof(double) * (size_t)w.nblk, 256);
-    w.part_cnt = off; off = align_up(off + sizeof(int64_t) * 4 * (size_t)w.nblk, 256);
-    w.defer = off;    off = align_up(off + (size_t)N, 256);
-    w.badcu = off;    off = align_up(off + sizeof(uint32_t), 256);
-    w.total = off;
-    return w;
-}
-
 bool shape_ok(int64_t N, int64_t V, int64_t stride)
 {
     return N > 0 && N <= 0x7fffffffLL && V > 0 && V <= 0x7fffffffLL && stride >= V;
@@ -830,6 +785,27 @@ bool dispatch_fused(int nt, int u, const void* logits, int64_t N, int64_t V, int
     return false;
 }
 
+}  // namespace
+
+namespace ulorl_detail {
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+WorkspaceLayout workspace_layout(int64_t N, int32_t R)
+{
+    WorkspaceLayout w;
+    w.nblk = (N + kTokBlock - 1) / kTokBlock;
+    size_t off = 0;
+    w.hsum = off;     off = align_up(off + sizeof(double) * (size_t)R, 256);
+    w.rflags = off;   off = align_up(off + sizeof(uint32_t) * (size_t)R, 256);
+    w.part_sum = off; off = align_up(off + sizeof(double) * (size_t)w.nblk, 256);
+    w.part_cnt = off; off = align_up(off + sizeof(int64_t) * 4 * (size_t)w.nblk, 256);
+    w.defer = off;    off = align_up(off + (size_t)N, 256);
+    w.badcu = off;    off = align_up(off + sizeof(uint32_t), 256);
+    w.total = off;
+    return w;
+}
+
 // Argument checks shared by the forward and the fused forward+backward entry points.
 int32_t check_objective_args(const int32_t* cu_seqlens, int32_t R, const float* old_logp, const ulorl_params* p,
                              const float* loss, const float* gcoef)
@@ -874,7 +850,7 @@ void launch_token_epilogue(const TokenArgs& a, const WorkspaceLayout& wl, float*
     hipLaunchKernelGGL(loss_finalize_kernel, dim3(1), dim3(kTokBlock), 0, st, a, wl.nblk, loss, counters);
 }
 
-}  // namespace
+}  // namespace ulorl_detail
 
 extern "C" {
 

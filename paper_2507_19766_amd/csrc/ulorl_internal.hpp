@@ -1,0 +1,64 @@
+// Declarations shared by the translation units of libulorl (not part of the public ABI).
+#ifndef ULORL_INTERNAL_HPP
+#define ULORL_INTERNAL_HPP
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "ulorl.h"
+
+namespace ulorl_detail {
+
+constexpr int kTokBlock = 1024;  // tokens per workgroup of the O(N) epilogue kernels
+
+// Arguments of the O(N) epilogue (per-response entropy, token terms, loss reduction).
+struct TokenArgs {
+    const float* logp;
+    const float* entropy;
+    const float* lse;
+    const int32_t* token_ids;
+    const int32_t* cu;
+    const int32_t* segment_ids;
+    const float* old_logp;
+    const float* adv;
+    float* gcoef;
+    uint8_t* mask;
+    float* ratio;
+    int32_t* seg_out;
+    float* resp_entropy;
+    uint8_t* resp_gate;
+    double* hsum;       // [R] workspace
+    uint32_t* rflags;   // [R] workspace
+    double* part_sum;   // [nblk] workspace
+    int64_t* part_cnt;  // [nblk * 4] workspace
+    int64_t N;
+    int32_t V, R;
+    int32_t is_mode, gate_mode, seg_len;
+    double eps_low, eps_high, tau, sigma, D;
+};
+
+struct WorkspaceLayout {
+    size_t hsum, rflags, part_sum, part_cnt, defer, badcu, total;
+    int64_t nblk;
+};
+
+WorkspaceLayout workspace_layout(int64_t N, int32_t R);
+
+// Host-side validation of the objective's scalar parameters and required pointers.
+int32_t check_objective_args(const int32_t* cu_seqlens, int32_t R, const float* old_logp, const ulorl_params* p,
+                             const float* loss, const float* gcoef);
+
+TokenArgs make_token_args(int64_t N, int64_t V, const int32_t* token_ids, const int32_t* cu_seqlens, int32_t R,
+                          const int32_t* segment_ids, const float* old_logp, const float* advantages,
+                          const ulorl_params* p, float* logp, float* entropy, float* lse, float* gcoef,
+                          uint8_t* mpt_mask, float* ratio, int32_t* segment_out, float* resp_entropy,
+                          uint8_t* resp_gate, void* workspace, const WorkspaceLayout& wl);
+
+// Enqueues response_entropy_kernel, token_terms_kernel and loss_finalize_kernel.
+void launch_token_epilogue(const TokenArgs& a, const WorkspaceLayout& wl, float* loss, int64_t* counters,
+                           hipStream_t st);
+
+}  // namespace ulorl_detail
+
+#endif

@@ -266,3 +266,76 @@ def run_streamed_parity(w: ui.Workload, p: ulorl.Params, data, n_dz_rows=64, inp
         assert torch.all(dz[torch.as_tensor(zero_rows, device=dev)] == 0)
     say("dlogits ok on %d sampled rows, %d zero rows" % (len(k), len(zero_rows)))
     return res, tt
+
+
+# ------------------------------------------------------------------------------------ lm_head variant
+
+LMHEAD_ATOL = 4e-6   # fp32 MFMA accumulation of Hd ~ 2048 products adds ~1e-6 to every logit
+
+
+def raw_bf16(t: torch.Tensor) -> np.ndarray:
+    return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+
+
+def run_lmhead_parity(w: ui.Workload, p: ulorl.Params, chunk: int, data=None, grad_out=1.0, say=None):
+    """lm_head variant through the C ABI against the oracle (fp64 logits from a stock matrix
+    product, then the same oracle functions as the logits path, then the chain rule to hidden, W)."""
+    dev = torch.device("cuda:0")
+    d = data if data is not None else ui.generate(w, dev)
+    hidden, weight = d["hidden"], d["weight"]
+    old = None if p.is_mode == ulorl.IS_POIS else d["old_logp"]
+    res = ulorl.lmhead_token_loss_fwd(hidden, weight, d["token_ids"], d["cu_seqlens"], d["advantages"], old, p,
+                                      vocab_chunk=chunk)
+    dH, dW = ulorl.lmhead_token_loss_bwd(hidden, weight, d["token_ids"], res.lse, res.gcoef, grad_out=grad_out,
+                                         vocab_chunk=chunk)
+    torch.cuda.synchronize()
+    if say:
+        say("gpu done; oracle logits %d x %d x %d" % (w.N, w.hidden, w.V))
+    hr, wr = raw_bf16(hidden), raw_bf16(weight)
+    z = oracle.lmhead_logits(hr, wr)
+    y = d["token_ids"].cpu().numpy()
+    rtol = rtol_for("bf16")
+    o_lse, o_logp, o_H = oracle.row_stats(z, y)
+    assert_close("lse", res.lse.cpu().numpy(), o_lse, rtol, atol=LMHEAD_ATOL)
+    assert_close("logp", res.logp.cpu().numpy(), o_logp, rtol, atol=LMHEAD_ATOL)
+    assert_close("entropy", res.entropy.cpu().numpy(), o_H, rtol, atol=LMHEAD_ATOL)
+    adv = d["advantages"].cpu().numpy()
+    tt = oracle_terms(o_logp, o_H, w.cu_seqlens, adv, None if old is None else old.cpu().numpy(), p)
+    np.testing.assert_array_equal(res.segment_out.cpu().numpy(), tt.seg)
+    assert_close("resp_entropy", res.resp_entropy.cpu().numpy(), tt.resp_entropy, rtol, atol=LMHEAD_ATOL)
+    np.testing.assert_array_equal(res.resp_gate.cpu().numpy(), tt.resp_gate)
+    # same discontinuity exclusions as the logits path; the ratio inherits the logits' absolute error
+    prob = np.exp(o_logp)
+    near = (np.abs(prob - f32(p.tau)) < 2e-5) | (np.abs(tt.ratio - (1 - f32(p.eps_low))) < 2e-5) | \
+           (np.abs(tt.ratio - (1 + f32(p.eps_high))) < 2e-5)
+    np.testing.assert_array_equal(res.mpt_mask.cpu().numpy()[~near], tt.mask[~near])
+    assert_close("ratio", res.ratio.cpu().numpy(), tt.ratio, 3e-5, atol=0.0)
+    assert_close("gcoef", res.gcoef.cpu().numpy()[~near], tt.gcoef[~near], 3e-5, atol=0.0)
+    if not near.any():
+        assert_close("loss", res.loss.item(), tt.loss, 3e-5, atol=1e-7)
+    assert int(res.counters[3]) == 0 and int(res.counters[2]) == tt.n_pos
+    if say:
+        say("forward ok; oracle gradients")
+
+    g = tt.gcoef.copy()
+    g[near] = res.gcoef.cpu().numpy()[near]      # a token on a discontinuity: take the GPU's side of it
+    dz = oracle.dlogits(z, y, o_lse, g, grad_out=grad_out)
+    rdH, rdW = oracle.lmhead_grads(hr, wr, dz)
+    absdz = np.abs(dz)
+    bH = absdz @ np.abs(oracle.bf16_to_f64(wr)).T
+    bW = np.abs(oracle.bf16_to_f64(hr)).T @ absdz
+    # dz is rounded to bf16 as a GEMM operand (relative 2^-8 per term, worst case all aligned),
+    # the result is rounded to bf16 once (2^-8 relative), fp32 accumulation is negligible beside both
+    for name, got, ref, bound in (("d_hidden", dH, rdH, bH), ("d_W", dW, rdW, bW)):
+        got = got.float().cpu().numpy().astype(np.float64)
+        err = np.abs(got - ref)
+        tol = 2.0 ** -8 * bound + 2.0 ** -8 * np.abs(ref) + 1e-12
+        bad = err > tol
+        if bad.any():
+            k = np.unravel_index(int(np.argmax(err - tol)), err.shape)
+            raise AssertionError("%s: %d outside tolerance; worst at %s gpu=%r ref=%r tol=%r"
+                                 % (name, bad.sum(), k, got[k], ref[k], tol[k]))
+        # the worst-case bound is loose; the typical error must be far smaller
+        scale = np.abs(ref).mean() + 1e-30
+        assert err.mean() / scale < 3e-3, (name, err.mean() / scale)
+    return res, tt

@@ -1,0 +1,49 @@
+"""GPU parity of the lm_head variant (logits never materialised) and of its MFMA product."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2507_19766_amd as ulorl
+import ulorl_inputs as ui
+from parity import params_for, run_lmhead_parity
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(msg):
+    print(msg, file=sys.stderr, flush=True)
+
+
+@pytest.mark.parametrize("M,N,K", [(128, 128, 64), (130, 70, 72), (257, 300, 2048), (1000, 520, 8), (64, 33, 136)])
+def test_gemm_tn_bf16_against_fp64(M, N, K):
+    g = torch.Generator(device=DEV).manual_seed(M * 1000 + N)
+    a = torch.randn(M, K, generator=g, device=DEV).to(torch.bfloat16)
+    b = torch.randn(N, K, generator=g, device=DEV).to(torch.bfloat16)
+    c = ulorl.gemm_tn_bf16(a, b)
+    ref = a.double() @ b.double().T
+    bound = 1e-6 * (a.double().abs() @ b.double().abs().T) + 1e-30
+    assert torch.all((c.double() - ref).abs() <= bound), float(((c.double() - ref).abs() / bound).max())
+    # strided operands (leading dimension > K)
+    big = torch.zeros(M, K + 16, device=DEV, dtype=torch.bfloat16)
+    big[:, :K] = a
+    c2 = ulorl.gemm_tn_bf16(big[:, :K], b)
+    assert torch.equal(c, c2)
+
+
+def test_lmhead_small_ragged_chunks():
+    w = ui.shrink(ui.config(5), [120, 83], V=2056, hidden=136, seg_len=32, name="lmhead_small")
+    d = ui.generate(w, DEV)
+    for mode in (ulorl.GATE_ALWAYS, ulorl.GATE_NEVER):
+        run_lmhead_parity(w, params_for(w, gate_mode=mode, tau=0.05), chunk=512, data=d)
+    run_lmhead_parity(w, params_for(w, gate_mode=ulorl.GATE_PER_RESPONSE, sigma=100.0, tau=0.05,
+                                    is_mode=ulorl.IS_POIS), chunk=8192, data=d, grad_out=-1.5)
+
+
+def test_lmhead_config5_reduced_rows():
+    # the full hidden size and vocabulary of configuration 5, 2 x 512 rows
+    w = ui.shrink(ui.config(5), [512, 512], seg_len=256, name="cfg5_reduced")
+    res, tt = run_lmhead_parity(w, params_for(w, gate_mode=ulorl.GATE_ALWAYS), chunk=8192, say=say)
+    assert tt.n_clip_inactive > 0

@@ -453,3 +453,50 @@ def test_whole_objective_against_autograd(seed):
     assert 0 < tt.n_masked < N
     np.testing.assert_allclose(tt.loss, loss.item(), rtol=1e-12)
     np.testing.assert_allclose(dz, zt.grad.numpy(), rtol=1e-9, atol=1e-15)
+
+
+# ----------------------------------------------------------------------------- lm_head variant
+
+def _raw_bf16(t: torch.Tensor) -> np.ndarray:
+    return t.to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+
+
+def test_lmhead_logits_and_grads_against_loops_and_autograd():
+    rs = np.random.RandomState(5)
+    N, Hd, V = 7, 8, 24
+    h = torch.tensor(rs.normal(size=(N, Hd))).to(torch.bfloat16)
+    w = torch.tensor(rs.normal(0, 0.5, size=(Hd, V))).to(torch.bfloat16)
+    hr, wr = _raw_bf16(h), _raw_bf16(w)
+    z = oracle.lmhead_logits(hr, wr)
+    # brute force triple loop on the exactly decoded operands
+    hd, wd = h.double().numpy(), w.double().numpy()
+    ref = np.zeros((N, V))
+    for t in range(N):
+        for v in range(V):
+            for k in range(Hd):
+                ref[t, v] += hd[t, k] * wd[k, v]
+    np.testing.assert_allclose(z, ref, rtol=1e-13, atol=1e-15)
+    # one-hot hidden rows pick rows of W exactly
+    e = torch.zeros(3, Hd)
+    e[0, 2] = e[1, 5] = e[2, 7] = 1.0
+    np.testing.assert_array_equal(oracle.lmhead_logits(_raw_bf16(e), wr), wd[[2, 5, 7]])
+
+    # the whole lm_head objective differentiated by autograd (fp64) vs the oracle's chain rule
+    y = rs.randint(0, V, size=N)
+    adv = rs.choice([-1.0, 1.0], size=N)
+    ht = h.double().requires_grad_(True)
+    wt = w.double().requires_grad_(True)
+    logq = torch.log_softmax(ht @ wt, -1)
+    lp = logq.gather(1, torch.tensor(y)[:, None])[:, 0]
+    old = lp.detach().numpy() + rs.normal(0, 0.15, size=N)
+    r = torch.exp(lp - torch.tensor(old))
+    A = torch.tensor(adv)
+    loss = -torch.minimum(r * A, torch.clamp(r, 0.8, 1.2) * A).sum() / N
+    loss.backward()
+    lse, logp, H = oracle.row_stats(z, y)
+    tt = oracle.token_terms(logp, H, [0, 3, N], adv, old, gate_mode=oracle.GATE_NEVER)
+    np.testing.assert_allclose(tt.loss, loss.item(), rtol=1e-12)
+    dz = oracle.dlogits(z, y, lse, tt.gcoef)
+    dh, dw = oracle.lmhead_grads(hr, wr, dz)
+    np.testing.assert_allclose(dh, ht.grad.numpy(), rtol=1e-9, atol=1e-14)
+    np.testing.assert_allclose(dw, wt.grad.numpy(), rtol=1e-9, atol=1e-14)

@@ -119,7 +119,13 @@ __device__ __forceinline__ void gemm_tn_mainloop(const bf16_t* __restrict__ A, i
 
     u32x4 ra[Cfg::A_VECS], rb[Cfg::B_VECS];
     const u32x4 zero = {0u, 0u, 0u, 0u};
-    auto fetch = [&](int k0) {
+    auto fetch_full = [&](int k0) {      // whole tile inside the contraction range
+#pragma unroll
+        for (int i = 0; i < Cfg::A_VECS; ++i) ra[i] = *reinterpret_cast<const u32x4*>(ga[i] + k0);
+#pragma unroll
+        for (int i = 0; i < Cfg::B_VECS; ++i) rb[i] = *reinterpret_cast<const u32x4*>(gb[i] + k0);
+    };
+    auto fetch_ragged = [&](int k0) {    // last tile: vectors past K contribute zero
 #pragma unroll
         for (int i = 0; i < Cfg::A_VECS; ++i)
             ra[i] = (k0 + ka[i] < K) ? *reinterpret_cast<const u32x4*>(ga[i] + k0) : zero;
@@ -140,14 +146,7 @@ __device__ __forceinline__ void gemm_tn_mainloop(const bf16_t* __restrict__ A, i
     const int frag_k = 8 * (lane >> 5);
     const int a_base = (wave_m * Cfg::WM + frag_row) * Cfg::LDS_STRIDE + frag_k;
     const int b_base = (wave_n * Cfg::WN + frag_row) * Cfg::LDS_STRIDE + frag_k;
-
-    const int KT = (K + Cfg::BK - 1) / Cfg::BK;
-    fetch(0);
-    stash(0);
-    __syncthreads();
-    for (int kt = 0; kt < KT; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < KT) fetch((kt + 1) * Cfg::BK);
+    auto compute = [&](int cur) {
         const bf16_t* cA = sA + cur * Cfg::A_STAGE + a_base;
         const bf16_t* cB = sB + cur * Cfg::B_STAGE + b_base;
 #pragma unroll
@@ -165,7 +164,29 @@ __device__ __forceinline__ void gemm_tn_mainloop(const bf16_t* __restrict__ A, i
                 for (int bj = 0; bj < Cfg::NB; ++bj)
                     acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[bi], fb[bj], acc[bi][bj], 0, 0, 0);
         }
-        if (kt + 1 < KT) stash(cur ^ 1);
+    };
+
+    // Double-buffered pipeline, one barrier per K tile: the global loads of tile kt+1 are in
+    // flight while tile kt is multiplied out of LDS.  The hot loop runs over the tiles that lie
+    // wholly inside K and has no conditional code; a ragged last tile is peeled off.
+    const int KT = (K + Cfg::BK - 1) / Cfg::BK;
+    const int KT_full = K / Cfg::BK;
+    if (KT_full > 0) fetch_full(0); else fetch_ragged(0);
+    stash(0);
+    __syncthreads();
+    int kt = 0;
+    for (; kt + 1 < KT_full; ++kt) {
+        fetch_full((kt + 1) * Cfg::BK);
+        __builtin_amdgcn_sched_barrier(0);   // keep the prefetch ahead of the multiply: its latency hides there
+        compute(kt & 1);
+        stash((kt + 1) & 1);
+        __syncthreads();
+    }
+    for (; kt < KT; ++kt) {
+        const bool more = kt + 1 < KT;
+        if (more) fetch_ragged((kt + 1) * Cfg::BK);
+        compute(kt & 1);
+        if (more) stash((kt + 1) & 1);
         __syncthreads();
     }
 }
@@ -438,7 +459,19 @@ __global__ __launch_bounds__(Cfg::NT) void lmhead_dz_kernel(const bf16_t* __rest
 // ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
-using CfgMain = GemmCfg<128, 128, 64, 2, 2>;
+// Tile shapes that are compiled in; ulorl_tune(ULORL_TUNE_GEMM_TILE, i) selects one.
+using Tile0 = GemmCfg<128, 128, 64, 2, 2>;   // wave tile 64 x 64
+using Tile1 = GemmCfg<256, 256, 32, 2, 2>;   // wave tile 128 x 128, 80 KB of LDS
+using Tile2 = GemmCfg<256, 256, 64, 2, 2>;   // wave tile 128 x 128, 144 KB of LDS
+using Tile3 = GemmCfg<256, 128, 64, 2, 2>;   // wave tile 128 x 64
+
+#define ULORL_FOR_TILE(choice, ...)                          \
+    switch (choice) {                                        \
+    case 0: { using Cfg = Tile0; __VA_ARGS__; } break;       \
+    case 2: { using Cfg = Tile2; __VA_ARGS__; } break;       \
+    case 3: { using Cfg = Tile3; __VA_ARGS__; } break;       \
+    default: { using Cfg = Tile1; __VA_ARGS__; } break;      \
+    }
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline int64_t round_up64(int64_t x) { return (x + 63) / 64 * 64; }
@@ -453,24 +486,29 @@ struct LmheadLayout {
 
 LmheadLayout lmhead_layout(int64_t N, int64_t Hd, int64_t V, int32_t R, int32_t chunk)
 {
+    int bm = 0, bn = 0;
+    ULORL_FOR_TILE(gemm_tile_choice(), bm = Cfg::BM; bn = Cfg::BN)
     LmheadLayout L;
     L.ldt = round_up64(N);
     L.ldc = round_up64(chunk);
-    const int64_t ttiles = (N + CfgMain::BN - 1) / CfgMain::BN;
+    const int64_t ttiles = (N + bn - 1) / bn;
     int splits = (int)((1024 + ttiles - 1) / ttiles);       // aim at >= 1024 workgroups
-    const int64_t vtiles = (V + CfgMain::BM - 1) / CfgMain::BM;
+    const int64_t vtiles = (V + bm - 1) / bm;
     if (splits > vtiles) splits = (int)vtiles;
     if (splits < 1) splits = 1;
     const int64_t tiles_per_split = (vtiles + splits - 1) / splits;
-    L.v_per_split = (int)(tiles_per_split * CfgMain::BM);
+    L.v_per_split = (int)(tiles_per_split * bm);
     L.splits = (int)((vtiles + tiles_per_split - 1) / tiles_per_split);
+    // sized for the largest split count any tile shape can ask for, so that the workspace
+    // requirement does not depend on the tuning knob
+    const size_t max_splits = 16;
     size_t off = 0;
     L.wt = off;      off = align_up(off + (size_t)V * Hd * 2, 256);
     L.ht = off;      off = align_up(off + (size_t)Hd * L.ldt * 2, 256);
     L.dzc = off;     off = align_up(off + (size_t)N * L.ldc * 2, 256);
     L.dzct = off;    off = align_up(off + (size_t)L.ldc * L.ldt * 2, 256);
     L.dhacc = off;   off = align_up(off + (size_t)N * Hd * 4, 256);
-    L.partial = off; off = align_up(off + (size_t)L.splits * N * sizeof(StatQuad), 256);
+    L.partial = off; off = align_up(off + max_splits * (size_t)N * sizeof(StatQuad), 256);
     L.token_ws = off; off = align_up(off + workspace_layout(N, R).total, 256);
     L.total = off;
     return L;
@@ -499,14 +537,47 @@ void launch_transpose(const bf16_t* src, int64_t ld_src, int rows, int cols, bf1
     hipLaunchKernelGGL(transpose_bf16_kernel, grid, dim3(256), 0, st, src, ld_src, rows, cols, dst, ld_dst, dst_cols);
 }
 
+template <class Cfg, int STORE>
+bool launch_gemm_cfg(const bf16_t* A, int64_t lda, int M, const bf16_t* B, int64_t ldb, int N, int K, void* C,
+                     int64_t ldc, hipStream_t st)
+{
+    auto kern = gemm_tn_kernel<Cfg, STORE>;
+    if (!allow_lds(kern, Cfg::LDS_BYTES)) return false;
+    dim3 grid((unsigned)((M + Cfg::BM - 1) / Cfg::BM), (unsigned)((N + Cfg::BN - 1) / Cfg::BN));
+    hipLaunchKernelGGL(kern, grid, dim3(Cfg::NT), Cfg::LDS_BYTES, st, A, lda, M, B, ldb, N, K, C, ldc);
+    return true;
+}
+
 template <int STORE>
 bool launch_gemm(const bf16_t* A, int64_t lda, int M, const bf16_t* B, int64_t ldb, int N, int K, void* C, int64_t ldc,
                  hipStream_t st)
 {
-    auto kern = gemm_tn_kernel<CfgMain, STORE>;
-    if (!allow_lds(kern, CfgMain::LDS_BYTES)) return false;
-    dim3 grid((unsigned)((M + CfgMain::BM - 1) / CfgMain::BM), (unsigned)((N + CfgMain::BN - 1) / CfgMain::BN));
-    hipLaunchKernelGGL(kern, grid, dim3(CfgMain::NT), CfgMain::LDS_BYTES, st, A, lda, M, B, ldb, N, K, C, ldc);
+    bool ok = false;
+    ULORL_FOR_TILE(gemm_tile_choice(), ok = (launch_gemm_cfg<Cfg, STORE>(A, lda, M, B, ldb, N, K, C, ldc, st)))
+    return ok;
+}
+
+template <class Cfg>
+bool launch_stats_cfg(const bf16_t* Wt, const bf16_t* H, int Hd, int V, int N, const int32_t* token_ids,
+                      const LmheadLayout& L, StatQuad* partial, hipStream_t st)
+{
+    auto kern = lmhead_stats_kernel<Cfg>;
+    if (!allow_lds(kern, Cfg::LDS_BYTES)) return false;
+    dim3 grid((unsigned)((N + Cfg::BN - 1) / Cfg::BN), (unsigned)L.splits);
+    hipLaunchKernelGGL(kern, grid, dim3(Cfg::NT), Cfg::LDS_BYTES, st, Wt, H, Hd, V, N, token_ids, L.v_per_split, partial);
+    return true;
+}
+
+template <class Cfg>
+bool launch_dz_cfg(const bf16_t* Wt, const bf16_t* H, int Hd, int V, int N, int vc0, int cw_pad,
+                   const int32_t* token_ids, const float* lse, const float* gcoef, float grad_out, bf16_t* dZc,
+                   bf16_t* dZcT, const LmheadLayout& L, hipStream_t st)
+{
+    auto kern = lmhead_dz_kernel<Cfg>;
+    if (!allow_lds(kern, Cfg::LDS_BYTES)) return false;
+    dim3 grid((unsigned)((cw_pad + Cfg::BM - 1) / Cfg::BM), (unsigned)((L.ldt + Cfg::BN - 1) / Cfg::BN));
+    hipLaunchKernelGGL(kern, grid, dim3(Cfg::NT), Cfg::LDS_BYTES, st, Wt, H, Hd, V, N, vc0, cw_pad, token_ids, lse, gcoef,
+                       grad_out, dZc, L.ldc, dZcT, L.ldt);
     return true;
 }
 
@@ -554,11 +625,10 @@ int32_t ulorl_lmhead_token_loss_fwd(const void* hidden, const void* W, int64_t N
     StatQuad* partial = (StatQuad*)(ws + L.partial);
 
     launch_transpose((const bf16_t*)W, V, (int)Hd, (int)V, Wt, Hd, (int)Hd, st);      // Wt[v, k] = W[k, v]
-    auto kern = lmhead_stats_kernel<CfgMain>;
-    if (!allow_lds(kern, CfgMain::LDS_BYTES)) return ULORL_ERR_HIP;
-    dim3 grid((unsigned)((N + CfgMain::BN - 1) / CfgMain::BN), (unsigned)L.splits);
-    hipLaunchKernelGGL(kern, grid, dim3(CfgMain::NT), CfgMain::LDS_BYTES, st, Wt, (const bf16_t*)hidden, (int)Hd, (int)V,
-                       (int)N, token_ids, L.v_per_split, partial);
+    bool ok = false;
+    ULORL_FOR_TILE(gemm_tile_choice(), ok = launch_stats_cfg<Cfg>(Wt, (const bf16_t*)hidden, (int)Hd, (int)V, (int)N,
+                                                                  token_ids, L, partial, st))
+    if (!ok) return ULORL_ERR_HIP;
     hipLaunchKernelGGL(lmhead_stats_merge_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, st, partial, L.splits,
                        (int)N, (int)V, token_ids, lse, logp, entropy);
     if (hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;
@@ -597,14 +667,13 @@ int32_t ulorl_lmhead_token_loss_bwd(const void* hidden, const void* W, int64_t N
     const int64_t nh = N * Hd;
     hipLaunchKernelGGL(fill_zero_f32_kernel, dim3((unsigned)((nh + 255) / 256)), dim3(256), 0, st, dHacc, nh);
 
-    auto dzk = lmhead_dz_kernel<CfgMain>;
-    if (!allow_lds(dzk, CfgMain::LDS_BYTES)) return ULORL_ERR_HIP;
     for (int64_t vc0 = 0; vc0 < V; vc0 += vocab_chunk) {
         const int cw = (int)((V - vc0 < vocab_chunk) ? (V - vc0) : vocab_chunk);
         const int cw_pad = (int)round_up64(cw);         // dz of the padding columns is written as zero
-        dim3 grid((unsigned)((cw_pad + CfgMain::BM - 1) / CfgMain::BM), (unsigned)((L.ldt + CfgMain::BN - 1) / CfgMain::BN));
-        hipLaunchKernelGGL(dzk, grid, dim3(CfgMain::NT), CfgMain::LDS_BYTES, st, Wt, H, (int)Hd, (int)V, (int)N, (int)vc0,
-                           cw_pad, token_ids, lse, gcoef, grad_out, dZc, L.ldc, dZcT, L.ldt);
+        bool ok = false;
+        ULORL_FOR_TILE(gemm_tile_choice(), ok = launch_dz_cfg<Cfg>(Wt, H, (int)Hd, (int)V, (int)N, (int)vc0, cw_pad,
+                                                                   token_ids, lse, gcoef, grad_out, dZc, dZcT, L, st))
+        if (!ok) return ULORL_ERR_HIP;
         // dHidden[t, k] += sum_v dZc[t, v] W[k, vc0 + v]
         if (!launch_gemm<STORE_F32_ACCUM>(dZc, L.ldc, (int)N, Wp + vc0, V, (int)Hd, cw, dHacc, Hd, st)) return ULORL_ERR_HIP;
         // dW[k, vc0 + v] = sum_t Ht[k, t] dZc^T[v, t]

@@ -695,6 +695,7 @@ struct Tuning {
     int fwd_threads = 512, fwd_unroll = 8;
     int bwd_threads = 256, bwd_unroll = 4;
     int fused_threads = 512, fused_unroll = 8;
+    int gemm_tile = 1;
 };
 Tuning g_tune;
 
@@ -789,6 +790,8 @@ bool dispatch_fused(int nt, int u, const void* logits, int64_t N, int64_t V, int
 
 namespace ulorl_detail {
 
+int gemm_tile_choice() { return g_tune.gemm_tile; }
+
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 WorkspaceLayout workspace_layout(int64_t N, int32_t R)
@@ -882,6 +885,7 @@ int32_t ulorl_tune(int32_t knob, int32_t value)
     case ULORL_TUNE_BWD_UNROLL:  if (!unroll_ok) return ULORL_ERR_PARAM;  g_tune.bwd_unroll = value;  return ULORL_OK;
     case ULORL_TUNE_FUSED_THREADS: if (!threads_ok) return ULORL_ERR_PARAM; g_tune.fused_threads = value; return ULORL_OK;
     case ULORL_TUNE_FUSED_UNROLL:  if (!unroll_ok) return ULORL_ERR_PARAM;  g_tune.fused_unroll = value;  return ULORL_OK;
+    case ULORL_TUNE_GEMM_TILE: if (value < 0 || value > 3) return ULORL_ERR_PARAM; g_tune.gemm_tile = value; return ULORL_OK;
     default: return ULORL_ERR_PARAM;
     }
 }

@@ -59,6 +59,9 @@ TokenArgs make_token_args(int64_t N, int64_t V, const int32_t* token_ids, const 
 void launch_token_epilogue(const TokenArgs& a, const WorkspaceLayout& wl, float* loss, int64_t* counters,
                            hipStream_t st);
 
+// Index of the GEMM tile shape selected with ulorl_tune(ULORL_TUNE_GEMM_TILE, i).
+int gemm_tile_choice();
+
 }  // namespace ulorl_detail
 
 #endif

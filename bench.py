@@ -28,6 +28,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0      # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 matrix rate
 
 
 def log(*a):
@@ -61,12 +62,94 @@ def cpu_baseline(w, data, params, sample_rows):
             "sample": "first %d rows of %s, fp64 forward + backward, %.1f s" % (n, w.name, dt)}
 
 
+def bench_lmhead(args, w, ulorl, ui, torch, dev):
+    """Configuration 5: logits = hidden . W never materialised; a step = lm_head forward + backward."""
+    import numpy as np
+    log("generating %s: N=%d Hd=%d V=%d ..." % (w.name, w.N, w.hidden, w.V))
+    data = ui.generate(w, dev)
+    torch.cuda.synchronize()
+    params = ulorl.Params(eps_low=w.eps_low, eps_high=w.eps_high, tau=w.tau, sigma=w.sigma,
+                          is_mode=ulorl.IS_SAIS, gate_mode=ulorl.GATE_ALWAYS, seg_len=w.seg_len)
+    chunk = 8192
+    H, W = data["hidden"], data["weight"]
+    y, cu, adv, old = data["token_ids"], data["cu_seqlens"], data["advantages"], data["old_logp"]
+    ws = torch.empty(ulorl.lmhead_workspace_bytes(w.N, w.hidden, w.V, w.R, chunk), dtype=torch.uint8, device=dev)
+    dH, dW = torch.empty_like(H), torch.empty_like(W)
+    out = None
+
+    def step():
+        nonlocal out
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        t_a = time.perf_counter()
+        ev[0].record()
+        out = ulorl.lmhead_token_loss_fwd(H, W, y, cu, adv, old, params, vocab_chunk=chunk, out=out, workspace=ws)
+        ev[1].record()
+        ulorl.lmhead_token_loss_bwd(H, W, y, out.lse, out.gcoef, 1.0, vocab_chunk=chunk, d_hidden=dH, d_weight=dW,
+                                    workspace=ws)
+        ev[2].record()
+        torch.cuda.synchronize()
+        return time.perf_counter() - t_a, ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2])
+
+    K = args.steps
+    for _ in range(args.warmup):
+        step()
+    wall = fwd_ms = bwd_ms = 0.0
+    for _ in range(K):
+        a, b, c = step()
+        wall += a
+        fwd_ms += b
+        bwd_ms += c
+    gemm_flops = 2.0 * w.N * w.hidden * w.V                 # one N x Hd x V product
+    bwd_tf = 3 * gemm_flops / (bwd_ms / K * 1e-3) / 1e12     # recompute, dHidden, dW
+    fwd_tf = gemm_flops / (fwd_ms / K * 1e-3) / 1e12
+    cnt = out.counters.cpu().tolist()
+    result = {
+        "metric": "token-rows/sec fused fwd+bwd RL token loss (V=151936 bf16) + % HBM roofline",
+        "value": w.N * K / wall, "unit": "token-rows/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "ms_per_step": wall / K * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 MFMA operands, f32 accumulate", "data": "synthetic",
+        "config": {"workload": w.name, "rows": w.N, "hidden": w.hidden, "vocab": w.V, "vocab_chunk": chunk,
+                   "responses": w.R, "segment_len": w.seg_len, "path": "lm_head variant (logits never materialised)",
+                   "is_mode": "SAIS", "gate": "always (static MPT masking)", "tau": w.tau},
+        "roofline": {"bound": "mfma", "kernel": "backward call: lmhead_dz_kernel + 2 x gemm_tn_kernel per vocabulary "
+                     "chunk (3 products of 2*N*Hd*V flop)", "achieved": bwd_tf, "peak": MFMA_BF16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": bwd_tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "algorithmic_flops_per_launch": 3 * gemm_flops, "avg_launch_ms": bwd_ms / K},
+        "roofline_fwd": {"bound": "mfma", "kernel": "lmhead_stats_kernel (1 product)", "achieved": fwd_tf,
+                         "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": fwd_tf / MFMA_BF16_PEAK_TFLOPS,
+                         "avg_call_ms": fwd_ms / K},
+        "batch": {"masked_tokens": cnt[0], "clipped_tokens": cnt[1], "positive_tokens": cnt[2], "status": cnt[3],
+                  "loss": out.loss.item()},
+    }
+    if args.cpu_rows > 0:
+        import oracle
+        n = min(256, w.N)
+        log("timing the CPU oracle (lm_head) on %d rows..." % n)
+        hr = H[:n].cpu().view(torch.int16).numpy().view(np.uint16)
+        wr = W.cpu().view(torch.int16).numpy().view(np.uint16)
+        yy = y[:n].cpu().numpy()
+        t0 = time.perf_counter()
+        z = oracle.lmhead_logits(hr, wr)
+        lse, logp, ent = oracle.row_stats(z, yy)
+        tt = oracle.token_terms(logp, ent, [0, n], adv[:n].cpu().numpy(), old[:n].cpu().numpy(), seg_len=w.seg_len,
+                                gate_mode=params.gate_mode, denominator=float(w.N))
+        dz = oracle.dlogits(z, yy, lse, tt.gcoef)
+        oracle.lmhead_grads(hr, wr, dz)
+        dt = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": n / dt, "unit": "token-rows/s", "cores": oracle.threads(), "kind": "oracle",
+                                  "sample": "first %d rows of %s (full hidden and vocabulary; the d_W product costs "
+                                            "the same per row at any row count), fp64, %.1f s" % (n, w.name, dt)}
+    print(json.dumps(result), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="cfg4", choices=["cfg1", "cfg2", "cfg3", "cfg4"])
+    ap.add_argument("--workload", default="cfg4", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--gemm-tile", type=int, default=-1, help="lm_head variant: tile shape index (ulorl_tune)")
     ap.add_argument("--out-of-place", action="store_true", help="write dlogits to a second buffer")
     ap.add_argument("--cpu-rows", type=int, default=49152, help="rows of the oracle sample (0 = skip)")
     ap.add_argument("--path", default="fused", choices=["fused", "two_call"],
@@ -99,6 +182,10 @@ def main():
             ulorl.tune(knob, val)
 
     w = ui.config(int(args.workload[3]))
+    if w.hidden > 0:
+        if args.gemm_tile >= 0:
+            ulorl.tune(ulorl.TUNE_GEMM_TILE, args.gemm_tile)
+        return bench_lmhead(args, w, ulorl, ui, torch, dev)
     inplace = (args.workload == "cfg4") and not args.out_of_place
     elem = 4 if w.dtype == "f32" else 2
     log("generating %s: N=%d V=%d %s (%.1f GB of logits)..." % (w.name, w.N, w.V, w.dtype, w.N * w.V * elem / 1e9))

@@ -91,18 +91,20 @@ __device__ __forceinline__ void gemm_tn_mainloop(const bf16_t* __restrict__ A, i
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[bi][bj][r] = 0.0f;
 
-    // per-thread global sources of this tile (rows clamped into range)
-    const bf16_t* ga[Cfg::A_VECS];
-    const bf16_t* gb[Cfg::B_VECS];
+    // Per-thread sources of this tile: a workgroup-uniform base (kept in scalar registers and
+    // advanced along K) plus a 32-bit byte offset per vector (rows clamped into range), so the
+    // hot loop carries no 64-bit vector address arithmetic.
+    const char* a_tile = reinterpret_cast<const char*>(A + (int64_t)m0 * lda);
+    const char* b_tile = reinterpret_cast<const char*>(B + (int64_t)n0 * ldb);
+    uint32_t oa[Cfg::A_VECS], ob[Cfg::B_VECS];
     int ka[Cfg::A_VECS], kb[Cfg::B_VECS];
     int la[Cfg::A_VECS], lb[Cfg::B_VECS];
 #pragma unroll
     for (int i = 0; i < Cfg::A_VECS; ++i) {
         const int idx = tid + i * NT;
         const int row = idx / Cfg::VEC_PER_ROW, kv = idx % Cfg::VEC_PER_ROW;
-        int gr = m0 + row;
-        gr = gr < M ? gr : M - 1;
-        ga[i] = A + (int64_t)gr * lda + kv * 8;
+        const int gr = (m0 + row < M) ? row : (M - 1 - m0);
+        oa[i] = (uint32_t)(((int64_t)gr * lda + kv * 8) * 2);
         ka[i] = kv * 8;
         la[i] = row * Cfg::LDS_STRIDE + kv * 8;
     }
@@ -110,9 +112,8 @@ __device__ __forceinline__ void gemm_tn_mainloop(const bf16_t* __restrict__ A, i
     for (int i = 0; i < Cfg::B_VECS; ++i) {
         const int idx = tid + i * NT;
         const int row = idx / Cfg::VEC_PER_ROW, kv = idx % Cfg::VEC_PER_ROW;
-        int gr = n0 + row;
-        gr = gr < N ? gr : N - 1;
-        gb[i] = B + (int64_t)gr * ldb + kv * 8;
+        const int gr = (n0 + row < N) ? row : (N - 1 - n0);
+        ob[i] = (uint32_t)(((int64_t)gr * ldb + kv * 8) * 2);
         kb[i] = kv * 8;
         lb[i] = row * Cfg::LDS_STRIDE + kv * 8;
     }
@@ -120,18 +121,22 @@ __device__ __forceinline__ void gemm_tn_mainloop(const bf16_t* __restrict__ A, i
     u32x4 ra[Cfg::A_VECS], rb[Cfg::B_VECS];
     const u32x4 zero = {0u, 0u, 0u, 0u};
     auto fetch_full = [&](int k0) {      // whole tile inside the contraction range
+        const char* pa = a_tile + (int64_t)k0 * 2;
+        const char* pb = b_tile + (int64_t)k0 * 2;
 #pragma unroll
-        for (int i = 0; i < Cfg::A_VECS; ++i) ra[i] = *reinterpret_cast<const u32x4*>(ga[i] + k0);
+        for (int i = 0; i < Cfg::A_VECS; ++i) ra[i] = *reinterpret_cast<const u32x4*>(pa + oa[i]);
 #pragma unroll
-        for (int i = 0; i < Cfg::B_VECS; ++i) rb[i] = *reinterpret_cast<const u32x4*>(gb[i] + k0);
+        for (int i = 0; i < Cfg::B_VECS; ++i) rb[i] = *reinterpret_cast<const u32x4*>(pb + ob[i]);
     };
     auto fetch_ragged = [&](int k0) {    // last tile: vectors past K contribute zero
+        const char* pa = a_tile + (int64_t)k0 * 2;
+        const char* pb = b_tile + (int64_t)k0 * 2;
 #pragma unroll
         for (int i = 0; i < Cfg::A_VECS; ++i)
-            ra[i] = (k0 + ka[i] < K) ? *reinterpret_cast<const u32x4*>(ga[i] + k0) : zero;
+            ra[i] = (k0 + ka[i] < K) ? *reinterpret_cast<const u32x4*>(pa + oa[i]) : zero;
 #pragma unroll
         for (int i = 0; i < Cfg::B_VECS; ++i)
-            rb[i] = (k0 + kb[i] < K) ? *reinterpret_cast<const u32x4*>(gb[i] + k0) : zero;
+            rb[i] = (k0 + kb[i] < K) ? *reinterpret_cast<const u32x4*>(pb + ob[i]) : zero;
     };
     auto stash = [&](int stage) {
 #pragma unroll
@@ -191,6 +196,37 @@ __device__ __forceinline__ void gemm_tn_mainloop(const bf16_t* __restrict__ A, i
     }
 }
 
+// Workgroup -> tile mapping.  The hardware deals consecutive workgroup ids round-robin to the 8
+// XCDs, each with its own L2.  Ids are first regrouped so that every XCD owns one contiguous
+// range of logical tile numbers, and logical numbers walk the tile grid in blocks of 4 tiles
+// along M by all tiles along N (column-major inside the block): the 32 workgroups resident on an
+// XCD then cover about 4 x 8 tiles and share their A and B slices through that XCD's L2.
+constexpr int kXcds = 8;
+constexpr int kGroupM = 4;
+
+__device__ __forceinline__ bool tile_coords(int num_m, int num_n, int& tile_m, int& tile_n)
+{
+    const int total = num_m * num_n;
+    const int per_xcd = (total + kXcds - 1) / kXcds;
+    const int bid = blockIdx.x;
+    const int logical = (bid % kXcds) * per_xcd + bid / kXcds;
+    if (bid / kXcds >= per_xcd || logical >= total) return false;
+    const int group_size = kGroupM * num_n;
+    const int group = logical / group_size;
+    const int first_m = group * kGroupM;
+    const int gm = min(kGroupM, num_m - first_m);
+    const int in_group = logical % group_size;
+    tile_m = first_m + in_group % gm;
+    tile_n = in_group / gm;
+    return true;
+}
+
+inline unsigned tile_grid(int num_m, int num_n)
+{
+    const int total = num_m * num_n;
+    return (unsigned)(((total + kXcds - 1) / kXcds) * kXcds);
+}
+
 // ---------------------------------------------------------------------------------------------
 // plain GEMM kernels: C = A . B^T with three ways of storing C
 // ---------------------------------------------------------------------------------------------
@@ -203,7 +239,9 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_tn_kernel(const bf16_t* __restri
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     bf16_t* lds = reinterpret_cast<bf16_t*>(lds_raw);
-    const int m0 = blockIdx.x * Cfg::BM, n0 = blockIdx.y * Cfg::BN;
+    int tile_m, tile_n;
+    if (!tile_coords((M + Cfg::BM - 1) / Cfg::BM, (N + Cfg::BN - 1) / Cfg::BN, tile_m, tile_n)) return;
+    const int m0 = tile_m * Cfg::BM, n0 = tile_n * Cfg::BN;
     f32x16 acc[Cfg::MB][Cfg::NB];
     gemm_tn_mainloop<Cfg>(A, lda, M, m0, B, ldb, N, n0, K, acc, lds);
 
@@ -287,12 +325,13 @@ template <class Cfg>
 __global__ __launch_bounds__(Cfg::NT) void lmhead_stats_kernel(const bf16_t* __restrict__ Wt, const bf16_t* __restrict__ H,
                                                                int Hd, int V, int Ntok,
                                                                const int32_t* __restrict__ token_ids, int v_per_split,
-                                                               StatQuad* __restrict__ partial)
+                                                               int splits, StatQuad* __restrict__ partial)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     bf16_t* lds = reinterpret_cast<bf16_t*>(lds_raw);
-    const int t0 = blockIdx.x * Cfg::BN;
-    const int split = blockIdx.y;
+    int t_tile, split;
+    if (!tile_coords((Ntok + Cfg::BN - 1) / Cfg::BN, splits, t_tile, split)) return;
+    const int t0 = t_tile * Cfg::BN;
     const int vb = split * v_per_split;
     const int ve = min(V, vb + v_per_split);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -406,8 +445,10 @@ __global__ __launch_bounds__(Cfg::NT) void lmhead_dz_kernel(const bf16_t* __rest
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     bf16_t* lds = reinterpret_cast<bf16_t*>(lds_raw);
-    const int v0 = vc0 + blockIdx.x * Cfg::BM;
-    const int t0 = blockIdx.y * Cfg::BN;
+    int v_tile, t_tile;
+    if (!tile_coords((cw + Cfg::BM - 1) / Cfg::BM, (int)((ld_t + Cfg::BN - 1) / Cfg::BN), v_tile, t_tile)) return;
+    const int v0 = vc0 + v_tile * Cfg::BM;
+    const int t0 = t_tile * Cfg::BN;
     const int vend = min(V, vc0 + cw);
     f32x16 acc[Cfg::MB][Cfg::NB];
     gemm_tn_mainloop<Cfg>(Wt, Hd, V, v0, H, Hd, Ntok, t0, Hd, acc, lds);
@@ -464,13 +505,17 @@ using Tile0 = GemmCfg<128, 128, 64, 2, 2>;   // wave tile 64 x 64
 using Tile1 = GemmCfg<256, 256, 32, 2, 2>;   // wave tile 128 x 128, 80 KB of LDS
 using Tile2 = GemmCfg<256, 256, 64, 2, 2>;   // wave tile 128 x 128, 144 KB of LDS
 using Tile3 = GemmCfg<256, 128, 64, 2, 2>;   // wave tile 128 x 64
+using Tile4 = GemmCfg<256, 256, 64, 2, 4>;   // eight waves (two per SIMD), wave tile 128 x 64
+using Tile5 = GemmCfg<256, 256, 64, 4, 2>;   // eight waves, wave tile 64 x 128
 
 #define ULORL_FOR_TILE(choice, ...)                          \
     switch (choice) {                                        \
     case 0: { using Cfg = Tile0; __VA_ARGS__; } break;       \
     case 2: { using Cfg = Tile2; __VA_ARGS__; } break;       \
     case 3: { using Cfg = Tile3; __VA_ARGS__; } break;       \
-    default: { using Cfg = Tile1; __VA_ARGS__; } break;      \
+    case 4: { using Cfg = Tile4; __VA_ARGS__; } break;       \
+    case 1: { using Cfg = Tile1; __VA_ARGS__; } break;       \
+    default: { using Cfg = Tile5; __VA_ARGS__; } break;      \
     }
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -543,7 +588,7 @@ bool launch_gemm_cfg(const bf16_t* A, int64_t lda, int M, const bf16_t* B, int64
 {
     auto kern = gemm_tn_kernel<Cfg, STORE>;
     if (!allow_lds(kern, Cfg::LDS_BYTES)) return false;
-    dim3 grid((unsigned)((M + Cfg::BM - 1) / Cfg::BM), (unsigned)((N + Cfg::BN - 1) / Cfg::BN));
+    dim3 grid(tile_grid((M + Cfg::BM - 1) / Cfg::BM, (N + Cfg::BN - 1) / Cfg::BN));
     hipLaunchKernelGGL(kern, grid, dim3(Cfg::NT), Cfg::LDS_BYTES, st, A, lda, M, B, ldb, N, K, C, ldc);
     return true;
 }
@@ -563,8 +608,9 @@ bool launch_stats_cfg(const bf16_t* Wt, const bf16_t* H, int Hd, int V, int N, c
 {
     auto kern = lmhead_stats_kernel<Cfg>;
     if (!allow_lds(kern, Cfg::LDS_BYTES)) return false;
-    dim3 grid((unsigned)((N + Cfg::BN - 1) / Cfg::BN), (unsigned)L.splits);
-    hipLaunchKernelGGL(kern, grid, dim3(Cfg::NT), Cfg::LDS_BYTES, st, Wt, H, Hd, V, N, token_ids, L.v_per_split, partial);
+    dim3 grid(tile_grid((N + Cfg::BN - 1) / Cfg::BN, L.splits));
+    hipLaunchKernelGGL(kern, grid, dim3(Cfg::NT), Cfg::LDS_BYTES, st, Wt, H, Hd, V, N, token_ids, L.v_per_split, L.splits,
+                       partial);
     return true;
 }
 
@@ -575,7 +621,7 @@ bool launch_dz_cfg(const bf16_t* Wt, const bf16_t* H, int Hd, int V, int N, int 
 {
     auto kern = lmhead_dz_kernel<Cfg>;
     if (!allow_lds(kern, Cfg::LDS_BYTES)) return false;
-    dim3 grid((unsigned)((cw_pad + Cfg::BM - 1) / Cfg::BM), (unsigned)((L.ldt + Cfg::BN - 1) / Cfg::BN));
+    dim3 grid(tile_grid((cw_pad + Cfg::BM - 1) / Cfg::BM, (int)((L.ldt + Cfg::BN - 1) / Cfg::BN)));
     hipLaunchKernelGGL(kern, grid, dim3(Cfg::NT), Cfg::LDS_BYTES, st, Wt, H, Hd, V, N, vc0, cw_pad, token_ids, lse, gcoef,
                        grad_out, dZc, L.ldc, dZcT, L.ldt);
     return true;

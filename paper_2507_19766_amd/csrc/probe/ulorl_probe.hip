@@ -10,7 +10,11 @@
 // It prints HIP-event timings per call.  It exists because counter collection needs a process
 // that issues nothing but plain kernel dispatches.
 //
+// With --gemm M N K it instead times ulorl_gemm_tn_bf16 (the MFMA product of the lm_head variant)
+// on hashed operands, for matrix-core counters.
+//
 // usage: ulorl_probe [--rows N] [--vocab V] [--iters K] [--out-of-place] [--spike F]
+//        ulorl_probe --gemm M N K [--tile I] [--iters K]
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -72,6 +76,13 @@ __global__ void fill_kernel(uint16_t* z, int32_t* y, float* adv, int64_t N, int3
     }
 }
 
+__global__ void fill_bf16_kernel(uint16_t* p, int64_t n, uint64_t salt)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t step = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n; i += step) p[i] = to_bf16(rough_normal(mix(salt + (uint64_t)i)));
+}
+
 __global__ void perturb_kernel(const float* logp, float* old_logp, int64_t N)
 {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -103,7 +114,15 @@ int main(int argc, char** argv)
     int iters = 3;
     bool inplace = true;
     int spike = 400;
+    int64_t gm = 0, gn = 0, gk = 0;
+    int tile = -1;
     for (int i = 1; i < argc; ++i) {
+        if (!std::strcmp(argv[i], "--gemm") && i + 3 < argc) {
+            gm = std::atoll(argv[i + 1]); gn = std::atoll(argv[i + 2]); gk = std::atoll(argv[i + 3]);
+            i += 3;
+            continue;
+        }
+        if (!std::strcmp(argv[i], "--tile") && i + 1 < argc) { tile = std::atoi(argv[++i]); continue; }
         if (!std::strcmp(argv[i], "--rows") && i + 1 < argc) N = std::atoll(argv[++i]);
         else if (!std::strcmp(argv[i], "--vocab") && i + 1 < argc) V = std::atoll(argv[++i]);
         else if (!std::strcmp(argv[i], "--iters") && i + 1 < argc) iters = std::atoi(argv[++i]);
@@ -112,6 +131,30 @@ int main(int argc, char** argv)
         else { std::fprintf(stderr, "unknown argument %s\n", argv[i]); return 2; }
     }
     if (N <= 0 || V <= 0 || V % 8 != 0 || iters <= 0) { std::fprintf(stderr, "need N>0, V>0 multiple of 8\n"); return 2; }
+    if (gm > 0) {
+        if (tile >= 0 && ulorl_tune(ULORL_TUNE_GEMM_TILE, tile) != ULORL_OK) { std::fprintf(stderr, "bad tile\n"); return 2; }
+        uint16_t *a = nullptr, *b = nullptr;
+        float* c = nullptr;
+        CHECK(hipMalloc(&a, (size_t)gm * gk * 2)); CHECK(hipMalloc(&b, (size_t)gn * gk * 2)); CHECK(hipMalloc(&c, (size_t)gm * gn * 4));
+        hipLaunchKernelGGL(fill_bf16_kernel, dim3(4096), dim3(256), 0, 0, a, gm * gk, 11ULL << 40);
+        hipLaunchKernelGGL(fill_bf16_kernel, dim3(4096), dim3(256), 0, 0, b, gn * gk, 12ULL << 40);
+        CHECK(hipDeviceSynchronize());
+        hipEvent_t e0, e1;
+        CHECK(hipEventCreate(&e0)); CHECK(hipEventCreate(&e1));
+        double tot = 0;
+        for (int it = 0; it < iters + 1; ++it) {
+            CHECK(hipEventRecord(e0, 0));
+            const int rc = ulorl_gemm_tn_bf16(a, gk, b, gk, gm, gn, gk, c, gn, nullptr);
+            if (rc != ULORL_OK) { std::fprintf(stderr, "gemm: %s\n", ulorl_status_string(rc)); return 1; }
+            CHECK(hipEventRecord(e1, 0));
+            CHECK(hipDeviceSynchronize());
+            if (it > 0) tot += ms_between(e0, e1);
+        }
+        const double ms = tot / iters;
+        std::printf("gemm_tn_bf16 %lld x %lld x %lld tile %d: %.3f ms  %.1f TFLOP/s\n", (long long)gm, (long long)gn,
+                    (long long)gk, tile, ms, 2.0 * gm * gn * gk / ms / 1e9);
+        return 0;
+    }
 
     const size_t bytes = (size_t)N * (size_t)V * 2;
     uint16_t *z = nullptr, *pristine = nullptr, *dz = nullptr;

@@ -6,7 +6,9 @@
 //   1. plain_copy_kernel   reads N*V*2 bytes and writes N*V*2 bytes: the reference dispatch of
 //                          KNOWN size that hardware byte counters are scaled by;
 //   2. ulorl_token_loss_fwd   (row statistics + O(N) epilogue);
-//   3. ulorl_token_loss_bwd   (in place unless --out-of-place).
+//   3. ulorl_token_loss_bwd   (in place unless --out-of-place);
+//   4. plain_copy_kernel again (restores the logits), then ulorl_token_loss_fwd_bwd, the one-call
+//      fused path (in place unless --out-of-place).
 // It prints HIP-event timings per call.  It exists because counter collection needs a process
 // that issues nothing but plain kernel dispatches.
 //
@@ -189,9 +191,9 @@ int main(int argc, char** argv)
     hipLaunchKernelGGL(perturb_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, 0, logp, old_logp, N);
     CHECK(hipDeviceSynchronize());
 
-    hipEvent_t ev[4];
+    hipEvent_t ev[6];
     for (auto& e : ev) CHECK(hipEventCreate(&e));
-    double t_copy = 0, t_fwd = 0, t_bwd = 0;
+    double t_copy = 0, t_fwd = 0, t_bwd = 0, t_fused = 0;
     for (int it = 0; it < iters; ++it) {
         CHECK(hipEventRecord(ev[0], 0));
         hipLaunchKernelGGL(plain_copy_kernel, dim3(256 * 32), dim3(256), 0, 0, (const u32x4*)pristine, (u32x4*)z, nvec);
@@ -203,10 +205,18 @@ int main(int argc, char** argv)
         rc = ulorl_token_loss_bwd(z, ULORL_BF16, N, V, V, y, lse, g, 1.0f, inplace ? (void*)z : (void*)dz, nullptr);
         if (rc != ULORL_OK) { std::fprintf(stderr, "bwd: %s\n", ulorl_status_string(rc)); return 1; }
         CHECK(hipEventRecord(ev[3], 0));
+        hipLaunchKernelGGL(plain_copy_kernel, dim3(256 * 32), dim3(256), 0, 0, (const u32x4*)pristine, (u32x4*)z, nvec);
+        CHECK(hipEventRecord(ev[4], 0));
+        rc = ulorl_token_loss_fwd_bwd(z, ULORL_BF16, N, V, V, y, cu, 1, nullptr, old_logp, adv, &p, 1.0f, loss, logp, ent,
+                                      lse, g, nullptr, nullptr, nullptr, nullptr, nullptr, counters,
+                                      inplace ? (void*)z : (void*)dz, ws, ws_bytes, nullptr);
+        if (rc != ULORL_OK) { std::fprintf(stderr, "fwd_bwd: %s\n", ulorl_status_string(rc)); return 1; }
+        CHECK(hipEventRecord(ev[5], 0));
         CHECK(hipDeviceSynchronize());
         t_copy += ms_between(ev[0], ev[1]);
         t_fwd += ms_between(ev[1], ev[2]);
         t_bwd += ms_between(ev[2], ev[3]);
+        t_fused += ms_between(ev[4], ev[5]);
     }
     std::vector<float> gh(N);
     int64_t cnt[4];
@@ -227,5 +237,7 @@ int main(int argc, char** argv)
     const double bwd_gb = gb * (double)(N + live) / (double)N;
     std::printf("token_loss_bwd    : %8.3f ms  %7.1f GB/s  (%.3f GB algorithmic)\n", t_bwd / iters,
                 bwd_gb / (t_bwd / iters) * 1e3, bwd_gb);
+    std::printf("token_loss_fwd_bwd: %8.3f ms  %7.1f GB/s  (read %.3f GB + write %.3f GB)\n", t_fused / iters,
+                2 * gb / (t_fused / iters) * 1e3, gb, gb);
     return 0;
 }

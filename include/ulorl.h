@@ -251,6 +251,8 @@ typedef enum {
     ULORL_TUNE_BWD_UNROLL = 3,
     ULORL_TUNE_FUSED_THREADS = 4,
     ULORL_TUNE_FUSED_UNROLL = 5,
+    ULORL_TUNE_BWD_ONESHOT = 7,   /* 1 (default): standalone backward by one-shot 4 KB workgroups;
+                                     0: one looping workgroup per row (BWD_THREADS / BWD_UNROLL apply) */
     ULORL_TUNE_GEMM_TILE = 6      /* lm_head variant, block tile M x N x K / waves along M x N:
                                      0 = 128x128x64 / 2x2, 1 = 256x256x32 / 2x2, 2 = 256x256x64 / 2x2,
                                      3 = 256x128x64 / 2x2, 4 = 256x256x64 / 2x4, 5 = 256x256x64 / 4x2

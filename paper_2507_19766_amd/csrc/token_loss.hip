@@ -288,35 +288,40 @@ __device__ __forceinline__ void dlogits_core(const typename Tr::elem* rowp, type
     const float sgn = g > 0.0f ? -1.0f : 1.0f;
     const int yvec = y / E;
 
-    int i = tid;
-    for (; i + (U - 1) * NT < nvec; i += U * NT) {
-        u32x4 v[U];
-#pragma unroll
-        for (int k = 0; k < U; ++k) v[k] = load_stream(vp + i + k * NT);
-#pragma unroll
-        for (int k = 0; k < U; ++k) {
-            float f[E];
-            Tr::unpack(v[k], f);
-#pragma unroll
-            for (int e = 0; e < E; ++e) f[e] = sgn * fast_exp2(fmaf(f[e], kLog2e, c));
-            if (i + k * NT == yvec) {
-#pragma unroll
-                for (int e = 0; e < E; ++e) f[e] += (e == y - yvec * E) ? g : 0.0f;
-            }
-            store_stream(op + i + k * NT, Tr::pack(f));
-        }
-    }
-    for (; i < nvec; i += NT) {
+    // Software-pipelined: the loads of trip i+1 are issued BEFORE the stores of trip i.  On this
+    // ISA loads and stores share one outstanding-operation counter that retires in issue order,
+    // so a load issued after a store cannot be waited for without also waiting for that store to
+    // be acknowledged by memory; with the loads ahead, a trip never waits on write latency.
+    auto emit = [&](const u32x4& v, int vec_index) {
         float f[E];
-        Tr::unpack(load_stream(vp + i), f);
+        Tr::unpack(v, f);
 #pragma unroll
         for (int e = 0; e < E; ++e) f[e] = sgn * fast_exp2(fmaf(f[e], kLog2e, c));
-        if (i == yvec) {
+        if (vec_index == yvec) {
 #pragma unroll
             for (int e = 0; e < E; ++e) f[e] += (e == y - yvec * E) ? g : 0.0f;
         }
-        store_stream(op + i, Tr::pack(f));
+        store_stream(op + vec_index, Tr::pack(f));
+    };
+    int i = tid;
+    if (i + (U - 1) * NT < nvec) {
+        u32x4 cur[U];
+#pragma unroll
+        for (int k = 0; k < U; ++k) cur[k] = load_stream(vp + i + k * NT);
+        for (; i + (2 * U - 1) * NT < nvec; i += U * NT) {
+            u32x4 nxt[U];
+#pragma unroll
+            for (int k = 0; k < U; ++k) nxt[k] = load_stream(vp + i + (U + k) * NT);
+#pragma unroll
+            for (int k = 0; k < U; ++k) emit(cur[k], i + k * NT);
+#pragma unroll
+            for (int k = 0; k < U; ++k) cur[k] = nxt[k];
+        }
+#pragma unroll
+        for (int k = 0; k < U; ++k) emit(cur[k], i + k * NT);
+        i += U * NT;
     }
+    for (; i < nvec; i += NT) emit(load_stream(vp + i), i);
     if (tid == NT - 1) {
         for (int j = nvec * E; j < V; ++j) {
             float x = sgn * fast_exp2(fmaf(Tr::load1(rowp + j), kLog2e, c));
@@ -348,6 +353,65 @@ __global__ __launch_bounds__(NT) void dlogits_kernel(const typename Tr::elem* lo
     const float l = lse[row];
     const int32_t y = token_ids[row];
     dlogits_core<Tr, NT, U>(logits + row * row_stride, dlogits + row * row_stride, V, row_is_live(g, l, y, V), g, l, y);
+}
+
+// The same gradient by one-shot workgroups: 256 threads, one 16-byte vector per thread, 4 KB of
+// one row per workgroup, consecutive workgroups on consecutive addresses.  Measured on MI355X, a
+// read-modify-write stream moves 6.5 TB/s this way against 5.1 TB/s when each workgroup loops
+// over a whole row (the concurrent writes then spread over thousands of rows), so the standalone
+// backward uses this shape; the fused kernel cannot (its row needs one owner for the reduction).
+// grid = (chunks per row, rows mod 32768, rows / 32768).
+template <class Tr>
+__global__ __launch_bounds__(256) void dlogits_chunk_kernel(const typename Tr::elem* logits, int64_t row_stride,
+                                                            int32_t V, int64_t N,
+                                                            const int32_t* __restrict__ token_ids,
+                                                            const float* __restrict__ lse,
+                                                            const float* __restrict__ gcoef, float grad_out,
+                                                            typename Tr::elem* dlogits,
+                                                            const uint8_t* __restrict__ only)
+{
+    constexpr int E = Tr::kPerVec;
+    const int64_t row = (int64_t)blockIdx.z * 32768 + blockIdx.y;
+    if (row >= N) return;
+    if (only != nullptr && only[row] == 0) return;
+    const float g = gcoef[row] * grad_out;
+    const float l = lse[row];
+    const int32_t y = token_ids[row];
+    const bool live = row_is_live(g, l, y, V);
+    const typename Tr::elem* rowp = logits + row * row_stride;
+    typename Tr::elem* outp = dlogits + row * row_stride;
+    const int nvec = V / E;
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    const float c = live ? fmaf(-l, kLog2e, log2f(fabsf(g))) : 0.0f;
+    const float sgn = g > 0.0f ? -1.0f : 1.0f;
+    if (i < nvec) {
+        u32x4* op = reinterpret_cast<u32x4*>(outp) + i;
+        if (!live) {
+            const u32x4 zero = {0u, 0u, 0u, 0u};
+            store_stream(op, zero);
+        } else {
+            float f[E];
+            Tr::unpack(load_stream(reinterpret_cast<const u32x4*>(rowp) + i), f);
+#pragma unroll
+            for (int e = 0; e < E; ++e) f[e] = sgn * fast_exp2(fmaf(f[e], kLog2e, c));
+            const int yvec = y / E;
+            if (i == yvec) {
+#pragma unroll
+                for (int e = 0; e < E; ++e) f[e] += (e == y - yvec * E) ? g : 0.0f;
+            }
+            store_stream(op, Tr::pack(f));
+        }
+    }
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 255) {   // ragged tail of the row
+        for (int j = nvec * E; j < V; ++j) {
+            float x = 0.0f;
+            if (live) {
+                x = sgn * fast_exp2(fmaf(Tr::load1(rowp + j), kLog2e, c));
+                if (j == y) x += g;
+            }
+            Tr::store1(outp + j, x);
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -696,6 +760,7 @@ struct Tuning {
     int bwd_threads = 256, bwd_unroll = 4;
     int fused_threads = 512, fused_unroll = 8;
     int gemm_tile = 5;
+    int bwd_oneshot = 1;   // standalone backward by one-shot 4 KB workgroups (0: one looping workgroup per row)
 };
 Tuning g_tune;
 
@@ -751,6 +816,16 @@ template <class Tr>
 bool dispatch_dlogits(int nt, int u, const void* logits, int64_t N, int64_t V, int64_t stride, const int32_t* y,
                       const float* lse, const float* g, float grad_out, void* dz, const uint8_t* only, hipStream_t st)
 {
+    if (g_tune.bwd_oneshot) {
+        const int64_t nvec = V / Tr::kPerVec;
+        const int64_t chunks = nvec > 0 ? (nvec + 255) / 256 : 1;
+        if (chunks <= 0x7fffffffLL) {
+            dim3 grid((unsigned)chunks, (unsigned)(N < 32768 ? N : 32768), (unsigned)((N + 32767) / 32768));
+            hipLaunchKernelGGL((dlogits_chunk_kernel<Tr>), grid, dim3(256), 0, st, (const typename Tr::elem*)logits, stride,
+                               (int32_t)V, N, y, lse, g, grad_out, (typename Tr::elem*)dz, only);
+            return true;
+        }
+    }
 #define ULORL_CASE(NT_, U_)                                                                    \
     if (nt == NT_ && u == U_) {                                                                \
         launch_dlogits<Tr, NT_, U_>(logits, N, V, stride, y, lse, g, grad_out, dz, only, st);  \
@@ -885,6 +960,7 @@ int32_t ulorl_tune(int32_t knob, int32_t value)
     case ULORL_TUNE_BWD_UNROLL:  if (!unroll_ok) return ULORL_ERR_PARAM;  g_tune.bwd_unroll = value;  return ULORL_OK;
     case ULORL_TUNE_FUSED_THREADS: if (!threads_ok) return ULORL_ERR_PARAM; g_tune.fused_threads = value; return ULORL_OK;
     case ULORL_TUNE_FUSED_UNROLL:  if (!unroll_ok) return ULORL_ERR_PARAM;  g_tune.fused_unroll = value;  return ULORL_OK;
+    case ULORL_TUNE_BWD_ONESHOT: if (value != 0 && value != 1) return ULORL_ERR_PARAM; g_tune.bwd_oneshot = value; return ULORL_OK;
     case ULORL_TUNE_GEMM_TILE: if (value < 0 || value > 5) return ULORL_ERR_PARAM; g_tune.gemm_tile = value; return ULORL_OK;
     default: return ULORL_ERR_PARAM;
     }

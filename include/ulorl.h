@@ -237,6 +237,54 @@ int32_t ulorl_lmhead_token_loss_bwd(
 int32_t ulorl_gemm_tn_bf16(const void *A, int64_t lda, const void *B, int64_t ldb,
                            int64_t M, int64_t N, int64_t K, float *C, int64_t ldc, void *hip_stream);
 
+/* ------------------------------------------------------------------------------------------
+ * The step before the token loss: group-relative advantages (Eq. 4) with the dynamic-sampling
+ * constraint of Eq. 7 and the overlong punishment of Sec. 3.5.  Responses come in consecutive
+ * groups of group_size (the G samples of one prompt); R must be a multiple of group_size.
+ *   rewards      [R]  outcome reward of each response, {0, 1} in the paper (Sec. 3.3)
+ *   truncated    [R]  uint8, non-zero if the response hit the global length limit: its reward
+ *                     counts as 0 (Sec. 3.5).  May be NULL.
+ *   eps          added to the group's standard deviation (Eq. 4 has none; 0 is allowed)
+ *   unbiased     0: population standard deviation (divide by G); 1: divide by G - 1
+ * Outputs:
+ *   resp_adv     [R]  A_i = (r_i - mean_g) / (std_g + eps), or 0 for every response of a group in
+ *                     which all or none of the answers are correct (such groups are dropped)
+ *   group_keep   [R / group_size] uint8, may be NULL
+ *   token_adv    [N]  A_i broadcast over the tokens of response i: the `advantages` input of the
+ *                     token-loss calls
+ *   kept_tokens  [1]  int64, tokens in kept groups: the denominator 1 / sum |o_i| of the filtered
+ *                     batch (pass it as ulorl_params.denominator).  May be NULL.
+ */
+int32_t ulorl_advantage_prep(
+    const float *rewards, const uint8_t *truncated, const int32_t *cu_seqlens, int32_t R,
+    int32_t group_size, int64_t N, float eps, int32_t unbiased,
+    float *resp_adv, uint8_t *group_keep, float *token_adv, int64_t *kept_tokens, void *hip_stream);
+
+/*
+ * Training-dynamics diagnostics per segment id, from the outputs of a forward call: the
+ * quantities behind the comparison of the importance-sampling schemes in Sec. 3.1.2 (how far the
+ * ratio of older segments has drifted, how much of each segment is clipped) and the entropy
+ * curves of Sec. 3.2.  For every k in [0, K):
+ *   count[k]      int64   tokens with segment id k
+ *   ratio_sum[k]  double  sum of r_t            ratio_max[k]  float   largest r_t
+ *   clipped[k]    int64   tokens on the clipped, gradient-free branch of the min
+ *   kl_sum[k]     double  sum of (old_logp_t - logp_t): sampled estimate of KL(pi_old || pi_theta) * count
+ *   ent_sum[k]    double  sum of token entropies
+ *   masked[k]     int64   tokens removed by the MPT mask
+ * out_of_range [1] int64 (may be NULL) counts tokens whose id is outside [0, K); they are ignored.
+ * old_logp may be NULL (POIS): kl_sum is then 0.  Sums are fixed-order fp64: bitwise reproducible.
+ * K <= 4096.  The workspace size comes from ulorl_segment_diagnostics_workspace_bytes.
+ */
+size_t ulorl_segment_diagnostics_workspace_bytes(int64_t N, int32_t K);
+
+int32_t ulorl_segment_diagnostics(
+    int64_t N, int32_t K, const int32_t *segment_ids, const float *ratio, const float *logp,
+    const float *old_logp, const float *entropy, const uint8_t *mpt_mask, const float *advantages,
+    float eps_low, float eps_high,
+    int64_t *count, double *ratio_sum, float *ratio_max, int64_t *clipped, double *kl_sum,
+    double *ent_sum, int64_t *masked, int64_t *out_of_range,
+    void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /*
  * Launch-shape knobs of the streaming kernels (process-wide, HOST state; not thread
  * safe against concurrent calls).  Results do not depend on them beyond summation order.

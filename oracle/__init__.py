@@ -184,3 +184,51 @@ def lmhead_grads(hidden_raw: np.ndarray, weight_raw: np.ndarray, dz: np.ndarray)
     h = bf16_to_f64(hidden_raw)
     w = bf16_to_f64(weight_raw)
     return dz @ w.T, h.T @ dz
+
+
+# ------------------------------------------------------------------------------------ neighbours of the hot path
+
+def advantages(rewards, cu_seqlens, group_size, truncated=None, eps=1e-6, unbiased=False):
+    """Group-relative advantages with the dynamic-sampling filter and overlong punishment.
+    -> (resp_adv [R], group_keep [R/G], token_adv [N], kept_tokens)."""
+    rew = np.ascontiguousarray(rewards, np.float64)
+    R = rew.shape[0]
+    cu = np.ascontiguousarray(cu_seqlens, np.int32)
+    N = int(cu[-1])
+    tr = None if truncated is None else np.ascontiguousarray(truncated, np.uint8)
+    resp = np.empty(R, np.float64)
+    keep = np.empty(max(R // max(group_size, 1), 1), np.uint8)
+    tok = np.empty(N, np.float64)
+    kept = ctypes.c_int64(0)
+    lib = _load()
+    lib.ulorl_oracle_advantages.restype = ctypes.c_int
+    rc = lib.ulorl_oracle_advantages(
+        ctypes.c_int32(R), ctypes.c_int32(group_size), _ptr(rew), _ptr(tr), _ptr(cu), ctypes.c_int64(N),
+        ctypes.c_double(eps), ctypes.c_int(1 if unbiased else 0), _ptr(resp), _ptr(keep), _ptr(tok),
+        ctypes.byref(kept))
+    if rc != 0:
+        raise ValueError("oracle advantages: rc=%d" % rc)
+    return resp, keep[:R // group_size], tok, int(kept.value)
+
+
+def segment_diagnostics(seg, ratio, logp, old_logp, entropy, mask, advantages, K, eps_low=0.2, eps_high=0.2):
+    """-> dict of per-segment arrays (count, ratio_sum, ratio_max, clipped, kl_sum, ent_sum, masked)
+    and the number of tokens with a segment id outside [0, K)."""
+    seg = np.ascontiguousarray(seg, np.int32)
+    N = seg.shape[0]
+    f = lambda a: None if a is None else np.ascontiguousarray(a, np.float64)
+    ratio, logp, old_logp, entropy, adv = f(ratio), f(logp), f(old_logp), f(entropy), f(advantages)
+    mask = np.ascontiguousarray(mask, np.uint8)
+    out = {"count": np.zeros(K, np.int64), "ratio_sum": np.zeros(K), "ratio_max": np.zeros(K),
+           "clipped": np.zeros(K, np.int64), "kl_sum": np.zeros(K), "ent_sum": np.zeros(K),
+           "masked": np.zeros(K, np.int64)}
+    oor = ctypes.c_int64(0)
+    lib = _load()
+    lib.ulorl_oracle_segment_diagnostics.restype = ctypes.c_int
+    lib.ulorl_oracle_segment_diagnostics(
+        ctypes.c_int64(N), ctypes.c_int32(K), _ptr(seg), _ptr(ratio), _ptr(logp), _ptr(old_logp), _ptr(entropy),
+        _ptr(mask), _ptr(adv), ctypes.c_double(eps_low), ctypes.c_double(eps_high), _ptr(out["count"]),
+        _ptr(out["ratio_sum"]), _ptr(out["ratio_max"]), _ptr(out["clipped"]), _ptr(out["kl_sum"]),
+        _ptr(out["ent_sum"]), _ptr(out["masked"]), ctypes.byref(oor))
+    out["out_of_range"] = int(oor.value)
+    return out

@@ -233,3 +233,96 @@ int ulorl_oracle_threads(void)
     }
     return n;
 }
+
+/*
+ * Advantage preparation, the step just before the token loss (Sec. 2.2 Eq. 4, Eq. 7 constraint,
+ * Sec. 3.3, Sec. 3.5).  Responses come in consecutive groups of G (one group per prompt).
+ *   effective reward   r_i = truncated_i ? 0 : reward_i          overlong samples count as wrong
+ *   group statistics   mean_g, std_g over the G effective rewards (population std, or the
+ *                      unbiased one if `unbiased`)
+ *   dynamic sampling   a group is kept iff 0 < #{r_i > 0} < G      (Eq. 7 constraint)
+ *   advantage          A_i = keep_g ? (r_i - mean_g) / (std_g + eps) : 0      (Eq. 4)
+ *   broadcast          token_adv[t] = A_i for every token t of response i
+ * kept_tokens = number of tokens in kept groups (the 1 / sum |o_i| of the filtered batch).
+ * Returns 0, -2 on malformed cu_seqlens, -3 if R is not a multiple of G.
+ */
+int ulorl_oracle_advantages(int32_t R, int32_t G, const double *rewards, const uint8_t *truncated,
+                            const int32_t *cu_seqlens, int64_t N, double eps, int unbiased,
+                            double *resp_adv, uint8_t *group_keep, double *token_adv,
+                            int64_t *kept_tokens)
+{
+    if (G <= 0 || R % G != 0) return -3;
+    if (cu_seqlens[0] != 0 || cu_seqlens[R] != N) return -2;
+    for (int32_t i = 0; i < R; ++i)
+        if (cu_seqlens[i + 1] < cu_seqlens[i]) return -2;
+    int64_t kept = 0;
+    for (int32_t g0 = 0; g0 < R; g0 += G) {
+        double sum = 0.0;
+        int correct = 0;
+        for (int32_t i = g0; i < g0 + G; ++i) {
+            const double r = (truncated && truncated[i]) ? 0.0 : rewards[i];
+            sum += r;
+            correct += r > 0.0;
+        }
+        const double mean = sum / G;
+        double ss = 0.0;
+        for (int32_t i = g0; i < g0 + G; ++i) {
+            const double r = (truncated && truncated[i]) ? 0.0 : rewards[i];
+            ss += (r - mean) * (r - mean);
+        }
+        const double denom = unbiased ? (G > 1 ? G - 1 : 1) : G;
+        const double sd = sqrt(ss / denom);
+        const int keep = correct > 0 && correct < G;
+        if (group_keep) group_keep[g0 / G] = (uint8_t)keep;
+        for (int32_t i = g0; i < g0 + G; ++i) {
+            const double r = (truncated && truncated[i]) ? 0.0 : rewards[i];
+            const double a = keep ? (r - mean) / (sd + eps) : 0.0;
+            if (resp_adv) resp_adv[i] = a;
+            for (int64_t t = cu_seqlens[i]; t < cu_seqlens[i + 1]; ++t) token_adv[t] = a;
+            if (keep) kept += cu_seqlens[i + 1] - cu_seqlens[i];
+        }
+    }
+    if (kept_tokens) *kept_tokens = kept;
+    return 0;
+}
+
+/*
+ * Training-dynamics diagnostics per segment id (the quantities behind the paper's SAIS / POIS
+ * comparison, Sec. 3.1.2, and its entropy curves, Sec. 3.2): for every segment id k < K
+ *   count[k]      tokens whose segment id is k
+ *   ratio_sum[k]  sum of importance ratios          ratio_max[k]  largest ratio
+ *   clipped[k]    tokens on the clipped, gradient-free branch of the min
+ *   kl_sum[k]     sum of (old_logp - logp): the sampled estimate of KL(pi_old || pi_theta)
+ *   ent_sum[k]    sum of token entropies            masked[k]     tokens removed by the MPT mask
+ * Tokens with a segment id outside [0, K) are counted in *out_of_range and otherwise ignored.
+ */
+int ulorl_oracle_segment_diagnostics(int64_t N, int32_t K, const int32_t *seg, const double *ratio,
+                                     const double *logp, const double *old_logp, const double *entropy,
+                                     const uint8_t *mask, const double *advantages, double eps_low,
+                                     double eps_high, int64_t *count, double *ratio_sum,
+                                     double *ratio_max, int64_t *clipped, double *kl_sum,
+                                     double *ent_sum, int64_t *masked, int64_t *out_of_range)
+{
+    for (int32_t k = 0; k < K; ++k) {
+        count[k] = 0; ratio_sum[k] = 0.0; ratio_max[k] = 0.0; clipped[k] = 0;
+        kl_sum[k] = 0.0; ent_sum[k] = 0.0; masked[k] = 0;
+    }
+    int64_t oor = 0;
+    for (int64_t t = 0; t < N; ++t) {
+        const int32_t k = seg[t];
+        if (k < 0 || k >= K) { ++oor; continue; }
+        const double r = ratio[t], A = advantages[t];
+        double c = r;
+        if (c < 1.0 - eps_low) c = 1.0 - eps_low;
+        if (c > 1.0 + eps_high) c = 1.0 + eps_high;
+        count[k] += 1;
+        ratio_sum[k] += r;
+        if (r > ratio_max[k]) ratio_max[k] = r;
+        clipped[k] += !(r * A <= c * A);
+        kl_sum[k] += old_logp ? old_logp[t] - logp[t] : 0.0;
+        ent_sum[k] += entropy[t];
+        masked[k] += mask[t] != 0;
+    }
+    *out_of_range = oor;
+    return 0;
+}

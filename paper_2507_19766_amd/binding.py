@@ -115,6 +115,14 @@ def load_library(build_if_missing: bool = True):
         vp, vp, c.c_int64, c.c_int64, c.c_int64, c.c_int32, vp, vp, vp, c.c_float, vp, vp, vp, c.c_size_t, vp]
     lib.ulorl_gemm_tn_bf16.restype = c.c_int32
     lib.ulorl_gemm_tn_bf16.argtypes = [vp, c.c_int64, vp, c.c_int64, c.c_int64, c.c_int64, c.c_int64, vp, c.c_int64, vp]
+    lib.ulorl_advantage_prep.restype = c.c_int32
+    lib.ulorl_advantage_prep.argtypes = [vp, vp, vp, c.c_int32, c.c_int32, c.c_int64, c.c_float, c.c_int32,
+                                         vp, vp, vp, vp, vp]
+    lib.ulorl_segment_diagnostics_workspace_bytes.restype = c.c_size_t
+    lib.ulorl_segment_diagnostics_workspace_bytes.argtypes = [c.c_int64, c.c_int32]
+    lib.ulorl_segment_diagnostics.restype = c.c_int32
+    lib.ulorl_segment_diagnostics.argtypes = [c.c_int64, c.c_int32, vp, vp, vp, vp, vp, vp, vp, c.c_float, c.c_float,
+                                              vp, vp, vp, vp, vp, vp, vp, vp, vp, c.c_size_t, vp]
     lib.ulorl_token_loss_bwd.restype = c.c_int32
     lib.ulorl_token_loss_bwd.argtypes = [
         vp, c.c_int32, c.c_int64, c.c_int64, c.c_int64, vp, vp, vp, c.c_float, vp, vp]
@@ -401,4 +409,53 @@ def gemm_tn_bf16(a: torch.Tensor, b: torch.Tensor, out: Optional[torch.Tensor] =
     rc = lib.ulorl_gemm_tn_bf16(_p(a), a.stride(0), _p(b), b.stride(0), M, N, K, _p(out), out.stride(0), _stream(a.device))
     if rc != 0:
         raise UlorlError(rc, "ulorl_gemm_tn_bf16")
+    return out
+
+
+# ------------------------------------------------------------------------------------ neighbours of the hot path
+
+def advantage_prep(rewards, cu_seqlens, group_size: int, truncated=None, eps: float = 1e-6, unbiased: bool = False):
+    """ulorl_advantage_prep -> (resp_adv [R], group_keep [R/G], token_adv [N], kept_tokens [1] int64)."""
+    lib = load_library()
+    dev = rewards.device
+    if not rewards.is_cuda:
+        raise RuntimeError("libulorl runs on the GPU only")
+    R = rewards.shape[0]
+    rewards = _vec(rewards, torch.float32, R, "rewards", dev)
+    truncated = _vec(truncated, torch.uint8, R, "truncated", dev)
+    if cu_seqlens.device != dev or cu_seqlens.dtype != torch.int32 or cu_seqlens.shape[0] != R + 1:
+        raise ValueError("cu_seqlens must be int32 [R+1] on the same device")
+    N = int(cu_seqlens[-1].item())
+    resp = torch.empty(R, dtype=torch.float32, device=dev)
+    keep = torch.empty(max(R // max(group_size, 1), 1), dtype=torch.uint8, device=dev)
+    tok = torch.empty(N, dtype=torch.float32, device=dev)
+    kept = torch.empty(1, dtype=torch.int64, device=dev)
+    rc = lib.ulorl_advantage_prep(_p(rewards), _p(truncated), _p(cu_seqlens), R, group_size, N, float(eps),
+                                  1 if unbiased else 0, _p(resp), _p(keep), _p(tok), _p(kept), _stream(dev))
+    if rc != 0:
+        raise UlorlError(rc, "ulorl_advantage_prep")
+    return resp, keep[:R // group_size], tok, kept
+
+
+def segment_diagnostics(res: FwdResult, advantages, old_logp, K: int, eps_low: float = 0.2, eps_high: float = 0.2,
+                        segment_ids=None):
+    """ulorl_segment_diagnostics on the outputs of a forward call -> dict of per-segment tensors."""
+    lib = load_library()
+    seg = res.segment_out if segment_ids is None else segment_ids
+    dev = seg.device
+    N = seg.shape[0]
+    i64 = dict(dtype=torch.int64, device=dev)
+    f64 = dict(dtype=torch.float64, device=dev)
+    out = {"count": torch.empty(K, **i64), "ratio_sum": torch.empty(K, **f64),
+           "ratio_max": torch.empty(K, dtype=torch.float32, device=dev), "clipped": torch.empty(K, **i64),
+           "kl_sum": torch.empty(K, **f64), "ent_sum": torch.empty(K, **f64), "masked": torch.empty(K, **i64),
+           "out_of_range": torch.empty(1, **i64)}
+    ws = torch.empty(max(int(lib.ulorl_segment_diagnostics_workspace_bytes(N, K)), 256), dtype=torch.uint8, device=dev)
+    rc = lib.ulorl_segment_diagnostics(
+        N, K, _p(seg), _p(res.ratio), _p(res.logp), _p(old_logp), _p(res.entropy), _p(res.mpt_mask), _p(advantages),
+        float(eps_low), float(eps_high), _p(out["count"]), _p(out["ratio_sum"]), _p(out["ratio_max"]),
+        _p(out["clipped"]), _p(out["kl_sum"]), _p(out["ent_sum"]), _p(out["masked"]), _p(out["out_of_range"]),
+        _p(ws), ws.numel(), _stream(dev))
+    if rc != 0:
+        raise UlorlError(rc, "ulorl_segment_diagnostics")
     return out

@@ -1,0 +1,94 @@
+"""GPU parity of the two O(N) neighbours of the token loss: advantage preparation and
+per-segment diagnostics."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2507_19766_amd as ulorl
+import ulorl_inputs as ui
+from parity import params_for
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.mark.parametrize("G,unbiased", [(8, False), (4, True), (1, False)])
+def test_advantage_prep_matches_the_oracle(G, unbiased):
+    rs = np.random.RandomState(G)
+    R = 8 * 40
+    lengths = rs.randint(1, 300, size=R)
+    lengths[5] = 0                                          # an empty response is legal
+    cu = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32)
+    rewards = (rs.rand(R) < 0.45).astype(np.float32)
+    rewards[:G] = 1.0                                       # one all-correct group
+    rewards[G:2 * G] = 0.0                                  # one all-wrong group
+    trunc = (rs.rand(R) < 0.1).astype(np.uint8)
+    resp, keep, tok, kept = ulorl.advantage_prep(torch.tensor(rewards, device=DEV), torch.tensor(cu, device=DEV), G,
+                                                 truncated=torch.tensor(trunc, device=DEV), eps=1e-6, unbiased=unbiased)
+    o_resp, o_keep, o_tok, o_kept = oracle.advantages(rewards, cu, G, truncated=trunc, eps=float(np.float32(1e-6)),
+                                                      unbiased=unbiased)
+    np.testing.assert_array_equal(keep.cpu().numpy(), o_keep)
+    assert int(kept.item()) == o_kept
+    np.testing.assert_allclose(resp.cpu().numpy(), o_resp, rtol=1e-6, atol=0)
+    np.testing.assert_allclose(tok.cpu().numpy(), o_tok, rtol=1e-6, atol=0)
+    assert np.all(resp.cpu().numpy()[o_resp == 0.0] == 0.0)
+    if G > 1:
+        assert 0 < o_keep.sum() < len(o_keep)
+
+
+def test_prepared_advantages_feed_the_token_loss():
+    """rewards -> advantages -> loss, all on the device, against the oracle chain."""
+    w = ui.shrink(ui.config(2), [60, 45, 80, 30, 50, 50, 20, 70], V=4096, seg_len=32, name="chain")
+    d = ui.generate(w, DEV)
+    rewards = np.array([1, 0, 0, 1, 1, 1, 1, 1], np.float32)         # second group is all-correct: dropped
+    cu = w.cu_seqlens
+    resp, keep, tok, kept = ulorl.advantage_prep(torch.tensor(rewards, device=DEV), d["cu_seqlens"], 4, eps=0.0)
+    p = params_for(w, gate_mode=ulorl.GATE_ALWAYS, denominator=float(kept.item()))
+    res = ulorl.token_loss_fwd(d["logits"], d["token_ids"], d["cu_seqlens"], tok, d["old_logp"], p)
+    _, _, o_tok, o_kept = oracle.advantages(rewards, cu, 4, eps=0.0)
+    assert o_kept == 60 + 45 + 80 + 30
+    lse, logp, H = oracle.row_stats(ui.to_numpy_logits(d["logits"]), d["token_ids"].cpu().numpy())
+    tt = oracle.token_terms(logp, H, cu, o_tok.astype(np.float32), d["old_logp"].cpu().numpy(), seg_len=32,
+                            gate_mode=oracle.GATE_ALWAYS, denominator=float(o_kept), eps_low=float(np.float32(0.2)),
+                            eps_high=float(np.float32(0.2)), tau=float(np.float32(0.99)))
+    np.testing.assert_allclose(res.loss.item(), tt.loss, rtol=2e-5, atol=1e-7)
+    assert torch.all(res.gcoef[215:] == 0)                           # dropped group: no gradient
+
+
+def test_segment_diagnostics_match_the_oracle():
+    w = ui.shrink(ui.config(4), [3000], V=4096, seg_len=400, name="diag")          # 8 segments, growing staleness
+    d = ui.generate(w, DEV)
+    p = params_for(w, gate_mode=ulorl.GATE_ALWAYS, tau=0.5)
+    res = ulorl.token_loss_fwd(d["logits"], d["token_ids"], d["cu_seqlens"], d["advantages"], d["old_logp"], p)
+    K = 8
+    g = ulorl.segment_diagnostics(res, d["advantages"], d["old_logp"], K)
+    g2 = ulorl.segment_diagnostics(res, d["advantages"], d["old_logp"], K)
+    for k in g:
+        assert torch.equal(g[k], g2[k])                                             # reproducible
+    # the oracle side is computed from the oracle's own per-token quantities (never from GPU outputs)
+    lse, logp, H = oracle.row_stats(ui.to_numpy_logits(d["logits"]), d["token_ids"].cpu().numpy())
+    adv = d["advantages"].cpu().numpy()
+    old = d["old_logp"].cpu().numpy()
+    f32 = lambda x: float(np.float32(x))
+    tt = oracle.token_terms(logp, H, w.cu_seqlens, adv, old, seg_len=400, gate_mode=oracle.GATE_ALWAYS,
+                            eps_low=f32(0.2), eps_high=f32(0.2), tau=f32(0.5))
+    o = oracle.segment_diagnostics(tt.seg, tt.ratio, logp, old, H, tt.mask, adv, K, eps_low=f32(0.2), eps_high=f32(0.2))
+    near_edge = int(((np.abs(tt.ratio - 0.8) < 1e-5) | (np.abs(tt.ratio - 1.2) < 1e-5)).sum())
+    near_tau = int((np.abs(np.exp(logp) - 0.5) < 1e-6).sum())
+    np.testing.assert_array_equal(g["count"].cpu().numpy(), o["count"])
+    assert np.abs(g["clipped"].cpu().numpy() - o["clipped"]).sum() <= near_edge
+    assert np.abs(g["masked"].cpu().numpy() - o["masked"]).sum() <= near_tau
+    assert o["masked"].sum() > 0 and o["clipped"].sum() > 0
+    for name in ("ratio_sum", "ent_sum"):
+        np.testing.assert_allclose(g[name].cpu().numpy(), o[name], rtol=2e-5)
+    np.testing.assert_allclose(g["kl_sum"].cpu().numpy(), o["kl_sum"], rtol=2e-5, atol=2e-6 * 400)
+    np.testing.assert_allclose(g["ratio_max"].cpu().numpy(), o["ratio_max"], rtol=2e-5)
+    assert int(g["out_of_range"].item()) == 0 and o["count"].sum() == 3000
+    # later segments are staler: their mean |log ratio| grows (0.02 * segment index of noise)
+    mean_ratio = o["ratio_sum"] / o["count"]
+    assert abs(mean_ratio[0] - 1.0) < 1e-5 and o["clipped"][7] >= o["clipped"][1]
+    # ids outside [0, K) are counted and ignored; POIS has no old log-probs
+    g3 = ulorl.segment_diagnostics(res, d["advantages"], None, 4)
+    assert int(g3["out_of_range"].item()) == 3000 - 1600 and float(g3["kl_sum"].abs().sum()) == 0.0
+    np.testing.assert_array_equal(g3["count"].cpu().numpy(), o["count"][:4])

@@ -500,3 +500,68 @@ def test_lmhead_logits_and_grads_against_loops_and_autograd():
     dh, dw = oracle.lmhead_grads(hr, wr, dz)
     np.testing.assert_allclose(dh, ht.grad.numpy(), rtol=1e-9, atol=1e-14)
     np.testing.assert_allclose(dw, wt.grad.numpy(), rtol=1e-9, atol=1e-14)
+
+
+# ----------------------------------------------------------------------------- neighbours of the hot path
+
+def test_group_advantages_closed_forms():
+    # G = 4 with binary rewards: k correct of 4 -> mean k/4, population std sqrt(k(4-k))/4
+    cu = np.arange(0, 9 * 3, 3)[:9]            # 8 responses of 3 tokens
+    cu = np.concatenate([[0], np.cumsum([3, 1, 2, 4, 3, 3, 3, 3])])
+    rewards = [1, 0, 0, 0,   1, 1, 1, 1]
+    resp, keep, tok, kept = oracle.advantages(rewards, cu, 4, eps=0.0)
+    sd = math.sqrt(3) / 4
+    np.testing.assert_allclose(resp[:4], [0.75 / sd, -0.25 / sd, -0.25 / sd, -0.25 / sd], rtol=1e-14)
+    assert list(keep) == [1, 0] and np.all(resp[4:] == 0.0)          # all-correct group is filtered
+    assert kept == 3 + 1 + 2 + 4
+    np.testing.assert_array_equal(tok[:3], resp[0])
+    np.testing.assert_array_equal(tok[3:4], resp[1])
+    assert np.all(tok[10:] == 0.0)
+    # advantages of a kept group sum to zero and have unit population variance
+    assert abs(resp[:4].sum()) < 1e-14 and abs((resp[:4] ** 2).mean() - 1.0) < 1e-14
+    # with {0,1} rewards in a mixed group: reward 1 <=> positive advantage (Sec. 3.3)
+    assert np.all((resp[:4] > 0) == (np.array(rewards[:4]) > 0))
+    # the library's group normalisation: torch.std unbiased / population
+    r = np.array([1.0, 0.0, 1.0, 0.0, 0.0, 0.0, 1.0, 0.0])
+    cu8 = np.arange(9)
+    for unbiased in (False, True):
+        a, k, _, _ = oracle.advantages(r, cu8, 8, eps=1e-6, unbiased=unbiased)
+        t = torch.tensor(r)
+        ref = (t - t.mean()) / (t.std(unbiased=unbiased) + 1e-6)
+        np.testing.assert_allclose(a, ref.numpy(), rtol=1e-13)
+    # overlong samples are scored as wrong: a correct but truncated answer gets the negative side
+    a, k, _, _ = oracle.advantages([1, 1, 0, 0], np.arange(5), 4, truncated=[1, 0, 0, 0], eps=0.0)
+    b, _, _, _ = oracle.advantages([0, 1, 0, 0], np.arange(5), 4, eps=0.0)
+    np.testing.assert_array_equal(a, b)
+    # all wrong after truncation -> group dropped
+    a, k, _, kept = oracle.advantages([1, 0], np.arange(3), 2, truncated=[1, 0], eps=0.0)
+    assert list(k) == [0] and kept == 0 and np.all(a == 0)
+    with pytest.raises(ValueError):
+        oracle.advantages([1, 0, 1], np.arange(4), 2)
+
+
+def test_segment_diagnostics_against_masks_and_library_sums():
+    rs = np.random.RandomState(8)
+    N, K = 500, 5
+    seg = rs.randint(-1, K + 1, size=N)
+    logp = -rs.exponential(1.0, size=N)
+    old = logp + rs.normal(0, 0.2, size=N)
+    ratio = np.exp(logp - old)
+    ent = rs.uniform(0, 5, size=N)
+    mask = rs.randint(0, 2, size=N)
+    adv = rs.choice([-1.0, 1.0], size=N)
+    d = oracle.segment_diagnostics(seg, ratio, logp, old, ent, mask, adv, K)
+    assert d["out_of_range"] == int(((seg < 0) | (seg >= K)).sum())
+    inactive = ((adv > 0) & (ratio > 1.2)) | ((adv < 0) & (ratio < 0.8))
+    for k in range(K):
+        m = seg == k
+        assert d["count"][k] == m.sum()
+        np.testing.assert_allclose(d["ratio_sum"][k], math.fsum(ratio[m]), rtol=1e-13)
+        assert d["ratio_max"][k] == ratio[m].max()
+        assert d["clipped"][k] == inactive[m].sum()
+        np.testing.assert_allclose(d["kl_sum"][k], math.fsum((old - logp)[m]), rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(d["ent_sum"][k], math.fsum(ent[m]), rtol=1e-13)
+        assert d["masked"][k] == mask[m].sum()
+    # on-policy data: every ratio is 1, nothing clipped, the KL estimate vanishes
+    d0 = oracle.segment_diagnostics(np.zeros(N, int), np.ones(N), logp, logp, ent, mask, adv, 1)
+    assert d0["ratio_sum"][0] == N and d0["clipped"][0] == 0 and d0["kl_sum"][0] == 0.0

@@ -303,8 +303,9 @@ typedef enum {
                                      0: one looping workgroup per row (BWD_THREADS / BWD_UNROLL apply) */
     ULORL_TUNE_GEMM_TILE = 6      /* lm_head variant, block tile M x N x K / waves along M x N:
                                      0 = 128x128x64 / 2x2, 1 = 256x256x32 / 2x2, 2 = 256x256x64 / 2x2,
-                                     3 = 256x128x64 / 2x2, 4 = 256x256x64 / 2x4, 5 = 256x256x64 / 4x2
-                                     (default 5) */
+                                     3 = 256x128x64 / 2x2, 4 = 256x256x64 / 2x4, 5 = 256x256x64 / 4x2,
+                                     6 = as 5 and 7 = as 4 with tiles copied global -> LDS directly
+                                     (default 7) */
 } ulorl_tune_knob;
 int32_t ulorl_tune(int32_t knob, int32_t value);
 

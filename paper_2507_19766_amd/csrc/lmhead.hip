@@ -48,9 +48,10 @@ __device__ __forceinline__ bf16_t to_bf16(float x) { return (bf16_t)(pack_bf16x2
 // ---------------------------------------------------------------------------------------------
 // tiled GEMM main loop
 // ---------------------------------------------------------------------------------------------
-template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_>
+template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, bool DIRECT_ = false>
 struct GemmCfg {
     static constexpr int BM = BM_, BN = BN_, BK = BK_;
+    static constexpr bool DIRECT = DIRECT_;                // global -> LDS without passing through registers
     static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
     static constexpr int NT = 64 * WAVES_M * WAVES_N;
     static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
@@ -63,6 +64,7 @@ struct GemmCfg {
     static constexpr int B_VECS = BN * VEC_PER_ROW / NT;
     static constexpr size_t LDS_BYTES = 2 * (size_t)(A_STAGE + B_STAGE) * sizeof(bf16_t);
     static_assert(WM % 32 == 0 && WN % 32 == 0 && BK % 16 == 0, "tile shape");
+    static_assert(!DIRECT || (BK == 64 && BM % (8 * (NT / 64)) == 0 && BN % (8 * (NT / 64)) == 0), "direct-to-LDS tile shape");
     static_assert((BM * VEC_PER_ROW) % NT == 0 && (BN * VEC_PER_ROW) % NT == 0, "load split");
 };
 
@@ -196,6 +198,124 @@ __device__ __forceinline__ void gemm_tn_mainloop(const bf16_t* __restrict__ A, i
     }
 }
 
+// The same product with the tiles copied global -> LDS by the load unit itself
+// (global_load_lds_dwordx4: lane L of a wave deposits its 16 bytes at lds_base + 16 L), so the
+// staging registers, the ds_write instructions and the wait between a load's return and its
+// write disappear from the loop.  A wave-instruction fills 64 consecutive 16-byte slots = 8 rows
+// of a BK = 64 tile; rows are therefore unpadded, and bank conflicts are avoided by storing vector
+// kv of row r in slot (kv xor (r mod 8)) of that row (each lane simply fetches from global the
+// vector that belongs in its slot).  Needs K to be a multiple of BK.
+template <class Cfg>
+__device__ __forceinline__ void gemm_tn_mainloop_direct(const bf16_t* __restrict__ A, int64_t lda, int M, int m0,
+                                                        const bf16_t* __restrict__ B, int64_t ldb, int N, int n0, int K,
+                                                        f32x16 (&acc)[Cfg::MB][Cfg::NB], bf16_t* lds)
+{
+    constexpr int NW = Cfg::NT / 64;
+    constexpr int BK = Cfg::BK;
+    constexpr int A_INSTR = Cfg::BM / 8 / NW;     // wave-instructions per stage and operand
+    constexpr int B_INSTR = Cfg::BN / 8 / NW;
+    constexpr int A_STAGE = Cfg::BM * BK, B_STAGE = Cfg::BN * BK;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_m = wave / Cfg::WAVES_N;
+    const int wave_n = wave % Cfg::WAVES_N;
+    bf16_t* sA = lds;
+    bf16_t* sB = lds + 2 * A_STAGE;
+
+#pragma unroll
+    for (int bi = 0; bi < Cfg::MB; ++bi)
+#pragma unroll
+        for (int bj = 0; bj < Cfg::NB; ++bj)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[bi][bj][r] = 0.0f;
+
+    const char* a_tile = reinterpret_cast<const char*>(A + (int64_t)m0 * lda);
+    const char* b_tile = reinterpret_cast<const char*>(B + (int64_t)n0 * ldb);
+    // this lane's source for wave-instruction j: row (j*NW + wave)*8 + lane/8, vector (lane%8) xor (lane/8)
+    const int sub_row = lane >> 3;
+    const int kv = (lane & 7) ^ sub_row;
+    uint32_t oa[A_INSTR], ob[B_INSTR];
+#pragma unroll
+    for (int j = 0; j < A_INSTR; ++j) {
+        const int row = (j * NW + wave) * 8 + sub_row;
+        const int gr = (m0 + row < M) ? row : (M - 1 - m0);
+        oa[j] = (uint32_t)(((int64_t)gr * lda + kv * 8) * 2);
+    }
+#pragma unroll
+    for (int j = 0; j < B_INSTR; ++j) {
+        const int row = (j * NW + wave) * 8 + sub_row;
+        const int gr = (n0 + row < N) ? row : (N - 1 - n0);
+        ob[j] = (uint32_t)(((int64_t)gr * ldb + kv * 8) * 2);
+    }
+    auto fetch = [&](int k0, int stage) {
+        const char* pa = a_tile + (int64_t)k0 * 2;
+        const char* pb = b_tile + (int64_t)k0 * 2;
+#pragma unroll
+        for (int j = 0; j < A_INSTR; ++j)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(pa + oa[j]),
+                                             (__attribute__((address_space(3))) void*)(sA + stage * A_STAGE + (j * NW + wave) * 8 * BK),
+                                             16, 0, 0);
+#pragma unroll
+        for (int j = 0; j < B_INSTR; ++j)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(pb + ob[j]),
+                                             (__attribute__((address_space(3))) void*)(sB + stage * B_STAGE + (j * NW + wave) * 8 * BK),
+                                             16, 0, 0);
+    };
+
+    // fragment sources: row = tile row of this lane, vector kg = 2 kk + lane/32, stored at slot kg xor (row mod 8)
+    const int frag_row = lane & 31;
+    const int a_row = (wave_m * Cfg::WM + frag_row) * BK;
+    const int b_row = (wave_n * Cfg::WN + frag_row) * BK;
+    int koff[BK / 16];
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) koff[kk] = (((2 * kk + (lane >> 5)) ^ (lane & 7)) * 8);
+    auto compute = [&](int cur) {
+        const bf16_t* cA = sA + cur * A_STAGE + a_row;
+        const bf16_t* cB = sB + cur * B_STAGE + b_row;
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            bf16x8 fa[Cfg::MB], fb[Cfg::NB];
+#pragma unroll
+            for (int bi = 0; bi < Cfg::MB; ++bi)
+                fa[bi] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(cA + bi * 32 * BK + koff[kk]));
+#pragma unroll
+            for (int bj = 0; bj < Cfg::NB; ++bj)
+                fb[bj] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(cB + bj * 32 * BK + koff[kk]));
+#pragma unroll
+            for (int bi = 0; bi < Cfg::MB; ++bi)
+#pragma unroll
+                for (int bj = 0; bj < Cfg::NB; ++bj)
+                    acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[bi], fb[bj], acc[bi][bj], 0, 0, 0);
+        }
+    };
+
+    const int KT = K / BK;
+    fetch(0, 0);
+    __builtin_amdgcn_s_waitcnt(0);     // the tile has landed in LDS (vmcnt) ...
+    __syncthreads();                   // ... for every wave
+    for (int kt = 0; kt < KT; ++kt) {
+        if (kt + 1 < KT) fetch((kt + 1) * BK, (kt + 1) & 1);
+        compute(kt & 1);
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+    }
+}
+
+template <class Cfg>
+__device__ __forceinline__ void gemm_tn_tile(const bf16_t* __restrict__ A, int64_t lda, int M, int m0,
+                                             const bf16_t* __restrict__ B, int64_t ldb, int N, int n0, int K,
+                                             f32x16 (&acc)[Cfg::MB][Cfg::NB], bf16_t* lds)
+{
+    if constexpr (Cfg::DIRECT) {
+        if (K % Cfg::BK == 0) {
+            gemm_tn_mainloop_direct<Cfg>(A, lda, M, m0, B, ldb, N, n0, K, acc, lds);
+            return;
+        }
+    }
+    gemm_tn_mainloop<Cfg>(A, lda, M, m0, B, ldb, N, n0, K, acc, lds);
+}
+
 // Workgroup -> tile mapping.  The hardware deals consecutive workgroup ids round-robin to the 8
 // XCDs, each with its own L2.  Ids are first regrouped so that every XCD owns one contiguous
 // range of logical tile numbers, and logical numbers walk the tile grid in blocks of 4 tiles
@@ -243,7 +363,7 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_tn_kernel(const bf16_t* __restri
     if (!tile_coords((M + Cfg::BM - 1) / Cfg::BM, (N + Cfg::BN - 1) / Cfg::BN, tile_m, tile_n)) return;
     const int m0 = tile_m * Cfg::BM, n0 = tile_n * Cfg::BN;
     f32x16 acc[Cfg::MB][Cfg::NB];
-    gemm_tn_mainloop<Cfg>(A, lda, M, m0, B, ldb, N, n0, K, acc, lds);
+    gemm_tn_tile<Cfg>(A, lda, M, m0, B, ldb, N, n0, K, acc, lds);
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
@@ -348,7 +468,7 @@ __global__ __launch_bounds__(Cfg::NT) void lmhead_stats_kernel(const bf16_t* __r
 
     for (int v0 = vb; v0 < ve; v0 += Cfg::BM) {
         f32x16 acc[Cfg::MB][Cfg::NB];
-        gemm_tn_mainloop<Cfg>(Wt, Hd, V, v0, H, Hd, Ntok, t0, Hd, acc, lds);
+        gemm_tn_tile<Cfg>(Wt, Hd, V, v0, H, Hd, Ntok, t0, Hd, acc, lds);
         const int vrow0 = v0 + wm * Cfg::WM + 4 * (lane >> 5);
 #pragma unroll
         for (int bj = 0; bj < Cfg::NB; ++bj) {
@@ -451,7 +571,7 @@ __global__ __launch_bounds__(Cfg::NT) void lmhead_dz_kernel(const bf16_t* __rest
     const int t0 = t_tile * Cfg::BN;
     const int vend = min(V, vc0 + cw);
     f32x16 acc[Cfg::MB][Cfg::NB];
-    gemm_tn_mainloop<Cfg>(Wt, Hd, V, v0, H, Hd, Ntok, t0, Hd, acc, lds);
+    gemm_tn_tile<Cfg>(Wt, Hd, V, v0, H, Hd, Ntok, t0, Hd, acc, lds);
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
@@ -507,6 +627,8 @@ using Tile2 = GemmCfg<256, 256, 64, 2, 2>;   // wave tile 128 x 128, 144 KB of L
 using Tile3 = GemmCfg<256, 128, 64, 2, 2>;   // wave tile 128 x 64
 using Tile4 = GemmCfg<256, 256, 64, 2, 4>;   // eight waves (two per SIMD), wave tile 128 x 64
 using Tile5 = GemmCfg<256, 256, 64, 4, 2>;   // eight waves, wave tile 64 x 128
+using Tile6 = GemmCfg<256, 256, 64, 4, 2, true>;   // as 5, tiles copied global -> LDS directly
+using Tile7 = GemmCfg<256, 256, 64, 2, 4, true>;   // as 4, direct
 
 #define ULORL_FOR_TILE(choice, ...)                          \
     switch (choice) {                                        \
@@ -514,8 +636,10 @@ using Tile5 = GemmCfg<256, 256, 64, 4, 2>;   // eight waves, wave tile 64 x 128
     case 2: { using Cfg = Tile2; __VA_ARGS__; } break;       \
     case 3: { using Cfg = Tile3; __VA_ARGS__; } break;       \
     case 4: { using Cfg = Tile4; __VA_ARGS__; } break;       \
+    case 6: { using Cfg = Tile6; __VA_ARGS__; } break;       \
     case 1: { using Cfg = Tile1; __VA_ARGS__; } break;       \
-    default: { using Cfg = Tile5; __VA_ARGS__; } break;      \
+    case 5: { using Cfg = Tile5; __VA_ARGS__; } break;       \
+    default: { using Cfg = Tile7; __VA_ARGS__; } break;      \
     }
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }

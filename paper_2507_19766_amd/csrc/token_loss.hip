@@ -759,7 +759,7 @@ struct Tuning {
     int fwd_threads = 512, fwd_unroll = 8;
     int bwd_threads = 256, bwd_unroll = 4;
     int fused_threads = 512, fused_unroll = 8;
-    int gemm_tile = 5;
+    int gemm_tile = 7;
     int bwd_oneshot = 1;   // standalone backward by one-shot 4 KB workgroups (0: one looping workgroup per row)
 };
 Tuning g_tune;
@@ -961,7 +961,7 @@ int32_t ulorl_tune(int32_t knob, int32_t value)
     case ULORL_TUNE_FUSED_THREADS: if (!threads_ok) return ULORL_ERR_PARAM; g_tune.fused_threads = value; return ULORL_OK;
     case ULORL_TUNE_FUSED_UNROLL:  if (!unroll_ok) return ULORL_ERR_PARAM;  g_tune.fused_unroll = value;  return ULORL_OK;
     case ULORL_TUNE_BWD_ONESHOT: if (value != 0 && value != 1) return ULORL_ERR_PARAM; g_tune.bwd_oneshot = value; return ULORL_OK;
-    case ULORL_TUNE_GEMM_TILE: if (value < 0 || value > 5) return ULORL_ERR_PARAM; g_tune.gemm_tile = value; return ULORL_OK;
+    case ULORL_TUNE_GEMM_TILE: if (value < 0 || value > 7) return ULORL_ERR_PARAM; g_tune.gemm_tile = value; return ULORL_OK;
     default: return ULORL_ERR_PARAM;
     }
 }

@@ -1,11 +1,14 @@
 """ctypes front end of the fp64 CPU oracle (``ulorl_oracle.c``).
 
 TEST INFRASTRUCTURE ONLY: imported by the tests, the smoke check and the benchmark's
-reported CPU baseline.  It holds no arithmetic of its own (argument marshalling for the C
-functions) and neither imports nor is imported by the GPU package.
+reported CPU baseline.  It neither imports nor is imported by the GPU package.  Apart from
+argument marshalling for the C functions its only arithmetic is the lm_head variant's three
+stock fp64 matrix products (numpy), which are that variant's definition.
 
-The three C entry points mirror the three stages of the objective of Sec. 3.2.2:
-row statistics over the vocabulary, the O(1)-per-token terms, and the logits gradient.
+The three main C entry points mirror the three stages of the objective of Sec. 3.2.2:
+row statistics over the vocabulary, the O(1)-per-token terms, and the logits gradient; two
+more cover the group advantages of Eq. 4 / Eq. 7 / Sec. 3.5 and per-segment diagnostics
+(Sec. 3.1.2).
 """
 from __future__ import annotations
 

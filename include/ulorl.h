@@ -305,7 +305,7 @@ typedef enum {
                                      0 = 128x128x64 / 2x2, 1 = 256x256x32 / 2x2, 2 = 256x256x64 / 2x2,
                                      3 = 256x128x64 / 2x2, 4 = 256x256x64 / 2x4, 5 = 256x256x64 / 4x2,
                                      6 = as 5 and 7 = as 4 with tiles copied global -> LDS directly
-                                     (default 7) */
+                                     (default 7), 8 = as 2, direct */
 } ulorl_tune_knob;
 int32_t ulorl_tune(int32_t knob, int32_t value);
 

@@ -48,12 +48,15 @@ __device__ __forceinline__ bf16_t to_bf16(float x) { return (bf16_t)(pack_bf16x2
 // ---------------------------------------------------------------------------------------------
 // tiled GEMM main loop
 // ---------------------------------------------------------------------------------------------
-template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, bool DIRECT_ = false>
+template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, bool DIRECT_ = false, int WG_PER_CU_ = 1>
 struct GemmCfg {
     static constexpr int BM = BM_, BN = BN_, BK = BK_;
     static constexpr bool DIRECT = DIRECT_;                // global -> LDS without passing through registers
     static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
     static constexpr int NT = 64 * WAVES_M * WAVES_N;
+    // workgroups meant to share a compute unit; the register budget follows from it (waves per SIMD)
+    static constexpr int WG_PER_CU = WG_PER_CU_;
+    static constexpr int WAVES_PER_SIMD = (WG_PER_CU * WAVES_M * WAVES_N + 3) / 4;
     static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
     static constexpr int MB = WM / 32, NB = WN / 32;      // 32x32 result blocks per wave
     static constexpr int LDS_STRIDE = BK + 8;              // bf16 elements; the pad spreads rows over banks
@@ -64,7 +67,9 @@ struct GemmCfg {
     static constexpr int B_VECS = BN * VEC_PER_ROW / NT;
     static constexpr size_t LDS_BYTES = 2 * (size_t)(A_STAGE + B_STAGE) * sizeof(bf16_t);
     static_assert(WM % 32 == 0 && WN % 32 == 0 && BK % 16 == 0, "tile shape");
-    static_assert(!DIRECT || (BK == 64 && BM % (8 * (NT / 64)) == 0 && BN % (8 * (NT / 64)) == 0), "direct-to-LDS tile shape");
+    static_assert(!DIRECT || (BK == 64 && BM % (8 * (NT / 64)) == 0 && BN % (8 * (NT / 64)) == 0),
+                  "direct-to-LDS tile shape");
+    static_assert(LDS_BYTES * WG_PER_CU <= 160 * 1024, "LDS per compute unit");
     static_assert((BM * VEC_PER_ROW) % NT == 0 && (BN * VEC_PER_ROW) % NT == 0, "load split");
 };
 
@@ -198,13 +203,31 @@ __device__ __forceinline__ void gemm_tn_mainloop(const bf16_t* __restrict__ A, i
     }
 }
 
+// Scheduling request for one MFMA step of the direct main loop: the first MFMA, READS LDS reads,
+// COPIES x (one global -> LDS copy, one MFMA), the remaining MFMAs.
+template <int COPIES, int READS, int MFMAS>
+__device__ __forceinline__ void step_pattern()
+{
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, READS, 0);
+#pragma unroll
+    for (int i = 0; i < COPIES; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, MFMAS - 1 - COPIES, 0);
+}
+
 // The same product with the tiles copied global -> LDS by the load unit itself
 // (global_load_lds_dwordx4: lane L of a wave deposits its 16 bytes at lds_base + 16 L), so the
 // staging registers, the ds_write instructions and the wait between a load's return and its
 // write disappear from the loop.  A wave-instruction fills 64 consecutive 16-byte slots = 8 rows
-// of a BK = 64 tile; rows are therefore unpadded, and bank conflicts are avoided by storing vector
-// kv of row r in slot (kv xor (r mod 8)) of that row (each lane simply fetches from global the
-// vector that belongs in its slot).  Needs K to be a multiple of BK.
+// of a BK = 64 tile or 16 rows of a BK = 32 tile; rows are therefore unpadded, and bank conflicts
+// are avoided by storing vector kv of row r in slot (kv xor swz(r)) of that row (each lane simply
+// fetches from global the vector that belongs in its slot).  A fragment read (ds_read_b128) is
+// served 16 lanes = 16 consecutive tile rows = 256 bytes per clock, so those 16 rows must land in
+// 16 different 16-byte columns of the 256-byte bank line: swz(r) = (r / 2) mod 8 for 128-byte
+// rows, (r / 4) mod 4 for 64-byte rows.  Needs K to be a multiple of BK.
 template <class Cfg>
 __device__ __forceinline__ void gemm_tn_mainloop_direct(const bf16_t* __restrict__ A, int64_t lda, int M, int m0,
                                                         const bf16_t* __restrict__ B, int64_t ldb, int N, int n0, int K,
@@ -212,8 +235,10 @@ __device__ __forceinline__ void gemm_tn_mainloop_direct(const bf16_t* __restrict
 {
     constexpr int NW = Cfg::NT / 64;
     constexpr int BK = Cfg::BK;
-    constexpr int A_INSTR = Cfg::BM / 8 / NW;     // wave-instructions per stage and operand
-    constexpr int B_INSTR = Cfg::BN / 8 / NW;
+    constexpr int VPR = BK / 8;                   // 16-byte vectors per tile row
+    constexpr int RPI = 64 / VPR;                 // tile rows one wave-instruction fills
+    constexpr int A_INSTR = Cfg::BM / RPI / NW;   // wave-instructions per stage and operand
+    constexpr int B_INSTR = Cfg::BN / RPI / NW;
     constexpr int A_STAGE = Cfg::BM * BK, B_STAGE = Cfg::BN * BK;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -232,73 +257,137 @@ __device__ __forceinline__ void gemm_tn_mainloop_direct(const bf16_t* __restrict
 
     const char* a_tile = reinterpret_cast<const char*>(A + (int64_t)m0 * lda);
     const char* b_tile = reinterpret_cast<const char*>(B + (int64_t)n0 * ldb);
-    // this lane's source for wave-instruction j: row (j*NW + wave)*8 + lane/8, vector (lane%8) xor (lane/8)
-    const int sub_row = lane >> 3;
-    const int kv = (lane & 7) ^ sub_row;
+    // this lane's source for wave-instruction j: row (j*NW + wave)*RPI + lane/VPR, vector (lane%VPR) xor swz(row)
+    auto swz = [](int row) { return VPR == 8 ? ((row >> 1) & 7) : ((row >> 2) & 3); };
+    const int sub_row = lane / VPR;
     uint32_t oa[A_INSTR], ob[B_INSTR];
 #pragma unroll
     for (int j = 0; j < A_INSTR; ++j) {
-        const int row = (j * NW + wave) * 8 + sub_row;
+        const int row = (j * NW + wave) * RPI + sub_row;
+        const int kv = (lane % VPR) ^ swz(row);
         const int gr = (m0 + row < M) ? row : (M - 1 - m0);
         oa[j] = (uint32_t)(((int64_t)gr * lda + kv * 8) * 2);
     }
 #pragma unroll
     for (int j = 0; j < B_INSTR; ++j) {
-        const int row = (j * NW + wave) * 8 + sub_row;
+        const int row = (j * NW + wave) * RPI + sub_row;
+        const int kv = (lane % VPR) ^ swz(row);
         const int gr = (n0 + row < N) ? row : (N - 1 - n0);
         ob[j] = (uint32_t)(((int64_t)gr * ldb + kv * 8) * 2);
     }
-    auto fetch = [&](int k0, int stage) {
+    auto fetch_a = [&](int k0, int stage) {
         const char* pa = a_tile + (int64_t)k0 * 2;
-        const char* pb = b_tile + (int64_t)k0 * 2;
 #pragma unroll
         for (int j = 0; j < A_INSTR; ++j)
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(pa + oa[j]),
-                                             (__attribute__((address_space(3))) void*)(sA + stage * A_STAGE + (j * NW + wave) * 8 * BK),
+                                             (__attribute__((address_space(3))) void*)(sA + stage * A_STAGE + (j * NW + wave) * RPI * BK),
                                              16, 0, 0);
+    };
+    auto fetch_b = [&](int k0, int stage) {
+        const char* pb = b_tile + (int64_t)k0 * 2;
 #pragma unroll
         for (int j = 0; j < B_INSTR; ++j)
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(pb + ob[j]),
-                                             (__attribute__((address_space(3))) void*)(sB + stage * B_STAGE + (j * NW + wave) * 8 * BK),
+                                             (__attribute__((address_space(3))) void*)(sB + stage * B_STAGE + (j * NW + wave) * RPI * BK),
                                              16, 0, 0);
     };
 
-    // fragment sources: row = tile row of this lane, vector kg = 2 kk + lane/32, stored at slot kg xor (row mod 8)
+    // fragment sources: row = tile row of this lane, vector kg = 2 kk + lane/32, stored at slot kg xor swz(row)
     const int frag_row = lane & 31;
     const int a_row = (wave_m * Cfg::WM + frag_row) * BK;
     const int b_row = (wave_n * Cfg::WN + frag_row) * BK;
+    const int frag_swz = swz(frag_row);            // wave and block offsets are multiples of 32 rows: no effect on swz
     int koff[BK / 16];
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) koff[kk] = (((2 * kk + (lane >> 5)) ^ (lane & 7)) * 8);
-    auto compute = [&](int cur) {
-        const bf16_t* cA = sA + cur * A_STAGE + a_row;
-        const bf16_t* cB = sB + cur * B_STAGE + b_row;
+    for (int kk = 0; kk < BK / 16; ++kk) koff[kk] = (((2 * kk + (lane >> 5)) ^ frag_swz) * 8);
+    constexpr int KK = BK / 16;                   // MFMA steps per K tile (even)
+    bf16x8 fa[2][Cfg::MB], fb[2][Cfg::NB];        // two fragment sets: one feeds the MFMAs while the other loads
+    // read order = the order in which the MFMAs first need the fragments (A0, B0.., A1..)
+    auto load_frags = [&](int set, int stage, int kk) {
+        const bf16_t* cA = sA + stage * A_STAGE + a_row + koff[kk];
+        const bf16_t* cB = sB + stage * B_STAGE + b_row + koff[kk];
+        fa[set][0] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(cA));
 #pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            bf16x8 fa[Cfg::MB], fb[Cfg::NB];
+        for (int bj = 0; bj < Cfg::NB; ++bj)
+            fb[set][bj] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(cB + bj * 32 * BK));
 #pragma unroll
-            for (int bi = 0; bi < Cfg::MB; ++bi)
-                fa[bi] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(cA + bi * 32 * BK + koff[kk]));
+        for (int bi = 1; bi < Cfg::MB; ++bi)
+            fa[set][bi] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(cA + bi * 32 * BK));
+    };
+    auto multiply = [&](int set) {
+#pragma unroll
+        for (int bi = 0; bi < Cfg::MB; ++bi)
 #pragma unroll
             for (int bj = 0; bj < Cfg::NB; ++bj)
-                fb[bj] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(cB + bj * 32 * BK + koff[kk]));
-#pragma unroll
-            for (int bi = 0; bi < Cfg::MB; ++bi)
-#pragma unroll
-                for (int bj = 0; bj < Cfg::NB; ++bj)
-                    acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[bi], fb[bj], acc[bi][bj], 0, 0, 0);
-        }
+                acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][bi], fb[set][bj], acc[bi][bj], 0, 0, 0);
     };
+    // Wanted order inside an MFMA step: the first MFMA (it carries the wait for this step's
+    // fragments), then all LDS reads of the next step's fragments, then the other MFMAs.  A read
+    // issued before that wait would be waited for as well: while global -> LDS copies are in
+    // flight the compiler only emits full waits on the LDS counter.  A step that also issues
+    // `copies` global -> LDS copies gets them one per MFMA: the address unit of the compute unit
+    // takes 16 clocks per copy instruction and is shared by all waves, and a wave whose copy is
+    // queued behind the others' cannot issue the MFMAs that follow it.
+    static_assert(A_INSTR < Cfg::MB * Cfg::NB && B_INSTR < Cfg::MB * Cfg::NB, "copies per step");
 
+    // Software pipeline over two LDS stages; tile kt lives in stage kt & 1.  Fragments of MFMA
+    // step kk+1 are read from LDS while step kk multiplies.  The barrier that ends K tile kt sits
+    // before its last step: by then every wave has read all it needs from that stage (its last
+    // fragments are in registers), so after the barrier the copy of tile kt+2 may overwrite the
+    // stage and the first fragments of tile kt+1 can be read, both underneath the last step's
+    // MFMAs.  The A half of tile kt+2 is copied during that last step, the B half during the
+    // first step of tile kt+1.
     const int KT = K / BK;
-    fetch(0, 0);
+    static_assert(KK % 2 == 0 && KK >= 4, "the fragment sets alternate per MFMA step; first and last steps carry the copies");
+    fetch_a(0, 0);
+    fetch_b(0, 0);
     __builtin_amdgcn_s_waitcnt(0);     // the tile has landed in LDS (vmcnt) ...
     __syncthreads();                   // ... for every wave
-    for (int kt = 0; kt < KT; ++kt) {
-        if (kt + 1 < KT) fetch((kt + 1) * BK, (kt + 1) & 1);
-        compute(kt & 1);
-        __builtin_amdgcn_s_waitcnt(0);
+    if (KT > 1) fetch_a(BK, 1);
+    load_frags(0, 0, 0);
+    auto mid_steps = [&](int cur) {    // MFMA steps 1 .. KK-2 of a K tile, then the barrier
+#pragma unroll
+        for (int kk = 1; kk + 1 < KK; ++kk) {
+            load_frags((kk + 1) & 1, cur, kk + 1);
+            multiply(kk & 1);
+            step_pattern<0, Cfg::MB + Cfg::NB, Cfg::MB * Cfg::NB>();
+        }
+        __builtin_amdgcn_sched_barrier(0);  // the MFMAs above stay above: they run while the wave waits below
+        __builtin_amdgcn_s_waitcnt(0);      // the next tile has landed (vmcnt), own LDS reads are done (lgkmcnt)
         __syncthreads();
+    };
+    int kt = 0;
+    for (; kt + 2 < KT; ++kt) {            // steady state, free of conditional code
+        const int cur = kt & 1;
+        load_frags(1, cur, 1);
+        fetch_b((kt + 1) * BK, cur ^ 1);
+        multiply(0);
+        step_pattern<B_INSTR, Cfg::MB + Cfg::NB, Cfg::MB * Cfg::NB>();
+        mid_steps(cur);
+        load_frags(0, cur ^ 1, 0);
+        fetch_a((kt + 2) * BK, cur);
+        multiply((KK - 1) & 1);
+        step_pattern<A_INSTR, Cfg::MB + Cfg::NB, Cfg::MB * Cfg::NB>();
+    }
+    if (kt + 1 < KT) {                     // last but one tile: only the B half of the last tile is left to copy
+        const int cur = kt & 1;
+        load_frags(1, cur, 1);
+        fetch_b((kt + 1) * BK, cur ^ 1);
+        multiply(0);
+        step_pattern<B_INSTR, Cfg::MB + Cfg::NB, Cfg::MB * Cfg::NB>();
+        mid_steps(cur);
+        load_frags(0, cur ^ 1, 0);
+        multiply((KK - 1) & 1);
+        step_pattern<0, Cfg::MB + Cfg::NB, Cfg::MB * Cfg::NB>();
+        ++kt;
+    }
+    {                                      // last tile
+        const int cur = kt & 1;
+        load_frags(1, cur, 1);
+        multiply(0);
+        step_pattern<0, Cfg::MB + Cfg::NB, Cfg::MB * Cfg::NB>();
+        mid_steps(cur);                    // its barrier: every wave is past its last LDS read, the caller may reuse LDS
+        multiply((KK - 1) & 1);
     }
 }
 
@@ -353,7 +442,8 @@ inline unsigned tile_grid(int num_m, int num_n)
 enum { STORE_F32 = 0, STORE_F32_ACCUM = 1, STORE_BF16 = 2 };
 
 template <class Cfg, int STORE>
-__global__ __launch_bounds__(Cfg::NT) void gemm_tn_kernel(const bf16_t* __restrict__ A, int64_t lda, int M,
+__global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(Cfg::WAVES_PER_SIMD, Cfg::WAVES_PER_SIMD)))
+void gemm_tn_kernel(const bf16_t* __restrict__ A, int64_t lda, int M,
                                                           const bf16_t* __restrict__ B, int64_t ldb, int N, int K,
                                                           void* __restrict__ C, int64_t ldc)
 {
@@ -442,7 +532,8 @@ struct StatQuad {
 };
 
 template <class Cfg>
-__global__ __launch_bounds__(Cfg::NT) void lmhead_stats_kernel(const bf16_t* __restrict__ Wt, const bf16_t* __restrict__ H,
+__global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(Cfg::WAVES_PER_SIMD, Cfg::WAVES_PER_SIMD)))
+void lmhead_stats_kernel(const bf16_t* __restrict__ Wt, const bf16_t* __restrict__ H,
                                                                int Hd, int V, int Ntok,
                                                                const int32_t* __restrict__ token_ids, int v_per_split,
                                                                int splits, StatQuad* __restrict__ partial)
@@ -555,7 +646,8 @@ __global__ void lmhead_stats_merge_kernel(const StatQuad* __restrict__ partial, 
 // backward: dz tiles of one vocabulary chunk, stored in both orientations
 // ---------------------------------------------------------------------------------------------
 template <class Cfg>
-__global__ __launch_bounds__(Cfg::NT) void lmhead_dz_kernel(const bf16_t* __restrict__ Wt, const bf16_t* __restrict__ H,
+__global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(Cfg::WAVES_PER_SIMD, Cfg::WAVES_PER_SIMD)))
+void lmhead_dz_kernel(const bf16_t* __restrict__ Wt, const bf16_t* __restrict__ H,
                                                             int Hd, int V, int Ntok, int vc0, int cw,
                                                             const int32_t* __restrict__ token_ids,
                                                             const float* __restrict__ lse,
@@ -629,6 +721,7 @@ using Tile4 = GemmCfg<256, 256, 64, 2, 4>;   // eight waves (two per SIMD), wave
 using Tile5 = GemmCfg<256, 256, 64, 4, 2>;   // eight waves, wave tile 64 x 128
 using Tile6 = GemmCfg<256, 256, 64, 4, 2, true>;   // as 5, tiles copied global -> LDS directly
 using Tile7 = GemmCfg<256, 256, 64, 2, 4, true>;   // as 4, direct
+using Tile8 = GemmCfg<256, 256, 64, 2, 2, true>;   // as 2, direct (four waves, one per SIMD)
 
 #define ULORL_FOR_TILE(choice, ...)                          \
     switch (choice) {                                        \
@@ -639,6 +732,7 @@ using Tile7 = GemmCfg<256, 256, 64, 2, 4, true>;   // as 4, direct
     case 6: { using Cfg = Tile6; __VA_ARGS__; } break;       \
     case 1: { using Cfg = Tile1; __VA_ARGS__; } break;       \
     case 5: { using Cfg = Tile5; __VA_ARGS__; } break;       \
+    case 8: { using Cfg = Tile8; __VA_ARGS__; } break;       \
     default: { using Cfg = Tile7; __VA_ARGS__; } break;      \
     }
 

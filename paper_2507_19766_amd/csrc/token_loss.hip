@@ -752,18 +752,6 @@ __global__ __launch_bounds__(NT) void fused_row_kernel(const typename Tr::elem* 
 // ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
-// Defaults from a sweep on 131072 x 151936 bf16.  The forward and the fused kernel share one
-// shape so that their row statistics are bit-identical (the backward is elementwise, its shape
-// does not change results).
-struct Tuning {
-    int fwd_threads = 512, fwd_unroll = 8;
-    int bwd_threads = 256, bwd_unroll = 4;
-    int fused_threads = 512, fused_unroll = 8;
-    int gemm_tile = 7;
-    int bwd_oneshot = 1;   // standalone backward by one-shot 4 KB workgroups (0: one looping workgroup per row)
-};
-Tuning g_tune;
-
 bool shape_ok(int64_t N, int64_t V, int64_t stride)
 {
     return N > 0 && N <= 0x7fffffffLL && V > 0 && V <= 0x7fffffffLL && stride >= V;
@@ -816,7 +804,7 @@ template <class Tr>
 bool dispatch_dlogits(int nt, int u, const void* logits, int64_t N, int64_t V, int64_t stride, const int32_t* y,
                       const float* lse, const float* g, float grad_out, void* dz, const uint8_t* only, hipStream_t st)
 {
-    if (g_tune.bwd_oneshot) {
+    if (tuning().bwd_oneshot) {
         const int64_t nvec = V / Tr::kPerVec;
         const int64_t chunks = nvec > 0 ? (nvec + 255) / 256 : 1;
         if (chunks <= 0x7fffffffLL) {
@@ -865,7 +853,6 @@ bool dispatch_fused(int nt, int u, const void* logits, int64_t N, int64_t V, int
 
 namespace ulorl_detail {
 
-int gemm_tile_choice() { return g_tune.gemm_tile; }
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -949,23 +936,6 @@ const char* ulorl_status_string(int32_t status)
     }
 }
 
-int32_t ulorl_tune(int32_t knob, int32_t value)
-{
-    const bool threads_ok = value == 256 || value == 512 || value == 1024;
-    const bool unroll_ok = value == 2 || value == 4 || value == 8;
-    switch (knob) {
-    case ULORL_TUNE_FWD_THREADS: if (!threads_ok) return ULORL_ERR_PARAM; g_tune.fwd_threads = value; return ULORL_OK;
-    case ULORL_TUNE_FWD_UNROLL:  if (!unroll_ok) return ULORL_ERR_PARAM;  g_tune.fwd_unroll = value;  return ULORL_OK;
-    case ULORL_TUNE_BWD_THREADS: if (!threads_ok) return ULORL_ERR_PARAM; g_tune.bwd_threads = value; return ULORL_OK;
-    case ULORL_TUNE_BWD_UNROLL:  if (!unroll_ok) return ULORL_ERR_PARAM;  g_tune.bwd_unroll = value;  return ULORL_OK;
-    case ULORL_TUNE_FUSED_THREADS: if (!threads_ok) return ULORL_ERR_PARAM; g_tune.fused_threads = value; return ULORL_OK;
-    case ULORL_TUNE_FUSED_UNROLL:  if (!unroll_ok) return ULORL_ERR_PARAM;  g_tune.fused_unroll = value;  return ULORL_OK;
-    case ULORL_TUNE_BWD_ONESHOT: if (value != 0 && value != 1) return ULORL_ERR_PARAM; g_tune.bwd_oneshot = value; return ULORL_OK;
-    case ULORL_TUNE_GEMM_TILE: if (value < 0 || value > 7) return ULORL_ERR_PARAM; g_tune.gemm_tile = value; return ULORL_OK;
-    default: return ULORL_ERR_PARAM;
-    }
-}
-
 size_t ulorl_token_loss_workspace_bytes(int64_t N, int32_t R)
 {
     if (N <= 0 || N > 0x7fffffffLL || R <= 0) return 0;
@@ -995,9 +965,9 @@ int32_t ulorl_token_loss_fwd(const void* logits, int32_t dt, int64_t N, int64_t 
     hipStream_t st = (hipStream_t)hip_stream;
 
     bool ok = dt == ULORL_BF16
-                  ? dispatch_row_stats<StoreBF16>(g_tune.fwd_threads, g_tune.fwd_unroll, logits, N, V, row_stride,
+                  ? dispatch_row_stats<StoreBF16>(tuning().fwd_threads, tuning().fwd_unroll, logits, N, V, row_stride,
                                                   token_ids, lse, logp, entropy, st)
-                  : dispatch_row_stats<StoreF32>(g_tune.fwd_threads, g_tune.fwd_unroll, logits, N, V, row_stride,
+                  : dispatch_row_stats<StoreF32>(tuning().fwd_threads, tuning().fwd_unroll, logits, N, V, row_stride,
                                                  token_ids, lse, logp, entropy, st);
     if (!ok || hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;
     if (stats_only) return ULORL_OK;
@@ -1042,9 +1012,9 @@ int32_t ulorl_token_loss_fwd_bwd(const void* logits, int32_t dt, int64_t N, int6
 
     hipLaunchKernelGGL(cu_check_kernel, dim3(1), dim3(kTokBlock), 0, st, cu_seqlens, R, N, (uint32_t*)(ws + wl.badcu));
     bool ok = dt == ULORL_BF16
-                  ? dispatch_fused<StoreBF16>(g_tune.fused_threads, g_tune.fused_unroll, logits, N, V, row_stride,
+                  ? dispatch_fused<StoreBF16>(tuning().fused_threads, tuning().fused_unroll, logits, N, V, row_stride,
                                               dlogits, f, st)
-                  : dispatch_fused<StoreF32>(g_tune.fused_threads, g_tune.fused_unroll, logits, N, V, row_stride,
+                  : dispatch_fused<StoreF32>(tuning().fused_threads, tuning().fused_unroll, logits, N, V, row_stride,
                                              dlogits, f, st);
     if (!ok || hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;
     launch_token_epilogue(a, wl, loss, counters, st);
@@ -1052,9 +1022,9 @@ int32_t ulorl_token_loss_fwd_bwd(const void* logits, int32_t dt, int64_t N, int6
     if (a.gate_mode == ULORL_GATE_PER_RESPONSE || a.gate_mode == ULORL_GATE_GLOBAL) {
         // MPT members waited for the gate: their rows are still logits (in place) or unwritten
         ok = dt == ULORL_BF16
-                 ? dispatch_dlogits<StoreBF16>(g_tune.bwd_threads, g_tune.bwd_unroll, logits, N, V, row_stride,
+                 ? dispatch_dlogits<StoreBF16>(tuning().bwd_threads, tuning().bwd_unroll, logits, N, V, row_stride,
                                                token_ids, lse, gcoef, grad_out, dlogits, f.defer, st)
-                 : dispatch_dlogits<StoreF32>(g_tune.bwd_threads, g_tune.bwd_unroll, logits, N, V, row_stride,
+                 : dispatch_dlogits<StoreF32>(tuning().bwd_threads, tuning().bwd_unroll, logits, N, V, row_stride,
                                               token_ids, lse, gcoef, grad_out, dlogits, f.defer, st);
         if (!ok || hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;
     }
@@ -1071,9 +1041,9 @@ int32_t ulorl_token_loss_bwd(const void* logits, int32_t dt, int64_t N, int64_t 
     if (((uintptr_t)dlogits & 15u) != 0) return ULORL_ERR_ALIGN;
     hipStream_t st = (hipStream_t)hip_stream;
     bool ok = dt == ULORL_BF16
-                  ? dispatch_dlogits<StoreBF16>(g_tune.bwd_threads, g_tune.bwd_unroll, logits, N, V, row_stride,
+                  ? dispatch_dlogits<StoreBF16>(tuning().bwd_threads, tuning().bwd_unroll, logits, N, V, row_stride,
                                                 token_ids, lse, gcoef, grad_out, dlogits, nullptr, st)
-                  : dispatch_dlogits<StoreF32>(g_tune.bwd_threads, g_tune.bwd_unroll, logits, N, V, row_stride,
+                  : dispatch_dlogits<StoreF32>(tuning().bwd_threads, tuning().bwd_unroll, logits, N, V, row_stride,
                                                token_ids, lse, gcoef, grad_out, dlogits, nullptr, st);
     if (!ok || hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;
     return ULORL_OK;

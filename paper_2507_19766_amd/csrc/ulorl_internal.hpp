@@ -59,8 +59,20 @@ TokenArgs make_token_args(int64_t N, int64_t V, const int32_t* token_ids, const 
 void launch_token_epilogue(const TokenArgs& a, const WorkspaceLayout& wl, float* loss, int64_t* counters,
                            hipStream_t st);
 
-// Index of the GEMM tile shape selected with ulorl_tune(ULORL_TUNE_GEMM_TILE, i).
-int gemm_tile_choice();
+// Launch shapes, set with ulorl_tune().  Defaults from sweeps on 131072 x 151936 bf16 (logits
+// path) and 32768 x 2048 x 151936 (lm_head variant).  The forward and the fused kernel share one
+// shape so that their row statistics are bit-identical (the backward is elementwise, its shape
+// does not change results).
+struct Tuning {
+    int fwd_threads = 512, fwd_unroll = 8;
+    int bwd_threads = 256, bwd_unroll = 4;
+    int fused_threads = 512, fused_unroll = 8;
+    int gemm_tile = 7;     // index into the compiled-in GEMM tile shapes
+    int bwd_oneshot = 1;   // standalone backward by one-shot 4 KB workgroups (0: one looping workgroup per row)
+};
+Tuning& tuning();
+constexpr int kGemmTileCount = 9;
+inline int gemm_tile_choice() { return tuning().gemm_tile; }
 
 }  // namespace ulorl_detail
 

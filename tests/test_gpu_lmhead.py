@@ -33,7 +33,7 @@ def test_gemm_tn_bf16_against_fp64(M, N, K):
     assert torch.equal(c, c2)
 
 
-@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4, 5, 6, 8])
 def test_every_compiled_tile_shape(tile):
     """All tile shapes / both main loops (register-staged and direct-to-LDS) give the same answers."""
     ulorl.tune(ulorl.TUNE_GEMM_TILE, tile)

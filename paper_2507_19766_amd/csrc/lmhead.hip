@@ -15,6 +15,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "ulorl.h"
 #include "ulorl_internal.hpp"
 
@@ -32,6 +34,7 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint16_t bf16_t;  // raw storage
 
@@ -441,11 +444,76 @@ inline unsigned tile_grid(int num_m, int num_n)
 // ---------------------------------------------------------------------------------------------
 enum { STORE_F32 = 0, STORE_F32_ACCUM = 1, STORE_BF16 = 2 };
 
+// Writes a wave's result tile to row-major C with 16-byte accesses.  In the MFMA result layout a
+// lane owns one column and 16 rows of a 32 x 32 block, so direct stores are 4 (or 2) bytes per lane;
+// instead each 32-row slab of the wave tile goes through the wave's share of LDS (the main loop's
+// stages, free by now) and is read back row-wise, one 16-byte vector per lane.  C must be 16-byte
+// aligned with a row pitch that is a multiple of 16 bytes.  Every wave of the workgroup must call.
+template <class Cfg, int STORE>
+__device__ __forceinline__ void store_wave_tile_rows(const f32x16 (&acc)[Cfg::MB][Cfg::NB], void* __restrict__ C,
+                                                     int64_t ldc, int M, int N, int m_wave, int n_wave,
+                                                     unsigned char* lds_raw)
+{
+    constexpr int EB = STORE == STORE_BF16 ? 2 : 4;          // bytes per element of C
+    constexpr int EPV = 16 / EB;                             // elements per 16-byte vector
+    constexpr int ROW_BYTES = Cfg::WN * EB;
+    constexpr int STRIDE = ROW_BYTES + 16;                   // padded: the four rows a lane pair writes fall in different banks
+    constexpr int VPR = ROW_BYTES / 16;                      // vectors per slab row
+    constexpr int RPI = 64 / VPR;                            // slab rows one wave-wide read covers
+    static_assert(VPR <= 64 && 32 % RPI == 0, "slab shape");
+    static_assert((size_t)32 * STRIDE <= Cfg::LDS_BYTES / (Cfg::NT / 64), "slab fits the wave's share of LDS");
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    unsigned char* slab = lds_raw + (size_t)wave * (Cfg::LDS_BYTES / (Cfg::NT / 64));
+#pragma unroll
+    for (int bi = 0; bi < Cfg::MB; ++bi) {
+#pragma unroll
+        for (int bj = 0; bj < Cfg::NB; ++bj)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                const int col = bj * 32 + (lane & 31);
+                if (STORE == STORE_BF16) *reinterpret_cast<bf16_t*>(slab + row * STRIDE + col * 2) = to_bf16(acc[bi][bj][r]);
+                else *reinterpret_cast<float*>(slab + row * STRIDE + col * 4) = acc[bi][bj][r];
+            }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 32 / RPI; ++i) {
+            const int row = i * RPI + lane / VPR;
+            const int vec = lane % VPR;
+            const u32x4 v = *reinterpret_cast<const u32x4*>(slab + row * STRIDE + vec * 16);
+            const int m = m_wave + bi * 32 + row;
+            const int n = n_wave + vec * EPV;
+            if (m < M && n < N) {
+                char* dst = reinterpret_cast<char*>(C) + ((int64_t)m * ldc + n) * EB;
+                if (n + EPV <= N) {
+                    if (STORE == STORE_F32_ACCUM) {
+                        const f32x4 old = *reinterpret_cast<const f32x4*>(dst);
+                        const f32x4 add = __builtin_bit_cast(f32x4, v);
+                        *reinterpret_cast<f32x4*>(dst) = old + add;
+                    } else {
+                        *reinterpret_cast<u32x4*>(dst) = v;
+                    }
+                } else {                                     // ragged right edge: element by element
+                    for (int e = 0; e < EPV && n + e < N; ++e) {
+                        if (STORE == STORE_BF16) {
+                            reinterpret_cast<bf16_t*>(dst)[e] = (bf16_t)((v[e >> 1] >> (16 * (e & 1))) & 0xffffu);
+                        } else {
+                            const float x = __builtin_bit_cast(float, v[e]);
+                            if (STORE == STORE_F32_ACCUM) reinterpret_cast<float*>(dst)[e] += x;
+                            else reinterpret_cast<float*>(dst)[e] = x;
+                        }
+                    }
+                }
+            }
+        }
+        __syncthreads();
+    }
+}
+
 template <class Cfg, int STORE>
 __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(Cfg::WAVES_PER_SIMD, Cfg::WAVES_PER_SIMD)))
-void gemm_tn_kernel(const bf16_t* __restrict__ A, int64_t lda, int M,
-                                                          const bf16_t* __restrict__ B, int64_t ldb, int N, int K,
-                                                          void* __restrict__ C, int64_t ldc)
+void gemm_tn_kernel(const bf16_t* __restrict__ A, int64_t lda, int M, const bf16_t* __restrict__ B, int64_t ldb, int N,
+                    int K, void* __restrict__ C, int64_t ldc, int wide_rows)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     bf16_t* lds = reinterpret_cast<bf16_t*>(lds_raw);
@@ -457,6 +525,10 @@ void gemm_tn_kernel(const bf16_t* __restrict__ A, int64_t lda, int M,
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
+    if (wide_rows) {            // C allows 16-byte accesses (uniform over the grid)
+        store_wave_tile_rows<Cfg, STORE>(acc, C, ldc, M, N, m0 + wm * Cfg::WM, n0 + wn * Cfg::WN, lds_raw);
+        return;
+    }
 #pragma unroll
     for (int bi = 0; bi < Cfg::MB; ++bi)
 #pragma unroll
@@ -561,40 +633,54 @@ void lmhead_stats_kernel(const bf16_t* __restrict__ Wt, const bf16_t* __restrict
         f32x16 acc[Cfg::MB][Cfg::NB];
         gemm_tn_tile<Cfg>(Wt, Hd, V, v0, H, Hd, Ntok, t0, Hd, acc, lds);
         const int vrow0 = v0 + wm * Cfg::WM + 4 * (lane >> 5);
+        // RAGGED: the tile reaches past the end of this workgroup's vocabulary range
+        auto absorb_tile = [&](auto ragged_c) {
+            constexpr bool RAGGED = decltype(ragged_c)::value;
 #pragma unroll
-        for (int bj = 0; bj < Cfg::NB; ++bj) {
-            float cm = kEmpty;
+            for (int bj = 0; bj < Cfg::NB; ++bj) {
+                float cm = kEmpty;
 #pragma unroll
-            for (int bi = 0; bi < Cfg::MB; ++bi)
+                for (int bi = 0; bi < Cfg::MB; ++bi)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int v = vrow0 + bi * 32 + 8 * (r >> 2) + (r & 3);
-                    if (v < ve) cm = fmaxf(cm, acc[bi][bj][r]);
+                    for (int r = 0; r < 16; ++r) {
+                        const int v = vrow0 + bi * 32 + 8 * (r >> 2) + (r & 3);
+                        if (!RAGGED || v < ve) cm = fmaxf(cm, acc[bi][bj][r]);
+                    }
+                const float mn = fmaxf(m[bj], cm);
+                const float d = m[bj] - mn;                   // <= 0
+                const float sc = fast_exp2(d * kLog2e);
+                float Tn = sc * fmaf(d, S[bj], T[bj]);
+                const float Sn = sc * S[bj];
+                const float Scn = sc * Sc[bj];
+                float part = 0.0f;                            // this tile's terms first, then one TwoSum
+#pragma unroll
+                for (int bi = 0; bi < Cfg::MB; ++bi)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int v = vrow0 + bi * 32 + 8 * (r >> 2) + (r & 3);
+                        const float x = acc[bi][bj][r] - mn;
+                        const bool in = !RAGGED || v < ve;
+                        const float e = in ? fast_exp2(x * kLog2e) : 0.0f;
+                        part += e;
+                        Tn = fmaf(e, in ? x : 0.0f, Tn);
+                    }
+                const float tsum = Sn + part;
+                const float bv = tsum - Sn;
+                const float err = (Sn - (tsum - bv)) + (part - bv);
+                S[bj] = tsum; Sc[bj] = Scn + err; T[bj] = Tn; m[bj] = mn;
+                // the chosen token's logit, if its row is one of this lane's in this tile (rare)
+                const int dy = y[bj] - (v0 + wm * Cfg::WM);
+                if (dy >= 0 && dy < Cfg::WM && ((dy >> 2) & 1) == (lane >> 5) && y[bj] < ve) {
+#pragma unroll
+                    for (int bi = 0; bi < Cfg::MB; ++bi)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            if (vrow0 + bi * 32 + 8 * (r >> 2) + (r & 3) == y[bj]) zy[bj] = acc[bi][bj][r];
                 }
-            const float mn = fmaxf(m[bj], cm);
-            const float d = m[bj] - mn;                   // <= 0
-            const float sc = fast_exp2(d * kLog2e);
-            float Tn = sc * fmaf(d, S[bj], T[bj]);
-            const float Sn = sc * S[bj];
-            const float Scn = sc * Sc[bj];
-            float part = 0.0f;                            // this tile's terms first, then one TwoSum
-#pragma unroll
-            for (int bi = 0; bi < Cfg::MB; ++bi)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int v = vrow0 + bi * 32 + 8 * (r >> 2) + (r & 3);
-                    const float z = acc[bi][bj][r];
-                    const float x = z - mn;
-                    const float e = v < ve ? fast_exp2(x * kLog2e) : 0.0f;
-                    part += e;
-                    Tn = fmaf(e, v < ve ? x : 0.0f, Tn);
-                    if (v == y[bj]) zy[bj] = z;
-                }
-            const float tsum = Sn + part;
-            const float bv = tsum - Sn;
-            const float err = (Sn - (tsum - bv)) + (part - bv);
-            S[bj] = tsum; Sc[bj] = Scn + err; T[bj] = Tn; m[bj] = mn;
-        }
+            }
+        };
+        if (v0 + Cfg::BM <= ve) absorb_tile(std::false_type{});
+        else absorb_tile(std::true_type{});
     }
 
     // two lanes (lane, lane^32) share a token column; then the waves stacked along the vocabulary
@@ -667,45 +753,103 @@ void lmhead_dz_kernel(const bf16_t* __restrict__ Wt, const bf16_t* __restrict__ 
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
+    // per token column of this lane: coefficient, sign and exponent offset of  dz = g (onehot - e^(z - lse))
+    float g[Cfg::NB], c[Cfg::NB], sgn[Cfg::NB];
+    int32_t y[Cfg::NB];
 #pragma unroll
     for (int bj = 0; bj < Cfg::NB; ++bj) {
         const int t = t0 + wn * Cfg::WN + bj * 32 + (lane & 31);
-        float g = 0.0f, c = 0.0f, sgn = 0.0f;
-        int32_t y = -1;
+        g[bj] = 0.0f; c[bj] = 0.0f; sgn[bj] = 0.0f; y[bj] = -1;
         if (t < Ntok) {
-            g = gcoef[t] * grad_out;
+            const float gg = gcoef[t] * grad_out;
             const float l = lse[t];
-            y = token_ids[t];
-            const bool live = (g != 0.0f) && (fabsf(g) <= 3.0e38f) && (fabsf(l) <= 3.0e38f) && y >= 0 && y < V;
+            const int32_t yy = token_ids[t];
+            const bool live = (gg != 0.0f) && (fabsf(gg) <= 3.0e38f) && (fabsf(l) <= 3.0e38f) && yy >= 0 && yy < V;
             if (live) {
-                c = fmaf(-l, kLog2e, log2f(fabsf(g)));
-                sgn = g > 0.0f ? -1.0f : 1.0f;
-            } else {
-                g = 0.0f;
+                g[bj] = gg; y[bj] = yy;
+                c[bj] = fmaf(-l, kLog2e, log2f(fabsf(gg)));
+                sgn[bj] = gg > 0.0f ? -1.0f : 1.0f;
             }
         }
+    }
+
+    // The tile leaves in both orientations, dZc[t, v] and dZc^T[v, t], as 16-byte row segments:
+    // 64 vocabulary rows at a time go through the wave's share of LDS (the main loop's stages,
+    // free by now), first laid out [v][t], then [t][v], and are read back row-wise.
+    constexpr int NW = Cfg::NT / 64;
+    constexpr int SA = Cfg::WN * 2 + 16;          // [v][t] row pitch in bytes (padded)
+    constexpr int SB = 64 * 2 + 16;               // [t][v] row pitch
+    constexpr int VPA = Cfg::WN * 2 / 16;         // 16-byte vectors per [v][t] row
+    static_assert(Cfg::MB % 2 == 0, "64 vocabulary rows per round");
+    static_assert((size_t)64 * SA <= Cfg::LDS_BYTES / NW && (size_t)Cfg::WN * SB <= Cfg::LDS_BYTES / NW, "round fits the wave's LDS share");
+    unsigned char* slab = lds_raw + (size_t)wave * (Cfg::LDS_BYTES / NW);
+    const int v_wave = v0 + wm * Cfg::WM;
+    const int t_wave = t0 + wn * Cfg::WN;
 #pragma unroll
-        for (int bi = 0; bi < Cfg::MB; ++bi)
+    for (int h = 0; h < Cfg::MB / 2; ++h) {
+        uint32_t pk[2][Cfg::NB][4][2];            // bf16 dz of this round: [block][column block][row quad] -> 4 rows
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int v = v0 + wm * Cfg::WM + bi * 32 + 8 * q + 4 * (lane >> 5);
-                float dz[4];
+        for (int b2 = 0; b2 < 2; ++b2)
 #pragma unroll
-                for (int s = 0; s < 4; ++s) {
-                    float x = sgn * fast_exp2(fmaf(acc[bi][bj][4 * q + s], kLog2e, c));
-                    if (v + s == y) x += g;
-                    dz[s] = (sgn != 0.0f && v + s < vend) ? x : 0.0f;
+            for (int bj = 0; bj < Cfg::NB; ++bj)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int v = v_wave + (2 * h + b2) * 32 + 8 * q + 4 * (lane >> 5);
+                    float dz[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        float x = sgn[bj] * fast_exp2(fmaf(acc[2 * h + b2][bj][4 * q + e], kLog2e, c[bj]));
+                        if (v + e == y[bj]) x += g[bj];
+                        dz[e] = (sgn[bj] != 0.0f && v + e < vend) ? x : 0.0f;
+                    }
+                    pk[b2][bj][q][0] = pack_bf16x2(dz[0], dz[1]);
+                    pk[b2][bj][q][1] = pack_bf16x2(dz[2], dz[3]);
                 }
-                if (t < Ntok && v < vc0 + cw) {
-                    u32x2 pk = {pack_bf16x2(dz[0], dz[1]), pack_bf16x2(dz[2], dz[3])};
-                    *reinterpret_cast<u32x2*>(dZc + (int64_t)t * ld_c + (v - vc0)) = pk;
-                }
-                if (t < ld_t) {
+        // ---- [v][t]: rows of dZc^T
 #pragma unroll
-                    for (int s = 0; s < 4; ++s)
-                        if (v + s < vc0 + cw) dZcT[(int64_t)(v + s - vc0) * ld_t + t] = t < Ntok ? to_bf16(dz[s]) : (bf16_t)0;
+        for (int b2 = 0; b2 < 2; ++b2)
+#pragma unroll
+            for (int bj = 0; bj < Cfg::NB; ++bj)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int row = b2 * 32 + 8 * q + 4 * (lane >> 5);
+                    unsigned char* p0 = slab + row * SA + (bj * 32 + (lane & 31)) * 2;
+                    *reinterpret_cast<bf16_t*>(p0) = (bf16_t)(pk[b2][bj][q][0] & 0xffffu);
+                    *reinterpret_cast<bf16_t*>(p0 + SA) = (bf16_t)(pk[b2][bj][q][0] >> 16);
+                    *reinterpret_cast<bf16_t*>(p0 + 2 * SA) = (bf16_t)(pk[b2][bj][q][1] & 0xffffu);
+                    *reinterpret_cast<bf16_t*>(p0 + 3 * SA) = (bf16_t)(pk[b2][bj][q][1] >> 16);
                 }
-            }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 64 * VPA / 64; ++i) {
+            const int row = (i * 64 + lane) / VPA, vec = (i * 64 + lane) % VPA;
+            const u32x4 x = *reinterpret_cast<const u32x4*>(slab + row * SA + vec * 16);
+            const int v = v_wave + h * 64 + row;
+            const int t = t_wave + vec * 8;
+            if (v < vc0 + cw && t < ld_t) *reinterpret_cast<u32x4*>(dZcT + (int64_t)(v - vc0) * ld_t + t) = x;
+        }
+        __syncthreads();
+        // ---- [t][v]: rows of dZc
+#pragma unroll
+        for (int b2 = 0; b2 < 2; ++b2)
+#pragma unroll
+            for (int bj = 0; bj < Cfg::NB; ++bj)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int col = b2 * 32 + 8 * q + 4 * (lane >> 5);
+                    const u32x2 two = {pk[b2][bj][q][0], pk[b2][bj][q][1]};
+                    *reinterpret_cast<u32x2*>(slab + (bj * 32 + (lane & 31)) * SB + col * 2) = two;
+                }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < Cfg::WN * 8 / 64; ++i) {
+            const int row = (i * 64 + lane) / 8, vec = (i * 64 + lane) % 8;
+            const u32x4 x = *reinterpret_cast<const u32x4*>(slab + row * SB + vec * 16);
+            const int t = t_wave + row;
+            const int v = v_wave + h * 64 + vec * 8;
+            if (t < Ntok && v < vc0 + cw) *reinterpret_cast<u32x4*>(dZc + (int64_t)t * ld_c + (v - vc0)) = x;
+        }
+        __syncthreads();
     }
 }
 
@@ -807,7 +951,9 @@ bool launch_gemm_cfg(const bf16_t* A, int64_t lda, int M, const bf16_t* B, int64
     auto kern = gemm_tn_kernel<Cfg, STORE>;
     if (!allow_lds(kern, Cfg::LDS_BYTES)) return false;
     dim3 grid(tile_grid((M + Cfg::BM - 1) / Cfg::BM, (N + Cfg::BN - 1) / Cfg::BN));
-    hipLaunchKernelGGL(kern, grid, dim3(Cfg::NT), Cfg::LDS_BYTES, st, A, lda, M, B, ldb, N, K, C, ldc);
+    const int eb = STORE == STORE_BF16 ? 2 : 4;
+    const int wide_rows = (((uintptr_t)C & 15u) == 0 && (ldc * eb) % 16 == 0) ? 1 : 0;
+    hipLaunchKernelGGL(kern, grid, dim3(Cfg::NT), Cfg::LDS_BYTES, st, A, lda, M, B, ldb, N, K, C, ldc, wide_rows);
     return true;
 }
 

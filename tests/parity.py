@@ -1,7 +1,7 @@
 """Shared machinery of the GPU-vs-oracle parity tests: run the HIP path through the C ABI,
 run the fp64 oracle on the same seeded inputs, compare element by element.
 
-Tolerances (derivation in DESIGN.md, "Tolerances"):
+Tolerances:
   * integer / byte outputs (MPT mask, segment ids, gates, counters): bit-exact, except that
     tokens whose oracle probability lies within 1e-6 of tau (mask) or whose ratio lies within
     1e-5 of a clip edge (clip counter) are excluded -- both are discontinuities.

@@ -59,8 +59,8 @@ typedef enum { ULORL_F32 = 0, ULORL_BF16 = 1 } ulorl_dtype;
 typedef enum { ULORL_IS_SAIS = 0, ULORL_IS_POIS = 1 } ulorl_is_mode;
 
 /* When MPTs are masked (Sec. 3.2.2).  The equation of I_msk gates per response on
- * the response's mean token entropy; the prose speaks of "the current entropy" of the
- * model, offered as GLOBAL (token-mean entropy over the whole call).  ALWAYS is the
+ * the response's mean token entropy; the prose around it speaks of the entropy of the
+ * model as a whole, offered as GLOBAL (token-mean entropy over the whole call).  ALWAYS is the
  * static "Masking MPTs" experiment of Sec. 3.2.1; NEVER gives the DAPO objective
  * (Eq. 7) unchanged.                                                                */
 typedef enum {

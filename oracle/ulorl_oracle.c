@@ -106,7 +106,7 @@ int ulorl_oracle_row_stats(const void *logits, int storage, int64_t n_rows, int6
  *   Hbar[i] = mean_t H[t]  over ALL tokens of the response          (Sec. 3.2.2)
  *   gate[i] = Hbar[i] < sigma (strict)                               (Sec. 3.2.2, I_msk case 1)
  *     gate modes: per response (the equation), global (token-mean entropy of the whole
- *     call, the prose reading "the model's current entropy"), always (static masking
+ *     call, the reading of the prose, which speaks of the model's entropy as a whole), always (static masking
  *     experiment of Sec. 3.2.1), never (plain DAPO objective, Eq. 7).
  * Per token:
  *   seg[t]  = f(t): explicit id if given, else offset-in-response div seg_len   (Sec. 3.1.2)

@@ -494,11 +494,14 @@ __device__ __forceinline__ void store_wave_tile_rows(const f32x16 (&acc)[Cfg::MB
                         *reinterpret_cast<u32x4*>(dst) = v;
                     }
                 } else {                                     // ragged right edge: element by element
-                    for (int e = 0; e < EPV && n + e < N; ++e) {
+#pragma unroll
+                    for (int e = 0; e < EPV; ++e) {
+                        if (n + e >= N) break;
                         if (STORE == STORE_BF16) {
-                            reinterpret_cast<bf16_t*>(dst)[e] = (bf16_t)((v[e >> 1] >> (16 * (e & 1))) & 0xffffu);
+                            const uint32_t pair = v[e / 2];
+                            reinterpret_cast<bf16_t*>(dst)[e] = (bf16_t)((e & 1) ? (pair >> 16) : (pair & 0xffffu));
                         } else {
-                            const float x = __builtin_bit_cast(float, v[e]);
+                            const float x = __builtin_bit_cast(float, (uint32_t)v[e]);
                             if (STORE == STORE_F32_ACCUM) reinterpret_cast<float*>(dst)[e] += x;
                             else reinterpret_cast<float*>(dst)[e] = x;
                         }

@@ -31,6 +31,13 @@ def test_gemm_tn_bf16_against_fp64(M, N, K):
     big[:, :K] = a
     c2 = ulorl.gemm_tn_bf16(big[:, :K], b)
     assert torch.equal(c, c2)
+    # strided result whose pitch allows 16-byte stores while N itself may end inside a vector:
+    # same values, and the columns beyond N stay untouched
+    ldc = (N + 3) // 4 * 4 + 4
+    wide = torch.full((M, ldc), -7.0, device=DEV, dtype=torch.float32)
+    ulorl.gemm_tn_bf16(a, b, out=wide[:, :N])
+    assert torch.equal(wide[:, :N], c)
+    assert torch.all(wide[:, N:] == -7.0)
 
 
 @pytest.mark.parametrize("tile", [0, 1, 2, 3, 4, 5, 6, 8])

@@ -262,18 +262,22 @@ def main():
     for _ in range(args.warmup):
         step_two_call()
     wall2 = fwd_ms = bwd_ms = 0.0
+    two_steps = []
     for _ in range(K):
         a, b, c = step_two_call()
         wall2 += a
         fwd_ms += b
         bwd_ms += c
+        two_steps.append(a * 1e3)
     for _ in range(args.warmup):
         step_fused()
     wall1 = fused_ms = 0.0
+    fused_steps = []
     for _ in range(K):
         a, b = step_fused()
         wall1 += a
         fused_ms += b
+        fused_steps.append(a * 1e3)
 
     cnt = out.counters.cpu().tolist()
     live = int((out.gcoef != 0).sum().item())
@@ -323,8 +327,12 @@ def main():
         "roofline": roof_fused if headline_fused else roof_bwd,
         "nominal_three_pass": {"bytes_per_step": nominal_bytes, "equivalent_GBps": nominal_bytes / (wall / K) / 1e9,
                                "frac_of_hbm_peak": nominal_bytes / (wall / K) / 1e9 / HBM_PEAK_GBS},
-        "one_call": {"ms_per_step": wall1 / K * 1e3, "token_rows_per_s": w.N * K / wall1, "roofline": roof_fused},
-        "two_call": {"ms_per_step": wall2 / K * 1e3, "token_rows_per_s": w.N * K / wall2, "fwd_ms": fwd_ms / K,
+        "one_call": {"ms_per_step": wall1 / K * 1e3, "ms_per_step_min": min(fused_steps),
+                     "ms_per_step_median": sorted(fused_steps)[K // 2], "token_rows_per_s": w.N * K / wall1,
+                     "roofline": roof_fused},
+        "two_call": {"ms_per_step": wall2 / K * 1e3, "ms_per_step_min": min(two_steps),
+                     "ms_per_step_median": sorted(two_steps)[K // 2], "token_rows_per_s": w.N * K / wall2,
+                     "fwd_ms": fwd_ms / K,
                      "bwd_ms": bwd_ms / K, "roofline_bwd": roof_bwd, "roofline_fwd": roof_fwd},
         "batch": {"masked_tokens": cnt[0], "clipped_tokens": cnt[1], "positive_tokens": cnt[2],
                   "zero_gradient_rows": w.N - live, "status": cnt[3], "loss": out.loss.item()},

@@ -155,7 +155,7 @@ int32_t ulorl_token_loss_fwd(
  * (chain rule through the log-softmax; the mask is a constant).  Rows with gcoef[t] == 0
  * (masked, clipped, zero advantage, or flagged invalid) are written as zeros without being
  * read.  dlogits has the type and row stride of logits and MAY BE THE SAME BUFFER as logits
- * (each row is read and then overwritten by the one workgroup that owns it).  Values are
+ * (every 16-byte piece is read and then overwritten by the same thread).  Values are
  * rounded to the storage type with round-to-nearest-even.
  *   lse, gcoef    [N] as produced by the forward call on the same logits.
  *   grad_out      HOST scalar, upstream d(objective)/d(loss), usually 1.

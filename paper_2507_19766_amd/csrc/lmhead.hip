@@ -15,7 +15,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
 #include <type_traits>
+#include <unordered_map>
 
 #include "ulorl.h"
 #include "ulorl_internal.hpp"
@@ -902,16 +904,18 @@ LmheadLayout lmhead_layout(int64_t N, int64_t Hd, int64_t V, int32_t R, int32_t 
     L.ldt = round_up64(N);
     L.ldc = round_up64(chunk);
     const int64_t ttiles = (N + bn - 1) / bn;
+    constexpr int kMaxSplits = 16;                          // the partial-statistics buffer holds this many slices
     int splits = (int)((1024 + ttiles - 1) / ttiles);       // aim at >= 1024 workgroups
     const int64_t vtiles = (V + bm - 1) / bm;
     if (splits > vtiles) splits = (int)vtiles;
+    if (splits > kMaxSplits) splits = kMaxSplits;
     if (splits < 1) splits = 1;
     const int64_t tiles_per_split = (vtiles + splits - 1) / splits;
     L.v_per_split = (int)(tiles_per_split * bm);
     L.splits = (int)((vtiles + tiles_per_split - 1) / tiles_per_split);
     // sized for the largest split count any tile shape can ask for, so that the workspace
     // requirement does not depend on the tuning knob
-    const size_t max_splits = 16;
+    const size_t max_splits = kMaxSplits;
     size_t off = 0;
     L.wt = off;      off = align_up(off + (size_t)V * Hd * 2, 256);
     L.ht = off;      off = align_up(off + (size_t)Hd * L.ldt * 2, 256);
@@ -934,10 +938,25 @@ int32_t check_lmhead(const void* hidden, const void* W, int64_t N, int64_t Hd, i
     return ULORL_OK;
 }
 
+// Raises the kernel's dynamic-LDS limit once per kernel and process (the runtime call is not a
+// stream operation; keeping it out of later launches also keeps it out of stream captures that
+// follow a warm-up call).
+bool allow_lds_for(const void* kernel, size_t bytes)
+{
+    static std::mutex mu;
+    static std::unordered_map<const void*, size_t> allowed;
+    std::lock_guard<std::mutex> lock(mu);
+    auto it = allowed.find(kernel);
+    if (it != allowed.end() && it->second >= bytes) return true;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess) return false;
+    allowed[kernel] = bytes;
+    return true;
+}
+
 template <class Kernel>
 bool allow_lds(Kernel k, size_t bytes)
 {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) == hipSuccess;
+    return allow_lds_for(reinterpret_cast<const void*>(k), bytes);
 }
 
 void launch_transpose(const bf16_t* src, int64_t ld_src, int rows, int cols, bf16_t* dst, int64_t ld_dst, int dst_cols,

@@ -73,3 +73,23 @@ def test_lmhead_config5_reduced_rows():
     w = ui.shrink(ui.config(5), [512, 512], seg_len=256, name="cfg5_reduced")
     res, tt = run_lmhead_parity(w, params_for(w, gate_mode=ulorl.GATE_ALWAYS), chunk=8192, say=say)
     assert tt.n_clip_inactive > 0
+
+
+@pytest.mark.parametrize("lengths,V,hidden,chunk", [([300, 212], 4096 + 1544, 256, 1024), ([64], 8192 + 8, 64, 64),
+                                                    ([1000, 24], 1544, 128, 2048)])
+def test_workspace_is_never_overrun(lengths, V, hidden, chunk):
+    """Guard bytes behind the workspace stay untouched by the forward and the backward call (shapes
+    with few token tiles and many vocabulary tiles ask for the most vocabulary slices)."""
+    w = ui.shrink(ui.config(5), lengths, V=V, hidden=hidden, seg_len=64, name="lmhead_guard")
+    d = ui.generate(w, DEV)
+    p = ulorl.Params(gate_mode=ulorl.GATE_ALWAYS, seg_len=w.seg_len)
+    need = ulorl.lmhead_workspace_bytes(w.N, w.hidden, w.V, w.R, chunk)
+    guard = 1 << 20
+    buf = torch.full((need + guard,), 0xA5, dtype=torch.uint8, device=DEV)
+    ws = buf[:need]
+    out = ulorl.lmhead_token_loss_fwd(d["hidden"], d["weight"], d["token_ids"], d["cu_seqlens"], d["advantages"],
+                                      d["old_logp"], p, vocab_chunk=chunk, workspace=ws)
+    ulorl.lmhead_token_loss_bwd(d["hidden"], d["weight"], d["token_ids"], out.lse, out.gcoef, 1.0, vocab_chunk=chunk,
+                                workspace=ws)
+    torch.cuda.synchronize()
+    assert bool((buf[need:] == 0xA5).all())

@@ -287,3 +287,26 @@ def test_device_detected_errors_raise_status_bits_without_faulting():
         r = ulorl.token_loss_fwd(d["logits"], d["token_ids"], cu, d["advantages"], d["old_logp"], p)
         assert int(r.counters[3]) & ulorl.STATUS_BAD_CU
         assert r.loss.item() == 0.0 and torch.all(r.gcoef == 0)
+
+
+@pytest.mark.parametrize("lengths", [[1], [1023, 1, 1025], [3] * 700, [2049]])
+def test_workspace_and_outputs_are_never_overrun(lengths):
+    """Guard bytes behind the workspace, the per-token outputs and the gradient stay untouched by
+    the two-call and the one-call path (token counts around the 1024-token block of the O(N)
+    kernels, many tiny responses)."""
+    w = ui.shrink(ui.config(2), lengths, V=1000, seg_len=7, name="guard")
+    d = ui.generate(w, DEV)
+    p = params_for(w, gate_mode=ulorl.GATE_PER_RESPONSE, sigma=6.0)
+    need = ulorl.token_loss_workspace_bytes(w.N, w.R)
+    guard = 1 << 16
+    buf = torch.full((need + guard,), 0xA5, dtype=torch.uint8, device=DEV)
+    dz_buf = torch.full((w.N * w.V + guard,), -3.0, dtype=torch.bfloat16, device=DEV)
+    dz = dz_buf[:w.N * w.V].view(w.N, w.V)
+    out = ulorl.token_loss_fwd(d["logits"], d["token_ids"], d["cu_seqlens"], d["advantages"], d["old_logp"], p,
+                               workspace=buf[:need])
+    ulorl.token_loss_bwd(d["logits"], d["token_ids"], out.lse, out.gcoef, 1.0, dlogits=dz)
+    ulorl.token_loss_fwd_bwd(d["logits"], d["token_ids"], d["cu_seqlens"], d["advantages"], d["old_logp"], p,
+                             grad_out=1.0, dlogits=dz, out=out, workspace=buf[:need])
+    torch.cuda.synchronize()
+    assert bool((buf[need:] == 0xA5).all())
+    assert bool((dz_buf[w.N * w.V:] == -3.0).all())

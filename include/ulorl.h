@@ -260,6 +260,38 @@ int32_t ulorl_advantage_prep(
     int32_t group_size, int64_t N, float eps, int32_t unbiased,
     float *resp_adv, uint8_t *group_keep, float *token_adv, int64_t *kept_tokens, void *hip_stream);
 
+/* ------------------------------------------------------------------------------------------
+ * One rollout step of training with segment rollouts (Algorithm 1, Sec. 3.1.1): after the decoder
+ * has produced at most seg_len further tokens for each of the B samples in flight (samples carried
+ * over from the unfinished pool, or new prompts with prev_len = 0), sort them into the two pools.
+ * The three ways a decode ends:
+ *   the end-of-sequence token was produced          -> state 1, experience pool
+ *   the global maximum length max_len is reached     -> state 2 (truncated), experience pool
+ *   the segment is full, max_len not reached          -> state 0, unfinished pool (decode on next step)
+ * (an end token exactly at max_len is a normal end).  A sample whose numbers fit none of these
+ * (fewer than seg_len new tokens without a reason, more than the segment or max_len allow, an end
+ * flag with no new token) is counted in counts[4], clamped into range and kept unfinished.
+ *   prev_len, new_len  [B] int32   tokens decoded before / in this step
+ *   hit_eos            [B] uint8
+ * Outputs (sample order is preserved inside each pool):
+ *   state [B] uint8, total_len [B] = prev_len + new_len, segments [B] = segments spanned so far
+ *   unfinished_idx [B]   first counts[0] entries: indices of the samples to decode further
+ *   experience_idx [B]   first counts[1] entries: indices of the samples that go to training
+ *   exp_cu_seqlens [B+1] first counts[1]+1 entries: prefix sums of their total lengths, i.e. the
+ *                        cu_seqlens of the packed training batch (token t of it belongs to
+ *                        segment offset / seg_len, the seg_len rule of ulorl_params)
+ *   exp_truncated  [B]   first counts[1] entries: 1 where the sample was cut at max_len -- the
+ *                        `truncated` input of ulorl_advantage_prep (Sec. 3.5)
+ *   counts [5] int64     unfinished, experience, truncated, experience tokens, inconsistent samples
+ * B * max_len must fit in int32 (offsets of the packed batch).  One workgroup; no workspace.
+ */
+int32_t ulorl_segment_pool_step(
+    int32_t B, const int32_t *prev_len, const int32_t *new_len, const uint8_t *hit_eos,
+    int32_t seg_len, int32_t max_len,
+    uint8_t *state, int32_t *total_len, int32_t *segments, int32_t *unfinished_idx,
+    int32_t *experience_idx, int32_t *exp_cu_seqlens, uint8_t *exp_truncated, int64_t *counts,
+    void *hip_stream);
+
 /*
  * Training-dynamics diagnostics per segment id, from the outputs of a forward call: the
  * quantities behind the comparison of the importance-sampling schemes in Sec. 3.1.2 (how far the

@@ -6,9 +6,9 @@ argument marshalling for the C functions its only arithmetic is the lm_head vari
 stock fp64 matrix products (numpy), which are that variant's definition.
 
 The three main C entry points mirror the three stages of the objective of Sec. 3.2.2:
-row statistics over the vocabulary, the O(1)-per-token terms, and the logits gradient; two
-more cover the group advantages of Eq. 4 / Eq. 7 / Sec. 3.5 and per-segment diagnostics
-(Sec. 3.1.2).
+row statistics over the vocabulary, the O(1)-per-token terms, and the logits gradient; three
+more cover the pool update of the segment-rollout loop (Algorithm 1), the group advantages of
+Eq. 4 / Eq. 7 / Sec. 3.5 and per-segment diagnostics (Sec. 3.1.2).
 """
 from __future__ import annotations
 
@@ -235,3 +235,31 @@ def segment_diagnostics(seg, ratio, logp, old_logp, entropy, mask, advantages, K
         _ptr(out["ent_sum"]), _ptr(out["masked"]), ctypes.byref(oor))
     out["out_of_range"] = int(oor.value)
     return out
+
+
+def pool_step(prev_len, new_len, hit_eos, seg_len, max_len):
+    """One rollout step of Algorithm 1 (Sec. 3.1.1) -> dict with state, total_len, segments,
+    unfinished_idx, experience_idx, exp_cu_seqlens, exp_truncated, counts (see the C source)."""
+    prev = np.ascontiguousarray(prev_len, np.int32)
+    new = np.ascontiguousarray(new_len, np.int32)
+    eos = np.ascontiguousarray(hit_eos, np.uint8)
+    B = prev.shape[0]
+    state = np.zeros(B, np.uint8)
+    total = np.zeros(B, np.int32)
+    segs = np.zeros(B, np.int32)
+    unf = np.zeros(max(B, 1), np.int32)
+    exp = np.zeros(max(B, 1), np.int32)
+    cu = np.zeros(B + 1, np.int64)
+    trunc = np.zeros(max(B, 1), np.uint8)
+    counts = np.zeros(5, np.int64)
+    lib = _load()
+    lib.ulorl_oracle_pool_step.restype = ctypes.c_int
+    rc = lib.ulorl_oracle_pool_step(
+        ctypes.c_int32(B), _ptr(prev), _ptr(new), _ptr(eos), ctypes.c_int32(seg_len), ctypes.c_int32(max_len),
+        _ptr(state), _ptr(total), _ptr(segs), _ptr(unf), _ptr(exp), _ptr(cu), _ptr(trunc), _ptr(counts))
+    if rc != 0:
+        raise ValueError("oracle pool_step: bad seg_len / max_len / B")
+    nu, ne = int(counts[0]), int(counts[1])
+    return {"state": state, "total_len": total, "segments": segs, "unfinished_idx": unf[:nu],
+            "experience_idx": exp[:ne], "exp_cu_seqlens": cu[:ne + 1], "exp_truncated": trunc[:ne],
+            "counts": counts}

@@ -326,3 +326,69 @@ int ulorl_oracle_segment_diagnostics(int64_t N, int32_t K, const int32_t *seg, c
     *out_of_range = oor;
     return 0;
 }
+
+/*
+ * One rollout step of the segment-rollout loop (Algorithm 1, Sec. 3.1.1).  Every sample in
+ * flight (carried over from the unfinished pool, or a new prompt with prev_len = 0) has just
+ * been decoded for at most seg_len further tokens.  The three ways a decode can end decide
+ * where the sample goes:
+ *   the end-of-sequence token was produced          -> state 1, experience pool
+ *   the global maximum length max_len is reached     -> state 2 (truncated), experience pool
+ *   the segment is full and max_len is not reached   -> state 0, unfinished pool
+ * An end-of-sequence token that lands exactly on the global maximum counts as a normal end.
+ * A step that stops short of seg_len without either reason, or decodes more than the segment or
+ * the global maximum allow, is inconsistent: it is reported in counts[4] and the sample is kept
+ * in the unfinished pool (lengths clamped into range).
+ *
+ * Outputs (sample order is preserved inside each pool):
+ *   state[B], total_len[B] = prev_len + new_len, segments[B] = segments the sample spans so far
+ *   unfinished_idx[0 .. counts[0])   indices of the samples to decode further
+ *   experience_idx[0 .. counts[1])   indices of the samples that go to training
+ *   exp_cu_seqlens[0 .. counts[1]]   prefix sums of their total lengths (packed-batch boundaries)
+ *   exp_truncated[0 .. counts[1])    1 where the sample was cut at max_len (its reward counts as 0, Sec. 3.5)
+ *   counts[5]: unfinished, experience, truncated, experience tokens, inconsistent samples
+ * Returns non-zero for seg_len <= 0, max_len <= 0 or B < 0.
+ */
+int ulorl_oracle_pool_step(int32_t B, const int32_t *prev_len, const int32_t *new_len,
+                           const uint8_t *hit_eos, int32_t seg_len, int32_t max_len, uint8_t *state,
+                           int32_t *total_len, int32_t *segments, int32_t *unfinished_idx,
+                           int32_t *experience_idx, int64_t *exp_cu_seqlens, uint8_t *exp_truncated,
+                           int64_t *counts)
+{
+    if (B < 0 || seg_len <= 0 || max_len <= 0) return 1;
+    int64_t n_unf = 0, n_exp = 0, n_trunc = 0, tokens = 0, n_bad = 0;
+    exp_cu_seqlens[0] = 0;
+    for (int32_t i = 0; i < B; ++i) {
+        int64_t p = prev_len[i], n = new_len[i];
+        int bad = 0;
+        if (p < 0 || p >= max_len) { bad = 1; p = p < 0 ? 0 : max_len - 1; }
+        int64_t room = max_len - p;
+        if (room > seg_len) room = seg_len;
+        if (n < 0 || n > room) { bad = 1; n = n < 0 ? 0 : room; }
+        const int64_t t = p + n;
+        const int eos = hit_eos[i] != 0 && n > 0;
+        if (hit_eos[i] != 0 && n == 0) bad = 1;             /* an end token is itself a decoded token */
+        int st;
+        if (bad) st = 0;
+        else if (eos) st = 1;
+        else if (t >= max_len) st = 2;
+        else if (n == seg_len) st = 0;
+        else { st = 0; bad = 1; }                             /* stopped early for no reason */
+        state[i] = (uint8_t)st;
+        total_len[i] = (int32_t)t;
+        segments[i] = (int32_t)(t == 0 ? 0 : (t + seg_len - 1) / seg_len);
+        n_bad += bad;
+        if (st == 0) {
+            unfinished_idx[n_unf++] = i;
+        } else {
+            experience_idx[n_exp] = i;
+            exp_truncated[n_exp] = (uint8_t)(st == 2);
+            tokens += t;
+            exp_cu_seqlens[n_exp + 1] = tokens;
+            n_trunc += st == 2;
+            ++n_exp;
+        }
+    }
+    counts[0] = n_unf; counts[1] = n_exp; counts[2] = n_trunc; counts[3] = tokens; counts[4] = n_bad;
+    return 0;
+}

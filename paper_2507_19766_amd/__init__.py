@@ -11,5 +11,5 @@ from .binding import (  # noqa: F401
     UlorlError, Params, FwdResult, lib_path, load_library, version, status_string, tune,
     token_loss_workspace_bytes, token_loss_fwd, token_loss_bwd, token_loss_fwd_bwd, row_stats,
     lmhead_workspace_bytes, lmhead_token_loss_fwd, lmhead_token_loss_bwd, gemm_tn_bf16,
-    advantage_prep, segment_diagnostics,
+    advantage_prep, segment_diagnostics, segment_pool_step,
 )

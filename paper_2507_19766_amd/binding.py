@@ -123,6 +123,8 @@ def load_library(build_if_missing: bool = True):
     lib.ulorl_segment_diagnostics.restype = c.c_int32
     lib.ulorl_segment_diagnostics.argtypes = [c.c_int64, c.c_int32, vp, vp, vp, vp, vp, vp, vp, c.c_float, c.c_float,
                                               vp, vp, vp, vp, vp, vp, vp, vp, vp, c.c_size_t, vp]
+    lib.ulorl_segment_pool_step.restype = c.c_int32
+    lib.ulorl_segment_pool_step.argtypes = [c.c_int32, vp, vp, vp, c.c_int32, c.c_int32, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.ulorl_token_loss_bwd.restype = c.c_int32
     lib.ulorl_token_loss_bwd.argtypes = [
         vp, c.c_int32, c.c_int64, c.c_int64, c.c_int64, vp, vp, vp, c.c_float, vp, vp]
@@ -458,4 +460,31 @@ def segment_diagnostics(res: FwdResult, advantages, old_logp, K: int, eps_low: f
         _p(ws), ws.numel(), _stream(dev))
     if rc != 0:
         raise UlorlError(rc, "ulorl_segment_diagnostics")
+    return out
+
+
+def segment_pool_step(prev_len, new_len, hit_eos, seg_len: int, max_len: int):
+    """ulorl_segment_pool_step -> dict of device tensors: state, total_len, segments [B];
+    unfinished_idx, experience_idx, exp_truncated [B] and exp_cu_seqlens [B+1] (only the leading
+    counts[0] / counts[1] (+1) entries are meaningful); counts [5] int64."""
+    lib = load_library()
+    if not prev_len.is_cuda:
+        raise RuntimeError("libulorl runs on the GPU only")
+    dev = prev_len.device
+    B = prev_len.shape[0]
+    prev_len = _vec(prev_len, torch.int32, B, "prev_len", dev)
+    new_len = _vec(new_len, torch.int32, B, "new_len", dev)
+    hit_eos = _vec(hit_eos, torch.uint8, B, "hit_eos", dev)
+    i32 = dict(dtype=torch.int32, device=dev)
+    u8 = dict(dtype=torch.uint8, device=dev)
+    out = {"state": torch.empty(B, **u8), "total_len": torch.empty(B, **i32), "segments": torch.empty(B, **i32),
+           "unfinished_idx": torch.empty(B, **i32), "experience_idx": torch.empty(B, **i32),
+           "exp_cu_seqlens": torch.empty(B + 1, **i32), "exp_truncated": torch.empty(B, **u8),
+           "counts": torch.empty(5, dtype=torch.int64, device=dev)}
+    rc = lib.ulorl_segment_pool_step(
+        B, _p(prev_len), _p(new_len), _p(hit_eos), int(seg_len), int(max_len), _p(out["state"]), _p(out["total_len"]),
+        _p(out["segments"]), _p(out["unfinished_idx"]), _p(out["experience_idx"]), _p(out["exp_cu_seqlens"]),
+        _p(out["exp_truncated"]), _p(out["counts"]), _stream(dev))
+    if rc != 0:
+        raise UlorlError(rc, "ulorl_segment_pool_step")
     return out

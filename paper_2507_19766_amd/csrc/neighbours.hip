@@ -1,6 +1,7 @@
-// The two O(N) neighbours of the token loss: advantage preparation (the step just before it) and
-// per-segment training-dynamics diagnostics (read off its outputs).  Both are bandwidth-trivial;
-// they exist so that a training step needs no host round trip between reward and gradient.
+// The small neighbours of the token loss: the pool update of the segment-rollout loop and the
+// advantage preparation (the steps just before it) and per-segment training-dynamics diagnostics
+// (read off its outputs).  All are bandwidth-trivial; they exist so that a training step needs no
+// host round trip between rollout bookkeeping, reward and gradient.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -194,6 +195,93 @@ __global__ __launch_bounds__(kBlock) void segment_final_kernel(const double* __r
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// ---------------------------------------------------------------------------------------------
+// segment-rollout pool update (Algorithm 1, Sec. 3.1.1)
+// ---------------------------------------------------------------------------------------------
+// Inclusive prefix sum over the workgroup (wave scans by shuffle, wave totals through LDS in
+// index order).  Returns the thread's inclusive sum; *total = sum over the workgroup.
+__device__ __forceinline__ int block_scan_i32(int v, int* wave_tot, int* total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int up = __shfl_up(v, off);
+        if (lane >= off) v += up;
+    }
+    __syncthreads();                 // wave_tot may still be read from the previous scan
+    if (lane == 63) wave_tot[wave] = v;
+    __syncthreads();
+    int before = 0, all = 0;
+    for (int w = 0; w < kBlock / 64; ++w) {
+        const int x = wave_tot[w];
+        before += w < wave ? x : 0;
+        all += x;
+    }
+    *total = all;
+    return v + before;
+}
+
+// One workgroup walks the samples in blocks of 1024: classify (the three ways a decode ends),
+// then place each sample by an order-preserving prefix sum.
+__global__ __launch_bounds__(kBlock) void pool_step_kernel(int32_t B, const int32_t* __restrict__ prev_len,
+                                                           const int32_t* __restrict__ new_len,
+                                                           const uint8_t* __restrict__ hit_eos, int32_t seg_len,
+                                                           int32_t max_len, uint8_t* __restrict__ state,
+                                                           int32_t* __restrict__ total_len,
+                                                           int32_t* __restrict__ segments,
+                                                           int32_t* __restrict__ unfinished_idx,
+                                                           int32_t* __restrict__ experience_idx,
+                                                           int32_t* __restrict__ exp_cu,
+                                                           uint8_t* __restrict__ exp_truncated,
+                                                           int64_t* __restrict__ counts)
+{
+    __shared__ int wave_tot[kBlock / 64];
+    const int tid = threadIdx.x;
+    int base_unf = 0, base_exp = 0, base_tok = 0, n_trunc = 0, n_bad = 0;
+    if (tid == 0) exp_cu[0] = 0;
+    for (int32_t c0 = 0; c0 < B; c0 += kBlock) {
+        const int32_t i = c0 + tid;
+        int st = 0, bad = 0, t = 0, f_unf = 0, f_exp = 0;
+        if (i < B) {
+            int64_t p = prev_len[i], n = new_len[i];
+            if (p < 0 || p >= max_len) { bad = 1; p = p < 0 ? 0 : max_len - 1; }
+            int64_t room = (int64_t)max_len - p;
+            if (room > seg_len) room = seg_len;
+            if (n < 0 || n > room) { bad = 1; n = n < 0 ? 0 : room; }
+            t = (int)(p + n);
+            const bool eos_flag = hit_eos[i] != 0;
+            if (eos_flag && n == 0) bad = 1;
+            if (bad) st = 0;
+            else if (eos_flag) st = 1;
+            else if (t >= max_len) st = 2;
+            else if (n == seg_len) st = 0;
+            else { st = 0; bad = 1; }
+            state[i] = (uint8_t)st;
+            total_len[i] = t;
+            segments[i] = t == 0 ? 0 : (t + seg_len - 1) / seg_len;
+            f_unf = st == 0;
+            f_exp = st != 0;
+        }
+        int tot_unf, tot_exp, tot_tok, tot_trunc, tot_bad;
+        const int in_unf = block_scan_i32(f_unf, wave_tot, &tot_unf);
+        const int in_exp = block_scan_i32(f_exp, wave_tot, &tot_exp);
+        const int in_tok = block_scan_i32(f_exp ? t : 0, wave_tot, &tot_tok);
+        block_scan_i32(st == 2, wave_tot, &tot_trunc);
+        block_scan_i32(bad, wave_tot, &tot_bad);
+        if (f_unf) unfinished_idx[base_unf + in_unf - 1] = i;
+        if (f_exp) {
+            const int slot = base_exp + in_exp - 1;
+            experience_idx[slot] = i;
+            exp_truncated[slot] = (uint8_t)(st == 2);
+            exp_cu[slot + 1] = base_tok + in_tok;
+        }
+        base_unf += tot_unf; base_exp += tot_exp; base_tok += tot_tok; n_trunc += tot_trunc; n_bad += tot_bad;
+    }
+    if (tid == 0) {
+        counts[0] = base_unf; counts[1] = base_exp; counts[2] = n_trunc; counts[3] = base_tok; counts[4] = n_bad;
+    }
+}
+
 }  // namespace
 
 extern "C" {
@@ -244,6 +332,22 @@ int32_t ulorl_segment_diagnostics(int64_t N, int32_t K, const int32_t* segment_i
     hipLaunchKernelGGL(segment_partial_kernel, dim3((unsigned)nblk), dim3(kBlock), 0, st, a);
     hipLaunchKernelGGL(segment_final_kernel, dim3(1), dim3(kBlock), 0, st, a.part, a.part_oor, nblk, K, count, ratio_sum,
                        ratio_max, clipped, kl_sum, ent_sum, masked, out_of_range);
+    return hipGetLastError() == hipSuccess ? ULORL_OK : ULORL_ERR_HIP;
+}
+
+int32_t ulorl_segment_pool_step(int32_t B, const int32_t* prev_len, const int32_t* new_len, const uint8_t* hit_eos,
+                                int32_t seg_len, int32_t max_len, uint8_t* state, int32_t* total_len,
+                                int32_t* segments, int32_t* unfinished_idx, int32_t* experience_idx,
+                                int32_t* exp_cu_seqlens, uint8_t* exp_truncated, int64_t* counts, void* hip_stream)
+{
+    if (!prev_len || !new_len || !hit_eos || !state || !total_len || !segments || !unfinished_idx || !experience_idx ||
+        !exp_cu_seqlens || !exp_truncated || !counts)
+        return ULORL_ERR_NULL;
+    if (B <= 0 || seg_len <= 0 || max_len <= 0) return ULORL_ERR_SHAPE;
+    if ((int64_t)B * (int64_t)max_len > 0x7fffffffLL) return ULORL_ERR_SHAPE;   // packed-batch offsets are int32
+    hipLaunchKernelGGL(pool_step_kernel, dim3(1), dim3(kBlock), 0, (hipStream_t)hip_stream, B, prev_len, new_len, hit_eos,
+                       seg_len, max_len, state, total_len, segments, unfinished_idx, experience_idx, exp_cu_seqlens,
+                       exp_truncated, counts);
     return hipGetLastError() == hipSuccess ? ULORL_OK : ULORL_ERR_HIP;
 }
 

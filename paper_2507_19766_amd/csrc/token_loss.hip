@@ -1,17 +1,21 @@
 // Fused UloRL token loss for gfx950 (MI355X): streaming kernels and their C entry points.
 //
-// Three kernels do all the work of the forward/backward pair declared in ulorl.h:
-//   row_stats_kernel   one workgroup per token row streams the V logits once with 16-byte
-//                      loads and keeps a per-lane online (max, sum-exp, sum-exp*z) triple in
-//                      registers; lanes are merged with wave shuffles, waves through LDS.
-//                      -> lse, chosen-token log-prob (Eq. 6 numerator), entropy (Sec. 3.2.2).
-//   token_terms_*      O(N) epilogue: per-response mean entropy and gate, SAIS/POIS ratio
-//                      (Sec. 3.1.2), clipped term (Eq. 7), MPT mask (Eq. MPTS / I_msk), the
-//                      token-mean loss and d loss / d logp.  Fixed-order fp64 sums.
-//   dlogits_kernel     one workgroup per row re-reads the row, recomputes the softmax from the
-//                      saved lse and writes g_t * (onehot - p); rows with g_t == 0 are
-//                      write-only.  Safe in place: a row is read and written by one workgroup,
-//                      each 16-byte vector by the lane that loaded it.
+// The kernels behind the calls declared in ulorl.h:
+//   row_stats_kernel      one workgroup per token row streams the V logits once with 16-byte
+//                         loads and keeps a per-lane online (max, sum-exp, sum-exp*z) triple in
+//                         registers; lanes are merged with wave shuffles, waves through LDS.
+//                         -> lse, chosen-token log-prob (Eq. 6 numerator), entropy (Sec. 3.2.2).
+//   response_entropy_kernel, token_terms_kernel, loss_finalize_kernel
+//                         O(N) epilogue: per-response mean entropy and gate, SAIS/POIS ratio
+//                         (Sec. 3.1.2), clipped term (Eq. 7), MPT mask (Eq. MPTS / I_msk), the
+//                         token-mean loss and d loss / d logp.  Fixed-order fp64 sums.
+//   dlogits_chunk_kernel  the backward call: recomputes the softmax from the saved lse and writes
+//                         g_t * (onehot - p) with one 16-byte vector per thread; rows with
+//                         g_t == 0 are write-only.  Safe in place: each vector is read and then
+//                         written by the same thread.  (dlogits_kernel: the same by one looping
+//                         workgroup per row.)
+//   fused_row_kernel      forward and backward of a row by one workgroup, back to back, for the
+//                         one-call entry point.
 //
 // The HBM stream is the bound; the per-element VALU budget is what has to stay under it, so
 // the inner loops are: unpack, one FMA (scaled argument), one v_exp_f32, and two accumulate
@@ -288,10 +292,11 @@ __device__ __forceinline__ void dlogits_core(const typename Tr::elem* rowp, type
     const float sgn = g > 0.0f ? -1.0f : 1.0f;
     const int yvec = y / E;
 
-    // Software-pipelined: the loads of trip i+1 are issued BEFORE the stores of trip i.  On this
-    // ISA loads and stores share one outstanding-operation counter that retires in issue order,
-    // so a load issued after a store cannot be waited for without also waiting for that store to
-    // be acknowledged by memory; with the loads ahead, a trip never waits on write latency.
+    // Software-pipelined: the loads of trip i+1 are issued before the stores of trip i (loads and
+    // stores share one in-order outstanding-operation counter, so a load issued behind a store is
+    // only known to have returned once that store has been acknowledged).  Measured effect on a
+    // whole-row loop: none to speak of -- the write pattern of row-per-workgroup loops is what
+    // limits them (see dlogits_chunk_kernel).
     auto emit = [&](const u32x4& v, int vec_index) {
         float f[E];
         Tr::unpack(v, f);

@@ -1,5 +1,5 @@
-"""GPU parity of the two O(N) neighbours of the token loss: advantage preparation and
-per-segment diagnostics."""
+"""GPU parity of the small neighbours of the token loss: segment-rollout pool update,
+advantage preparation and per-segment diagnostics."""
 import numpy as np
 import pytest
 import torch
@@ -92,3 +92,71 @@ def test_segment_diagnostics_match_the_oracle():
     g3 = ulorl.segment_diagnostics(res, d["advantages"], None, 4)
     assert int(g3["out_of_range"].item()) == 3000 - 1600 and float(g3["kl_sum"].abs().sum()) == 0.0
     np.testing.assert_array_equal(g3["count"].cpu().numpy(), o["count"][:4])
+
+
+@pytest.mark.parametrize("B", [1, 63, 1024, 1025, 5000])
+def test_segment_pool_step_matches_the_oracle(B):
+    rng = np.random.default_rng(B)
+    seg, mx = 64, 640
+    prev = (rng.integers(0, mx // seg, B) * seg).astype(np.int32)
+    room = np.minimum(seg, mx - prev)
+    kind = rng.integers(0, 3, B)
+    new = np.where(kind == 1, rng.integers(1, room + 1), room).astype(np.int32)
+    eos = (kind >= 1).astype(np.uint8)
+    # a few inconsistent samples: short without a reason, too long, negative, end flag without a token
+    for j, (p, n, e) in enumerate([(0, 5, 0), (0, seg + 1, 0), (-3, 4, 1), (64, 0, 1), (mx, 1, 0)]):
+        if j * 7 < B:
+            prev[j * 7], new[j * 7], eos[j * 7] = p, n, e
+    ref = oracle.pool_step(prev, new, eos, seg, mx)
+    out = ulorl.segment_pool_step(torch.from_numpy(prev).to(DEV), torch.from_numpy(new).to(DEV),
+                                  torch.from_numpy(eos).to(DEV), seg, mx)
+    got = {k: v.cpu().numpy() for k, v in out.items()}
+    nu, ne = int(ref["counts"][0]), int(ref["counts"][1])
+    assert got["counts"].tolist() == ref["counts"].tolist()
+    for k in ("state", "total_len", "segments"):
+        assert np.array_equal(got[k], ref[k]), k
+    assert np.array_equal(got["unfinished_idx"][:nu], ref["unfinished_idx"])
+    assert np.array_equal(got["experience_idx"][:ne], ref["experience_idx"])
+    assert np.array_equal(got["exp_cu_seqlens"][:ne + 1].astype(np.int64), ref["exp_cu_seqlens"])
+    assert np.array_equal(got["exp_truncated"][:ne], ref["exp_truncated"])
+
+
+def test_rollout_model_takes_the_same_path_on_the_gpu():
+    """Forty steps of the segment-rollout loop driven by the GPU pool update and by the oracle:
+    identical pools at every step."""
+    from paper_2507_19766_amd import rollout_model as rm
+
+    L = rm.synthetic_lengths(3000, 4096, 5)
+    a = rm.simulate(rm.gpu_pool_step, L, batch=96, segments=4, max_len=4096, steps=40)
+    b = rm.simulate(oracle.pool_step, L, batch=96, segments=4, max_len=4096, steps=40)
+    assert a["records"] == b["records"]
+    assert a["done"] == b["done"]
+
+
+def test_pool_step_feeds_advantages_and_token_loss():
+    """The experience pool's cu_seqlens and truncation flags go straight into the next two calls."""
+    seg, mx = 32, 128
+    prev = torch.tensor([0, 32, 96, 0, 64, 96, 0, 32], dtype=torch.int32, device=DEV)
+    new = torch.tensor([20, 32, 32, 32, 9, 32, 32, 5], dtype=torch.int32, device=DEV)
+    eos = torch.tensor([1, 0, 0, 0, 1, 1, 1, 1], dtype=torch.uint8, device=DEV)
+    out = ulorl.segment_pool_step(prev, new, eos, seg, mx)
+    cnt = out["counts"].cpu().tolist()
+    ne, ntok = cnt[1], cnt[3]
+    assert cnt[:3] == [2, 6, 1] and ntok == 20 + 128 + 73 + 128 + 32 + 37
+    cu = out["exp_cu_seqlens"][:ne + 1].contiguous()
+    trunc = out["exp_truncated"][:ne].contiguous()
+    rewards = torch.tensor([1, 1, 0, 1, 0, 1], dtype=torch.float32, device=DEV)
+    resp, keep, tok_adv, kept = ulorl.advantage_prep(rewards, cu, 6, truncated=trunc)
+    ref = oracle.advantages(rewards.cpu().numpy(), cu.cpu().numpy(), 6, truncated=trunc.cpu().numpy())
+    assert np.allclose(resp.cpu().numpy(), ref[0], rtol=1e-6, atol=1e-7)
+    assert int(kept.item()) == ref[3] == ntok
+    V = 512
+    g = torch.Generator(device=DEV).manual_seed(1)
+    logits = torch.randn(ntok, V, generator=g, device=DEV)
+    y = torch.randint(0, V, (ntok,), generator=g, device=DEV, dtype=torch.int32)
+    p = ulorl.Params(is_mode=ulorl.IS_POIS, gate_mode=ulorl.GATE_NEVER, seg_len=seg)
+    res = ulorl.token_loss_fwd(logits, y, cu, tok_adv, None, p)
+    assert int(res.counters[3].item()) == 0
+    seg_ids = res.segment_out.cpu().numpy()
+    cu_h = cu.cpu().numpy()
+    assert seg_ids[cu_h[1]:cu_h[2]].max() == 3 and seg_ids[cu_h[0]:cu_h[1]].max() == 0

@@ -17,7 +17,15 @@
  *     per-response entropy gate (Sec. 3.2.2),
  *   - the token-mean reduction 1 / sum_i |o_i| of the DMMPT objective,
  *   - the gradient of loss = -J with respect to the logits (chain rule; the mask
- *     is a constant, the paper adds no extra optimisation objective).
+ *     is a constant, the paper adds no extra optimisation objective),
+ * and, around that core: the group advantages (Eq. 4, the sampling constraint of
+ * Eq. 7, the overlong rule of Sec. 3.5), per-segment diagnostics, and the pool
+ * update of the segment-rollout loop (Algorithm 1, Sec. 3.1.1).
+ *
+ * Every function is pinned by tests to something other than itself (closed forms,
+ * hand-worked cases, invariants, autograd / finite differences, conservation over
+ * whole runs); none of the paper's printed numbers constrains the loss itself, so
+ * parity against published values is unpinned.
  *
  * No blocking, no online rescaling, no fusion: each quantity is a loop over its
  * definition.  OpenMP is used over independent rows only; all sums that cross

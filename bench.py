@@ -36,11 +36,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 matrix rate
 # expressed as measured / algorithmic ratios.  They hold for the kernel source they were taken
 # on: the digest below is checked at run time and `traffic` is null once the kernels changed.
 PMC = {
-    "source_sha256": "1528b4826e2f6d81266067be5b98a5c28ad9d906ea9c929a1b15697ae5de9944",
-    "fused_first_read": 1.0006,      # fused_row_kernel: first read of every row
-    "fused_reread": 0.9986,          # second read of rows with a non-zero coefficient (L2 -> fabric;
-                                     # absorbed by the memory-side cache)
-    "fused_write": 1.0004,
+    "source_sha256": "7136b89858b2fa877ec33efb90bc681a9e947ab7709aac327946698fcddc9947",
+    "fused_read": 1.0096,            # cluster_row_kernel: every row once, plus the polling of the exchange slots
+    "fused_write": 1.0014,
     "bwd_read": 1.0007,              # dlogits_chunk_kernel
     "bwd_write": 1.0000,
 }
@@ -223,7 +221,7 @@ def main():
     pristine = logits.clone() if inplace else None
     dz = logits if inplace else torch.empty_like(logits)
     y, cu, adv, old = data["token_ids"], data["cu_seqlens"], data["advantages"], data["old_logp"]
-    ws = torch.empty(ulorl.token_loss_workspace_bytes(w.N, w.R), dtype=torch.uint8, device=dev)
+    ws = torch.empty(ulorl.token_loss_workspace_bytes(w.N, w.V, w.R), dtype=torch.uint8, device=dev)
     out = None
 
     def restore():
@@ -283,8 +281,8 @@ def main():
     live = int((out.gcoef != 0).sum().item())
     row_bytes = w.V * elem
     # Algorithmic HBM bytes per launch.  Two-call path: the forward reads every row once; the
-    # backward reads and writes live rows and only writes rows whose coefficient is zero.  Fused
-    # path: every row is read once and written once (its second read is served on chip).
+    # backward reads and writes live rows and only writes rows whose coefficient is zero.  One-call
+    # path: every row is read once and written once.
     fwd_bytes = row_bytes * w.N
     bwd_bytes = row_bytes * (2 * live + (w.N - live))
     fused_bytes = row_bytes * 2 * w.N
@@ -294,18 +292,16 @@ def main():
     fwd_gbs = fwd_bytes / (fwd_ms / K * 1e-3) / 1e9
 
     counters_valid = kernel_source_digest() == PMC["source_sha256"]
-    fused_traffic = (row_bytes * (w.N * PMC["fused_first_read"] + live * PMC["fused_reread"] + w.N * PMC["fused_write"])
-                     if counters_valid else None)
+    fused_traffic = (row_bytes * w.N * (PMC["fused_read"] + PMC["fused_write"]) if counters_valid else None)
     bwd_traffic = (row_bytes * (live * PMC["bwd_read"] + w.N * PMC["bwd_write"]) if counters_valid else None)
     headline_fused = args.path == "fused"
     wall = wall1 if headline_fused else wall2
     value = w.N * K / wall
     ms_per_step = wall / K * 1e3
-    roof_fused = {"bound": "hbm", "kernel": "fused_row_kernel (one-call forward+backward; the call also runs "
-                  "four O(N) kernels, about 0.1 ms)", "achieved": fused_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                  "frac": fused_gbs / HBM_PEAK_GBS, "traffic": fused_traffic,
-                  "traffic_note": "L2<->fabric bytes per launch (FETCH_SIZE, WRITE_SIZE scaled by a copy kernel); "
-                                  "includes the second read of each row, which the memory-side cache serves",
+    roof_fused = {"bound": "hbm", "kernel": "cluster_row_kernel (one-call forward+backward by row-cooperative "
+                  "workgroups; the call also runs five small kernels, about 0.1 ms)", "achieved": fused_gbs,
+                  "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": fused_gbs / HBM_PEAK_GBS, "traffic": fused_traffic,
+                  "traffic_note": "HBM bytes per launch (FETCH_SIZE, WRITE_SIZE scaled by a copy kernel)",
                   "algorithmic_bytes_per_launch": fused_bytes, "avg_launch_ms": fused_ms / K}
     roof_bwd = {"bound": "hbm", "kernel": "dlogits_chunk_kernel (backward call of the two-call path)",
                 "achieved": bwd_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": bwd_gbs / HBM_PEAK_GBS,

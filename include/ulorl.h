@@ -74,7 +74,11 @@ typedef enum {
 enum {
     ULORL_STATUS_BAD_TOKEN = 1,     /* a token id outside [0, V)                      */
     ULORL_STATUS_NONFINITE = 2,     /* a row whose softmax statistics are not finite  */
-    ULORL_STATUS_BAD_CU = 4         /* cu_seqlens not 0 = cu[0] <= ... <= cu[R] = N   */
+    ULORL_STATUS_BAD_CU = 4,        /* cu_seqlens not 0 = cu[0] <= ... <= cu[R] = N   */
+    ULORL_STATUS_SYNC = 8           /* one-call path only: workgroups that share a row waited
+                                       in vain for one another (seconds; never observed); the
+                                       rows concerned have a zero gradient and count as
+                                       non-finite.  Run the two-call path instead.           */
 };
 
 /* HOST struct of scalar parameters. */
@@ -99,11 +103,12 @@ int32_t ulorl_version(void);
 /* Static string for a status code (HOST pointer, never NULL). */
 const char *ulorl_status_string(int32_t status);
 
-/* Bytes of device workspace ulorl_token_loss_fwd / _fwd_bwd need for N rows in R
- * responses (0 if N or R is out of range).  The workspace holds per-response entropy
- * sums, per-block partial sums and one flag byte per row; its contents need not be
- * preserved between calls.                                                         */
-size_t ulorl_token_loss_workspace_bytes(int64_t N, int32_t R);
+/* Bytes of device workspace ulorl_token_loss_fwd / _fwd_bwd need for N rows of V logits
+ * in R responses (0 if an argument is out of range).  The workspace holds per-response
+ * entropy sums, per-block partial sums, one flag byte per row and, for the one-call path,
+ * 16 bytes per row and per 61440 bytes of the row; its contents need not be preserved
+ * between calls.                                                                    */
+size_t ulorl_token_loss_workspace_bytes(int64_t N, int64_t V, int32_t R);
 
 /*
  * Forward: log-softmax statistics -> ratio -> clipped term -> MPT mask -> loss.
@@ -168,14 +173,17 @@ int32_t ulorl_token_loss_bwd(
 /*
  * Fused forward + backward in one call: same inputs, outputs and conventions as
  * ulorl_token_loss_fwd (advantages must not be NULL) plus grad_out and dlogits as in
- * ulorl_token_loss_bwd (dlogits MAY BE logits).  Each row's statistics and gradient are
- * produced by one workgroup back to back, so the second read of the row is served by the
- * on-chip caches and HBM sees one read and one write per row instead of two reads and a write.
- * A row's gradient can be formed at once unless it waits for the entropy gate of Sec. 3.2.2:
- * under the PER_RESPONSE and GLOBAL gates the members of the MPT set (A_t > 0, p_t >= tau) are
- * finished by a second, filtered backward launch after the gate is known.  Results are
- * bit-identical to ulorl_token_loss_fwd followed by ulorl_token_loss_bwd when the launch
- * shapes (ulorl_tune) of the three streaming kernels are equal, as they are by default.
+ * ulorl_token_loss_bwd (dlogits MAY BE logits).  A row is shared by a few workgroups that keep
+ * their pieces in registers and exchange the pieces' softmax statistics through the workspace,
+ * so every logit is read once and every gradient written once: HBM sees one read and one write
+ * per row instead of two reads and a write.  A row's gradient can be formed at once unless it
+ * waits for the entropy gate of Sec. 3.2.2: under the PER_RESPONSE and GLOBAL gates the members
+ * of the MPT set (A_t > 0, p_t >= tau) are finished by a second, filtered backward launch after
+ * the gate is known.  Results agree with ulorl_token_loss_fwd followed by ulorl_token_loss_bwd
+ * to rounding (the row sums are formed in a different order); they are bit-identical when
+ * ulorl_tune(ULORL_TUNE_FUSED_CLUSTER, 0) selects the older one-workgroup-per-row kernel (whose
+ * second read of a row is served by the on-chip caches) with the forward kernel's launch shape.
+ * The workgroups of a row wait for each other with a bounded wait: see ULORL_STATUS_SYNC.
  */
 int32_t ulorl_token_loss_fwd_bwd(
     const void *logits, int32_t dt, int64_t N, int64_t V, int64_t row_stride,
@@ -333,6 +341,8 @@ typedef enum {
     ULORL_TUNE_FUSED_UNROLL = 5,
     ULORL_TUNE_BWD_ONESHOT = 7,   /* 1 (default): standalone backward by one-shot 4 KB workgroups;
                                      0: one looping workgroup per row (BWD_THREADS / BWD_UNROLL apply) */
+    ULORL_TUNE_FUSED_CLUSTER = 8, /* 1 (default): one-call path by row-cooperative workgroups;
+                                     0: one looping workgroup per row (FUSED_THREADS / FUSED_UNROLL apply) */
     ULORL_TUNE_GEMM_TILE = 6      /* lm_head variant, block tile M x N x K / waves along M x N:
                                      0 = 128x128x64 / 2x2, 1 = 256x256x32 / 2x2, 2 = 256x256x64 / 2x2,
                                      3 = 256x128x64 / 2x2, 4 = 256x256x64 / 2x4, 5 = 256x256x64 / 4x2,

@@ -16,9 +16,9 @@ import torch
 F32, BF16 = 0, 1
 IS_SAIS, IS_POIS = 0, 1
 GATE_PER_RESPONSE, GATE_GLOBAL, GATE_ALWAYS, GATE_NEVER = 0, 1, 2, 3
-STATUS_BAD_TOKEN, STATUS_NONFINITE, STATUS_BAD_CU = 1, 2, 4
+STATUS_BAD_TOKEN, STATUS_NONFINITE, STATUS_BAD_CU, STATUS_SYNC = 1, 2, 4, 8
 TUNE_FWD_THREADS, TUNE_FWD_UNROLL, TUNE_BWD_THREADS, TUNE_BWD_UNROLL = 0, 1, 2, 3
-TUNE_FUSED_THREADS, TUNE_FUSED_UNROLL, TUNE_GEMM_TILE, TUNE_BWD_ONESHOT = 4, 5, 6, 7
+TUNE_FUSED_THREADS, TUNE_FUSED_UNROLL, TUNE_GEMM_TILE, TUNE_BWD_ONESHOT, TUNE_FUSED_CLUSTER = 4, 5, 6, 7, 8
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 
@@ -80,7 +80,7 @@ def load_library(build_if_missing: bool = True):
     lib.ulorl_tune.restype = c.c_int32
     lib.ulorl_tune.argtypes = [c.c_int32, c.c_int32]
     lib.ulorl_token_loss_workspace_bytes.restype = c.c_size_t
-    lib.ulorl_token_loss_workspace_bytes.argtypes = [c.c_int64, c.c_int32]
+    lib.ulorl_token_loss_workspace_bytes.argtypes = [c.c_int64, c.c_int64, c.c_int32]
     vp = c.c_void_p
     lib.ulorl_token_loss_fwd.restype = c.c_int32
     lib.ulorl_token_loss_fwd.argtypes = [
@@ -146,8 +146,8 @@ def tune(knob: int, value: int) -> None:
         raise UlorlError(rc, "ulorl_tune")
 
 
-def token_loss_workspace_bytes(N: int, R: int) -> int:
-    return int(load_library().ulorl_token_loss_workspace_bytes(N, R))
+def token_loss_workspace_bytes(N: int, V: int, R: int) -> int:
+    return int(load_library().ulorl_token_loss_workspace_bytes(N, V, R))
 
 
 # ------------------------------------------------------------------------------------ helpers
@@ -224,7 +224,7 @@ def _prepare_objective(logits, token_ids, cu_seqlens, advantages, old_logp, para
         out.resp_gate = torch.empty(max(R, 1), dtype=torch.uint8, device=dev)[:R]
         out.counters = torch.empty(4, dtype=torch.int64, device=dev)
     if workspace is None:
-        workspace = torch.empty(max(token_loss_workspace_bytes(N, R), 256), dtype=torch.uint8, device=dev)
+        workspace = torch.empty(max(token_loss_workspace_bytes(N, V, R), 256), dtype=torch.uint8, device=dev)
     ws_bytes = workspace.numel() * workspace.element_size()
     return (dt, N, V, stride, dev, token_ids, R, advantages, old_logp, segment_ids, params.to_c(), out,
             workspace, ws_bytes)

@@ -923,7 +923,7 @@ LmheadLayout lmhead_layout(int64_t N, int64_t Hd, int64_t V, int32_t R, int32_t 
     L.dzct = off;    off = align_up(off + (size_t)L.ldc * L.ldt * 2, 256);
     L.dhacc = off;   off = align_up(off + (size_t)N * Hd * 4, 256);
     L.partial = off; off = align_up(off + max_splits * (size_t)N * sizeof(StatQuad), 256);
-    L.token_ws = off; off = align_up(off + workspace_layout(N, R).total, 256);
+    L.token_ws = off; off = align_up(off + workspace_layout(N, 0, R).total, 256);
     L.total = off;
     return L;
 }
@@ -1065,7 +1065,7 @@ int32_t ulorl_lmhead_token_loss_fwd(const void* hidden, const void* W, int64_t N
                        (int)N, (int)V, token_ids, lse, logp, entropy);
     if (hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;
 
-    const WorkspaceLayout wl = workspace_layout(N, R);
+    const WorkspaceLayout wl = workspace_layout(N, 0, R);
     const TokenArgs a = make_token_args(N, V, token_ids, cu_seqlens, R, segment_ids, old_logp, advantages, p, logp,
                                         entropy, lse, gcoef, mpt_mask, ratio, segment_out, resp_entropy, resp_gate,
                                         ws + L.token_ws, wl);

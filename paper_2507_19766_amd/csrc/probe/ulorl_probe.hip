@@ -167,7 +167,7 @@ int main(int argc, char** argv)
     float *adv, *old_logp, *loss, *logp, *ent, *lse, *g;
     int64_t* counters;
     void* ws;
-    const size_t ws_bytes = ulorl_token_loss_workspace_bytes(N, 1);
+    const size_t ws_bytes = ulorl_token_loss_workspace_bytes(N, V, 1);
     CHECK(hipMalloc(&y, N * 4)); CHECK(hipMalloc(&cu, 8));
     CHECK(hipMalloc(&adv, N * 4)); CHECK(hipMalloc(&old_logp, N * 4)); CHECK(hipMalloc(&loss, 4));
     CHECK(hipMalloc(&logp, N * 4)); CHECK(hipMalloc(&ent, N * 4)); CHECK(hipMalloc(&lse, N * 4));

@@ -21,6 +21,7 @@
 // the inner loops are: unpack, one FMA (scaled argument), one v_exp_f32, and two accumulate
 // ops in the forward; unpack, FMA, v_exp_f32 and a pack in the backward.
 #include <hip/hip_runtime.h>
+#include <math.h>
 #include <stdint.h>
 
 #include "ulorl.h"
@@ -444,20 +445,20 @@ struct TokenEval {
 };
 
 __device__ __forceinline__ TokenEval token_eval(float lpf, float advf, float oldf, int is_mode, double eps_low,
-                                                double eps_high, double tau, double D)
+                                                double eps_high, double log_tau, double inv_D)
 {
+    // Kept short: in the row-cooperative kernel one thread evaluates it while its workgroup waits.
+    // p >= tau is tested as logp >= ln(tau); the ratio is one hardware exp2 (relative error ~2e-7).
     TokenEval ev;
-    const double lp = (double)lpf;
     const double A = (double)advf;
-    const double p = exp(lp);
     ev.positive = A > 0.0;
-    ev.mpt = ev.positive && (p >= tau);
-    ev.r = (is_mode == ULORL_IS_POIS) ? 1.0 : exp(lp - (double)oldf);
+    ev.mpt = ev.positive && ((double)lpf >= log_tau);
+    ev.r = (is_mode == ULORL_IS_POIS) ? 1.0 : (double)fast_exp2((lpf - oldf) * kLog2e);
     const double c = fmin(fmax(ev.r, 1.0 - eps_low), 1.0 + eps_high);
     const double u = ev.r * A, v = c * A;
     ev.active = u <= v;
     ev.s = ev.active ? u : v;
-    ev.g = ev.active ? (float)(-(ev.r * A) / D) : 0.0f;
+    ev.g = ev.active ? (float)(-(ev.r * A) * inv_D) : 0.0f;
     return ev;
 }
 
@@ -499,12 +500,12 @@ __device__ __forceinline__ long long block_sum_i64(long long x, long long* scrat
     return s;
 }
 
-// Bitwise OR of the three status bits over the workgroup (__syncthreads_or is a logical OR).
+// Bitwise OR of the status bits over the workgroup (__syncthreads_or is a logical OR).
 __device__ __forceinline__ int block_or_bits(int flags)
 {
     int r = 0;
 #pragma unroll
-    for (int bit = 1; bit <= 4; bit <<= 1) r |= __syncthreads_or(flags & bit) ? bit : 0;
+    for (int bit = 1; bit <= 8; bit <<= 1) r |= __syncthreads_or(flags & bit) ? bit : 0;
     return r;
 }
 
@@ -600,7 +601,7 @@ __global__ __launch_bounds__(kTokBlock) void token_terms_kernel(TokenArgs a)
         uint8_t m_out = 0;
         if (!bad_tok && !nonfinite && !badcu) {
             const TokenEval ev = token_eval(lpf, a.adv[t], a.is_mode == ULORL_IS_POIS ? 0.0f : a.old_logp[t],
-                                            a.is_mode, a.eps_low, a.eps_high, a.tau, a.D);
+                                            a.is_mode, a.eps_low, a.eps_high, a.log_tau, a.inv_D);
             const bool I = gate && ev.mpt;
             contrib = I ? 0.0 : ev.s;
             g_out = I ? 0.0f : ev.g;
@@ -679,6 +680,7 @@ __global__ __launch_bounds__(kTokBlock) void loss_finalize_kernel(TokenArgs a, i
     c2 = block_sum_i64<kTokBlock>(c2, iscratch);
     fl = block_or_bits(fl);
     if (threadIdx.x == 0) {
+        if (a.sync_fail != nullptr && *a.sync_fail != 0u) fl |= ULORL_STATUS_SYNC;
         *loss = (float)(-s / D);
         if (counters) {
             counters[0] = c0;
@@ -708,7 +710,7 @@ struct FusedArgs {
     uint8_t* defer;
     const uint32_t* badcu;  // one word: non-zero if cu_seqlens is malformed (then nothing is trained)
     int32_t is_mode, gate_mode;
-    double eps_low, eps_high, tau, D;
+    double eps_low, eps_high, log_tau, inv_D;
     float grad_out;
 };
 
@@ -733,7 +735,7 @@ __global__ __launch_bounds__(NT) void fused_row_kernel(const typename Tr::elem* 
         const bool bad = (y < 0 || y >= V) || not_finite(lp) || not_finite(ent) || not_finite(lse) || *a.badcu != 0;
         if (!bad) {
             const TokenEval ev = token_eval(lp, a.adv[row], a.is_mode == ULORL_IS_POIS ? 0.0f : a.old_logp[row],
-                                            a.is_mode, a.eps_low, a.eps_high, a.tau, a.D);
+                                            a.is_mode, a.eps_low, a.eps_high, a.log_tau, a.inv_D);
             const bool gate_known = a.gate_mode == ULORL_GATE_ALWAYS || a.gate_mode == ULORL_GATE_NEVER;
             if (ev.mpt && !gate_known) {
                 mode = 2;
@@ -752,6 +754,257 @@ __global__ __launch_bounds__(NT) void fused_row_kernel(const typename Tr::elem* 
     const int mode = bc_mode;
     if (mode == 2) return;
     dlogits_core<Tr, NT, U>(rowp, dlogits + row * row_stride, V, mode == 1, bc_g, bc_l, y);
+}
+
+// ---------------------------------------------------------------------------------------------
+// fused forward + backward, one read and one write of HBM per row: row-cooperative workgroups
+// ---------------------------------------------------------------------------------------------
+// C workgroups of 256 threads share a row; each keeps its piece (VPT 16-byte vectors per thread)
+// in registers, computes the piece's statistics, publishes them, waits for the other pieces',
+// and turns its registers into the gradient.  Nothing is read twice, and because consecutive
+// workgroups work on consecutive pieces of consecutive rows the chip reads and writes a narrow
+// moving window of addresses (measured: 12.3 ms for 131072 x 151936 bf16, the rate of a plain
+// one-shot copy; one workgroup per row reaches 16.3 ms).
+//
+// Exchange: piece c of a row owns two 64-bit words, {m, S} and {T, 1}, zero before the launch.
+// Each is written and read with relaxed agent-scope atomics, and each carries its own validity
+// (S >= 1 for a non-empty piece; the tag), so no ordering between memory locations and no cache
+// maintenance is needed.  Workgroups are dispatched in order of their linear id and a row's
+// pieces have consecutive ids, so the partners of a resident workgroup are resident or next in
+// line; the wait is nevertheless bounded (kSpinLimit polls): on expiry the row is given a zero
+// gradient, not-a-number statistics and the SYNC status bit.  Every workgroup of a row merges the
+// same pieces in the same order and therefore takes the same decisions.
+constexpr int kClusterThreads = 256;
+constexpr int kClusterMaxPieces = 64;         // one polled piece per lane of a wave
+constexpr int kSpinLimit = 1 << 24;           // polls of ~0.25 us each: seconds
+
+// Absorbs vectors v[K .. VPT) in power-of-two groups, largest first (absorb<> wants a power of two).
+template <class Tr, int VPT, int K>
+__device__ __forceinline__ void absorb_vectors(const u32x4 (&v)[VPT], LaneAcc& acc)
+{
+    constexpr int REM = VPT - K;
+    if constexpr (REM > 0) {
+        constexpr int G = REM >= 8 ? 8 : REM >= 4 ? 4 : REM >= 2 ? 2 : 1;
+        constexpr int E = Tr::kPerVec;
+        float f[G * E];
+#pragma unroll
+        for (int q = 0; q < G; ++q) Tr::unpack(v[K + q], f + q * E);
+        absorb<G * E>(f, acc);
+        absorb_vectors<Tr, VPT, K + G>(v, acc);
+    }
+}
+
+struct ClusterArgs {
+    FusedArgs f;
+    unsigned long long* slots;   // [N * C * 2]
+    uint32_t* sync_fail;         // one word, set if any wait expired
+    int64_t N;
+    int32_t C;
+};
+
+template <class Tr, int VPT>
+__global__ __launch_bounds__(kClusterThreads) void cluster_row_kernel(const typename Tr::elem* logits, int64_t row_stride,
+                                                                      int32_t V, typename Tr::elem* dlogits,
+                                                                      ClusterArgs a)
+{
+    constexpr int NT = kClusterThreads;
+    constexpr int E = Tr::kPerVec;
+    constexpr int P = NT * VPT;                 // vectors per piece
+    const int c = blockIdx.x;
+    const int C = a.C;
+    const int64_t row = (int64_t)blockIdx.z * 32768 + blockIdx.y;
+    if (row >= a.N) return;
+    const int tid = threadIdx.x;
+    const typename Tr::elem* rowp = logits + row * row_stride;
+    typename Tr::elem* outp = dlogits + row * row_stride;
+    const u32x4* vp = reinterpret_cast<const u32x4*>(rowp);
+    u32x4* op = reinterpret_cast<u32x4*>(outp);
+    const int nvec = V / E;
+    const int first = c * P;
+    const bool full = first + P <= nvec;        // every thread holds VPT vectors
+    const bool owns_tail = (c == C - 1) && (tid == NT - 1) && (nvec * E < V);
+
+    // Per-row scalars, fetched first so that their latency hides under the row's loads.  The
+    // chosen logit in particular must have arrived before this piece is published: from then
+    // on a partner may overwrite the row (in place).
+    const int32_t y = a.f.token_ids[row];
+    const float adv_row = a.f.adv[row];
+    const float old_row = a.f.is_mode == ULORL_IS_POIS ? 0.0f : a.f.old_logp[row];
+    const uint32_t badcu = *a.f.badcu;
+    float zy = 0.0f;
+    if (tid == 0 && y >= 0 && y < V) zy = Tr::load1(rowp + y);
+
+    // ---- phase 1: the piece into registers, its statistics
+    u32x4 v[VPT];
+    LaneAcc acc = {kEmpty, kEmpty * kLog2e, 0.0f, 0.0f, 0.0f};
+    if (full) {
+#pragma unroll
+        for (int k = 0; k < VPT; ++k) v[k] = load_stream(vp + first + k * NT + tid);
+        absorb_vectors<Tr, VPT, 0>(v, acc);
+    } else {
+#pragma unroll
+        for (int k = 0; k < VPT; ++k) {
+            const int i = first + k * NT + tid;
+            if (i < nvec) {
+                v[k] = load_stream(vp + i);
+                float f[E];
+                Tr::unpack(v[k], f);
+                absorb<E>(f, acc);
+            }
+        }
+    }
+    if (owns_tail) {
+        for (int j = nvec * E; j < V; ++j) {
+            float f = Tr::load1(rowp + j);
+            absorb<1>(&f, acc);
+        }
+    }
+    const float delta = fmaf(acc.m, kLog2e, -acc.mL);
+    const float un = fast_exp2(-delta);
+    float m = acc.m;
+    float S = un * (acc.S + acc.Sc);
+    float T = un * fmaf(-delta, acc.S, acc.T);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const float m2 = __shfl_xor(m, off);
+        const float S2 = __shfl_xor(S, off);
+        const float T2 = __shfl_xor(T, off);
+        merge(m, S, T, m2, S2, T2);
+    }
+    __shared__ float sm[NT / 64], sS[NT / 64], sT[NT / 64];
+    __shared__ float bc_g, bc_l;
+    __shared__ int bc_mode;      // 0: write zeros, 1: write gradient, 2: deferred (leave the row alone)
+    if ((tid & 63) == 0) {
+        sm[tid >> 6] = m;
+        sS[tid >> 6] = S;
+        sT[tid >> 6] = T;
+    }
+    __syncthreads();
+
+    // ---- exchange (first wave)
+    if (tid < 64) {
+        unsigned long long* slot = a.slots + (row * C) * 2;
+        if (tid == 0) {
+#pragma unroll
+            for (int w = 1; w < NT / 64; ++w) merge(m, S, T, sm[w], sS[w], sT[w]);
+            __builtin_amdgcn_s_waitcnt(0);      // every load of this thread, the chosen logit included, has returned
+            const unsigned long long w0 = ((unsigned long long)__float_as_uint(S) << 32) | __float_as_uint(m);
+            const unsigned long long w1 = (1ull << 32) | __float_as_uint(T);
+            __hip_atomic_store(slot + 2 * c, w0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(slot + 2 * c + 1, w1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        float pm = kEmpty, pS = 0.0f, pT = 0.0f;
+        int expired = 0;
+        if (tid < C) {
+            unsigned long long w0 = 0, w1 = 0;
+            int spins = 0;
+            for (;;) {
+                if (w0 == 0) w0 = __hip_atomic_load(slot + 2 * tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (w1 == 0) w1 = __hip_atomic_load(slot + 2 * tid + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (w0 != 0 && w1 != 0) break;
+                if (++spins >= kSpinLimit) { expired = 1; break; }
+                __builtin_amdgcn_s_sleep(4);
+            }
+            if (!expired) {
+                pm = __uint_as_float((uint32_t)w0);
+                pS = __uint_as_float((uint32_t)(w0 >> 32));
+                pT = __uint_as_float((uint32_t)w1);
+            }
+        }
+        expired = __any(expired);
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const float m2 = __shfl_xor(pm, off);
+            const float S2 = __shfl_xor(pS, off);
+            const float T2 = __shfl_xor(pT, off);
+            merge(pm, pS, pT, m2, S2, T2);
+        }
+        if (tid == 0) {
+            const float lnS = logf(pS);
+            float lp = __builtin_nanf("");
+            if (y >= 0 && y < V) lp = (zy - pm) - lnS;
+            float lse = pm + lnS;
+            float ent = lnS - (pT * kLn2) / pS;
+            if (expired) {
+                lse = lp = ent = __builtin_nanf("");
+                *a.sync_fail = 1u;
+            }
+            int mode = 0;
+            float g = 0.0f;
+            const bool bad = (y < 0 || y >= V) || not_finite(lp) || not_finite(ent) || not_finite(lse) || badcu != 0;
+            if (!bad) {
+                const TokenEval ev = token_eval(lp, adv_row, old_row, a.f.is_mode, a.f.eps_low, a.f.eps_high, a.f.log_tau,
+                                                a.f.inv_D);
+                const bool gate_known = a.f.gate_mode == ULORL_GATE_ALWAYS || a.f.gate_mode == ULORL_GATE_NEVER;
+                if (ev.mpt && !gate_known) {
+                    mode = 2;
+                } else {
+                    const bool I = ev.mpt && a.f.gate_mode == ULORL_GATE_ALWAYS;
+                    g = (I ? 0.0f : ev.g) * a.f.grad_out;
+                    mode = row_is_live(g, lse, y, V) ? 1 : 0;
+                }
+            }
+            if (c == 0) {
+                a.f.lse[row] = lse;
+                a.f.logp[row] = lp;
+                a.f.entropy[row] = ent;
+                a.f.defer[row] = mode == 2 ? 1 : 0;
+            }
+            bc_g = g;
+            bc_l = lse;
+            bc_mode = mode;
+        }
+    }
+    __syncthreads();
+
+    // ---- phase 2: the gradient from the registers
+    const int mode = bc_mode;
+    if (mode == 2) return;
+    if (mode == 0) {
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int k = 0; k < VPT; ++k) {
+            const int i = first + k * NT + tid;
+            if (i < nvec) store_stream(op + i, zero);
+        }
+        if (owns_tail)
+            for (int j = nvec * E; j < V; ++j) Tr::store1(outp + j, 0.0f);
+        return;
+    }
+    const float g = bc_g;
+    const float cexp = fmaf(-bc_l, kLog2e, log2f(fabsf(g)));
+    const float sgn = g > 0.0f ? -1.0f : 1.0f;
+    const int yvec = y / E;
+#pragma unroll
+    for (int k = 0; k < VPT; ++k) {
+        const int i = first + k * NT + tid;
+        if (full || i < nvec) {
+            float f[E];
+            Tr::unpack(v[k], f);
+#pragma unroll
+            for (int e = 0; e < E; ++e) f[e] = sgn * fast_exp2(fmaf(f[e], kLog2e, cexp));
+            if (i == yvec) {
+#pragma unroll
+                for (int e = 0; e < E; ++e) f[e] += (e == y - yvec * E) ? g : 0.0f;
+            }
+            store_stream(op + i, Tr::pack(f));
+        }
+    }
+    if (owns_tail) {
+        // the tail's logits have not been overwritten: only this thread writes them
+        for (int j = nvec * E; j < V; ++j) {
+            float x = sgn * fast_exp2(fmaf(Tr::load1(rowp + j), kLog2e, cexp));
+            if (j == y) x += g;
+            Tr::store1(outp + j, x);
+        }
+    }
+}
+
+__global__ void fill_zero_u64_kernel(unsigned long long* p, int64_t n, uint32_t* flag)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0ull;
+    if (i == 0) *flag = 0u;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -854,6 +1107,23 @@ bool dispatch_fused(int nt, int u, const void* logits, int64_t N, int64_t V, int
     return false;
 }
 
+template <class Tr>
+bool launch_cluster(int vpt, const void* logits, int64_t N, int64_t V, int64_t stride, void* dz, const ClusterArgs& a,
+                    hipStream_t st)
+{
+    // x: piece (fastest, so a row's pieces have consecutive linear ids), y/z: row
+    dim3 grid((unsigned)a.C, (unsigned)(N < 32768 ? N : 32768), (unsigned)((N + 32767) / 32768));
+#define ULORL_CASE(VPT_)                                                                                       \
+    if (vpt == VPT_) {                                                                                         \
+        hipLaunchKernelGGL((cluster_row_kernel<Tr, VPT_>), grid, dim3(kClusterThreads), 0, st,                 \
+                           (const typename Tr::elem*)logits, stride, (int32_t)V, (typename Tr::elem*)dz, a);   \
+        return true;                                                                                           \
+    }
+    ULORL_CASE(4) ULORL_CASE(8) ULORL_CASE(15)
+#undef ULORL_CASE
+    return false;
+}
+
 }  // namespace
 
 namespace ulorl_detail {
@@ -861,11 +1131,29 @@ namespace ulorl_detail {
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-WorkspaceLayout workspace_layout(int64_t N, int32_t R)
+// Shape of the row-cooperative kernel for a row of V elements: vectors per thread and pieces
+// (workgroups) per row; pieces == 0 if the row is too long for one wave to poll its pieces.
+ClusterShape cluster_shape(int64_t V, int32_t dt)
+{
+    const int64_t nvec = V / (dt == ULORL_F32 ? 4 : 8);
+    ClusterShape c;
+    c.vpt = nvec >= 256 * 15 ? 15 : nvec >= 256 * 8 ? 8 : 4;
+    const int64_t per_piece = 256 * (int64_t)c.vpt;
+    const int64_t pieces = nvec > 0 ? (nvec + per_piece - 1) / per_piece : 1;
+    c.pieces = pieces <= 64 ? (int)pieces : 0;
+    return c;
+}
+
+WorkspaceLayout workspace_layout(int64_t N, int64_t V, int32_t R)
 {
     WorkspaceLayout w;
     w.nblk = (N + kTokBlock - 1) / kTokBlock;
+    // exchange slots of the row-cooperative kernel, sized for the storage type that needs more pieces
+    const ClusterShape a = cluster_shape(V, ULORL_F32), b = cluster_shape(V, ULORL_BF16);
+    const int pieces = V > 0 ? (a.pieces > b.pieces ? a.pieces : b.pieces) : 0;
     size_t off = 0;
+    w.slots = off;    off = align_up(off + sizeof(unsigned long long) * 2 * (size_t)N * (size_t)pieces, 256);
+    w.syncfail = off; off = align_up(off + sizeof(uint32_t), 256);
     w.hsum = off;     off = align_up(off + sizeof(double) * (size_t)R, 256);
     w.rflags = off;   off = align_up(off + sizeof(uint32_t) * (size_t)R, 256);
     w.part_sum = off; off = align_up(off + sizeof(double) * (size_t)w.nblk, 256);
@@ -904,12 +1192,15 @@ TokenArgs make_token_args(int64_t N, int64_t V, const int32_t* token_ids, const 
     a.mask = mpt_mask; a.ratio = ratio; a.seg_out = segment_out; a.resp_entropy = resp_entropy;
     a.resp_gate = resp_gate;
     a.hsum = (double*)(ws + wl.hsum); a.rflags = (uint32_t*)(ws + wl.rflags);
+    a.sync_fail = nullptr;
     a.part_sum = (double*)(ws + wl.part_sum); a.part_cnt = (int64_t*)(ws + wl.part_cnt);
     a.N = N; a.V = (int32_t)V; a.R = R;
     a.is_mode = p->is_mode; a.gate_mode = p->gate_mode; a.seg_len = p->seg_len;
     a.eps_low = (double)p->eps_low; a.eps_high = (double)p->eps_high;
     a.tau = (double)p->tau; a.sigma = (double)p->sigma;
     a.D = p->denominator > 0.0 ? p->denominator : (double)N;
+    a.log_tau = log(a.tau);
+    a.inv_D = 1.0 / a.D;
     return a;
 }
 
@@ -941,10 +1232,10 @@ const char* ulorl_status_string(int32_t status)
     }
 }
 
-size_t ulorl_token_loss_workspace_bytes(int64_t N, int32_t R)
+size_t ulorl_token_loss_workspace_bytes(int64_t N, int64_t V, int32_t R)
 {
-    if (N <= 0 || N > 0x7fffffffLL || R <= 0) return 0;
-    return workspace_layout(N, R).total;
+    if (N <= 0 || N > 0x7fffffffLL || V <= 0 || V > 0x7fffffffLL || R <= 0) return 0;
+    return workspace_layout(N, V, R).total;
 }
 
 int32_t ulorl_token_loss_fwd(const void* logits, int32_t dt, int64_t N, int64_t V, int64_t row_stride,
@@ -963,7 +1254,7 @@ int32_t ulorl_token_loss_fwd(const void* logits, int32_t dt, int64_t N, int64_t 
     if (!stats_only) {
         rc = check_objective_args(cu_seqlens, R, old_logp, p, loss, gcoef);
         if (rc != ULORL_OK) return rc;
-        wl = workspace_layout(N, R);
+        wl = workspace_layout(N, V, R);
         if (!workspace || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < wl.total)
             return ULORL_ERR_WORKSPACE;
     }
@@ -999,12 +1290,12 @@ int32_t ulorl_token_loss_fwd_bwd(const void* logits, int32_t dt, int64_t N, int6
     if (((uintptr_t)dlogits & 15u) != 0) return ULORL_ERR_ALIGN;
     rc = check_objective_args(cu_seqlens, R, old_logp, p, loss, gcoef);
     if (rc != ULORL_OK) return rc;
-    const WorkspaceLayout wl = workspace_layout(N, R);
+    const WorkspaceLayout wl = workspace_layout(N, V, R);
     if (!workspace || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < wl.total) return ULORL_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)hip_stream;
     char* ws = (char*)workspace;
 
-    const TokenArgs a = make_token_args(N, V, token_ids, cu_seqlens, R, segment_ids, old_logp, advantages, p, logp,
+    TokenArgs a = make_token_args(N, V, token_ids, cu_seqlens, R, segment_ids, old_logp, advantages, p, logp,
                                         entropy, lse, gcoef, mpt_mask, ratio, segment_out, resp_entropy, resp_gate,
                                         workspace, wl);
     FusedArgs f;
@@ -1012,15 +1303,32 @@ int32_t ulorl_token_loss_fwd_bwd(const void* logits, int32_t dt, int64_t N, int6
     f.lse = lse; f.logp = logp; f.entropy = entropy;
     f.defer = (uint8_t*)(ws + wl.defer); f.badcu = (const uint32_t*)(ws + wl.badcu);
     f.is_mode = a.is_mode; f.gate_mode = a.gate_mode;
-    f.eps_low = a.eps_low; f.eps_high = a.eps_high; f.tau = a.tau; f.D = a.D;
+    f.eps_low = a.eps_low; f.eps_high = a.eps_high; f.log_tau = a.log_tau; f.inv_D = a.inv_D;
     f.grad_out = grad_out;
 
     hipLaunchKernelGGL(cu_check_kernel, dim3(1), dim3(kTokBlock), 0, st, cu_seqlens, R, N, (uint32_t*)(ws + wl.badcu));
-    bool ok = dt == ULORL_BF16
-                  ? dispatch_fused<StoreBF16>(tuning().fused_threads, tuning().fused_unroll, logits, N, V, row_stride,
-                                              dlogits, f, st)
-                  : dispatch_fused<StoreF32>(tuning().fused_threads, tuning().fused_unroll, logits, N, V, row_stride,
-                                             dlogits, f, st);
+    const ClusterShape shape = cluster_shape(V, dt);
+    bool ok;
+    if (tuning().fused_cluster && shape.pieces > 0) {
+        ClusterArgs ca;
+        ca.f = f;
+        ca.slots = (unsigned long long*)(ws + wl.slots);
+        ca.sync_fail = (uint32_t*)(ws + wl.syncfail);
+        ca.N = N;
+        ca.C = shape.pieces;
+        a.sync_fail = ca.sync_fail;
+        const int64_t nslots = 2 * N * (int64_t)shape.pieces;
+        hipLaunchKernelGGL(fill_zero_u64_kernel, dim3((unsigned)((nslots + 255) / 256)), dim3(256), 0, st, ca.slots, nslots,
+                           ca.sync_fail);
+        ok = dt == ULORL_BF16 ? launch_cluster<StoreBF16>(shape.vpt, logits, N, V, row_stride, dlogits, ca, st)
+                              : launch_cluster<StoreF32>(shape.vpt, logits, N, V, row_stride, dlogits, ca, st);
+    } else {
+        ok = dt == ULORL_BF16
+                 ? dispatch_fused<StoreBF16>(tuning().fused_threads, tuning().fused_unroll, logits, N, V, row_stride,
+                                             dlogits, f, st)
+                 : dispatch_fused<StoreF32>(tuning().fused_threads, tuning().fused_unroll, logits, N, V, row_stride,
+                                            dlogits, f, st);
+    }
     if (!ok || hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;
     launch_token_epilogue(a, wl, loss, counters, st);
     if (hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;

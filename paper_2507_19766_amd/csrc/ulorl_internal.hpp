@@ -28,6 +28,7 @@ struct TokenArgs {
     int32_t* seg_out;
     float* resp_entropy;
     uint8_t* resp_gate;
+    const uint32_t* sync_fail;  // one word (may be NULL): a wait of the row-cooperative kernel expired
     double* hsum;       // [R] workspace
     uint32_t* rflags;   // [R] workspace
     double* part_sum;   // [nblk] workspace
@@ -36,14 +37,22 @@ struct TokenArgs {
     int32_t V, R;
     int32_t is_mode, gate_mode, seg_len;
     double eps_low, eps_high, tau, sigma, D;
+    double log_tau, inv_D;   // ln(tau), 1 / D
 };
 
 struct WorkspaceLayout {
-    size_t hsum, rflags, part_sum, part_cnt, defer, badcu, total;
+    size_t slots, syncfail, hsum, rflags, part_sum, part_cnt, defer, badcu, total;
     int64_t nblk;
 };
 
-WorkspaceLayout workspace_layout(int64_t N, int32_t R);
+struct ClusterShape {
+    int vpt;      // 16-byte vectors per thread
+    int pieces;   // workgroups per row (0: shape not supported)
+};
+ClusterShape cluster_shape(int64_t V, int32_t dt);
+
+// V = 0: no exchange slots (callers that never run the row-cooperative kernel).
+WorkspaceLayout workspace_layout(int64_t N, int64_t V, int32_t R);
 
 // Host-side validation of the objective's scalar parameters and required pointers.
 int32_t check_objective_args(const int32_t* cu_seqlens, int32_t R, const float* old_logp, const ulorl_params* p,
@@ -69,6 +78,7 @@ struct Tuning {
     int fused_threads = 512, fused_unroll = 8;
     int gemm_tile = 7;     // index into the compiled-in GEMM tile shapes
     int bwd_oneshot = 1;   // standalone backward by one-shot 4 KB workgroups (0: one looping workgroup per row)
+    int fused_cluster = 1; // one-call path by row-cooperative workgroups (0: one looping workgroup per row)
 };
 Tuning& tuning();
 constexpr int kGemmTileCount = 9;

@@ -106,9 +106,33 @@ def check_dlogits(name, got_rows: torch.Tensor, ref, g_rows, dtype, rtol):
     assert np.all(got[zero_rows] == 0.0), "rows with zero coefficient must be exactly zero"
 
 
+def check_forward_against_oracle(res: ulorl.FwdResult, o_lse, o_logp, o_H, tt, p: ulorl.Params, rtol, loss_slack_rows=0):
+    """Every per-row, per-token and per-response output of a forward (or one-call) result against
+    the oracle's.  Returns (tokens near tau, tokens near a clip edge)."""
+    assert_close("lse", res.lse.cpu().numpy(), o_lse, rtol)
+    assert_close("logp", res.logp.cpu().numpy(), o_logp, rtol)
+    assert_close("entropy", res.entropy.cpu().numpy(), o_H, rtol)
+    np.testing.assert_array_equal(res.segment_out.cpu().numpy(), tt.seg)
+    assert_close("resp_entropy", res.resp_entropy.cpu().numpy(), tt.resp_entropy, rtol)
+    np.testing.assert_array_equal(res.resp_gate.cpu().numpy(), tt.resp_gate)
+    n_tau, n_edge = check_token_outputs(res, tt, o_logp, p, rtol)
+    if n_tau == 0 and n_edge == 0:
+        assert_close("loss", res.loss.cpu().numpy()[0], tt.loss, rtol, atol=1e-7)
+    elif loss_slack_rows:   # a token on a discontinuity may legitimately differ: bound its effect on the mean
+        assert abs(res.loss.item() - tt.loss) <= rtol * abs(tt.loss) + 2.0 * (n_tau + n_edge) / loss_slack_rows
+    return n_tau, n_edge
+
+
+def near_discontinuity(o_logp, tt, p: ulorl.Params):
+    return (np.abs(np.exp(o_logp) - f32(p.tau)) < 1e-6) | \
+           (np.abs(tt.ratio - (1 - f32(p.eps_low))) < 1e-5) | (np.abs(tt.ratio - (1 + f32(p.eps_high))) < 1e-5)
+
+
 def run_full_parity(w: ui.Workload, p: ulorl.Params, dz_rows=None, inplace=False, data=None,
                     grad_out=1.0):
-    """Whole path on the GPU vs whole oracle on the host, every row.  Returns (res, tt, info)."""
+    """Whole path on the GPU vs whole oracle on the host, every row: the two-call path, then (when
+    the logits survive, i.e. not in place) the one-call path in both of its kernels.
+    Returns (res, tt, info)."""
     dev = torch.device("cuda:0")
     d = data if data is not None else ui.generate(w, dev)
     logits = d["logits"]
@@ -119,67 +143,83 @@ def run_full_parity(w: ui.Workload, p: ulorl.Params, dz_rows=None, inplace=False
     rtol = rtol_for(w.dtype)
 
     o_lse, o_logp, o_H = oracle.row_stats(host_logits, y)
-    assert_close("lse", res.lse.cpu().numpy(), o_lse, rtol)
-    assert_close("logp", res.logp.cpu().numpy(), o_logp, rtol)
-    assert_close("entropy", res.entropy.cpu().numpy(), o_H, rtol)
-
     adv = d["advantages"].cpu().numpy()
     oldh = None if old is None else old.cpu().numpy()
     tt = oracle_terms(o_logp, o_H, w.cu_seqlens, adv, oldh, p)
-    np.testing.assert_array_equal(res.segment_out.cpu().numpy(), tt.seg)
-    assert_close("resp_entropy", res.resp_entropy.cpu().numpy(), tt.resp_entropy, rtol)
-    np.testing.assert_array_equal(res.resp_gate.cpu().numpy(), tt.resp_gate)
-    n_tau, n_edge = check_token_outputs(res, tt, o_logp, p, rtol)
-    if n_tau == 0 and n_edge == 0:
-        assert_close("loss", res.loss.cpu().numpy()[0], tt.loss, rtol, atol=1e-7)
+    n_tau, n_edge = check_forward_against_oracle(res, o_lse, o_logp, o_H, tt, p, rtol)
 
-    dz = ulorl.token_loss_bwd(logits, d["token_ids"], res.lse, res.gcoef, grad_out=grad_out,
-                              inplace=inplace)
     rows = np.arange(w.N) if dz_rows is None else np.asarray(dz_rows)
     # the oracle's gradient uses the oracle's own lse and coefficient
     ref = oracle.dlogits(host_logits, y, o_lse, tt.gcoef, grad_out=grad_out, rows=rows)
-    near = (np.abs(np.exp(o_logp) - f32(p.tau)) < 1e-6) | \
-           (np.abs(tt.ratio - (1 - f32(p.eps_low))) < 1e-5) | (np.abs(tt.ratio - (1 + f32(p.eps_high))) < 1e-5)
-    keep = ~near[rows]
-    check_dlogits(w.name, dz[torch.as_tensor(rows[keep], device=dev)], ref[keep],
-                  grad_out * tt.gcoef[rows][keep], w.dtype, rtol)
-    if not inplace:
-        check_fused_path(d, p, res, dz, grad_out=grad_out)
+    keep = ~near_discontinuity(o_logp, tt, p)[rows]
+    sel = torch.as_tensor(rows[keep], device=dev)
+
+    def compare_dz(name, dz_tensor):
+        check_dlogits(name, dz_tensor[sel], ref[keep], grad_out * tt.gcoef[rows][keep], w.dtype, rtol)
+
+    pristine = None if inplace else logits
+    if not inplace:     # the one-call path first, while the logits are intact
+        check_one_call_path(d, p, res, o_lse, o_logp, o_H, tt, rtol, compare_dz, grad_out=grad_out)
+    dz = ulorl.token_loss_bwd(logits, d["token_ids"], res.lse, res.gcoef, grad_out=grad_out,
+                              inplace=inplace)
+    compare_dz(w.name, dz)
+    if pristine is not None:
+        check_one_call_bitwise_with_the_row_kernel(d, p, res, dz, grad_out=grad_out)
     return res, tt, dict(n_near_tau=n_tau, n_near_edge=n_edge, dz=dz, data=d, o_H=o_H)
 
 
 def _bits(t: torch.Tensor) -> torch.Tensor:
-    if t.dtype == torch.bfloat16:
-        return t.contiguous().view(torch.int16)
     if t.dtype == torch.float32:
-        return t.contiguous().view(torch.int32)
+        return t.view(torch.int32)
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16)
     return t
 
 
 def assert_same_results(a: ulorl.FwdResult, b: ulorl.FwdResult, what=""):
-    for name in ("loss", "logp", "entropy", "lse", "gcoef", "mpt_mask", "ratio", "segment_out",
-                 "resp_entropy", "resp_gate", "counters"):
-        x, y = getattr(a, name), getattr(b, name)
-        assert torch.equal(_bits(x), _bits(y)), "%s: %s differs between the fused and the two-call path" % (what, name)
+    for name in ("loss", "logp", "entropy", "lse", "gcoef", "mpt_mask", "ratio", "segment_out", "resp_entropy",
+                 "resp_gate", "counters"):
+        x, yv = getattr(a, name), getattr(b, name)
+        assert torch.equal(_bits(x), _bits(yv)), "%s: %s differs between the fused and the two-call path" % (what, name)
 
 
-def check_fused_path(d, p: ulorl.Params, res: ulorl.FwdResult, dz_ref: torch.Tensor, grad_out=1.0,
-                     also_inplace=True):
-    """The one-call forward+backward must reproduce the two-call results bit for bit, out of place
-    and (on a copy of the logits) in place."""
+def check_one_call_path(d, p: ulorl.Params, res2: ulorl.FwdResult, o_lse, o_logp, o_H, tt, rtol, compare_dz,
+                        grad_out=1.0, also_inplace=True):
+    """The one-call forward+backward (row-cooperative kernel) against the oracle, out of place and
+    (on a copy of the logits) in place; and against the two-call result: the same integer
+    decisions wherever the oracle is not on a discontinuity."""
     old = None if p.is_mode == ulorl.IS_POIS else d["old_logp"]
-    r2, dz2 = ulorl.token_loss_fwd_bwd(d["logits"], d["token_ids"], d["cu_seqlens"], d["advantages"], old, p,
+    r1, dz1 = ulorl.token_loss_fwd_bwd(d["logits"], d["token_ids"], d["cu_seqlens"], d["advantages"], old, p,
                                        grad_out=grad_out)
-    assert_same_results(res, r2, "out of place")
-    assert torch.equal(_bits(dz2), _bits(dz_ref)), "fused dlogits differ from the two-call dlogits"
-    if also_inplace:
-        z = d["logits"].clone() if d["logits"].is_contiguous() else None
-        if z is not None:
-            r3, dz3 = ulorl.token_loss_fwd_bwd(z, d["token_ids"], d["cu_seqlens"], d["advantages"], old, p,
-                                               grad_out=grad_out, inplace=True)
-            assert dz3.data_ptr() == z.data_ptr()
-            assert_same_results(res, r3, "in place")
-            assert torch.equal(_bits(dz3), _bits(dz_ref)), "fused in-place dlogits differ"
+    check_forward_against_oracle(r1, o_lse, o_logp, o_H, tt, p, rtol)
+    compare_dz("one-call", dz1)
+    assert int(r1.counters[3].item()) & ulorl.STATUS_SYNC == 0
+    far = torch.as_tensor(~near_discontinuity(o_logp, tt, p), device=r1.mpt_mask.device)
+    assert torch.equal(r1.mpt_mask[far], res2.mpt_mask[far])
+    assert torch.equal((r1.gcoef == 0)[far], (res2.gcoef == 0)[far])
+    assert torch.equal(r1.resp_gate, res2.resp_gate) and torch.equal(r1.segment_out, res2.segment_out)
+    if also_inplace and d["logits"].is_contiguous():
+        z = d["logits"].clone()
+        r3, dz3 = ulorl.token_loss_fwd_bwd(z, d["token_ids"], d["cu_seqlens"], d["advantages"], old, p,
+                                           grad_out=grad_out, inplace=True)
+        assert dz3.data_ptr() == z.data_ptr()
+        assert_same_results(r1, r3, "in place")
+        assert torch.equal(_bits(dz3), _bits(dz1)), "one-call in-place dlogits differ from out-of-place"
+
+
+def check_one_call_bitwise_with_the_row_kernel(d, p: ulorl.Params, res: ulorl.FwdResult, dz_ref: torch.Tensor,
+                                               grad_out=1.0):
+    """With one looping workgroup per row (the older kernel) the one-call path reproduces the
+    two-call results bit for bit."""
+    old = None if p.is_mode == ulorl.IS_POIS else d["old_logp"]
+    ulorl.tune(ulorl.TUNE_FUSED_CLUSTER, 0)
+    try:
+        r2, dz2 = ulorl.token_loss_fwd_bwd(d["logits"], d["token_ids"], d["cu_seqlens"], d["advantages"], old, p,
+                                           grad_out=grad_out)
+    finally:
+        ulorl.tune(ulorl.TUNE_FUSED_CLUSTER, 1)
+    assert_same_results(res, r2, "row kernel")
+    assert torch.equal(_bits(dz2), _bits(dz_ref)), "row-kernel fused dlogits differ from the two-call dlogits"
 
 
 def sigma_between_responses(host_logits, y, cu, k=None):
@@ -217,54 +257,48 @@ def oracle_row_stats_streamed(logits: torch.Tensor, y_host: np.ndarray, block_ro
 
 
 def run_streamed_parity(w: ui.Workload, p: ulorl.Params, data, n_dz_rows=64, inplace=True, seed=0,
-                        say=print):
+                        say=print, one_call=False):
     """Full-size parity: every row's statistics and every token's terms against the oracle (logits
-    streamed to the host in blocks), the gradient on sampled rows."""
+    streamed to the host in blocks, before anything overwrites them), the gradient on sampled
+    rows.  one_call selects ulorl_token_loss_fwd_bwd instead of the forward / backward pair."""
     dev = data["logits"].device
     logits = data["logits"]
     rtol = rtol_for(w.dtype)
     y = data["token_ids"].cpu().numpy()
     adv = data["advantages"].cpu().numpy()
     old = None if p.is_mode == ulorl.IS_POIS else data["old_logp"]
-    res = ulorl.token_loss_fwd(logits, data["token_ids"], data["cu_seqlens"], data["advantages"], old, p)
-    torch.cuda.synchronize()
-    say("forward done; streaming %d rows to the oracle" % w.N)
 
     rs = np.random.RandomState(seed)
     rows = np.unique(np.concatenate([[0, w.N - 1], rs.choice(w.N, n_dz_rows, replace=False)]))
+    say("streaming %d rows to the oracle" % w.N)
     o_lse, o_logp, o_H, kept = oracle_row_stats_streamed(
         logits, y, keep_rows=rows,
         progress=lambda a, b: say("  oracle rows %d/%d" % (a, b)) if (a // 4096) % 8 == 0 or a == b else None)
-    assert_close("lse", res.lse.cpu().numpy(), o_lse, rtol)
-    assert_close("logp", res.logp.cpu().numpy(), o_logp, rtol)
-    assert_close("entropy", res.entropy.cpu().numpy(), o_H, rtol)
     tt = oracle_terms(o_logp, o_H, w.cu_seqlens, adv, None if old is None else old.cpu().numpy(), p)
-    np.testing.assert_array_equal(res.segment_out.cpu().numpy(), tt.seg)
-    assert_close("resp_entropy", res.resp_entropy.cpu().numpy(), tt.resp_entropy, rtol)
-    np.testing.assert_array_equal(res.resp_gate.cpu().numpy(), tt.resp_gate)
-    n_tau, n_edge = check_token_outputs(res, tt, o_logp, p, rtol)
-    if n_tau == 0 and n_edge == 0:
-        assert_close("loss", res.loss.cpu().numpy()[0], tt.loss, rtol, atol=1e-7)
-    else:   # a token on a discontinuity may legitimately differ: bound its effect on the mean
-        assert abs(res.loss.item() - tt.loss) <= rtol * abs(tt.loss) + 2.0 * (n_tau + n_edge) / w.N
+
+    if one_call:
+        res, dz = ulorl.token_loss_fwd_bwd(logits, data["token_ids"], data["cu_seqlens"], data["advantages"], old, p,
+                                           inplace=inplace)
+    else:
+        res = ulorl.token_loss_fwd(logits, data["token_ids"], data["cu_seqlens"], data["advantages"], old, p)
+        dz = ulorl.token_loss_bwd(logits, data["token_ids"], res.lse, res.gcoef, inplace=inplace)
+    torch.cuda.synchronize()
+    say("%s done" % ("one call" if one_call else "forward + backward"))
+    n_tau, n_edge = check_forward_against_oracle(res, o_lse, o_logp, o_H, tt, p, rtol, loss_slack_rows=w.N)
     say("token terms ok (masked %d, clipped %d, near tau %d, near clip edge %d)"
         % (tt.n_masked, tt.n_clip_inactive, n_tau, n_edge))
 
-    dz = ulorl.token_loss_bwd(logits, data["token_ids"], res.lse, res.gcoef, inplace=inplace)
-    torch.cuda.synchronize()
-    near = (np.abs(np.exp(o_logp) - f32(p.tau)) < 1e-6) | \
-           (np.abs(tt.ratio - (1 - f32(p.eps_low))) < 1e-5) | (np.abs(tt.ratio - (1 + f32(p.eps_high))) < 1e-5)
+    near = near_discontinuity(o_logp, tt, p)
     rows = np.array([r for r in rows if not near[r]])
     sub = np.stack([kept[int(r)] for r in rows])
-    k = np.arange(len(rows))
     ref = oracle.dlogits(sub, y[rows], o_lse[rows], tt.gcoef[rows])
     check_dlogits(w.name, dz[torch.as_tensor(rows, device=dev)], ref, tt.gcoef[rows], w.dtype, rtol)
-    # properties that hold at any size: masked / clipped rows are exactly zero, live rows sum to ~0
+    # properties that hold at any size: masked / clipped rows are exactly zero
     zero_rows = np.nonzero(tt.gcoef == 0.0)[0]
     zero_rows = zero_rows[~near[zero_rows]][:256]
     if len(zero_rows):
         assert torch.all(dz[torch.as_tensor(zero_rows, device=dev)] == 0)
-    say("dlogits ok on %d sampled rows, %d zero rows" % (len(k), len(zero_rows)))
+    say("dlogits ok on %d sampled rows, %d zero rows" % (len(rows), len(zero_rows)))
     return res, tt
 
 

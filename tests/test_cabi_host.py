@@ -35,11 +35,15 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_workspace_query():
-    assert ulorl.token_loss_workspace_bytes(0, 1) == 0
-    assert ulorl.token_loss_workspace_bytes(10, 0) == 0
-    a = ulorl.token_loss_workspace_bytes(131072, 1)
-    b = ulorl.token_loss_workspace_bytes(131072, 1024)
-    assert 0 < a < b < 1 << 20 and a % 256 == 0
+    assert ulorl.token_loss_workspace_bytes(0, 64, 1) == 0
+    assert ulorl.token_loss_workspace_bytes(10, 64, 0) == 0
+    assert ulorl.token_loss_workspace_bytes(10, 0, 1) == 0
+    a = ulorl.token_loss_workspace_bytes(131072, 4096, 1)
+    b = ulorl.token_loss_workspace_bytes(131072, 4096, 1024)
+    assert 0 < a < b < 4 << 20 and a % 256 == 0
+    # the one-call path keeps 16 bytes per row and piece of the row: 10 pieces for 151936 fp32 logits
+    c = ulorl.token_loss_workspace_bytes(131072, 151936, 1)
+    assert c - a == 131072 * 16 * (10 - 1)
 
 
 def _fwd(lib, logits=0x1000, dt=1, N=4, V=64, stride=64, y=0x2000, cu=0x3000, R=1, old=0x4000,
@@ -123,3 +127,5 @@ def test_tuning_knobs_validate():
         ulorl.tune(ulorl.TUNE_FWD_THREADS, 100)
     with pytest.raises(ulorl.UlorlError):
         ulorl.tune(9, 256)
+    with pytest.raises(ulorl.UlorlError):
+        ulorl.tune(ulorl.TUNE_FUSED_CLUSTER, 2)

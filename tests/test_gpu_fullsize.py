@@ -65,6 +65,35 @@ def test_cfg4_full_size_ultra_long_in_place():
     assert int(res.segment_out.max()) == 7
 
 
+def test_cfg4_full_size_one_call_in_place():
+    """The configuration and the call the benchmark times: 131072 x 151936 bf16, one call, in place."""
+    w = ui.config(4)
+    d = _generate(w)
+    res, tt = run_streamed_parity(w, params_for(w, gate_mode=ulorl.GATE_ALWAYS), d, inplace=True, say=say,
+                                  one_call=True)
+    assert tt.n_masked > 200 and tt.n_pos == w.N
+    assert int(res.counters[3].item()) == 0
+
+
+def test_cfg3_full_size_one_call_with_a_response_gate():
+    """Ragged responses, one call, in place, with the per-response entropy gate placed between two
+    responses' mean entropies: the members of the MPT set wait for the gate."""
+    w = ui.config(3)
+    d = _generate(w)
+    y = d["token_ids"].cpu().numpy()
+    from parity import oracle_row_stats_streamed
+    _, _, H, _ = oracle_row_stats_streamed(d["logits"], y)
+    cu = w.cu_seqlens
+    hbar = np.sort(np.array([H[cu[i]:cu[i + 1]].mean() for i in range(w.R)]))
+    gaps = np.diff(hbar)
+    j = int(np.argmax(gaps))
+    assert gaps[j] > 1e-3
+    sigma = float(0.5 * (hbar[j] + hbar[j + 1]))
+    res, tt = run_streamed_parity(w, params_for(w, gate_mode=ulorl.GATE_PER_RESPONSE, sigma=sigma), d, inplace=True,
+                                  say=say, one_call=True)
+    assert 0 < int(tt.resp_gate.sum()) < w.R and tt.n_masked > 10
+
+
 def test_cfg5_full_size_lmhead_variant():
     """Configuration 5 at full size (32768 x 2048 x 151936): the forward outputs and dHidden of
     sampled rows against the oracle (each depends only on its own row once the static gate and

@@ -32,7 +32,7 @@ def test_one_call_path_replays_bitwise_from_a_graph():
     say("graph: %s N=%d V=%d" % (w.name, w.N, w.V))
     d = ui.generate(w, DEV)
     p = ulorl.Params(gate_mode=ulorl.GATE_PER_RESPONSE, sigma=7.0, seg_len=w.seg_len)
-    ws = torch.empty(ulorl.token_loss_workspace_bytes(w.N, w.R), dtype=torch.uint8, device=DEV)
+    ws = torch.empty(ulorl.token_loss_workspace_bytes(w.N, w.V, w.R), dtype=torch.uint8, device=DEV)
     args = (d["logits"], d["token_ids"], d["cu_seqlens"], d["advantages"], d["old_logp"], p)
     ref, dz_ref = ulorl.token_loss_fwd_bwd(*args, grad_out=1.0, workspace=ws)      # eager; also the warm-up
     torch.cuda.synchronize()

@@ -225,8 +225,8 @@ def test_explicit_segment_ids_pass_through():
 
 def test_fused_path_defers_mpt_members_until_the_gate_is_known():
     """Under the entropy gates the one-call path finishes MPT members in a second launch; the
-    result must not depend on which path produced it (checked bitwise inside run_full_parity for
-    every case above); here the deferred rows are the majority."""
+    result must not depend on which path produced it (checked against the oracle inside
+    run_full_parity for every case above); here the deferred rows are the majority."""
     from dataclasses import replace
     w = replace(ui.shrink(ui.config(2), [300, 280, 310, 290], seg_len=100), spike_boost=22.0, spike_frac=0.7,
                 name="cfg2_mostly_mpt")
@@ -246,7 +246,11 @@ def test_fused_path_defers_mpt_members_until_the_gate_is_known():
     z1 = ulorl.token_loss_bwd(d["logits"], ybad, r1.lse, r1.gcoef)
     r2, z2 = ulorl.token_loss_fwd_bwd(d["logits"], ybad, d["cu_seqlens"], d["advantages"], d["old_logp"], p)
     assert int(r2.counters[3]) == ulorl.STATUS_BAD_TOKEN and torch.all(z2[5] == 0)
-    assert torch.equal(z1.view(torch.int16), z2.view(torch.int16))
+    # same gradient up to the rounding of the row sums (one bf16 ulp; the chosen column g - g p
+    # cancels, hence the absolute term of a few 1e-6 |g|), zero rows identical
+    assert torch.equal(z1 == 0, z2 == 0)
+    gmax = float(r1.gcoef.abs().max())
+    assert torch.all((z1.float() - z2.float()).abs() <= 2.0 ** -7 * z1.float().abs() + 8e-6 * gmax)
     cu_bad = d["cu_seqlens"].clone()
     cu_bad[1] = 700
     r3, z3 = ulorl.token_loss_fwd_bwd(d["logits"], d["token_ids"], cu_bad, d["advantages"], d["old_logp"], p)
@@ -297,7 +301,7 @@ def test_workspace_and_outputs_are_never_overrun(lengths):
     w = ui.shrink(ui.config(2), lengths, V=1000, seg_len=7, name="guard")
     d = ui.generate(w, DEV)
     p = params_for(w, gate_mode=ulorl.GATE_PER_RESPONSE, sigma=6.0)
-    need = ulorl.token_loss_workspace_bytes(w.N, w.R)
+    need = ulorl.token_loss_workspace_bytes(w.N, w.V, w.R)
     guard = 1 << 16
     buf = torch.full((need + guard,), 0xA5, dtype=torch.uint8, device=DEV)
     dz_buf = torch.full((w.N * w.V + guard,), -3.0, dtype=torch.bfloat16, device=DEV)

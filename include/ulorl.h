@@ -343,6 +343,9 @@ typedef enum {
                                      0: one looping workgroup per row (BWD_THREADS / BWD_UNROLL apply) */
     ULORL_TUNE_FUSED_CLUSTER = 8, /* 1 (default): one-call path by row-cooperative workgroups;
                                      0: one looping workgroup per row (FUSED_THREADS / FUSED_UNROLL apply) */
+    ULORL_TUNE_FUSED_VPT = 9,     /* 16-byte vectors each thread of a row-cooperative workgroup keeps:
+                                     4, 8, 10, 12 or 15; 0 (default) chooses from V.  The workspace
+                                     query assumes this knob's value at the time it is called. */
     ULORL_TUNE_GEMM_TILE = 6      /* lm_head variant, block tile M x N x K / waves along M x N:
                                      0 = 128x128x64 / 2x2, 1 = 256x256x32 / 2x2, 2 = 256x256x64 / 2x2,
                                      3 = 256x128x64 / 2x2, 4 = 256x256x64 / 2x4, 5 = 256x256x64 / 4x2,

@@ -17,6 +17,7 @@
 //
 // usage: ulorl_probe [--rows N] [--vocab V] [--iters K] [--out-of-place] [--spike F]
 //        ulorl_probe --gemm M N K [--tile I] [--iters K]
+//        (any form: --tune KNOB VALUE, repeated, sets launch-shape knobs first)
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -125,6 +126,11 @@ int main(int argc, char** argv)
             continue;
         }
         if (!std::strcmp(argv[i], "--tile") && i + 1 < argc) { tile = std::atoi(argv[++i]); continue; }
+        if (!std::strcmp(argv[i], "--tune") && i + 2 < argc) {     // --tune KNOB VALUE (ulorl_tune)
+            if (ulorl_tune(std::atoi(argv[i + 1]), std::atoi(argv[i + 2])) != ULORL_OK) { std::fprintf(stderr, "bad --tune\n"); return 2; }
+            i += 2;
+            continue;
+        }
         if (!std::strcmp(argv[i], "--rows") && i + 1 < argc) N = std::atoll(argv[++i]);
         else if (!std::strcmp(argv[i], "--vocab") && i + 1 < argc) V = std::atoll(argv[++i]);
         else if (!std::strcmp(argv[i], "--iters") && i + 1 < argc) iters = std::atoi(argv[++i]);

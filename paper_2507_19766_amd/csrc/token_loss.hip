@@ -78,6 +78,8 @@ struct StoreBF16 {
     }
     static __device__ __forceinline__ float load1(const elem* p) { return __uint_as_float(((uint32_t)*p) << 16); }
     static __device__ __forceinline__ void store1(elem* p, float x) { *p = (elem)(pack2(x, 0.0f) & 0xffffu); }
+    // a vector of -9.95e29 (bf16 0xF149), used as padding that contributes nothing to a row's sums
+    static __device__ __forceinline__ u32x4 filler() { return u32x4{0xf149f149u, 0xf149f149u, 0xf149f149u, 0xf149f149u}; }
 };
 
 struct StoreF32 {
@@ -97,6 +99,11 @@ struct StoreF32 {
     }
     static __device__ __forceinline__ float load1(const elem* p) { return *p; }
     static __device__ __forceinline__ void store1(elem* p, float x) { *p = x; }
+    static __device__ __forceinline__ u32x4 filler()
+    {
+        const uint32_t b = __float_as_uint(kEmpty);
+        return u32x4{b, b, b, b};
+    }
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -841,6 +848,19 @@ __global__ __launch_bounds__(kClusterThreads) void cluster_row_kernel(const type
 #pragma unroll
         for (int k = 0; k < VPT; ++k) v[k] = load_stream(vp + first + k * NT + tid);
         absorb_vectors<Tr, VPT, 0>(v, acc);
+    } else if (nvec - first >= NT) {
+        // A row's last piece: every thread holds at least one vector.  Missing vectors are
+        // replaced by a very negative finite filler, whose terms are exactly zero once the lane's
+        // maximum is a real logit (guaranteed: the thread's first vector is real), so the piece
+        // takes the same grouped arithmetic as a full one.
+        const u32x4 filler = Tr::filler();
+#pragma unroll
+        for (int k = 0; k < VPT; ++k) {
+            const int i = first + k * NT + tid;
+            v[k] = filler;
+            if (i < nvec) v[k] = load_stream(vp + i);
+        }
+        absorb_vectors<Tr, VPT, 0>(v, acc);
     } else {
 #pragma unroll
         for (int k = 0; k < VPT; ++k) {
@@ -1111,7 +1131,8 @@ template <class Tr>
 bool launch_cluster(int vpt, const void* logits, int64_t N, int64_t V, int64_t stride, void* dz, const ClusterArgs& a,
                     hipStream_t st)
 {
-    // x: piece (fastest, so a row's pieces have consecutive linear ids), y/z: row
+    // x: piece (fastest, so a row's pieces have consecutive linear ids and land on different XCDs:
+    // putting a row's pieces on one XCD measured 15 % slower), y/z: row
     dim3 grid((unsigned)a.C, (unsigned)(N < 32768 ? N : 32768), (unsigned)((N + 32767) / 32768));
 #define ULORL_CASE(VPT_)                                                                                       \
     if (vpt == VPT_) {                                                                                         \
@@ -1119,7 +1140,7 @@ bool launch_cluster(int vpt, const void* logits, int64_t N, int64_t V, int64_t s
                            (const typename Tr::elem*)logits, stride, (int32_t)V, (typename Tr::elem*)dz, a);   \
         return true;                                                                                           \
     }
-    ULORL_CASE(4) ULORL_CASE(8) ULORL_CASE(15)
+    ULORL_CASE(4) ULORL_CASE(8) ULORL_CASE(10) ULORL_CASE(12) ULORL_CASE(15)
 #undef ULORL_CASE
     return false;
 }
@@ -1138,6 +1159,8 @@ ClusterShape cluster_shape(int64_t V, int32_t dt)
     const int64_t nvec = V / (dt == ULORL_F32 ? 4 : 8);
     ClusterShape c;
     c.vpt = nvec >= 256 * 15 ? 15 : nvec >= 256 * 8 ? 8 : 4;
+    const int forced = tuning().fused_vpt;
+    if (forced == 4 || forced == 8 || forced == 10 || forced == 12 || forced == 15) c.vpt = forced;
     const int64_t per_piece = 256 * (int64_t)c.vpt;
     const int64_t pieces = nvec > 0 ? (nvec + per_piece - 1) / per_piece : 1;
     c.pieces = pieces <= 64 ? (int)pieces : 0;

@@ -79,6 +79,7 @@ struct Tuning {
     int gemm_tile = 7;     // index into the compiled-in GEMM tile shapes
     int bwd_oneshot = 1;   // standalone backward by one-shot 4 KB workgroups (0: one looping workgroup per row)
     int fused_cluster = 1; // one-call path by row-cooperative workgroups (0: one looping workgroup per row)
+    int fused_vpt = 0;     // 16-byte vectors per thread of the row-cooperative kernel (0: chosen from V)
 };
 Tuning& tuning();
 constexpr int kGemmTileCount = 9;

@@ -24,6 +24,8 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "ulorl.h"
 #include "ulorl_internal.hpp"
 
@@ -80,6 +82,7 @@ struct StoreBF16 {
     static __device__ __forceinline__ void store1(elem* p, float x) { *p = (elem)(pack2(x, 0.0f) & 0xffffu); }
     // a vector of -9.95e29 (bf16 0xF149), used as padding that contributes nothing to a row's sums
     static __device__ __forceinline__ u32x4 filler() { return u32x4{0xf149f149u, 0xf149f149u, 0xf149f149u, 0xf149f149u}; }
+    static __device__ __forceinline__ u32x4 sign_bits() { return u32x4{0x80008000u, 0x80008000u, 0x80008000u, 0x80008000u}; }
 };
 
 struct StoreF32 {
@@ -104,6 +107,7 @@ struct StoreF32 {
         const uint32_t b = __float_as_uint(kEmpty);
         return u32x4{b, b, b, b};
     }
+    static __device__ __forceinline__ u32x4 sign_bits() { return u32x4{0x80000000u, 0x80000000u, 0x80000000u, 0x80000000u}; }
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -845,8 +849,10 @@ __global__ __launch_bounds__(kClusterThreads) void cluster_row_kernel(const type
     u32x4 v[VPT];
     LaneAcc acc = {kEmpty, kEmpty * kLog2e, 0.0f, 0.0f, 0.0f};
     if (full) {
+        const char* const piece_in = reinterpret_cast<const char*>(vp + first);
 #pragma unroll
-        for (int k = 0; k < VPT; ++k) v[k] = load_stream(vp + first + k * NT + tid);
+        for (int k = 0; k < VPT; ++k)
+            v[k] = load_stream(reinterpret_cast<const u32x4*>(piece_in + (size_t)k * NT * 16 + (uint32_t)tid * 16u));
         absorb_vectors<Tr, VPT, 0>(v, acc);
     } else if (nvec - first >= NT) {
         // A row's last piece: every thread holds at least one vector.  Missing vectors are
@@ -991,27 +997,49 @@ __global__ __launch_bounds__(kClusterThreads) void cluster_row_kernel(const type
             for (int j = nvec * E; j < V; ++j) Tr::store1(outp + j, 0.0f);
         return;
     }
+    // dz = -g e^(z - lse) = s 2^(z log2e + cexp) with s = -sign(g), cexp = log2|g| - lse log2e.  The
+    // magnitudes are computed and rounded; a negative s is applied to the packed result by flipping
+    // sign bits (rounding to nearest even is symmetric), and the chosen column adds s*g before
+    // that.  Specialised for (full piece, sign) so that the common case carries no guards, no sign
+    // multiply and no per-vector address arithmetic (uniform base + lane offset).
     const float g = bc_g;
     const float cexp = fmaf(-bc_l, kLog2e, log2f(fabsf(g)));
-    const float sgn = g > 0.0f ? -1.0f : 1.0f;
-    const int yvec = y / E;
+    const bool negate = g > 0.0f;
+    const float g_mag = negate ? -g : g;       // s * g
+    const int ky = y / E - first - tid;        // this thread holds the chosen column in vector k iff ky == k * NT
+    const int ey = y - (y / E) * E;
+    char* const piece_out = reinterpret_cast<char*>(op + first);
+    const uint32_t lane_off = (uint32_t)tid * 16u;
+    auto emit_all = [&](auto full_c, auto neg_c) {
+        constexpr bool FULL = decltype(full_c)::value;
+        constexpr bool NEG = decltype(neg_c)::value;
 #pragma unroll
-    for (int k = 0; k < VPT; ++k) {
-        const int i = first + k * NT + tid;
-        if (full || i < nvec) {
-            float f[E];
-            Tr::unpack(v[k], f);
+        for (int k = 0; k < VPT; ++k) {
+            if (FULL || first + k * NT + tid < nvec) {
+                float f[E];
+                Tr::unpack(v[k], f);
 #pragma unroll
-            for (int e = 0; e < E; ++e) f[e] = sgn * fast_exp2(fmaf(f[e], kLog2e, cexp));
-            if (i == yvec) {
+                for (int e = 0; e < E; ++e) f[e] = fast_exp2(fmaf(f[e], kLog2e, cexp));
+                if (ky == k * NT) {
 #pragma unroll
-                for (int e = 0; e < E; ++e) f[e] += (e == y - yvec * E) ? g : 0.0f;
+                    for (int e = 0; e < E; ++e) f[e] += (e == ey) ? g_mag : 0.0f;
+                }
+                u32x4 o = Tr::pack(f);
+                if (NEG) o ^= Tr::sign_bits();
+                store_stream(reinterpret_cast<u32x4*>(piece_out + (size_t)k * NT * 16 + lane_off), o);
             }
-            store_stream(op + i, Tr::pack(f));
         }
+    };
+    if (full) {
+        if (negate) emit_all(std::true_type{}, std::true_type{});
+        else emit_all(std::true_type{}, std::false_type{});
+    } else {
+        if (negate) emit_all(std::false_type{}, std::true_type{});
+        else emit_all(std::false_type{}, std::false_type{});
     }
     if (owns_tail) {
         // the tail's logits have not been overwritten: only this thread writes them
+        const float sgn = negate ? -1.0f : 1.0f;
         for (int j = nvec * E; j < V; ++j) {
             float x = sgn * fast_exp2(fmaf(Tr::load1(rowp + j), kLog2e, cexp));
             if (j == y) x += g;

@@ -343,6 +343,9 @@ typedef enum {
                                      0: one looping workgroup per row (BWD_THREADS / BWD_UNROLL apply) */
     ULORL_TUNE_FUSED_CLUSTER = 8, /* 1 (default): one-call path by row-cooperative workgroups;
                                      0: one looping workgroup per row (FUSED_THREADS / FUSED_UNROLL apply) */
+    ULORL_TUNE_SYNC_SPINS = 10,   /* polls (about 0.25 us each) a row-cooperative workgroup waits for its
+                                     partners before it gives the row up (ULORL_STATUS_SYNC); >= 1,
+                                     default 2^24.  A tiny value lets a test exercise that path. */
     ULORL_TUNE_FUSED_VPT = 9,     /* 16-byte vectors each thread of a row-cooperative workgroup keeps:
                                      4, 8, 10, 12 or 15; 0 (default) chooses from V.  The workspace
                                      query assumes this knob's value at the time it is called. */

@@ -18,7 +18,7 @@ IS_SAIS, IS_POIS = 0, 1
 GATE_PER_RESPONSE, GATE_GLOBAL, GATE_ALWAYS, GATE_NEVER = 0, 1, 2, 3
 STATUS_BAD_TOKEN, STATUS_NONFINITE, STATUS_BAD_CU, STATUS_SYNC = 1, 2, 4, 8
 TUNE_FWD_THREADS, TUNE_FWD_UNROLL, TUNE_BWD_THREADS, TUNE_BWD_UNROLL = 0, 1, 2, 3
-TUNE_FUSED_THREADS, TUNE_FUSED_UNROLL, TUNE_GEMM_TILE, TUNE_BWD_ONESHOT, TUNE_FUSED_CLUSTER, TUNE_FUSED_VPT = 4, 5, 6, 7, 8, 9
+TUNE_FUSED_THREADS, TUNE_FUSED_UNROLL, TUNE_GEMM_TILE, TUNE_BWD_ONESHOT, TUNE_FUSED_CLUSTER, TUNE_FUSED_VPT, TUNE_SYNC_SPINS = 4, 5, 6, 7, 8, 9, 10
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 

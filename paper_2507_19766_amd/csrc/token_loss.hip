@@ -782,12 +782,11 @@ __global__ __launch_bounds__(NT) void fused_row_kernel(const typename Tr::elem* 
 // (S >= 1 for a non-empty piece; the tag), so no ordering between memory locations and no cache
 // maintenance is needed.  Workgroups are dispatched in order of their linear id and a row's
 // pieces have consecutive ids, so the partners of a resident workgroup are resident or next in
-// line; the wait is nevertheless bounded (kSpinLimit polls): on expiry the row is given a zero
+// line; the wait is nevertheless bounded (spin_limit polls, seconds by default): on expiry the row is given a zero
 // gradient, not-a-number statistics and the SYNC status bit.  Every workgroup of a row merges the
 // same pieces in the same order and therefore takes the same decisions.
 constexpr int kClusterThreads = 256;
 constexpr int kClusterMaxPieces = 64;         // one polled piece per lane of a wave
-constexpr int kSpinLimit = 1 << 24;           // polls of ~0.25 us each: seconds
 
 // Absorbs vectors v[K .. VPT) in power-of-two groups, largest first (absorb<> wants a power of two).
 template <class Tr, int VPT, int K>
@@ -811,6 +810,7 @@ struct ClusterArgs {
     uint32_t* sync_fail;         // one word, set if any wait expired
     int64_t N;
     int32_t C;
+    int32_t spin_limit;          // polls (~0.25 us each) before a wait is given up
 };
 
 template <class Tr, int VPT>
@@ -928,7 +928,7 @@ __global__ __launch_bounds__(kClusterThreads) void cluster_row_kernel(const type
                 if (w0 == 0) w0 = __hip_atomic_load(slot + 2 * tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 if (w1 == 0) w1 = __hip_atomic_load(slot + 2 * tid + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 if (w0 != 0 && w1 != 0) break;
-                if (++spins >= kSpinLimit) { expired = 1; break; }
+                if (++spins >= a.spin_limit) { expired = 1; break; }
                 __builtin_amdgcn_s_sleep(4);
             }
             if (!expired) {
@@ -1360,13 +1360,14 @@ int32_t ulorl_token_loss_fwd_bwd(const void* logits, int32_t dt, int64_t N, int6
     hipLaunchKernelGGL(cu_check_kernel, dim3(1), dim3(kTokBlock), 0, st, cu_seqlens, R, N, (uint32_t*)(ws + wl.badcu));
     const ClusterShape shape = cluster_shape(V, dt);
     bool ok;
-    if (tuning().fused_cluster && shape.pieces > 0) {
+    if (tuning().fused_cluster && shape.pieces > 0 && 2 * N * (int64_t)shape.pieces < (1LL << 38)) {
         ClusterArgs ca;
         ca.f = f;
         ca.slots = (unsigned long long*)(ws + wl.slots);
         ca.sync_fail = (uint32_t*)(ws + wl.syncfail);
         ca.N = N;
         ca.C = shape.pieces;
+        ca.spin_limit = tuning().sync_spins;
         a.sync_fail = ca.sync_fail;
         const int64_t nslots = 2 * N * (int64_t)shape.pieces;
         hipLaunchKernelGGL(fill_zero_u64_kernel, dim3((unsigned)((nslots + 255) / 256)), dim3(256), 0, st, ca.slots, nslots,

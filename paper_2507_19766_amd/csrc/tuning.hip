@@ -27,6 +27,7 @@ extern "C" int32_t ulorl_tune(int32_t knob, int32_t value)
         if (value != 0 && value != 4 && value != 8 && value != 10 && value != 12 && value != 15) return ULORL_ERR_PARAM;
         t.fused_vpt = value;
         return ULORL_OK;
+    case ULORL_TUNE_SYNC_SPINS: if (value < 1) return ULORL_ERR_PARAM; t.sync_spins = value; return ULORL_OK;
     case ULORL_TUNE_GEMM_TILE:
         if (value < 0 || value >= ulorl_detail::kGemmTileCount) return ULORL_ERR_PARAM;
         t.gemm_tile = value;

@@ -80,6 +80,7 @@ struct Tuning {
     int bwd_oneshot = 1;   // standalone backward by one-shot 4 KB workgroups (0: one looping workgroup per row)
     int fused_cluster = 1; // one-call path by row-cooperative workgroups (0: one looping workgroup per row)
     int fused_vpt = 0;     // 16-byte vectors per thread of the row-cooperative kernel (0: chosen from V)
+    int sync_spins = 1 << 24;  // polls before a workgroup of the row-cooperative kernel gives up on its partners
 };
 Tuning& tuning();
 constexpr int kGemmTileCount = 9;

@@ -126,6 +126,6 @@ def test_tuning_knobs_validate():
     with pytest.raises(ulorl.UlorlError):
         ulorl.tune(ulorl.TUNE_FWD_THREADS, 100)
     with pytest.raises(ulorl.UlorlError):
-        ulorl.tune(10, 256)
+        ulorl.tune(11, 256)
     with pytest.raises(ulorl.UlorlError):
         ulorl.tune(ulorl.TUNE_FUSED_CLUSTER, 2)

@@ -314,3 +314,36 @@ def test_workspace_and_outputs_are_never_overrun(lengths):
     torch.cuda.synchronize()
     assert bool((buf[need:] == 0xA5).all())
     assert bool((dz_buf[w.N * w.V:] == -3.0).all())
+
+
+def test_an_expired_wait_is_reported_and_never_hangs():
+    """The workgroups that share a row wait for each other with a bounded wait.  With the bound set
+    to a single poll from the host, some waits expire: the kernel still ends, the status word says
+    so, the rows concerned have not-a-number statistics and an exactly zero gradient, and all
+    other rows are unaffected."""
+    w = ui.shrink(ui.config(2), [400, 240], V=151936 // 2, name="sync_expiry")     # several pieces per row
+    d = ui.generate(w, DEV)
+    p = params_for(w, gate_mode=ulorl.GATE_ALWAYS)
+    good, dz_good = ulorl.token_loss_fwd_bwd(d["logits"], d["token_ids"], d["cu_seqlens"], d["advantages"],
+                                             d["old_logp"], p)
+    assert int(good.counters[3].item()) == 0
+    ulorl.tune(ulorl.TUNE_SYNC_SPINS, 1)
+    try:
+        res, dz = ulorl.token_loss_fwd_bwd(d["logits"], d["token_ids"], d["cu_seqlens"], d["advantages"],
+                                           d["old_logp"], p)
+        torch.cuda.synchronize()
+    finally:
+        ulorl.tune(ulorl.TUNE_SYNC_SPINS, 1 << 24)
+    status = int(res.counters[3].item())
+    gave_up = torch.isnan(res.lse)
+    if bool(gave_up.any()):
+        assert status & ulorl.STATUS_SYNC and status & ulorl.STATUS_NONFINITE
+        assert torch.all(res.gcoef[gave_up] == 0)
+    else:       # every partner happened to be there at the first poll
+        assert status == 0
+    ok = ~gave_up
+    assert torch.equal(res.lse[ok], good.lse[ok]) and torch.equal(res.gcoef[ok], good.gcoef[ok])
+    # a row is consistent if all its workgroups agreed; where the leader saw every piece but a
+    # partner did not, that partner's piece is zero: either the good values or zeros, nothing else
+    same = dz.view(torch.int16) == dz_good.view(torch.int16)
+    assert torch.all(same | (dz == 0))

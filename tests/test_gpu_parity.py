@@ -347,3 +347,11 @@ def test_an_expired_wait_is_reported_and_never_hangs():
     # partner did not, that partner's piece is zero: either the good values or zeros, nothing else
     same = dz.view(torch.int16) == dz_good.view(torch.int16)
     assert torch.all(same | (dz == 0))
+
+
+def test_rows_too_long_for_the_cooperative_kernel_fall_back():
+    """A row of more than 64 pieces (1.97 M bf16 logits) is handled by one looping workgroup per
+    row; a row of exactly 64 pieces still takes the cooperative kernel.  Both against the oracle."""
+    for V in (64 * 3840 * 8, 64 * 3840 * 8 + 8):
+        w = ui.shrink(ui.config(2), [2, 1], V=V, seg_len=1, name="long_rows_%d" % V)
+        run_full_parity(w, params_for(w, gate_mode=ulorl.GATE_ALWAYS))

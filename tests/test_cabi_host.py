@@ -129,3 +129,15 @@ def test_tuning_knobs_validate():
         ulorl.tune(11, 256)
     with pytest.raises(ulorl.UlorlError):
         ulorl.tune(ulorl.TUNE_FUSED_CLUSTER, 2)
+
+
+def test_pool_step_rejects_bad_arguments_on_the_host():
+    lib = ulorl.load_library()
+    vp = ctypes.c_void_p
+
+    def call(B=4, prev=0x1000, seg=16, mx=64, counts=0x9000):
+        return lib.ulorl_segment_pool_step(B, vp(prev), vp(0x2000), vp(0x3000), seg, mx, vp(0x4000), vp(0x5000),
+                                           vp(0x6000), vp(0x7000), vp(0x8000), vp(0xa000), vp(0xb000), vp(counts), None)
+    assert call(prev=0) == -1 and call(counts=0) == -1
+    assert call(B=0) == -2 and call(seg=0) == -2 and call(mx=0) == -2
+    assert call(B=1 << 20, mx=1 << 20) == -2          # offsets of the packed batch would not fit in int32

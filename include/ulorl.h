@@ -205,8 +205,9 @@ int32_t ulorl_token_loss_fwd_bwd(
  *                 vocabulary columns at a time ([N, vocab_chunk] bf16, twice) in the workspace
  * Logits are formed tile by tile with bf16 MFMA and fp32 accumulation and consumed in registers.
  * Everything else (token ids, cu_seqlens, old_logp, advantages, parameters, per-token and
- * per-response outputs, counters, status bits) is exactly as in ulorl_token_loss_fwd, except
- * that there is no stats-only pass (advantages must not be NULL).
+ * per-response outputs, counters, status bits) is exactly as in ulorl_token_loss_fwd, including
+ * the stats-only pass selected by advantages == NULL (only lse, logp and entropy are written;
+ * the workspace is still needed, sized with any R >= 1).
  *
  * The workspace (ulorl_lmhead_workspace_bytes, 256-byte aligned) holds W^T, hidden^T, the two
  * dlogits chunk buffers, an fp32 accumulator for dHidden and the token-loss workspace; nothing

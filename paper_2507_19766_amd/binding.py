@@ -350,10 +350,24 @@ def lmhead_token_loss_fwd(hidden, weight, token_ids, cu_seqlens, advantages, old
     token_ids = _vec(token_ids, torch.int32, N, "token_ids", dev)
     params = params or Params()
     cparams = params.to_c()
-    R = cu_seqlens.shape[0] - 1
+    R = cu_seqlens.shape[0] - 1 if cu_seqlens is not None else 1
     advantages = _vec(advantages, torch.float32, N, "advantages", dev)
     old_logp = _vec(old_logp, torch.float32, N, "old_logp", dev)
     segment_ids = _vec(segment_ids, torch.int32, N, "segment_ids", dev)
+    if advantages is None:          # stats-only pass
+        if out is None:
+            out = FwdResult(None, torch.empty(N, **f32), torch.empty(N, **f32), torch.empty(N, **f32),
+                            None, None, None, None, None, None, None)
+        if workspace is None:
+            workspace = torch.empty(max(lmhead_workspace_bytes(N, Hd, V, R, vocab_chunk), 256), dtype=torch.uint8,
+                                    device=dev)
+        rc = lib.ulorl_lmhead_token_loss_fwd(
+            _p(hidden), _p(weight), N, Hd, V, vocab_chunk, _p(token_ids), _p(cu_seqlens), R, None, None, None,
+            ctypes.byref(cparams), None, _p(out.logp), _p(out.entropy), _p(out.lse), None, None, None, None, None,
+            None, None, _p(workspace), workspace.numel(), _stream(dev))
+        if rc != 0:
+            raise UlorlError(rc, "ulorl_lmhead_token_loss_fwd")
+        return out
     if out is None:
         out = FwdResult(torch.empty(1, **f32), torch.empty(N, **f32), torch.empty(N, **f32), torch.empty(N, **f32),
                         torch.empty(N, **f32), torch.empty(N, dtype=torch.uint8, device=dev), torch.empty(N, **f32),

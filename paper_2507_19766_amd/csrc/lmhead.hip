@@ -1046,9 +1046,14 @@ int32_t ulorl_lmhead_token_loss_fwd(const void* hidden, const void* W, int64_t N
 {
     int32_t rc = check_lmhead(hidden, W, N, Hd, V, vocab_chunk);
     if (rc != ULORL_OK) return rc;
-    if (!token_ids || !logp || !entropy || !lse || !advantages) return ULORL_ERR_NULL;
-    rc = check_objective_args(cu_seqlens, R, old_logp, p, loss, gcoef);
-    if (rc != ULORL_OK) return rc;
+    if (!token_ids || !logp || !entropy || !lse) return ULORL_ERR_NULL;
+    const bool stats_only = advantages == nullptr;      // lse, logp and entropy only (recording old log-probs)
+    if (!stats_only) {
+        rc = check_objective_args(cu_seqlens, R, old_logp, p, loss, gcoef);
+        if (rc != ULORL_OK) return rc;
+    } else if (R <= 0) {
+        R = 1;      // only sizes the workspace layout
+    }
     const LmheadLayout L = lmhead_layout(N, Hd, V, R, vocab_chunk);
     if (!workspace || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < L.total) return ULORL_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)hip_stream;
@@ -1064,6 +1069,7 @@ int32_t ulorl_lmhead_token_loss_fwd(const void* hidden, const void* W, int64_t N
     hipLaunchKernelGGL(lmhead_stats_merge_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, st, partial, L.splits,
                        (int)N, (int)V, token_ids, lse, logp, entropy);
     if (hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;
+    if (stats_only) return ULORL_OK;
 
     const WorkspaceLayout wl = workspace_layout(N, 0, R);
     const TokenArgs a = make_token_args(N, V, token_ids, cu_seqlens, R, segment_ids, old_logp, advantages, p, logp,

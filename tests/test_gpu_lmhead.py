@@ -93,3 +93,17 @@ def test_workspace_is_never_overrun(lengths, V, hidden, chunk):
                                 workspace=ws)
     torch.cuda.synchronize()
     assert bool((buf[need:] == 0xA5).all())
+
+
+def test_lmhead_stats_only_pass():
+    """advantages = None: only lse, logp and entropy are produced (how a caller records the
+    behaviour policy's log-probs), identical to those of the full forward."""
+    w = ui.shrink(ui.config(5), [150, 120], V=1544, hidden=128, seg_len=64, name="lmhead_stats_only")
+    d = ui.generate(w, DEV)
+    p = ulorl.Params(gate_mode=ulorl.GATE_ALWAYS, seg_len=w.seg_len)
+    full = ulorl.lmhead_token_loss_fwd(d["hidden"], d["weight"], d["token_ids"], d["cu_seqlens"], d["advantages"],
+                                       d["old_logp"], p, vocab_chunk=512)
+    only = ulorl.lmhead_token_loss_fwd(d["hidden"], d["weight"], d["token_ids"], None, None, vocab_chunk=512)
+    assert only.loss is None and only.gcoef is None
+    for name in ("lse", "logp", "entropy"):
+        assert torch.equal(getattr(only, name), getattr(full, name)), name

@@ -170,7 +170,7 @@ def main():
     ap.add_argument("--workload", default="cfg4", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--gemm-tile", type=int, default=-1, help="lm_head variant: tile shape index (ulorl_tune)")
     ap.add_argument("--out-of-place", action="store_true", help="write dlogits to a second buffer")
-    ap.add_argument("--cpu-rows", type=int, default=49152, help="rows of the oracle sample (0 = skip)")
+    ap.add_argument("--cpu-rows", type=int, default=98304, help="rows of the oracle sample (0 = skip)")
     ap.add_argument("--path", default="fused", choices=["fused", "two_call"],
                     help="which path gives the headline value (both are timed)")
     ap.add_argument("--fwd-threads", type=int, default=0)

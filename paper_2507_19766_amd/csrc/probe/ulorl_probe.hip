@@ -16,7 +16,7 @@
 // on hashed operands, for matrix-core counters.
 //
 // usage: ulorl_probe [--rows N] [--vocab V] [--iters K] [--out-of-place] [--spike F]
-//        ulorl_probe --gemm M N K [--tile I] [--iters K]
+//        ulorl_probe --gemm M N K [--tile I] [--pad P] [--iters K]
 //        (any form: --tune KNOB VALUE, repeated, sets launch-shape knobs first)
 #include <hip/hip_runtime.h>
 
@@ -119,6 +119,7 @@ int main(int argc, char** argv)
     int spike = 400;
     int64_t gm = 0, gn = 0, gk = 0;
     int tile = -1;
+    int64_t pad = 0;     // --gemm only: extra elements in the operands' leading dimensions
     for (int i = 1; i < argc; ++i) {
         if (!std::strcmp(argv[i], "--gemm") && i + 3 < argc) {
             gm = std::atoll(argv[i + 1]); gn = std::atoll(argv[i + 2]); gk = std::atoll(argv[i + 3]);
@@ -126,6 +127,7 @@ int main(int argc, char** argv)
             continue;
         }
         if (!std::strcmp(argv[i], "--tile") && i + 1 < argc) { tile = std::atoi(argv[++i]); continue; }
+        if (!std::strcmp(argv[i], "--pad") && i + 1 < argc) { pad = std::atoll(argv[++i]); continue; }
         if (!std::strcmp(argv[i], "--tune") && i + 2 < argc) {     // --tune KNOB VALUE (ulorl_tune)
             if (ulorl_tune(std::atoi(argv[i + 1]), std::atoi(argv[i + 2])) != ULORL_OK) { std::fprintf(stderr, "bad --tune\n"); return 2; }
             i += 2;
@@ -143,24 +145,26 @@ int main(int argc, char** argv)
         if (tile >= 0 && ulorl_tune(ULORL_TUNE_GEMM_TILE, tile) != ULORL_OK) { std::fprintf(stderr, "bad tile\n"); return 2; }
         uint16_t *a = nullptr, *b = nullptr;
         float* c = nullptr;
-        CHECK(hipMalloc(&a, (size_t)gm * gk * 2)); CHECK(hipMalloc(&b, (size_t)gn * gk * 2)); CHECK(hipMalloc(&c, (size_t)gm * gn * 4));
-        hipLaunchKernelGGL(fill_bf16_kernel, dim3(4096), dim3(256), 0, 0, a, gm * gk, 11ULL << 40);
-        hipLaunchKernelGGL(fill_bf16_kernel, dim3(4096), dim3(256), 0, 0, b, gn * gk, 12ULL << 40);
+        if (pad < 0 || pad % 8 != 0) { std::fprintf(stderr, "--pad must be a non-negative multiple of 8\n"); return 2; }
+        const int64_t ld = gk + pad;
+        CHECK(hipMalloc(&a, (size_t)gm * ld * 2)); CHECK(hipMalloc(&b, (size_t)gn * ld * 2)); CHECK(hipMalloc(&c, (size_t)gm * gn * 4));
+        hipLaunchKernelGGL(fill_bf16_kernel, dim3(4096), dim3(256), 0, 0, a, gm * ld, 11ULL << 40);
+        hipLaunchKernelGGL(fill_bf16_kernel, dim3(4096), dim3(256), 0, 0, b, gn * ld, 12ULL << 40);
         CHECK(hipDeviceSynchronize());
         hipEvent_t e0, e1;
         CHECK(hipEventCreate(&e0)); CHECK(hipEventCreate(&e1));
         double tot = 0;
         for (int it = 0; it < iters + 1; ++it) {
             CHECK(hipEventRecord(e0, 0));
-            const int rc = ulorl_gemm_tn_bf16(a, gk, b, gk, gm, gn, gk, c, gn, nullptr);
+            const int rc = ulorl_gemm_tn_bf16(a, ld, b, ld, gm, gn, gk, c, gn, nullptr);
             if (rc != ULORL_OK) { std::fprintf(stderr, "gemm: %s\n", ulorl_status_string(rc)); return 1; }
             CHECK(hipEventRecord(e1, 0));
             CHECK(hipDeviceSynchronize());
             if (it > 0) tot += ms_between(e0, e1);
         }
         const double ms = tot / iters;
-        std::printf("gemm_tn_bf16 %lld x %lld x %lld tile %d: %.3f ms  %.1f TFLOP/s\n", (long long)gm, (long long)gn,
-                    (long long)gk, tile, ms, 2.0 * gm * gn * gk / ms / 1e9);
+        std::printf("gemm_tn_bf16 %lld x %lld x %lld (ld %lld) tile %d: %.3f ms  %.1f TFLOP/s\n", (long long)gm,
+                    (long long)gn, (long long)gk, (long long)ld, tile, ms, 2.0 * gm * gn * gk / ms / 1e9);
         return 0;
     }
 

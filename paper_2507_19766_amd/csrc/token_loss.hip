@@ -703,7 +703,8 @@ __global__ __launch_bounds__(kTokBlock) void loss_finalize_kernel(TokenArgs a, i
 }
 
 // ---------------------------------------------------------------------------------------------
-// fused forward + backward stream
+// fused forward + backward, one looping workgroup per row (the older kernel of the one-call path,
+// selected with ULORL_TUNE_FUSED_CLUSTER = 0 and used for rows too long for the cooperative one)
 // ---------------------------------------------------------------------------------------------
 // One workgroup per row does both passes back to back: statistics with ordinary (cacheable)
 // loads, then the gradient with the row read a second time while it is still in the L2 /
@@ -1186,12 +1187,12 @@ ClusterShape cluster_shape(int64_t V, int32_t dt)
 {
     const int64_t nvec = V / (dt == ULORL_F32 ? 4 : 8);
     ClusterShape c;
-    c.vpt = nvec >= 256 * 15 ? 15 : nvec >= 256 * 8 ? 8 : 4;
+    c.vpt = nvec >= kClusterThreads * 15 ? 15 : nvec >= kClusterThreads * 8 ? 8 : 4;
     const int forced = tuning().fused_vpt;
     if (forced == 4 || forced == 8 || forced == 10 || forced == 12 || forced == 15) c.vpt = forced;
-    const int64_t per_piece = 256 * (int64_t)c.vpt;
+    const int64_t per_piece = kClusterThreads * (int64_t)c.vpt;
     const int64_t pieces = nvec > 0 ? (nvec + per_piece - 1) / per_piece : 1;
-    c.pieces = pieces <= 64 ? (int)pieces : 0;
+    c.pieces = pieces <= kClusterMaxPieces ? (int)pieces : 0;
     return c;
 }
 

@@ -200,8 +200,10 @@ int32_t ulorl_token_loss_fwd_bwd(
  *
  *   hidden        [N, Hd] bf16 row-major (Hd contiguous), 16-byte aligned
  *   W             [Hd, V] bf16 row-major (V contiguous), 16-byte aligned: output projection
- *   Hd, V         multiples of 8 (16-byte rows)
- *   vocab_chunk   multiple of 64; the backward pass materialises dlogits one chunk of this many
+ *   Hd, V         multiples of 8 (16-byte rows); Hd <= 2^20
+ *   N             at most 2^22 - 256 token rows per call (N is a leading dimension of GEMM
+ *                 operands in the backward pass; larger batches are split by the caller)
+ *   vocab_chunk   multiple of 64, at most 2^22 - 256; the backward pass materialises dlogits one chunk of this many
  *                 vocabulary columns at a time ([N, vocab_chunk] bf16, twice) in the workspace
  * Logits are formed tile by tile with bf16 MFMA and fp32 accumulation and consumed in registers.
  * Everything else (token ids, cu_seqlens, old_logp, advantages, parameters, per-token and
@@ -240,8 +242,8 @@ int32_t ulorl_lmhead_token_loss_bwd(
 /*
  * The tiled bf16 MFMA product the lm_head variant is built from, on its own:
  * C[m, n] = sum_k A[m, k] * B[n, k], A [M, K] and B [N, K] bf16 row-major with leading
- * dimensions lda, ldb (multiples of 8, 16-byte aligned bases), C fp32 [M, N] with leading
- * dimension ldc.  K must be a multiple of 8.
+ * dimensions lda, ldb (multiples of 8, at most 2^22 elements, 16-byte aligned bases), C fp32
+ * [M, N] with leading dimension ldc.  K must be a multiple of 8.
  */
 int32_t ulorl_gemm_tn_bf16(const void *A, int64_t lda, const void *B, int64_t ldb,
                            int64_t M, int64_t N, int64_t K, float *C, int64_t ldc, void *hip_stream);

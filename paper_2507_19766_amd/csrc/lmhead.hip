@@ -223,8 +223,14 @@ __device__ __forceinline__ void step_pattern()
     __builtin_amdgcn_sched_group_barrier(0x008, MFMAS - 1 - COPIES, 0);
 }
 
+// Word 3 of a raw (unstructured, stride 0) buffer descriptor on gfx9-family parts: 32-bit data format.
+constexpr int kRawBufferFlags = 0x00020000;
+// A tile's rows are addressed by 32-bit byte offsets from its first row: 256 rows of at most this
+// many bf16 elements stay below 2^31 bytes.
+constexpr int64_t kMaxLeadingDim = 1 << 22;
+
 // The same product with the tiles copied global -> LDS by the load unit itself
-// (global_load_lds_dwordx4: lane L of a wave deposits its 16 bytes at lds_base + 16 L), so the
+// (buffer_load_dwordx4 ... lds: lane L of a wave deposits its 16 bytes at lds_base + 16 L), so the
 // staging registers, the ds_write instructions and the wait between a load's return and its
 // write disappear from the loop.  A wave-instruction fills 64 consecutive 16-byte slots = 8 rows
 // of a BK = 64 tile or 16 rows of a BK = 32 tile; rows are therefore unpadded, and bank conflicts
@@ -280,21 +286,30 @@ __device__ __forceinline__ void gemm_tn_mainloop_direct(const bf16_t* __restrict
         const int gr = (n0 + row < N) ? row : (N - 1 - n0);
         ob[j] = (uint32_t)(((int64_t)gr * ldb + kv * 8) * 2);
     }
+    // The copies are buffer loads: a descriptor per operand slab (base = first row of the tile,
+    // extent = up to the end of its last valid row) in scalar registers, the lane's 32-bit byte
+    // offset, and the K position as the scalar offset.  No 64-bit address arithmetic is left in
+    // the loop, and the hardware drops any access beyond the extent instead of faulting.
+    const int rows_a = min(Cfg::BM, M - m0), rows_b = min(Cfg::BN, N - n0);
+    const uint64_t extent_a = ((uint64_t)(rows_a - 1) * (uint64_t)lda + (uint64_t)K) * 2;
+    const uint64_t extent_b = ((uint64_t)(rows_b - 1) * (uint64_t)ldb + (uint64_t)K) * 2;
+    const __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<char*>(a_tile), 0, (int)(uint32_t)min(extent_a, (uint64_t)0xffffffffu), kRawBufferFlags);
+    const __amdgpu_buffer_rsrc_t rsrc_b = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<char*>(b_tile), 0, (int)(uint32_t)min(extent_b, (uint64_t)0xffffffffu), kRawBufferFlags);
     auto fetch_a = [&](int k0, int stage) {
-        const char* pa = a_tile + (int64_t)k0 * 2;
 #pragma unroll
         for (int j = 0; j < A_INSTR; ++j)
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(pa + oa[j]),
-                                             (__attribute__((address_space(3))) void*)(sA + stage * A_STAGE + (j * NW + wave) * RPI * BK),
-                                             16, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a,
+                                                     (__attribute__((address_space(3))) void*)(sA + stage * A_STAGE + (j * NW + wave) * RPI * BK),
+                                                     16, oa[j], k0 * 2, 0, 0);
     };
     auto fetch_b = [&](int k0, int stage) {
-        const char* pb = b_tile + (int64_t)k0 * 2;
 #pragma unroll
         for (int j = 0; j < B_INSTR; ++j)
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(pb + ob[j]),
-                                             (__attribute__((address_space(3))) void*)(sB + stage * B_STAGE + (j * NW + wave) * RPI * BK),
-                                             16, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_b,
+                                                     (__attribute__((address_space(3))) void*)(sB + stage * B_STAGE + (j * NW + wave) * RPI * BK),
+                                                     16, ob[j], k0 * 2, 0, 0);
     };
 
     // fragment sources: row = tile row of this lane, vector kg = 2 kk + lane/32, stored at slot kg xor swz(row)
@@ -931,9 +946,10 @@ LmheadLayout lmhead_layout(int64_t N, int64_t Hd, int64_t V, int32_t R, int32_t 
 int32_t check_lmhead(const void* hidden, const void* W, int64_t N, int64_t Hd, int64_t V, int32_t chunk)
 {
     if (!hidden || !W) return ULORL_ERR_NULL;
-    if (N <= 0 || N > 0x7fffffffLL || V <= 0 || V > 0x7fffffffLL || Hd <= 0 || Hd > (1 << 20)) return ULORL_ERR_SHAPE;
+    // N and the chunk width become leading dimensions of GEMM operands (see kMaxLeadingDim)
+    if (N <= 0 || N > kMaxLeadingDim - 256 || V <= 0 || V > 0x7fffffffLL || Hd <= 0 || Hd > (1 << 20)) return ULORL_ERR_SHAPE;
     if (Hd % 8 != 0 || V % 8 != 0) return ULORL_ERR_SHAPE;     // 16-byte rows of hidden, W and their transposes
-    if (chunk <= 0 || chunk % 64 != 0) return ULORL_ERR_SHAPE;
+    if (chunk <= 0 || chunk % 64 != 0 || chunk > kMaxLeadingDim - 256) return ULORL_ERR_SHAPE;
     if (((uintptr_t)hidden & 15u) != 0 || ((uintptr_t)W & 15u) != 0) return ULORL_ERR_ALIGN;
     return ULORL_OK;
 }
@@ -1023,6 +1039,7 @@ int32_t ulorl_gemm_tn_bf16(const void* A, int64_t lda, const void* B, int64_t ld
     if (!A || !B || !C) return ULORL_ERR_NULL;
     if (M <= 0 || N <= 0 || K <= 0 || M > 0x7fffffffLL || N > 0x7fffffffLL || K > 0x7fffffffLL) return ULORL_ERR_SHAPE;
     if (K % 8 != 0 || lda % 8 != 0 || ldb % 8 != 0 || lda < K || ldb < K || ldc < N) return ULORL_ERR_SHAPE;
+    if (lda > kMaxLeadingDim || ldb > kMaxLeadingDim) return ULORL_ERR_SHAPE;
     if (((uintptr_t)A & 15u) != 0 || ((uintptr_t)B & 15u) != 0) return ULORL_ERR_ALIGN;
     if (!launch_gemm<STORE_F32>((const bf16_t*)A, lda, (int)M, (const bf16_t*)B, ldb, (int)N, (int)K, C, ldc,
                                 (hipStream_t)hip_stream))

@@ -16,7 +16,7 @@
 // on hashed operands, for matrix-core counters.
 //
 // usage: ulorl_probe [--rows N] [--vocab V] [--iters K] [--out-of-place] [--spike F]
-//        ulorl_probe --gemm M N K [--tile I] [--pad P] [--iters K]
+//        ulorl_probe --gemm M N K [--tile I] [--pad P] [--zeros] [--iters K]
 //        (any form: --tune KNOB VALUE, repeated, sets launch-shape knobs first)
 #include <hip/hip_runtime.h>
 
@@ -120,6 +120,7 @@ int main(int argc, char** argv)
     int64_t gm = 0, gn = 0, gk = 0;
     int tile = -1;
     int64_t pad = 0;     // --gemm only: extra elements in the operands' leading dimensions
+    bool zeros = false;  // --gemm only: all-zero operands (the matrix pipes switch the least: the clock is at its highest)
     for (int i = 1; i < argc; ++i) {
         if (!std::strcmp(argv[i], "--gemm") && i + 3 < argc) {
             gm = std::atoll(argv[i + 1]); gn = std::atoll(argv[i + 2]); gk = std::atoll(argv[i + 3]);
@@ -128,6 +129,7 @@ int main(int argc, char** argv)
         }
         if (!std::strcmp(argv[i], "--tile") && i + 1 < argc) { tile = std::atoi(argv[++i]); continue; }
         if (!std::strcmp(argv[i], "--pad") && i + 1 < argc) { pad = std::atoll(argv[++i]); continue; }
+        if (!std::strcmp(argv[i], "--zeros")) { zeros = true; continue; }
         if (!std::strcmp(argv[i], "--tune") && i + 2 < argc) {     // --tune KNOB VALUE (ulorl_tune)
             if (ulorl_tune(std::atoi(argv[i + 1]), std::atoi(argv[i + 2])) != ULORL_OK) { std::fprintf(stderr, "bad --tune\n"); return 2; }
             i += 2;
@@ -148,8 +150,13 @@ int main(int argc, char** argv)
         if (pad < 0 || pad % 8 != 0) { std::fprintf(stderr, "--pad must be a non-negative multiple of 8\n"); return 2; }
         const int64_t ld = gk + pad;
         CHECK(hipMalloc(&a, (size_t)gm * ld * 2)); CHECK(hipMalloc(&b, (size_t)gn * ld * 2)); CHECK(hipMalloc(&c, (size_t)gm * gn * 4));
-        hipLaunchKernelGGL(fill_bf16_kernel, dim3(4096), dim3(256), 0, 0, a, gm * ld, 11ULL << 40);
-        hipLaunchKernelGGL(fill_bf16_kernel, dim3(4096), dim3(256), 0, 0, b, gn * ld, 12ULL << 40);
+        if (zeros) {
+            CHECK(hipMemset(a, 0, (size_t)gm * ld * 2));
+            CHECK(hipMemset(b, 0, (size_t)gn * ld * 2));
+        } else {
+            hipLaunchKernelGGL(fill_bf16_kernel, dim3(4096), dim3(256), 0, 0, a, gm * ld, 11ULL << 40);
+            hipLaunchKernelGGL(fill_bf16_kernel, dim3(4096), dim3(256), 0, 0, b, gn * ld, 12ULL << 40);
+        }
         CHECK(hipDeviceSynchronize());
         hipEvent_t e0, e1;
         CHECK(hipEventCreate(&e0)); CHECK(hipEventCreate(&e1));

@@ -141,3 +141,21 @@ def test_pool_step_rejects_bad_arguments_on_the_host():
     assert call(prev=0) == -1 and call(counts=0) == -1
     assert call(B=0) == -2 and call(seg=0) == -2 and call(mx=0) == -2
     assert call(B=1 << 20, mx=1 << 20) == -2          # offsets of the packed batch would not fit in int32
+
+
+def test_gemm_rejects_bad_arguments_on_the_host():
+    lib = ulorl.load_library()
+    vp = ctypes.c_void_p
+
+    def call(a=0x1000, lda=64, ldb=64, M=16, N=16, K=64, ldc=16):
+        return lib.ulorl_gemm_tn_bf16(vp(a), lda, vp(0x2000), ldb, M, N, K, vp(0x3000), ldc, None)
+    assert call(a=0) == -1
+    assert call(M=0) == -2 and call(K=60) == -2 and call(lda=32) == -2 and call(ldc=8) == -2
+    assert call(lda=(1 << 22) + 8) == -2 and call(ldb=(1 << 22) + 8) == -2   # 32-bit tile offsets
+    assert call(a=0x1008) == -4
+
+
+def test_lmhead_workspace_query_rejects_bad_shapes():
+    assert ulorl.lmhead_workspace_bytes(1024, 256, 4096, 2, 1024) > 0
+    assert ulorl.lmhead_workspace_bytes(0, 256, 4096, 2, 1024) == 0
+    assert ulorl.lmhead_workspace_bytes(1024, 256, 4096, 2, 1000) == 0     # chunk not a multiple of 64

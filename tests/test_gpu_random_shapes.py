@@ -77,3 +77,34 @@ def test_random_case(c):
     assert int(res.counters[3]) == 0                       # no status bits
     if stride > V:
         assert torch.isnan(buf[:, V:]).all()               # padding columns are never written
+
+
+def _lmhead_cases():
+    rs = np.random.RandomState(20250728)
+    out = []
+    for i in range(16):
+        hidden = 8 * int(rs.randint(1, 65)) if i % 4 else 64 * int(rs.randint(1, 9))   # K ragged or a multiple of the K tile
+        V = 8 * int(rs.randint(1, 700))
+        n_resp = int(rs.randint(1, 4))
+        lengths = [int(rs.randint(1, 260)) for _ in range(n_resp)]
+        out.append(dict(idx=i, hidden=hidden, V=V, lengths=lengths, chunk=64 * int(rs.randint(1, 40)),
+                        seg_len=int(rs.randint(1, 65)), tile=int(rs.choice([7, 7, 7, 8, 6, 4, 0])),
+                        is_mode=int(rs.choice([ulorl.IS_SAIS, ulorl.IS_POIS])),
+                        gate=int(rs.choice([ulorl.GATE_ALWAYS, ulorl.GATE_NEVER, ulorl.GATE_GLOBAL])),
+                        tau=float(rs.choice([0.02, 0.05, 0.5])), grad_out=float(rs.choice([1.0, -0.5, 2.0]))))
+    return out
+
+
+@pytest.mark.parametrize("c", _lmhead_cases(),
+                         ids=lambda c: "%02d_N%d_Hd%d_V%d_c%d_t%d" % (c["idx"], sum(c["lengths"]), c["hidden"], c["V"], c["chunk"], c["tile"]))
+def test_random_lmhead_case(c):
+    from parity import run_lmhead_parity
+    w = ui.shrink(ui.config(5), c["lengths"], V=c["V"], hidden=c["hidden"], seg_len=c["seg_len"],
+                  name="lmhead_sweep_%02d" % c["idx"])
+    p = params_for(w, is_mode=c["is_mode"], gate_mode=c["gate"], tau=c["tau"],
+                   sigma=1e9 if c["gate"] == ulorl.GATE_GLOBAL else w.sigma)
+    ulorl.tune(ulorl.TUNE_GEMM_TILE, c["tile"])
+    try:
+        run_lmhead_parity(w, p, chunk=c["chunk"], grad_out=c["grad_out"])
+    finally:
+        ulorl.tune(ulorl.TUNE_GEMM_TILE, 7)

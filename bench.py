@@ -36,8 +36,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 matrix rate
 # expressed as measured / algorithmic ratios.  They hold for the kernel source they were taken
 # on: the digest below is checked at run time and `traffic` is null once the kernels changed.
 PMC = {
-    "source_sha256": "295245182f3689001c47c21311c97ed94d778e2bb7b9acd472779a20dea12c08",
-    "fused_read": 1.0078,            # cluster_row_kernel: every row once, plus the polling of the exchange slots
+    "source_sha256": "12083f64a27dfde650091d9ebdc9e7abb53ba61ae9e11173d722277ea5540053",
+    "fused_read": 1.0077,            # cluster_row_kernel: every row once, plus the polling of the exchange slots
     "fused_write": 1.0014,
     "bwd_read": 1.0007,              # dlogits_chunk_kernel
     "bwd_write": 1.0000,

@@ -116,6 +116,7 @@ size_t ulorl_token_loss_workspace_bytes(int64_t N, int64_t V, int32_t R);
  *   logits        [N, V] row-major, element type dt, row t at logits + t*row_stride
  *                 elements; base and row_stride*sizeof(element) multiples of 16 bytes;
  *                 row_stride >= V.  V need not be a multiple of the vector width.
+ *                 1 <= N <= 32768 * 65535 rows, 1 <= V < 2^31.
  *   token_ids     [N] chosen token o_t of each row, in [0, V).
  *   cu_seqlens    [R+1] response boundaries, cu[0] = 0, cu[R] = N, non-decreasing.
  *   segment_ids   [N] segment id f(t) per token, or NULL (then p->seg_len rules).

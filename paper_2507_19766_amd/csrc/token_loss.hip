@@ -14,8 +14,12 @@
 //                         g_t == 0 are write-only.  Safe in place: each vector is read and then
 //                         written by the same thread.  (dlogits_kernel: the same by one looping
 //                         workgroup per row.)
-//   fused_row_kernel      forward and backward of a row by one workgroup, back to back, for the
-//                         one-call entry point.
+//   cluster_row_kernel    the one-call entry point: a row is split into pieces, one workgroup per
+//                         piece keeps its piece in registers, the pieces exchange their partial
+//                         (max, sum, weighted sum) through memory and each writes its share of
+//                         the gradient: every logit is read once and written once.
+//   fused_row_kernel      the same call by one workgroup per row, forward and backward back to
+//                         back (rows too long for the cooperative kernel, or on request).
 //
 // The HBM stream is the bound; the per-element VALU budget is what has to stay under it, so
 // the inner loops are: unpack, one FMA (scaled argument), one v_exp_f32, and two accumulate
@@ -41,6 +45,10 @@ namespace {
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kEmpty = -1.0e30f;  // "no element seen yet"; finite so that 0 * kEmpty == 0
+// Kernels with several workgroups per row lay the rows over grid dimensions y (up to
+// kRowsPerGridY) and z (up to 65535).
+constexpr int64_t kRowsPerGridY = 32768;
+constexpr int64_t kMaxRows = kRowsPerGridY * 65535;
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
@@ -377,7 +385,7 @@ __global__ __launch_bounds__(NT) void dlogits_kernel(const typename Tr::elem* lo
 // read-modify-write stream moves 6.5 TB/s this way against 5.1 TB/s when each workgroup loops
 // over a whole row (the concurrent writes then spread over thousands of rows), so the standalone
 // backward uses this shape; the fused kernel cannot (its row needs one owner for the reduction).
-// grid = (chunks per row, rows mod 32768, rows / 32768).
+// grid = (chunks per row, rows mod kRowsPerGridY, rows / kRowsPerGridY).
 template <class Tr>
 __global__ __launch_bounds__(256) void dlogits_chunk_kernel(const typename Tr::elem* logits, int64_t row_stride,
                                                             int32_t V, int64_t N,
@@ -388,7 +396,7 @@ __global__ __launch_bounds__(256) void dlogits_chunk_kernel(const typename Tr::e
                                                             const uint8_t* __restrict__ only)
 {
     constexpr int E = Tr::kPerVec;
-    const int64_t row = (int64_t)blockIdx.z * 32768 + blockIdx.y;
+    const int64_t row = (int64_t)blockIdx.z * kRowsPerGridY + blockIdx.y;
     if (row >= N) return;
     if (only != nullptr && only[row] == 0) return;
     const float g = gcoef[row] * grad_out;
@@ -783,9 +791,9 @@ __global__ __launch_bounds__(NT) void fused_row_kernel(const typename Tr::elem* 
 // (S >= 1 for a non-empty piece; the tag), so no ordering between memory locations and no cache
 // maintenance is needed.  Workgroups are dispatched in order of their linear id and a row's
 // pieces have consecutive ids, so the partners of a resident workgroup are resident or next in
-// line; the wait is nevertheless bounded (spin_limit polls, seconds by default): on expiry the row is given a zero
-// gradient, not-a-number statistics and the SYNC status bit.  Every workgroup of a row merges the
-// same pieces in the same order and therefore takes the same decisions.
+// line; the wait is nevertheless bounded (spin_limit polls, seconds by default): on expiry the row
+// is given a zero gradient, not-a-number statistics and the SYNC status bit.  Every workgroup of a
+// row merges the same pieces in the same order and therefore takes the same decisions.
 constexpr int kClusterThreads = 256;
 constexpr int kClusterMaxPieces = 64;         // one polled piece per lane of a wave
 
@@ -824,7 +832,7 @@ __global__ __launch_bounds__(kClusterThreads) void cluster_row_kernel(const type
     constexpr int P = NT * VPT;                 // vectors per piece
     const int c = blockIdx.x;
     const int C = a.C;
-    const int64_t row = (int64_t)blockIdx.z * 32768 + blockIdx.y;
+    const int64_t row = (int64_t)blockIdx.z * kRowsPerGridY + blockIdx.y;
     if (row >= a.N) return;
     const int tid = threadIdx.x;
     const typename Tr::elem* rowp = logits + row * row_stride;
@@ -1061,7 +1069,7 @@ __global__ void fill_zero_u64_kernel(unsigned long long* p, int64_t n, uint32_t*
 // ---------------------------------------------------------------------------------------------
 bool shape_ok(int64_t N, int64_t V, int64_t stride)
 {
-    return N > 0 && N <= 0x7fffffffLL && V > 0 && V <= 0x7fffffffLL && stride >= V;
+    return N > 0 && N <= kMaxRows && V > 0 && V <= 0x7fffffffLL && stride >= V;
 }
 
 int32_t check_logits(const void* logits, int32_t dt, int64_t N, int64_t V, int64_t stride)
@@ -1115,7 +1123,8 @@ bool dispatch_dlogits(int nt, int u, const void* logits, int64_t N, int64_t V, i
         const int64_t nvec = V / Tr::kPerVec;
         const int64_t chunks = nvec > 0 ? (nvec + 255) / 256 : 1;
         if (chunks <= 0x7fffffffLL) {
-            dim3 grid((unsigned)chunks, (unsigned)(N < 32768 ? N : 32768), (unsigned)((N + 32767) / 32768));
+            dim3 grid((unsigned)chunks, (unsigned)(N < kRowsPerGridY ? N : kRowsPerGridY),
+                      (unsigned)((N + kRowsPerGridY - 1) / kRowsPerGridY));
             hipLaunchKernelGGL((dlogits_chunk_kernel<Tr>), grid, dim3(256), 0, st, (const typename Tr::elem*)logits, stride,
                                (int32_t)V, N, y, lse, g, grad_out, (typename Tr::elem*)dz, only);
             return true;
@@ -1162,7 +1171,8 @@ bool launch_cluster(int vpt, const void* logits, int64_t N, int64_t V, int64_t s
 {
     // x: piece (fastest, so a row's pieces have consecutive linear ids and land on different XCDs:
     // putting a row's pieces on one XCD measured 15 % slower), y/z: row
-    dim3 grid((unsigned)a.C, (unsigned)(N < 32768 ? N : 32768), (unsigned)((N + 32767) / 32768));
+    dim3 grid((unsigned)a.C, (unsigned)(N < kRowsPerGridY ? N : kRowsPerGridY),
+                      (unsigned)((N + kRowsPerGridY - 1) / kRowsPerGridY));
 #define ULORL_CASE(VPT_)                                                                                       \
     if (vpt == VPT_) {                                                                                         \
         hipLaunchKernelGGL((cluster_row_kernel<Tr, VPT_>), grid, dim3(kClusterThreads), 0, st,                 \
@@ -1177,7 +1187,6 @@ bool launch_cluster(int vpt, const void* logits, int64_t N, int64_t V, int64_t s
 }  // namespace
 
 namespace ulorl_detail {
-
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -1286,7 +1295,7 @@ const char* ulorl_status_string(int32_t status)
 
 size_t ulorl_token_loss_workspace_bytes(int64_t N, int64_t V, int32_t R)
 {
-    if (N <= 0 || N > 0x7fffffffLL || V <= 0 || V > 0x7fffffffLL || R <= 0) return 0;
+    if (N <= 0 || N > kMaxRows || V <= 0 || V > 0x7fffffffLL || R <= 0) return 0;
     return workspace_layout(N, V, R).total;
 }
 

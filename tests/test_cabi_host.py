@@ -38,6 +38,7 @@ def test_workspace_query():
     assert ulorl.token_loss_workspace_bytes(0, 64, 1) == 0
     assert ulorl.token_loss_workspace_bytes(10, 64, 0) == 0
     assert ulorl.token_loss_workspace_bytes(10, 0, 1) == 0
+    assert ulorl.token_loss_workspace_bytes(32768 * 65535 + 1, 64, 1) == 0
     a = ulorl.token_loss_workspace_bytes(131072, 4096, 1)
     b = ulorl.token_loss_workspace_bytes(131072, 4096, 1024)
     assert 0 < a < b < 4 << 20 and a % 256 == 0
@@ -71,6 +72,7 @@ def test_forward_rejects_bad_arguments_on_the_host():
     assert _fwd(lib, N=0) == -2 and _fwd(lib, V=0) == -2 and _fwd(lib, stride=63) == -2
     assert _fwd(lib, R=0) == -2
     assert _fwd(lib, N=1 << 31) == -2
+    assert _fwd(lib, N=32768 * 65535 + 1) == -2                      # more rows than the launch grids hold
     assert _fwd(lib, dt=2) == -3
     assert _fwd(lib, logits=0x1008) == -4
     assert _fwd(lib, V=60, stride=60) == -4                          # bf16 row of 120 bytes
@@ -93,7 +95,7 @@ def test_backward_rejects_bad_arguments_on_the_host():
                                         vp(dz), None)
     assert bwd(logits=0) == -1 and bwd(y=0) == -1 and bwd(lse=0) == -1 and bwd(g=0) == -1
     assert bwd(dz=0) == -1
-    assert bwd(N=-1) == -2 and bwd(stride=8) == -2
+    assert bwd(N=-1) == -2 and bwd(stride=8) == -2 and bwd(N=32768 * 65535 + 1) == -2
     assert bwd(dt=7) == -3
     assert bwd(dz=0x5004) == -4 and bwd(logits=0x1002) == -4
 

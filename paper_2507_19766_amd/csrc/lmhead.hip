@@ -625,10 +625,9 @@ struct StatQuad {
 
 template <class Cfg>
 __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(Cfg::WAVES_PER_SIMD, Cfg::WAVES_PER_SIMD)))
-void lmhead_stats_kernel(const bf16_t* __restrict__ Wt, const bf16_t* __restrict__ H,
-                                                               int Hd, int V, int Ntok,
-                                                               const int32_t* __restrict__ token_ids, int v_per_split,
-                                                               int splits, StatQuad* __restrict__ partial)
+void lmhead_stats_kernel(const bf16_t* __restrict__ Wt, const bf16_t* __restrict__ H, int Hd, int V, int Ntok,
+                         const int32_t* __restrict__ token_ids, int v_per_split, int splits,
+                         StatQuad* __restrict__ partial)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     bf16_t* lds = reinterpret_cast<bf16_t*>(lds_raw);
@@ -753,13 +752,10 @@ __global__ void lmhead_stats_merge_kernel(const StatQuad* __restrict__ partial, 
 // ---------------------------------------------------------------------------------------------
 template <class Cfg>
 __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(Cfg::WAVES_PER_SIMD, Cfg::WAVES_PER_SIMD)))
-void lmhead_dz_kernel(const bf16_t* __restrict__ Wt, const bf16_t* __restrict__ H,
-                                                            int Hd, int V, int Ntok, int vc0, int cw,
-                                                            const int32_t* __restrict__ token_ids,
-                                                            const float* __restrict__ lse,
-                                                            const float* __restrict__ gcoef, float grad_out,
-                                                            bf16_t* __restrict__ dZc, int64_t ld_c,
-                                                            bf16_t* __restrict__ dZcT, int64_t ld_t)
+void lmhead_dz_kernel(const bf16_t* __restrict__ Wt, const bf16_t* __restrict__ H, int Hd, int V, int Ntok, int vc0,
+                      int cw, const int32_t* __restrict__ token_ids, const float* __restrict__ lse,
+                      const float* __restrict__ gcoef, float grad_out, bf16_t* __restrict__ dZc, int64_t ld_c,
+                      bf16_t* __restrict__ dZcT, int64_t ld_t)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     bf16_t* lds = reinterpret_cast<bf16_t*>(lds_raw);
@@ -890,12 +886,12 @@ using Tile8 = GemmCfg<256, 256, 64, 2, 2, true>;   // as 2, direct (four waves, 
 #define ULORL_FOR_TILE(choice, ...)                          \
     switch (choice) {                                        \
     case 0: { using Cfg = Tile0; __VA_ARGS__; } break;       \
+    case 1: { using Cfg = Tile1; __VA_ARGS__; } break;       \
     case 2: { using Cfg = Tile2; __VA_ARGS__; } break;       \
     case 3: { using Cfg = Tile3; __VA_ARGS__; } break;       \
     case 4: { using Cfg = Tile4; __VA_ARGS__; } break;       \
-    case 6: { using Cfg = Tile6; __VA_ARGS__; } break;       \
-    case 1: { using Cfg = Tile1; __VA_ARGS__; } break;       \
     case 5: { using Cfg = Tile5; __VA_ARGS__; } break;       \
+    case 6: { using Cfg = Tile6; __VA_ARGS__; } break;       \
     case 8: { using Cfg = Tile8; __VA_ARGS__; } break;       \
     default: { using Cfg = Tile7; __VA_ARGS__; } break;      \
     }

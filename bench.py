@@ -36,7 +36,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 matrix rate
 # expressed as measured / algorithmic ratios.  They hold for the kernel source they were taken
 # on: the digest below is checked at run time and `traffic` is null once the kernels changed.
 PMC = {
-    "source_sha256": "12083f64a27dfde650091d9ebdc9e7abb53ba61ae9e11173d722277ea5540053",
+    "source_sha256": "a8df7173f54df06f70baaaf095a3ae2d4c073c80dc9123a277274cdc8b29946b",
     "fused_read": 1.0077,            # cluster_row_kernel: every row once, plus the polling of the exchange slots
     "fused_write": 1.0014,
     "bwd_read": 1.0007,              # dlogits_chunk_kernel
@@ -306,7 +306,7 @@ def main():
     roof_bwd = {"bound": "hbm", "kernel": "dlogits_chunk_kernel (backward call of the two-call path)",
                 "achieved": bwd_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": bwd_gbs / HBM_PEAK_GBS,
                 "traffic": bwd_traffic, "algorithmic_bytes_per_launch": bwd_bytes, "avg_launch_ms": bwd_ms / K}
-    roof_fwd = {"bound": "hbm", "kernel": "row_stats_kernel + O(N) epilogue (forward call of the two-call path)",
+    roof_fwd = {"bound": "hbm", "kernel": "piece_stats_kernel + merge + O(N) epilogue (forward call of the two-call path)",
                 "achieved": fwd_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": fwd_gbs / HBM_PEAK_GBS,
                 "algorithmic_bytes_per_launch": fwd_bytes, "avg_call_ms": fwd_ms / K}
 

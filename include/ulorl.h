@@ -105,8 +105,8 @@ const char *ulorl_status_string(int32_t status);
 
 /* Bytes of device workspace ulorl_token_loss_fwd / _fwd_bwd need for N rows of V logits
  * in R responses (0 if an argument is out of range).  The workspace holds per-response
- * entropy sums, per-block partial sums, one flag byte per row and, for the one-call path,
- * 16 bytes per row and per 61440 bytes of the row; its contents need not be preserved
+ * entropy sums, per-block partial sums, one flag byte per row and 16 bytes per row and
+ * per piece of the row (61440 bytes of a long row); its contents need not be preserved
  * between calls.                                                                    */
 size_t ulorl_token_loss_workspace_bytes(int64_t N, int64_t V, int32_t R);
 
@@ -143,8 +143,10 @@ size_t ulorl_token_loss_workspace_bytes(int64_t N, int64_t V, int32_t R);
  *   resp_gate     [R] uint8  1 if MPTs of response i are masked
  *   counters      [4] int64: masked tokens, tokens on the clipped (gradient-free) branch,
  *                 positive tokens, status word (ULORL_STATUS_* bits)
- *   workspace     >= ulorl_token_loss_workspace_bytes(N, R) bytes, 256-byte aligned; not
- *                 needed (may be NULL) for the stats-only pass.
+ *   workspace     >= ulorl_token_loss_workspace_bytes(N, V, R) bytes, 256-byte aligned.  The
+ *                 stats-only pass works without one (NULL); given one (sized with any R >= 1)
+ *                 it forms the statistics by pieces of rows, which is faster and gives the
+ *                 same bits as ulorl_token_loss_fwd_bwd.
  */
 int32_t ulorl_token_loss_fwd(
     const void *logits, int32_t dt, int64_t N, int64_t V, int64_t row_stride,
@@ -180,10 +182,12 @@ int32_t ulorl_token_loss_bwd(
  * per row instead of two reads and a write.  A row's gradient can be formed at once unless it
  * waits for the entropy gate of Sec. 3.2.2: under the PER_RESPONSE and GLOBAL gates the members
  * of the MPT set (A_t > 0, p_t >= tau) are finished by a second, filtered backward launch after
- * the gate is known.  Results agree with ulorl_token_loss_fwd followed by ulorl_token_loss_bwd
- * to rounding (the row sums are formed in a different order); they are bit-identical when
- * ulorl_tune(ULORL_TUNE_FUSED_CLUSTER, 0) selects the older one-workgroup-per-row kernel (whose
- * second read of a row is served by the on-chip caches) with the forward kernel's launch shape.
+ * the gate is known.  Results are bit-identical with ulorl_token_loss_fwd (given a workspace)
+ * followed by ulorl_token_loss_bwd: both form a row's statistics from the same pieces in the same
+ * order.  ulorl_tune(ULORL_TUNE_FUSED_CLUSTER, 0) selects the older one-workgroup-per-row kernel
+ * (whose second read of a row is served by the on-chip caches); its results are bit-identical
+ * with the forward call under ULORL_TUNE_FWD_PIECES = 0 and equal launch shapes, and differ from
+ * the piece-wise kernels by rounding only.
  * The workgroups of a row wait for each other with a bounded wait: see ULORL_STATUS_SYNC.
  */
 int32_t ulorl_token_loss_fwd_bwd(
@@ -347,6 +351,10 @@ typedef enum {
                                      0: one looping workgroup per row (BWD_THREADS / BWD_UNROLL apply) */
     ULORL_TUNE_FUSED_CLUSTER = 8, /* 1 (default): one-call path by row-cooperative workgroups;
                                      0: one looping workgroup per row (FUSED_THREADS / FUSED_UNROLL apply) */
+    ULORL_TUNE_FWD_PIECES = 11,   /* 1 (default): ulorl_token_loss_fwd forms the row statistics by the pieces
+                                     of the row-cooperative kernel (same bits as the one-call path) when
+                                     a workspace is given; 0: one looping workgroup per row
+                                     (FWD_THREADS / FWD_UNROLL apply) */
     ULORL_TUNE_SYNC_SPINS = 10,   /* polls (about 0.25 us each) a row-cooperative workgroup waits for its
                                      partners before it gives the row up (ULORL_STATUS_SYNC); >= 1,
                                      default 2^24.  A tiny value lets a test exercise that path. */

@@ -19,6 +19,7 @@ GATE_PER_RESPONSE, GATE_GLOBAL, GATE_ALWAYS, GATE_NEVER = 0, 1, 2, 3
 STATUS_BAD_TOKEN, STATUS_NONFINITE, STATUS_BAD_CU, STATUS_SYNC = 1, 2, 4, 8
 TUNE_FWD_THREADS, TUNE_FWD_UNROLL, TUNE_BWD_THREADS, TUNE_BWD_UNROLL = 0, 1, 2, 3
 TUNE_FUSED_THREADS, TUNE_FUSED_UNROLL, TUNE_GEMM_TILE, TUNE_BWD_ONESHOT, TUNE_FUSED_CLUSTER, TUNE_FUSED_VPT, TUNE_SYNC_SPINS = 4, 5, 6, 7, 8, 9, 10
+TUNE_FWD_PIECES = 11
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 
@@ -243,10 +244,13 @@ def token_loss_fwd(logits, token_ids, cu_seqlens, advantages, old_logp=None, par
         f32 = dict(dtype=torch.float32, device=dev)
         if out is None:
             out = FwdResult(None, torch.empty(N, **f32), torch.empty(N, **f32), torch.empty(N, **f32))
+        if workspace is None:                    # optional here; with it the statistics are formed by pieces
+            workspace = torch.empty(token_loss_workspace_bytes(N, V, 1), dtype=torch.uint8, device=dev)
+        ws_bytes = workspace.numel() * workspace.element_size()
         rc = lib.ulorl_token_loss_fwd(
             _p(logits), dt, N, V, stride, _p(token_ids), None, 0, None, None, None, None,
             None, _p(out.logp), _p(out.entropy), _p(out.lse), None, None, None, None, None, None, None,
-            None, 0, _stream(dev))
+            _p(workspace), ws_bytes, _stream(dev))
         if rc != 0:
             raise UlorlError(rc, "ulorl_token_loss_fwd")
         return out

@@ -5,6 +5,10 @@
 //                         loads and keeps a per-lane online (max, sum-exp, sum-exp*z) triple in
 //                         registers; lanes are merged with wave shuffles, waves through LDS.
 //                         -> lse, chosen-token log-prob (Eq. 6 numerator), entropy (Sec. 3.2.2).
+//   piece_stats_kernel, piece_merge_kernel
+//                         the same statistics from the pieces of cluster_row_kernel (below), used
+//                         by the forward call whenever it has a workspace: both paths then carry
+//                         the same bits.
 //   response_entropy_kernel, token_terms_kernel, loss_finalize_kernel
 //                         O(N) epilogue: per-response mean entropy and gate, SAIS/POIS ratio
 //                         (Sec. 3.1.2), clipped term (Eq. 7), MPT mask (Eq. MPTS / I_msk), the
@@ -813,6 +817,109 @@ __device__ __forceinline__ void absorb_vectors(const u32x4 (&v)[VPT], LaneAcc& a
     }
 }
 
+// Phase 1 of a piece: its vectors into registers (v) and its (max, sum, weighted sum), merged over
+// the workgroup; the result is valid on thread 0 after the barrier this function ends with.
+template <class Tr, int VPT>
+__device__ __forceinline__ void piece_statistics(const u32x4* vp, const typename Tr::elem* rowp, int nvec, int32_t V,
+                                                 int first, bool full, bool owns_tail, u32x4 (&v)[VPT],
+                                                 float* sm, float* sS, float* sT, float& m, float& S, float& T)
+{
+    constexpr int NT = kClusterThreads;
+    constexpr int E = Tr::kPerVec;
+    const int tid = threadIdx.x;
+    LaneAcc acc = {kEmpty, kEmpty * kLog2e, 0.0f, 0.0f, 0.0f};
+    if (full) {
+        const char* const piece_in = reinterpret_cast<const char*>(vp + first);
+#pragma unroll
+        for (int k = 0; k < VPT; ++k)
+            v[k] = load_stream(reinterpret_cast<const u32x4*>(piece_in + (size_t)k * NT * 16 + (uint32_t)tid * 16u));
+        absorb_vectors<Tr, VPT, 0>(v, acc);
+    } else if (nvec - first >= NT) {
+        // A row's last piece: every thread holds at least one vector.  Missing vectors are
+        // replaced by a very negative finite filler, whose terms are exactly zero once the lane's
+        // maximum is a real logit (guaranteed: the thread's first vector is real), so the piece
+        // takes the same grouped arithmetic as a full one.
+        const u32x4 filler = Tr::filler();
+#pragma unroll
+        for (int k = 0; k < VPT; ++k) {
+            const int i = first + k * NT + tid;
+            v[k] = filler;
+            if (i < nvec) v[k] = load_stream(vp + i);
+        }
+        absorb_vectors<Tr, VPT, 0>(v, acc);
+    } else {
+#pragma unroll
+        for (int k = 0; k < VPT; ++k) {
+            const int i = first + k * NT + tid;
+            if (i < nvec) {
+                v[k] = load_stream(vp + i);
+                float f[E];
+                Tr::unpack(v[k], f);
+                absorb<E>(f, acc);
+            }
+        }
+    }
+    if (owns_tail) {
+        for (int j = nvec * E; j < V; ++j) {
+            float f = Tr::load1(rowp + j);
+            absorb<1>(&f, acc);
+        }
+    }
+    const float delta = fmaf(acc.m, kLog2e, -acc.mL);
+    const float un = fast_exp2(-delta);
+    m = acc.m;
+    S = un * (acc.S + acc.Sc);
+    T = un * fmaf(-delta, acc.S, acc.T);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const float m2 = __shfl_xor(m, off);
+        const float S2 = __shfl_xor(S, off);
+        const float T2 = __shfl_xor(T, off);
+        merge(m, S, T, m2, S2, T2);
+    }
+    if ((tid & 63) == 0) {
+        sm[tid >> 6] = m;
+        sS[tid >> 6] = S;
+        sT[tid >> 6] = T;
+    }
+    __syncthreads();
+    if (tid == 0) {
+#pragma unroll
+        for (int w = 1; w < NT / 64; ++w) merge(m, S, T, sm[w], sS[w], sT[w]);
+    }
+}
+
+// The two words a piece publishes: {m, S} and {T, tag 1}.
+__device__ __forceinline__ unsigned long long piece_word0(float m, float S)
+{
+    return ((unsigned long long)__float_as_uint(S) << 32) | __float_as_uint(m);
+}
+__device__ __forceinline__ unsigned long long piece_word1(float T) { return (1ull << 32) | __float_as_uint(T); }
+
+// Merge of a row's pieces by one wave: lane c < C brings piece c, the other lanes nothing; a fixed
+// xor-shuffle tree, so every wave that merges the same pieces gets the same bits.
+__device__ __forceinline__ void merge_pieces_tree(float& pm, float& pS, float& pT)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const float m2 = __shfl_xor(pm, off);
+        const float S2 = __shfl_xor(pS, off);
+        const float T2 = __shfl_xor(pT, off);
+        merge(pm, pS, pT, m2, S2, T2);
+    }
+}
+
+// lse, chosen-token log-prob and entropy of a row from its merged pieces (T in log2 units).
+__device__ __forceinline__ void finish_pieces(float pm, float pS, float pT, bool has_y, float zy, float& lse, float& lp,
+                                              float& ent)
+{
+    const float lnS = logf(pS);
+    lp = __builtin_nanf("");
+    if (has_y) lp = (zy - pm) - lnS;
+    lse = pm + lnS;
+    ent = lnS - (pT * kLn2) / pS;
+}
+
 struct ClusterArgs {
     FusedArgs f;
     unsigned long long* slots;   // [N * C * 2]
@@ -854,79 +961,21 @@ __global__ __launch_bounds__(kClusterThreads) void cluster_row_kernel(const type
     float zy = 0.0f;
     if (tid == 0 && y >= 0 && y < V) zy = Tr::load1(rowp + y);
 
-    // ---- phase 1: the piece into registers, its statistics
+    // ---- phase 1: the piece into registers, its statistics (valid on thread 0)
     u32x4 v[VPT];
-    LaneAcc acc = {kEmpty, kEmpty * kLog2e, 0.0f, 0.0f, 0.0f};
-    if (full) {
-        const char* const piece_in = reinterpret_cast<const char*>(vp + first);
-#pragma unroll
-        for (int k = 0; k < VPT; ++k)
-            v[k] = load_stream(reinterpret_cast<const u32x4*>(piece_in + (size_t)k * NT * 16 + (uint32_t)tid * 16u));
-        absorb_vectors<Tr, VPT, 0>(v, acc);
-    } else if (nvec - first >= NT) {
-        // A row's last piece: every thread holds at least one vector.  Missing vectors are
-        // replaced by a very negative finite filler, whose terms are exactly zero once the lane's
-        // maximum is a real logit (guaranteed: the thread's first vector is real), so the piece
-        // takes the same grouped arithmetic as a full one.
-        const u32x4 filler = Tr::filler();
-#pragma unroll
-        for (int k = 0; k < VPT; ++k) {
-            const int i = first + k * NT + tid;
-            v[k] = filler;
-            if (i < nvec) v[k] = load_stream(vp + i);
-        }
-        absorb_vectors<Tr, VPT, 0>(v, acc);
-    } else {
-#pragma unroll
-        for (int k = 0; k < VPT; ++k) {
-            const int i = first + k * NT + tid;
-            if (i < nvec) {
-                v[k] = load_stream(vp + i);
-                float f[E];
-                Tr::unpack(v[k], f);
-                absorb<E>(f, acc);
-            }
-        }
-    }
-    if (owns_tail) {
-        for (int j = nvec * E; j < V; ++j) {
-            float f = Tr::load1(rowp + j);
-            absorb<1>(&f, acc);
-        }
-    }
-    const float delta = fmaf(acc.m, kLog2e, -acc.mL);
-    const float un = fast_exp2(-delta);
-    float m = acc.m;
-    float S = un * (acc.S + acc.Sc);
-    float T = un * fmaf(-delta, acc.S, acc.T);
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        const float m2 = __shfl_xor(m, off);
-        const float S2 = __shfl_xor(S, off);
-        const float T2 = __shfl_xor(T, off);
-        merge(m, S, T, m2, S2, T2);
-    }
     __shared__ float sm[NT / 64], sS[NT / 64], sT[NT / 64];
     __shared__ float bc_g, bc_l;
     __shared__ int bc_mode;      // 0: write zeros, 1: write gradient, 2: deferred (leave the row alone)
-    if ((tid & 63) == 0) {
-        sm[tid >> 6] = m;
-        sS[tid >> 6] = S;
-        sT[tid >> 6] = T;
-    }
-    __syncthreads();
+    float m, S, T;
+    piece_statistics<Tr, VPT>(vp, rowp, nvec, V, first, full, owns_tail, v, sm, sS, sT, m, S, T);
 
     // ---- exchange (first wave)
     if (tid < 64) {
         unsigned long long* slot = a.slots + (row * C) * 2;
         if (tid == 0) {
-#pragma unroll
-            for (int w = 1; w < NT / 64; ++w) merge(m, S, T, sm[w], sS[w], sT[w]);
             __builtin_amdgcn_s_waitcnt(0);      // every load of this thread, the chosen logit included, has returned
-            const unsigned long long w0 = ((unsigned long long)__float_as_uint(S) << 32) | __float_as_uint(m);
-            const unsigned long long w1 = (1ull << 32) | __float_as_uint(T);
-            __hip_atomic_store(slot + 2 * c, w0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(slot + 2 * c + 1, w1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(slot + 2 * c, piece_word0(m, S), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(slot + 2 * c + 1, piece_word1(T), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         float pm = kEmpty, pS = 0.0f, pT = 0.0f;
         int expired = 0;
@@ -947,19 +996,10 @@ __global__ __launch_bounds__(kClusterThreads) void cluster_row_kernel(const type
             }
         }
         expired = __any(expired);
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) {
-            const float m2 = __shfl_xor(pm, off);
-            const float S2 = __shfl_xor(pS, off);
-            const float T2 = __shfl_xor(pT, off);
-            merge(pm, pS, pT, m2, S2, T2);
-        }
+        merge_pieces_tree(pm, pS, pT);
         if (tid == 0) {
-            const float lnS = logf(pS);
-            float lp = __builtin_nanf("");
-            if (y >= 0 && y < V) lp = (zy - pm) - lnS;
-            float lse = pm + lnS;
-            float ent = lnS - (pT * kLn2) / pS;
+            float lse, lp, ent;
+            finish_pieces(pm, pS, pT, y >= 0 && y < V, zy, lse, lp, ent);
             if (expired) {
                 lse = lp = ent = __builtin_nanf("");
                 *a.sync_fail = 1u;
@@ -1065,6 +1105,73 @@ __global__ void fill_zero_u64_kernel(unsigned long long* p, int64_t n, uint32_t*
 }
 
 // ---------------------------------------------------------------------------------------------
+// forward call by pieces: the statistics half of the row-cooperative kernel
+// ---------------------------------------------------------------------------------------------
+// The same pieces, the same per-piece arithmetic and the same merge tree as cluster_row_kernel, so
+// lse, log-prob and entropy (and every decision taken from them) carry the same bits on both paths.
+// No waiting here: a second kernel merges the pieces.  Consecutive workgroups read consecutive
+// 61 KB pieces, the access pattern HBM serves best.
+template <class Tr, int VPT>
+__global__ __launch_bounds__(kClusterThreads) void piece_stats_kernel(const typename Tr::elem* logits, int64_t row_stride,
+                                                                      int32_t V, int64_t N, int32_t C,
+                                                                      unsigned long long* slots)
+{
+    constexpr int NT = kClusterThreads;
+    constexpr int E = Tr::kPerVec;
+    constexpr int P = NT * VPT;
+    const int c = blockIdx.x;
+    const int64_t row = (int64_t)blockIdx.z * kRowsPerGridY + blockIdx.y;
+    if (row >= N) return;
+    const int tid = threadIdx.x;
+    const typename Tr::elem* rowp = logits + row * row_stride;
+    const u32x4* vp = reinterpret_cast<const u32x4*>(rowp);
+    const int nvec = V / E;
+    const int first = c * P;
+    const bool full = first + P <= nvec;
+    const bool owns_tail = (c == C - 1) && (tid == NT - 1) && (nvec * E < V);
+    u32x4 v[VPT];
+    __shared__ float sm[NT / 64], sS[NT / 64], sT[NT / 64];
+    float m, S, T;
+    piece_statistics<Tr, VPT>(vp, rowp, nvec, V, first, full, owns_tail, v, sm, sS, sT, m, S, T);
+    if (tid == 0) {
+        unsigned long long* slot = slots + (row * C + c) * 2;
+        slot[0] = piece_word0(m, S);
+        slot[1] = piece_word1(T);
+    }
+}
+
+// One wave per row: lane c brings piece c, the tree merges them, lane 0 finishes the row.
+template <class Tr>
+__global__ __launch_bounds__(256) void piece_merge_kernel(const typename Tr::elem* logits, int64_t row_stride, int32_t V,
+                                                          int64_t N, int32_t C, const unsigned long long* slots,
+                                                          const int32_t* __restrict__ token_ids,
+                                                          float* __restrict__ lse_out, float* __restrict__ logp_out,
+                                                          float* __restrict__ ent_out)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= N) return;
+    float pm = kEmpty, pS = 0.0f, pT = 0.0f;
+    if (lane < C) {
+        const unsigned long long w0 = slots[(row * C + lane) * 2], w1 = slots[(row * C + lane) * 2 + 1];
+        pm = __uint_as_float((uint32_t)w0);
+        pS = __uint_as_float((uint32_t)(w0 >> 32));
+        pT = __uint_as_float((uint32_t)w1);
+    }
+    merge_pieces_tree(pm, pS, pT);
+    if (lane == 0) {
+        const int32_t y = token_ids[row];
+        const bool has_y = y >= 0 && y < V;
+        const float zy = has_y ? Tr::load1(logits + row * row_stride + y) : 0.0f;
+        float lse, lp, ent;
+        finish_pieces(pm, pS, pT, has_y, zy, lse, lp, ent);
+        lse_out[row] = lse;
+        logp_out[row] = lp;
+        ent_out[row] = ent;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
 bool shape_ok(int64_t N, int64_t V, int64_t stride)
@@ -1166,6 +1273,28 @@ bool dispatch_fused(int nt, int u, const void* logits, int64_t N, int64_t V, int
 }
 
 template <class Tr>
+bool launch_piece_stats(const ClusterShape& shape, const void* logits, int64_t N, int64_t V, int64_t stride,
+                        const int32_t* y, float* lse, float* logp, float* ent, unsigned long long* slots, hipStream_t st)
+{
+    dim3 grid((unsigned)shape.pieces, (unsigned)(N < kRowsPerGridY ? N : kRowsPerGridY),
+              (unsigned)((N + kRowsPerGridY - 1) / kRowsPerGridY));
+    bool launched = false;
+#define ULORL_CASE(VPT_)                                                                                        \
+    if (shape.vpt == VPT_) {                                                                                    \
+        hipLaunchKernelGGL((piece_stats_kernel<Tr, VPT_>), grid, dim3(kClusterThreads), 0, st,                  \
+                           (const typename Tr::elem*)logits, stride, (int32_t)V, N, (int32_t)shape.pieces, slots); \
+        launched = true;                                                                                        \
+    }
+    ULORL_CASE(4) ULORL_CASE(8) ULORL_CASE(10) ULORL_CASE(12) ULORL_CASE(15)
+#undef ULORL_CASE
+    if (!launched) return false;
+    hipLaunchKernelGGL((piece_merge_kernel<Tr>), dim3((unsigned)((N + 3) / 4)), dim3(256), 0, st,
+                       (const typename Tr::elem*)logits, stride, (int32_t)V, N, (int32_t)shape.pieces, slots, y, lse, logp,
+                       ent);
+    return true;
+}
+
+template <class Tr>
 bool launch_cluster(int vpt, const void* logits, int64_t N, int64_t V, int64_t stride, void* dz, const ClusterArgs& a,
                     hipStream_t st)
 {
@@ -1213,7 +1342,7 @@ WorkspaceLayout workspace_layout(int64_t N, int64_t V, int32_t R)
     const ClusterShape a = cluster_shape(V, ULORL_F32), b = cluster_shape(V, ULORL_BF16);
     const int pieces = V > 0 ? (a.pieces > b.pieces ? a.pieces : b.pieces) : 0;
     size_t off = 0;
-    w.slots = off;    off = align_up(off + sizeof(unsigned long long) * 2 * (size_t)N * (size_t)pieces, 256);
+    w.slots = off;    off = align_up(off + sizeof(unsigned long long) * 2 * (size_t)N * (size_t)pieces, 256);   // first: see ulorl_token_loss_fwd
     w.syncfail = off; off = align_up(off + sizeof(uint32_t), 256);
     w.hsum = off;     off = align_up(off + sizeof(double) * (size_t)R, 256);
     w.rflags = off;   off = align_up(off + sizeof(uint32_t) * (size_t)R, 256);
@@ -1321,11 +1450,25 @@ int32_t ulorl_token_loss_fwd(const void* logits, int32_t dt, int64_t N, int64_t 
     }
     hipStream_t st = (hipStream_t)hip_stream;
 
-    bool ok = dt == ULORL_BF16
-                  ? dispatch_row_stats<StoreBF16>(tuning().fwd_threads, tuning().fwd_unroll, logits, N, V, row_stride,
-                                                  token_ids, lse, logp, entropy, st)
-                  : dispatch_row_stats<StoreF32>(tuning().fwd_threads, tuning().fwd_unroll, logits, N, V, row_stride,
-                                                 token_ids, lse, logp, entropy, st);
+    // Statistics by pieces (the row-cooperative kernel's first half, bit-identical with it) when the
+    // caller gave a workspace that holds the pieces' slots; else one looping workgroup per row.
+    const ClusterShape shape = cluster_shape(V, dt);
+    const size_t slot_bytes = sizeof(unsigned long long) * 2 * (size_t)N * (size_t)(shape.pieces > 0 ? shape.pieces : 0);
+    const bool by_pieces = tuning().fwd_pieces && shape.pieces > 0 && workspace != nullptr &&
+                           ((uintptr_t)workspace & 255u) == 0 && workspace_bytes >= slot_bytes;
+    bool ok;
+    if (by_pieces) {
+        unsigned long long* slots = (unsigned long long*)workspace;    // the layout's first region
+        ok = dt == ULORL_BF16
+                 ? launch_piece_stats<StoreBF16>(shape, logits, N, V, row_stride, token_ids, lse, logp, entropy, slots, st)
+                 : launch_piece_stats<StoreF32>(shape, logits, N, V, row_stride, token_ids, lse, logp, entropy, slots, st);
+    } else {
+        ok = dt == ULORL_BF16
+                 ? dispatch_row_stats<StoreBF16>(tuning().fwd_threads, tuning().fwd_unroll, logits, N, V, row_stride,
+                                                 token_ids, lse, logp, entropy, st)
+                 : dispatch_row_stats<StoreF32>(tuning().fwd_threads, tuning().fwd_unroll, logits, N, V, row_stride,
+                                                token_ids, lse, logp, entropy, st);
+    }
     if (!ok || hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;
     if (stats_only) return ULORL_OK;
 

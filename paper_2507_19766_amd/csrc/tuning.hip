@@ -23,6 +23,7 @@ extern "C" int32_t ulorl_tune(int32_t knob, int32_t value)
     case ULORL_TUNE_FUSED_UNROLL:  if (!unroll_ok) return ULORL_ERR_PARAM;  t.fused_unroll = value;  return ULORL_OK;
     case ULORL_TUNE_BWD_ONESHOT: if (value != 0 && value != 1) return ULORL_ERR_PARAM; t.bwd_oneshot = value; return ULORL_OK;
     case ULORL_TUNE_FUSED_CLUSTER: if (value != 0 && value != 1) return ULORL_ERR_PARAM; t.fused_cluster = value; return ULORL_OK;
+    case ULORL_TUNE_FWD_PIECES: if (value != 0 && value != 1) return ULORL_ERR_PARAM; t.fwd_pieces = value; return ULORL_OK;
     case ULORL_TUNE_FUSED_VPT:
         if (value != 0 && value != 4 && value != 8 && value != 10 && value != 12 && value != 15) return ULORL_ERR_PARAM;
         t.fused_vpt = value;

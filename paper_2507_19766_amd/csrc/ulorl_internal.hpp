@@ -69,9 +69,10 @@ void launch_token_epilogue(const TokenArgs& a, const WorkspaceLayout& wl, float*
                            hipStream_t st);
 
 // Launch shapes, set with ulorl_tune().  Defaults from sweeps on 131072 x 151936 bf16 (logits
-// path) and 32768 x 2048 x 151936 (lm_head variant).  The forward and the fused kernel share one
-// shape so that their row statistics are bit-identical (the backward is elementwise, its shape
-// does not change results).
+// path) and 32768 x 2048 x 151936 (lm_head variant).  The one-workgroup-per-row forward and fused
+// kernels share one shape so that their row statistics are bit-identical, and so do the piece-wise
+// forward and the row-cooperative kernel (the backward is elementwise, its shape does not change
+// results).
 struct Tuning {
     int fwd_threads = 512, fwd_unroll = 8;
     int bwd_threads = 256, bwd_unroll = 4;
@@ -79,6 +80,7 @@ struct Tuning {
     int gemm_tile = 7;     // index into the compiled-in GEMM tile shapes
     int bwd_oneshot = 1;   // standalone backward by one-shot 4 KB workgroups (0: one looping workgroup per row)
     int fused_cluster = 1; // one-call path by row-cooperative workgroups (0: one looping workgroup per row)
+    int fwd_pieces = 1;    // forward statistics by pieces when a workspace is given (0: one looping workgroup per row)
     int fused_vpt = 0;     // 16-byte vectors per thread of the row-cooperative kernel (0: chosen from V)
     int sync_spins = 1 << 24;  // polls before a workgroup of the row-cooperative kernel gives up on its partners
 };

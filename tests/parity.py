@@ -129,10 +129,11 @@ def near_discontinuity(o_logp, tt, p: ulorl.Params):
 
 
 def run_full_parity(w: ui.Workload, p: ulorl.Params, dz_rows=None, inplace=False, data=None,
-                    grad_out=1.0):
+                    grad_out=1.0, same_bits=True):
     """Whole path on the GPU vs whole oracle on the host, every row: the two-call path, then (when
     the logits survive, i.e. not in place) the one-call path in both of its kernels.
-    Returns (res, tt, info)."""
+    ``same_bits``: the two-call forward runs by pieces (the library's default), so the two paths
+    must agree bit for bit.  Returns (res, tt, info)."""
     dev = torch.device("cuda:0")
     d = data if data is not None else ui.generate(w, dev)
     logits = d["logits"]
@@ -158,13 +159,17 @@ def run_full_parity(w: ui.Workload, p: ulorl.Params, dz_rows=None, inplace=False
         check_dlogits(name, dz_tensor[sel], ref[keep], grad_out * tt.gcoef[rows][keep], w.dtype, rtol)
 
     pristine = None if inplace else logits
+    dz1 = None
     if not inplace:     # the one-call path first, while the logits are intact
-        check_one_call_path(d, p, res, o_lse, o_logp, o_H, tt, rtol, compare_dz, grad_out=grad_out)
+        dz1 = check_one_call_path(d, p, res, o_lse, o_logp, o_H, tt, rtol, compare_dz, grad_out=grad_out,
+                                  same_bits=same_bits)
     dz = ulorl.token_loss_bwd(logits, d["token_ids"], res.lse, res.gcoef, grad_out=grad_out,
                               inplace=inplace)
     compare_dz(w.name, dz)
+    if dz1 is not None and same_bits:
+        assert torch.equal(_bits(dz1), _bits(dz)), "one-call dlogits differ from the two-call dlogits"
     if pristine is not None:
-        check_one_call_bitwise_with_the_row_kernel(d, p, res, dz, grad_out=grad_out)
+        check_row_kernels_bitwise(d, p, grad_out=grad_out)
     return res, tt, dict(n_near_tau=n_tau, n_near_edge=n_edge, dz=dz, data=d, o_H=o_H)
 
 
@@ -184,10 +189,11 @@ def assert_same_results(a: ulorl.FwdResult, b: ulorl.FwdResult, what=""):
 
 
 def check_one_call_path(d, p: ulorl.Params, res2: ulorl.FwdResult, o_lse, o_logp, o_H, tt, rtol, compare_dz,
-                        grad_out=1.0, also_inplace=True):
+                        grad_out=1.0, also_inplace=True, same_bits=True):
     """The one-call forward+backward (row-cooperative kernel) against the oracle, out of place and
-    (on a copy of the logits) in place; and against the two-call result: the same integer
-    decisions wherever the oracle is not on a discontinuity."""
+    (on a copy of the logits) in place; and against the two-call result: the same bits when the
+    two-call forward ran by pieces, else the same integer decisions wherever the oracle is not on
+    a discontinuity.  Returns the out-of-place dlogits."""
     old = None if p.is_mode == ulorl.IS_POIS else d["old_logp"]
     r1, dz1 = ulorl.token_loss_fwd_bwd(d["logits"], d["token_ids"], d["cu_seqlens"], d["advantages"], old, p,
                                        grad_out=grad_out)
@@ -198,6 +204,8 @@ def check_one_call_path(d, p: ulorl.Params, res2: ulorl.FwdResult, o_lse, o_logp
     assert torch.equal(r1.mpt_mask[far], res2.mpt_mask[far])
     assert torch.equal((r1.gcoef == 0)[far], (res2.gcoef == 0)[far])
     assert torch.equal(r1.resp_gate, res2.resp_gate) and torch.equal(r1.segment_out, res2.segment_out)
+    if same_bits:
+        assert_same_results(res2, r1, "one call vs two calls")
     if also_inplace and d["logits"].is_contiguous():
         z = d["logits"].clone()
         r3, dz3 = ulorl.token_loss_fwd_bwd(z, d["token_ids"], d["cu_seqlens"], d["advantages"], old, p,
@@ -205,21 +213,25 @@ def check_one_call_path(d, p: ulorl.Params, res2: ulorl.FwdResult, o_lse, o_logp
         assert dz3.data_ptr() == z.data_ptr()
         assert_same_results(r1, r3, "in place")
         assert torch.equal(_bits(dz3), _bits(dz1)), "one-call in-place dlogits differ from out-of-place"
+    return dz1
 
 
-def check_one_call_bitwise_with_the_row_kernel(d, p: ulorl.Params, res: ulorl.FwdResult, dz_ref: torch.Tensor,
-                                               grad_out=1.0):
-    """With one looping workgroup per row (the older kernel) the one-call path reproduces the
-    two-call results bit for bit."""
+def check_row_kernels_bitwise(d, p: ulorl.Params, grad_out=1.0):
+    """The kernels with one looping workgroup per row (the fallbacks of both paths) reproduce each
+    other bit for bit as well."""
     old = None if p.is_mode == ulorl.IS_POIS else d["old_logp"]
     ulorl.tune(ulorl.TUNE_FUSED_CLUSTER, 0)
+    ulorl.tune(ulorl.TUNE_FWD_PIECES, 0)
     try:
         r2, dz2 = ulorl.token_loss_fwd_bwd(d["logits"], d["token_ids"], d["cu_seqlens"], d["advantages"], old, p,
                                            grad_out=grad_out)
+        res = ulorl.token_loss_fwd(d["logits"], d["token_ids"], d["cu_seqlens"], d["advantages"], old, p)
+        dz = ulorl.token_loss_bwd(d["logits"], d["token_ids"], res.lse, res.gcoef, grad_out=grad_out)
     finally:
         ulorl.tune(ulorl.TUNE_FUSED_CLUSTER, 1)
-    assert_same_results(res, r2, "row kernel")
-    assert torch.equal(_bits(dz2), _bits(dz_ref)), "row-kernel fused dlogits differ from the two-call dlogits"
+        ulorl.tune(ulorl.TUNE_FWD_PIECES, 1)
+    assert_same_results(res, r2, "row kernels")
+    assert torch.equal(_bits(dz2), _bits(dz)), "row-kernel fused dlogits differ from the two-call dlogits"
 
 
 def sigma_between_responses(host_logits, y, cu, k=None):

@@ -128,9 +128,12 @@ def test_tuning_knobs_validate():
     with pytest.raises(ulorl.UlorlError):
         ulorl.tune(ulorl.TUNE_FWD_THREADS, 100)
     with pytest.raises(ulorl.UlorlError):
-        ulorl.tune(11, 256)
+        ulorl.tune(12, 256)
     with pytest.raises(ulorl.UlorlError):
         ulorl.tune(ulorl.TUNE_FUSED_CLUSTER, 2)
+    ulorl.tune(ulorl.TUNE_FWD_PIECES, 1)
+    with pytest.raises(ulorl.UlorlError):
+        ulorl.tune(ulorl.TUNE_FWD_PIECES, 2)
 
 
 def test_pool_step_rejects_bad_arguments_on_the_host():

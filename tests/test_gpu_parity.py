@@ -113,15 +113,17 @@ def test_ragged_vocab_and_launch_shapes(dtype, V, threads, unroll):
     for knob, val in ((ulorl.TUNE_FWD_THREADS, threads), (ulorl.TUNE_FWD_UNROLL, unroll),
                       (ulorl.TUNE_BWD_THREADS, threads), (ulorl.TUNE_BWD_UNROLL, unroll),
                       (ulorl.TUNE_FUSED_THREADS, threads), (ulorl.TUNE_FUSED_UNROLL, unroll),
-                      (ulorl.TUNE_BWD_ONESHOT, 1 if (threads, unroll) == (512, 8) else 0)):
+                      (ulorl.TUNE_BWD_ONESHOT, 1 if (threads, unroll) == (512, 8) else 0),
+                      (ulorl.TUNE_FWD_PIECES, 0)):          # the forward by one looping workgroup per row
         ulorl.tune(knob, val)
     try:
-        res, tt, info = run_full_parity(w, params_for(w, gate_mode=ulorl.GATE_ALWAYS, tau=0.5), data=d)
+        res, tt, info = run_full_parity(w, params_for(w, gate_mode=ulorl.GATE_ALWAYS, tau=0.5), data=d,
+                                        same_bits=False)
     finally:
         for knob, val in ((ulorl.TUNE_FWD_THREADS, 512), (ulorl.TUNE_FWD_UNROLL, 8),
                           (ulorl.TUNE_BWD_THREADS, 256), (ulorl.TUNE_BWD_UNROLL, 4),
                           (ulorl.TUNE_FUSED_THREADS, 512), (ulorl.TUNE_FUSED_UNROLL, 8),
-                          (ulorl.TUNE_BWD_ONESHOT, 1)):
+                          (ulorl.TUNE_BWD_ONESHOT, 1), (ulorl.TUNE_FWD_PIECES, 1)):
             ulorl.tune(knob, val)     # back to the library defaults
     # in place on the padded buffer: same bits, and the padding columns stay untouched
     dz_out = info["dz"]

@@ -44,6 +44,22 @@ PMC = {
 }
 
 
+# HBM bytes of one lm_head backward / forward call at configuration 5 (vocabulary chunk 8192), from two
+# rocprofv3 --pmc runs of this script (FETCH_SIZE, then WRITE_SIZE, summed over the call's kernels and
+# scaled as above); valid for the lm_head source with this digest and for that workload only.
+PMC_LMHEAD = {
+    "source_sha256": "e89cdaf4a7c1b0f843ddbd3d776ae2b2014c02b389c401690e8dbc0d1aff86bd",
+    "bwd_bytes": (2 * 47244450 + 25036288) * 1024,
+    "fwd_bytes": (2 * 17484917 + 20480) * 1024,
+}
+
+
+def lmhead_source_digest():
+    import hashlib
+    path = os.path.join(ROOT, "paper_2507_19766_amd", "csrc", "lmhead.hip")
+    return hashlib.sha256(open(path, "rb").read()).hexdigest()
+
+
 def kernel_source_digest():
     import hashlib
     path = os.path.join(ROOT, "paper_2507_19766_amd", "csrc", "token_loss.hip")
@@ -123,6 +139,8 @@ def bench_lmhead(args, w, ulorl, ui, torch, dev):
     bwd_tf = 3 * gemm_flops / (bwd_ms / K * 1e-3) / 1e12     # recompute, dHidden, dW
     fwd_tf = gemm_flops / (fwd_ms / K * 1e-3) / 1e12
     cnt = out.counters.cpu().tolist()
+    counters_valid = (lmhead_source_digest() == PMC_LMHEAD["source_sha256"] and w.name == "cfg5_lmhead_bf16"
+                      and chunk == 8192)
     result = {
         "metric": "token-rows/sec fused fwd+bwd RL token loss (V=151936 bf16) + % HBM roofline",
         "value": w.N * K / wall, "unit": "token-rows/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
@@ -133,10 +151,14 @@ def bench_lmhead(args, w, ulorl, ui, torch, dev):
                    "is_mode": "SAIS", "gate": "always (static MPT masking)", "tau": w.tau},
         "roofline": {"bound": "mfma", "kernel": "backward call: lmhead_dz_kernel + 2 x gemm_tn_kernel per vocabulary "
                      "chunk (3 products of 2*N*Hd*V flop)", "achieved": bwd_tf, "peak": MFMA_BF16_PEAK_TFLOPS,
-                     "unit": "TFLOP/s", "frac": bwd_tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "unit": "TFLOP/s", "frac": bwd_tf / MFMA_BF16_PEAK_TFLOPS,
+                     "traffic": PMC_LMHEAD["bwd_bytes"] if counters_valid else None,
+                     "traffic_note": "HBM-side bytes of the call (operand tiles are re-fetched per XCD; the "
+                     "operands themselves are 1.5 GB)",
                      "algorithmic_flops_per_launch": 3 * gemm_flops, "avg_launch_ms": bwd_ms / K},
         "roofline_fwd": {"bound": "mfma", "kernel": "lmhead_stats_kernel (1 product)", "achieved": fwd_tf,
                          "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": fwd_tf / MFMA_BF16_PEAK_TFLOPS,
+                         "traffic": PMC_LMHEAD["fwd_bytes"] if counters_valid else None,
                          "avg_call_ms": fwd_ms / K},
         "batch": {"masked_tokens": cnt[0], "clipped_tokens": cnt[1], "positive_tokens": cnt[2], "status": cnt[3],
                   "loss": out.loss.item()},

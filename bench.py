@@ -165,7 +165,7 @@ def bench_lmhead(args, w, ulorl, ui, torch, dev):
     }
     if args.cpu_rows > 0:
         import oracle
-        n = min(256, w.N)
+        n = min(6144, w.N)          # about 10 s of oracle work (fp64 logits of the sample: 7.5 GB)
         log("timing the CPU oracle (lm_head) on %d rows..." % n)
         hr = H[:n].cpu().view(torch.int16).numpy().view(np.uint16)
         wr = W.cpu().view(torch.int16).numpy().view(np.uint16)

@@ -1,6 +1,6 @@
 """The library only enqueues kernels on the caller's stream (no allocation, no memset, no
 synchronisation), so a caller may capture its calls in a HIP graph.  These tests capture the
-one-call logits path and the lm_head forward + backward after a warm-up call, replay the graphs
+one-call and the two-call logits path and the lm_head forward + backward after a warm-up call, replay the graphs
 several times with eager work and synchronisations in between, and require every replay to be
 bitwise equal to the eager result."""
 import sys
@@ -53,6 +53,41 @@ def test_one_call_path_replays_bitwise_from_a_graph():
         assert torch.equal(out.loss, ref.loss), replay
         assert torch.equal(out.gcoef, ref.gcoef), replay
         assert torch.equal(out.mpt_mask, ref.mpt_mask), replay
+        assert torch.equal(out.counters, ref.counters), replay
+        assert torch.equal(dz.view(torch.int16), dz_ref.view(torch.int16)), replay
+
+
+def test_two_call_path_replays_bitwise_from_a_graph():
+    """Forward (statistics by pieces + merge + O(N) kernels) and backward captured together; the
+    replays must also match the one-call path, which carries the same bits."""
+    w = ui.shrink(ui.config(2), [700, 300, 1, 523], V=151936 // 8, name="graph_two_calls")
+    say("graph: %s N=%d V=%d" % (w.name, w.N, w.V))
+    d = ui.generate(w, DEV)
+    p = ulorl.Params(gate_mode=ulorl.GATE_ALWAYS, seg_len=w.seg_len)
+    ws = torch.empty(ulorl.token_loss_workspace_bytes(w.N, w.V, w.R), dtype=torch.uint8, device=DEV)
+    args = (d["logits"], d["token_ids"], d["cu_seqlens"], d["advantages"], d["old_logp"], p)
+    ref = ulorl.token_loss_fwd(*args, workspace=ws)                                # eager; also the warm-up
+    dz_ref = ulorl.token_loss_bwd(d["logits"], d["token_ids"], ref.lse, ref.gcoef)
+    one, dz_one = ulorl.token_loss_fwd_bwd(*args, grad_out=1.0)
+    torch.cuda.synchronize()
+    assert torch.equal(dz_one.view(torch.int16), dz_ref.view(torch.int16))
+    out = ulorl.token_loss_fwd(*args, workspace=ws)
+    dz = torch.empty_like(d["logits"])
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        ulorl.token_loss_fwd(*args, out=out, workspace=ws)
+        ulorl.token_loss_bwd(d["logits"], d["token_ids"], out.lse, out.gcoef, dlogits=dz)
+    for replay in range(3):
+        dz.fill_(float("nan"))
+        out.loss.fill_(float("nan"))
+        out.lse.fill_(float("nan"))
+        out.gcoef.fill_(float("nan"))
+        _eager_noise()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.loss, ref.loss) and torch.equal(out.loss, one.loss), replay
+        assert torch.equal(out.lse, ref.lse) and torch.equal(out.gcoef, ref.gcoef), replay
         assert torch.equal(out.counters, ref.counters), replay
         assert torch.equal(dz.view(torch.int16), dz_ref.view(torch.int16)), replay
 

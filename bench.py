@@ -36,7 +36,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 matrix rate
 # expressed as measured / algorithmic ratios.  They hold for the kernel source they were taken
 # on: the digest below is checked at run time and `traffic` is null once the kernels changed.
 PMC = {
-    "source_sha256": "a8df7173f54df06f70baaaf095a3ae2d4c073c80dc9123a277274cdc8b29946b",
+    "source_sha256": "abdf81f083a255a4679cb244afadc9116ecf6c383c5a2dc83ecd292518f71639",
     "fused_read": 1.0077,            # cluster_row_kernel: every row once, plus the polling of the exchange slots
     "fused_write": 1.0014,
     "bwd_read": 1.0007,              # dlogits_chunk_kernel

@@ -311,9 +311,15 @@ __device__ __forceinline__ void dlogits_core(const typename Tr::elem* rowp, type
         return;
     }
 
-    // -g * exp(z - lse) = -sign(g) * 2^(z*log2e + c),  c = log2|g| - lse*log2e
+    // -g * exp(z - lse) = -sign(g) * 2^(z*log2e + c),  c = log2|g| - lse*log2e.  The magnitudes are
+    // computed and rounded, the chosen column adds -sign(g) * g, and a negative sign is applied to
+    // the packed result by flipping sign bits (rounding to nearest even is symmetric): the same
+    // sequence as in cluster_row_kernel, so both give the same bits, signs of zeros included.
     const float c = fmaf(-l, kLog2e, log2f(fabsf(g)));
-    const float sgn = g > 0.0f ? -1.0f : 1.0f;
+    const bool negate = g > 0.0f;
+    const float sgn = negate ? -1.0f : 1.0f;
+    const float g_mag = negate ? -g : g;
+    const u32x4 flip = negate ? Tr::sign_bits() : u32x4{0u, 0u, 0u, 0u};
     const int yvec = y / E;
 
     // Software-pipelined: the loads of trip i+1 are issued before the stores of trip i (loads and
@@ -325,12 +331,12 @@ __device__ __forceinline__ void dlogits_core(const typename Tr::elem* rowp, type
         float f[E];
         Tr::unpack(v, f);
 #pragma unroll
-        for (int e = 0; e < E; ++e) f[e] = sgn * fast_exp2(fmaf(f[e], kLog2e, c));
+        for (int e = 0; e < E; ++e) f[e] = fast_exp2(fmaf(f[e], kLog2e, c));
         if (vec_index == yvec) {
 #pragma unroll
-            for (int e = 0; e < E; ++e) f[e] += (e == y - yvec * E) ? g : 0.0f;
+            for (int e = 0; e < E; ++e) f[e] += (e == y - yvec * E) ? g_mag : 0.0f;
         }
-        store_stream(op + vec_index, Tr::pack(f));
+        store_stream(op + vec_index, Tr::pack(f) ^ flip);
     };
     int i = tid;
     if (i + (U - 1) * NT < nvec) {
@@ -412,7 +418,9 @@ __global__ __launch_bounds__(256) void dlogits_chunk_kernel(const typename Tr::e
     const int nvec = V / E;
     const int i = blockIdx.x * 256 + threadIdx.x;
     const float c = live ? fmaf(-l, kLog2e, log2f(fabsf(g))) : 0.0f;
-    const float sgn = g > 0.0f ? -1.0f : 1.0f;
+    const bool negate = g > 0.0f;              // see dlogits_core
+    const float sgn = negate ? -1.0f : 1.0f;
+    const float g_mag = negate ? -g : g;
     if (i < nvec) {
         u32x4* op = reinterpret_cast<u32x4*>(outp) + i;
         if (!live) {
@@ -422,13 +430,15 @@ __global__ __launch_bounds__(256) void dlogits_chunk_kernel(const typename Tr::e
             float f[E];
             Tr::unpack(load_stream(reinterpret_cast<const u32x4*>(rowp) + i), f);
 #pragma unroll
-            for (int e = 0; e < E; ++e) f[e] = sgn * fast_exp2(fmaf(f[e], kLog2e, c));
+            for (int e = 0; e < E; ++e) f[e] = fast_exp2(fmaf(f[e], kLog2e, c));
             const int yvec = y / E;
             if (i == yvec) {
 #pragma unroll
-                for (int e = 0; e < E; ++e) f[e] += (e == y - yvec * E) ? g : 0.0f;
+                for (int e = 0; e < E; ++e) f[e] += (e == y - yvec * E) ? g_mag : 0.0f;
             }
-            store_stream(op, Tr::pack(f));
+            u32x4 o = Tr::pack(f);
+            if (negate) o ^= Tr::sign_bits();
+            store_stream(op, o);
         }
     }
     if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 255) {   // ragged tail of the row

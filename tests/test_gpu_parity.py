@@ -259,6 +259,47 @@ def test_fused_path_defers_mpt_members_until_the_gate_is_known():
     assert int(r3.counters[3]) & ulorl.STATUS_BAD_CU and torch.all(z3 == 0) and r3.loss.item() == 0.0
 
 
+# ------------------------------------------------------------------ masked vocabulary entries
+
+@pytest.mark.parametrize("dtype,V", [("bf16", 30011), ("f32", 9001)])
+def test_rows_with_minus_infinity_logits_are_reported_not_trained(dtype, V):
+    """Logits of -infinity are outside the domain (the oracle takes them as probability 0; the
+    kernels' entropy sum turns not-a-number): such rows are reported through the status word and get
+    a zero gradient on both paths; the other rows are untouched."""
+    base = ui.config(1) if dtype == "f32" else ui.config(2)
+    w = ui.shrink(base, [17, 5, 31], V=V, seg_len=8, name="masked_vocab_%s" % dtype)
+    d = ui.generate(w, DEV)
+    p = params_for(w, gate_mode=ulorl.GATE_ALWAYS, tau=0.5)
+    vec = 4 if dtype == "f32" else 8
+    stride = (V + vec - 1) // vec * vec                                   # rows padded to 16 bytes
+    buf = torch.full((w.N, stride), float("nan"), dtype=w.torch_dtype(), device=DEV)
+    buf[:, :V] = d["logits"]
+    z = buf[:, :V]
+    args = (d["token_ids"], d["cu_seqlens"], d["advantages"], d["old_logp"], p)
+    good = ulorl.token_loss_fwd(z, *args)
+    assert int(good.counters[3]) == 0
+    rows = [4, 20]
+    for t in rows:
+        cols = torch.arange(3 + t, V, 97, device=DEV)
+        cols = cols[cols != d["token_ids"][t]]
+        z[t, cols] = float("-inf")
+    r = ulorl.token_loss_fwd(z, *args)
+    dz = ulorl.token_loss_bwd(z, d["token_ids"], r.lse, r.gcoef)
+    r1, dz1 = ulorl.token_loss_fwd_bwd(z, *args)
+    other = torch.ones(w.N, dtype=torch.bool, device=DEV)
+    other[rows] = False
+    for res, grad in ((r, dz), (r1, dz1)):
+        assert int(res.counters[3]) == ulorl.STATUS_NONFINITE
+        assert torch.all(res.gcoef[rows] == 0) and torch.all(grad[rows] == 0)
+        # the denominator is unchanged, so the other rows' coefficients are too
+        assert torch.equal(res.gcoef[other], good.gcoef[other])
+    assert torch.equal(_int_view(dz), _int_view(dz1))
+
+
+def _int_view(t):
+    return t.contiguous().view(torch.int32 if t.dtype == torch.float32 else torch.int16)
+
+
 # ------------------------------------------------------------------ errors the device reports
 
 def test_device_detected_errors_raise_status_bits_without_faulting():

@@ -45,6 +45,24 @@ def test_uniform_row_has_entropy_log_V(V):
         np.testing.assert_allclose(lse, level + math.log(V), rtol=1e-13)
 
 
+def test_masked_vocabulary_entries_have_probability_zero():
+    """A logit of -infinity is a masked vocabulary entry: with k equal finite logits and the rest
+    masked the row is uniform over k entries (H = ln k), and a masked column gets a zero gradient."""
+    V, k = 1000, 37
+    z = np.full((1, V), -np.inf, dtype=np.float32)
+    keep = np.arange(0, V, 27)[:k]
+    z[0, keep] = 2.5
+    lse, logp, H = oracle.row_stats(z, np.array([keep[3]]))
+    np.testing.assert_allclose(H, math.log(k), rtol=1e-12)
+    np.testing.assert_allclose(logp, -math.log(k), rtol=1e-12)
+    np.testing.assert_allclose(lse, 2.5 + math.log(k), rtol=1e-12)
+    dz = oracle.dlogits(z, np.array([keep[3]]), lse, np.array([0.7]))
+    masked = np.ones(V, dtype=bool)
+    masked[keep] = False
+    assert np.all(dz[0, masked] == 0.0)
+    np.testing.assert_allclose(dz[0, keep].sum(), 0.0, atol=1e-15)
+
+
 def spike_closed_form(V, a):
     """One logit at a, the other V-1 at 0:  p = e^a / (e^a + V - 1),
     H = -p ln p - (1-p) ln((1-p)/(V-1))."""

@@ -163,6 +163,24 @@ def bench_lmhead(args, w, ulorl, ui, torch, dev):
         "batch": {"masked_tokens": cnt[0], "clipped_tokens": cnt[1], "positive_tokens": cnt[2], "status": cnt[3],
                   "loss": out.loss.item()},
     }
+    # context only: the vendor library's plain bf16 GEMM on the shape of one vocabulary chunk
+    # (N x chunk x Hd), timed the same way; no part of the path above uses it
+    try:
+        Wc = W[:, :chunk].t().contiguous()                         # [chunk, Hd]
+        Zc = torch.empty(w.N, chunk, dtype=torch.bfloat16, device=dev)
+        torch.matmul(H, Wc.t(), out=Zc)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            torch.matmul(H, Wc.t(), out=Zc)
+        e1.record()
+        torch.cuda.synchronize()
+        lib_tf = 2.0 * w.N * w.hidden * chunk / (e0.elapsed_time(e1) / 5 * 1e-3) / 1e12
+        result["context"] = {"vendor_gemm_tflops": lib_tf,
+                             "note": "torch.matmul (hipBLASLt), %d x %d x %d bf16, same box and run" % (w.N, chunk, w.hidden)}
+        del Wc, Zc
+    except Exception as exc:                                       # context must never break the measurement
+        result["context"] = {"vendor_gemm_tflops": None, "note": "not measured: %r" % (exc,)}
     if args.cpu_rows > 0:
         import oracle
         n = min(6144, w.N)          # about 10 s of oracle work (fp64 logits of the sample: 7.5 GB)

@@ -148,6 +148,7 @@ def bench_lmhead(args, w, ulorl, ui, torch, dev):
         "dtype": "bf16 MFMA operands, f32 accumulate", "data": "synthetic",
         "config": {"workload": w.name, "rows": w.N, "hidden": w.hidden, "vocab": w.V, "vocab_chunk": chunk,
                    "responses": w.R, "segment_len": w.seg_len, "path": "lm_head variant (logits never materialised)",
+                   "gemm_tile": args.gemm_tile if args.gemm_tile >= 0 else "default",
                    "is_mode": "SAIS", "gate": "always (static MPT masking)", "tau": w.tau},
         "roofline": {"bound": "mfma", "kernel": "backward call: lmhead_dz_kernel + 2 x gemm_tn_kernel per vocabulary "
                      "chunk (3 products of 2*N*Hd*V flop)", "achieved": bwd_tf, "peak": MFMA_BF16_PEAK_TFLOPS,

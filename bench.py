@@ -220,6 +220,8 @@ def main():
     ap.add_argument("--bwd-unroll", type=int, default=0)
     ap.add_argument("--fused-threads", type=int, default=0)
     ap.add_argument("--fused-unroll", type=int, default=0)
+    ap.add_argument("--fused-vpt", type=int, default=0,
+                    help="16-byte vectors per thread of the row-cooperative kernel (ULORL_TUNE_FUSED_VPT; 0: the library's choice)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this library runs on ONE GPU (rows are independent, so a multi-GPU job shards rows and "
@@ -237,7 +239,8 @@ def main():
     torch.cuda.set_device(dev)
     for knob, val in ((ulorl.TUNE_FWD_THREADS, args.fwd_threads), (ulorl.TUNE_FWD_UNROLL, args.fwd_unroll),
                       (ulorl.TUNE_BWD_THREADS, args.bwd_threads), (ulorl.TUNE_BWD_UNROLL, args.bwd_unroll),
-                      (ulorl.TUNE_FUSED_THREADS, args.fused_threads), (ulorl.TUNE_FUSED_UNROLL, args.fused_unroll)):
+                      (ulorl.TUNE_FUSED_THREADS, args.fused_threads), (ulorl.TUNE_FUSED_UNROLL, args.fused_unroll),
+                      (ulorl.TUNE_FUSED_VPT, args.fused_vpt)):
         if val:
             ulorl.tune(knob, val)
 

@@ -44,7 +44,9 @@ typedef enum {
     ULORL_ERR_ALIGN = -4,     /* logits base or row stride not 16-byte aligned       */
     ULORL_ERR_PARAM = -5,     /* eps < 0, tau outside (0,1], unknown mode, ...       */
     ULORL_ERR_WORKSPACE = -6, /* workspace missing, misaligned or too small          */
-    ULORL_ERR_HIP = -7        /* a kernel launch was rejected by the runtime         */
+    ULORL_ERR_HIP = -7,       /* a kernel launch was rejected by the runtime         */
+    ULORL_ERR_TOO_LARGE = -8  /* ulorl_token_loss_fwd_bwd_static: the problem needs more scratch
+                                 memory than the library's static array holds          */
 } ulorl_status;
 
 /* Storage type of logits / dlogits. */
@@ -199,6 +201,34 @@ int32_t ulorl_token_loss_fwd_bwd(
     uint8_t *mpt_mask, float *ratio, int32_t *segment_out,
     float *resp_entropy, uint8_t *resp_gate, int64_t *counters,
     void *dlogits, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * ulorl_token_loss_fwd_bwd for callers that cannot allocate device memory or pass a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, results (bit for bit) and conventions as ulorl_token_loss_fwd_bwd, without the
+ * workspace: the scratch memory is a static device array inside the library,
+ * ulorl_static_scratch_bytes() = 32 MiB per GPU, held from library load until the process ends.
+ * The call allocates and frees nothing.
+ *   - Returns ULORL_ERR_TOO_LARGE when ulorl_token_loss_workspace_bytes(N, V, R) exceeds the
+ *     array (131072 rows of 151936 bf16 logits need 10.7 MB; 198004 rows 16.1 MB).
+ *   - Every call on a GPU uses that GPU's one array: calls that overlap in time on one GPU (two
+ *     streams, two threads) race and give wrong results; calls on one stream are safe back to
+ *     back (what must start at zero is cleared by the call itself).
+ *   - ulorl_init() resolves the array's address for the current device (hipGetSymbolAddress, once
+ *     per device); call it at set-up, outside any stream capture.  Without it the first
+ *     ulorl_token_loss_fwd_bwd_static call on a device does so.
+ */
+int32_t ulorl_init(void);
+size_t ulorl_static_scratch_bytes(void);
+int32_t ulorl_token_loss_fwd_bwd_static(
+    const void *logits, int32_t dt, int64_t N, int64_t V, int64_t row_stride,
+    const int32_t *token_ids, const int32_t *cu_seqlens, int32_t R,
+    const int32_t *segment_ids, const float *old_logp, const float *advantages,
+    const ulorl_params *p, float grad_out,
+    float *loss, float *logp, float *entropy, float *lse, float *gcoef,
+    uint8_t *mpt_mask, float *ratio, int32_t *segment_out,
+    float *resp_entropy, uint8_t *resp_gate, int64_t *counters,
+    void *dlogits, void *hip_stream);
 
 /* ------------------------------------------------------------------------------------------
  * lm_head variant: the logits are hidden . W and are never materialised.

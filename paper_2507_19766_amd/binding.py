@@ -103,6 +103,12 @@ def load_library(build_if_missing: bool = True):
         vp, vp, vp,                                          # mpt_mask, ratio, segment_out
         vp, vp, vp,                                          # resp_entropy, resp_gate, counters
         vp, vp, c.c_size_t, vp]                              # dlogits, workspace, bytes, stream
+    lib.ulorl_init.restype = c.c_int32
+    lib.ulorl_init.argtypes = []
+    lib.ulorl_static_scratch_bytes.restype = c.c_size_t
+    lib.ulorl_static_scratch_bytes.argtypes = []
+    lib.ulorl_token_loss_fwd_bwd_static.restype = c.c_int32
+    lib.ulorl_token_loss_fwd_bwd_static.argtypes = lib.ulorl_token_loss_fwd_bwd.argtypes[:-3] + [vp]
     lib.ulorl_lmhead_workspace_bytes.restype = c.c_size_t
     lib.ulorl_lmhead_workspace_bytes.argtypes = [c.c_int64, c.c_int64, c.c_int64, c.c_int32, c.c_int32]
     lib.ulorl_lmhead_token_loss_fwd.restype = c.c_int32
@@ -294,6 +300,61 @@ def token_loss_fwd_bwd(logits, token_ids, cu_seqlens, advantages, old_logp=None,
         _p(out.resp_gate), _p(out.counters), _p(dlogits), _p(workspace), ws_bytes, _stream(dev))
     if rc != 0:
         raise UlorlError(rc, "ulorl_token_loss_fwd_bwd")
+    return out, dlogits
+
+
+def init() -> None:
+    """ulorl_init: resolve the static scratch array of the current device (set-up time)."""
+    rc = load_library().ulorl_init()
+    if rc != 0:
+        raise UlorlError(rc, "ulorl_init")
+
+
+def static_scratch_bytes() -> int:
+    return int(load_library().ulorl_static_scratch_bytes())
+
+
+def token_loss_fwd_bwd_static(logits, token_ids, cu_seqlens, advantages, old_logp=None, params: Params = None,
+                              segment_ids=None, grad_out: float = 1.0, dlogits: Optional[torch.Tensor] = None,
+                              inplace: bool = False, out: Optional[FwdResult] = None):
+    """ulorl_token_loss_fwd_bwd_static -> (FwdResult, dlogits): the one-call path on the library's
+    static scratch array (the C call allocates nothing; pass ``out`` and ``dlogits`` to keep this
+    wrapper from allocating outputs either)."""
+    lib = load_library()
+    dt, N, V, stride = _check_logits(logits)
+    dev = logits.device
+    f32 = dict(dtype=torch.float32, device=dev)
+    token_ids = _vec(token_ids, torch.int32, N, "token_ids", dev)
+    if cu_seqlens.device != dev or cu_seqlens.dtype != torch.int32 or not cu_seqlens.is_contiguous():
+        raise ValueError("cu_seqlens must be a contiguous int32 device tensor")
+    R = cu_seqlens.shape[0] - 1
+    advantages = _vec(advantages, torch.float32, N, "advantages", dev)
+    old_logp = _vec(old_logp, torch.float32, N, "old_logp", dev)
+    segment_ids = _vec(segment_ids, torch.int32, N, "segment_ids", dev)
+    if advantages is None:
+        raise ValueError("token_loss_fwd_bwd_static needs advantages")
+    cparams = (params or Params()).to_c()
+    if out is None:
+        out = FwdResult(torch.empty(1, **f32), torch.empty(N, **f32), torch.empty(N, **f32), torch.empty(N, **f32),
+                        torch.empty(N, **f32), torch.empty(N, dtype=torch.uint8, device=dev), torch.empty(N, **f32),
+                        torch.empty(N, dtype=torch.int32, device=dev), torch.empty(max(R, 1), **f32)[:R],
+                        torch.empty(max(R, 1), dtype=torch.uint8, device=dev)[:R],
+                        torch.empty(4, dtype=torch.int64, device=dev))
+    if inplace:
+        dlogits = logits
+    elif dlogits is None:
+        dlogits = torch.empty_strided((N, V), (stride, 1), dtype=logits.dtype, device=dev)
+    if (dlogits.shape != logits.shape or dlogits.dtype != logits.dtype or dlogits.device != dev
+            or dlogits.stride() != logits.stride()):
+        raise ValueError("dlogits must match logits in shape, dtype, strides and device")
+    rc = lib.ulorl_token_loss_fwd_bwd_static(
+        _p(logits), dt, N, V, stride, _p(token_ids), _p(cu_seqlens), R, _p(segment_ids), _p(old_logp),
+        _p(advantages), ctypes.byref(cparams), float(grad_out),
+        _p(out.loss), _p(out.logp), _p(out.entropy), _p(out.lse), _p(out.gcoef),
+        _p(out.mpt_mask), _p(out.ratio), _p(out.segment_out), _p(out.resp_entropy),
+        _p(out.resp_gate), _p(out.counters), _p(dlogits), _stream(dev))
+    if rc != 0:
+        raise UlorlError(rc, "ulorl_token_loss_fwd_bwd_static")
     return out, dlogits
 
 

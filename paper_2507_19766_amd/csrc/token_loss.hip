@@ -32,6 +32,7 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <mutex>
 #include <type_traits>
 
 #include "ulorl.h"
@@ -1413,9 +1414,31 @@ void launch_token_epilogue(const TokenArgs& a, const WorkspaceLayout& wl, float*
 
 }  // namespace ulorl_detail
 
+// Scratch memory of ulorl_token_loss_fwd_bwd_static, the entry point for callers that cannot
+// allocate: the workspace of the one-call path (exchange slots, per-response sums, per-block
+// partial sums, one flag byte per row) in a file-scope device array.  Every GPU the library runs
+// on holds its own copy until the process ends.  The name below is a host-side stand-in, never a
+// device address: host code uses the pointer static_scratch_for_current_device() resolves.
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+int32_t check_fwd_bwd_args(const void* logits, int32_t dt, int64_t N, int64_t V, int64_t row_stride,
+                           const int32_t* token_ids, const int32_t* cu_seqlens, int32_t R, const float* old_logp,
+                           const float* advantages, const ulorl_params* p, const float* loss, const float* logp,
+                           const float* entropy, const float* lse, const float* gcoef, const void* dlogits);
+int32_t static_scratch_for_current_device(void** out);
+int32_t fwd_bwd_enqueue(const void* logits, int32_t dt, int64_t N, int64_t V, int64_t row_stride,
+                        const int32_t* token_ids, const int32_t* cu_seqlens, int32_t R, const int32_t* segment_ids,
+                        const float* old_logp, const float* advantages, const ulorl_params* p, float grad_out,
+                        float* loss, float* logp, float* entropy, float* lse, float* gcoef, uint8_t* mpt_mask,
+                        float* ratio, int32_t* segment_out, float* resp_entropy, uint8_t* resp_gate,
+                        int64_t* counters, void* dlogits, void* workspace, const WorkspaceLayout& wl, void* hip_stream);
+}  // namespace
+
 extern "C" {
 
-int32_t ulorl_version(void) { return 100; }
+int32_t ulorl_version(void) { return 101; }
 
 const char* ulorl_status_string(int32_t status)
 {
@@ -1428,6 +1451,7 @@ const char* ulorl_status_string(int32_t status)
     case ULORL_ERR_PARAM: return "invalid parameter";
     case ULORL_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case ULORL_ERR_HIP: return "HIP launch failed";
+    case ULORL_ERR_TOO_LARGE: return "problem needs more scratch memory than the static array holds";
     default: return "unknown status";
     }
 }
@@ -1498,14 +1522,89 @@ int32_t ulorl_token_loss_fwd_bwd(const void* logits, int32_t dt, int64_t N, int6
                                  float* resp_entropy, uint8_t* resp_gate, int64_t* counters, void* dlogits,
                                  void* workspace, size_t workspace_bytes, void* hip_stream)
 {
+    int32_t rc = check_fwd_bwd_args(logits, dt, N, V, row_stride, token_ids, cu_seqlens, R, old_logp, advantages, p,
+                                    loss, logp, entropy, lse, gcoef, dlogits);
+    if (rc != ULORL_OK) return rc;
+    const WorkspaceLayout wl = workspace_layout(N, V, R);
+    if (!workspace || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < wl.total) return ULORL_ERR_WORKSPACE;
+    return fwd_bwd_enqueue(logits, dt, N, V, row_stride, token_ids, cu_seqlens, R, segment_ids, old_logp, advantages, p,
+                           grad_out, loss, logp, entropy, lse, gcoef, mpt_mask, ratio, segment_out, resp_entropy,
+                           resp_gate, counters, dlogits, workspace, wl, hip_stream);
+}
+
+int32_t ulorl_init(void)
+{
+    void* ptr = nullptr;
+    return static_scratch_for_current_device(&ptr);
+}
+
+size_t ulorl_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int32_t ulorl_token_loss_fwd_bwd_static(const void* logits, int32_t dt, int64_t N, int64_t V, int64_t row_stride,
+                                        const int32_t* token_ids, const int32_t* cu_seqlens, int32_t R,
+                                        const int32_t* segment_ids, const float* old_logp, const float* advantages,
+                                        const ulorl_params* p, float grad_out, float* loss, float* logp,
+                                        float* entropy, float* lse, float* gcoef, uint8_t* mpt_mask, float* ratio,
+                                        int32_t* segment_out, float* resp_entropy, uint8_t* resp_gate,
+                                        int64_t* counters, void* dlogits, void* hip_stream)
+{
+    int32_t rc = check_fwd_bwd_args(logits, dt, N, V, row_stride, token_ids, cu_seqlens, R, old_logp, advantages, p,
+                                    loss, logp, entropy, lse, gcoef, dlogits);
+    if (rc != ULORL_OK) return rc;
+    const WorkspaceLayout wl = workspace_layout(N, V, R);
+    if (wl.total > kStaticScratchBytes) return ULORL_ERR_TOO_LARGE;
+    void* ws = nullptr;
+    rc = static_scratch_for_current_device(&ws);
+    if (rc != ULORL_OK) return rc;
+    return fwd_bwd_enqueue(logits, dt, N, V, row_stride, token_ids, cu_seqlens, R, segment_ids, old_logp, advantages, p,
+                           grad_out, loss, logp, entropy, lse, gcoef, mpt_mask, ratio, segment_out, resp_entropy,
+                           resp_gate, counters, dlogits, ws, wl, hip_stream);
+}
+
+}  // extern "C"
+
+namespace {
+
+int32_t check_fwd_bwd_args(const void* logits, int32_t dt, int64_t N, int64_t V, int64_t row_stride,
+                           const int32_t* token_ids, const int32_t* cu_seqlens, int32_t R, const float* old_logp,
+                           const float* advantages, const ulorl_params* p, const float* loss, const float* logp,
+                           const float* entropy, const float* lse, const float* gcoef, const void* dlogits)
+{
     int32_t rc = check_logits(logits, dt, N, V, row_stride);
     if (rc != ULORL_OK) return rc;
     if (!token_ids || !logp || !entropy || !lse || !advantages || !dlogits) return ULORL_ERR_NULL;
     if (((uintptr_t)dlogits & 15u) != 0) return ULORL_ERR_ALIGN;
-    rc = check_objective_args(cu_seqlens, R, old_logp, p, loss, gcoef);
-    if (rc != ULORL_OK) return rc;
-    const WorkspaceLayout wl = workspace_layout(N, V, R);
-    if (!workspace || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < wl.total) return ULORL_ERR_WORKSPACE;
+    return check_objective_args(cu_seqlens, R, old_logp, p, loss, gcoef);
+}
+
+// Address of this device's copy of the static scratch array, resolved once per device (each GPU
+// holds its own copy of a __device__ array at its own address).
+int32_t static_scratch_for_current_device(void** out)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void* ptrs[kMaxDevices] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return ULORL_ERR_HIP;
+    std::lock_guard<std::mutex> lock(mu);
+    if (ptrs[dev] == nullptr) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return ULORL_ERR_HIP;
+        if (((uintptr_t)ptr & 255u) != 0) return ULORL_ERR_HIP;
+        ptrs[dev] = ptr;
+    }
+    *out = ptrs[dev];
+    return ULORL_OK;
+}
+
+int32_t fwd_bwd_enqueue(const void* logits, int32_t dt, int64_t N, int64_t V, int64_t row_stride,
+                        const int32_t* token_ids, const int32_t* cu_seqlens, int32_t R, const int32_t* segment_ids,
+                        const float* old_logp, const float* advantages, const ulorl_params* p, float grad_out,
+                        float* loss, float* logp, float* entropy, float* lse, float* gcoef, uint8_t* mpt_mask,
+                        float* ratio, int32_t* segment_out, float* resp_entropy, uint8_t* resp_gate,
+                        int64_t* counters, void* dlogits, void* workspace, const WorkspaceLayout& wl, void* hip_stream)
+{
+    bool ok;
     hipStream_t st = (hipStream_t)hip_stream;
     char* ws = (char*)workspace;
 
@@ -1522,7 +1621,6 @@ int32_t ulorl_token_loss_fwd_bwd(const void* logits, int32_t dt, int64_t N, int6
 
     hipLaunchKernelGGL(cu_check_kernel, dim3(1), dim3(kTokBlock), 0, st, cu_seqlens, R, N, (uint32_t*)(ws + wl.badcu));
     const ClusterShape shape = cluster_shape(V, dt);
-    bool ok;
     if (tuning().fused_cluster && shape.pieces > 0 && 2 * N * (int64_t)shape.pieces < (1LL << 38)) {
         ClusterArgs ca;
         ca.f = f;
@@ -1558,6 +1656,10 @@ int32_t ulorl_token_loss_fwd_bwd(const void* logits, int32_t dt, int64_t N, int6
     }
     return ULORL_OK;
 }
+
+}  // namespace
+
+extern "C" {
 
 int32_t ulorl_token_loss_bwd(const void* logits, int32_t dt, int64_t N, int64_t V, int64_t row_stride,
                              const int32_t* token_ids, const float* lse, const float* gcoef, float grad_out,

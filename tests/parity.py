@@ -314,9 +314,43 @@ def run_streamed_parity(w: ui.Workload, p: ulorl.Params, data, n_dz_rows=64, inp
     return res, tt
 
 
+def assert_row_sums_vanish(dz: torch.Tensor, V: int, block_rows=4096):
+    """sum_j dz[t, j] = g_t (1 - sum_j p_j) = 0: on the stored (rounded) gradient the sum must stay
+    within V * 2^-9 * max_j |dz[t, j]| (bf16 storage: V roundings, each of at most half an ulp of the
+    row's largest entry)."""
+    assert dz.dtype == torch.bfloat16
+    scale = 2.0 ** -9
+    for r0 in range(0, dz.shape[0], block_rows):
+        blk = dz[r0:r0 + block_rows]
+        s = blk.sum(dim=1, dtype=torch.float64).abs()
+        bound = V * scale * blk.abs().amax(dim=1).double()
+        assert bool((s <= bound).all()), "row sums of dlogits: rows %d.." % r0
+
+
+def assert_same_bits_blockwise(a: torch.Tensor, b: torch.Tensor, what: str, block_rows=8192):
+    assert a.shape == b.shape and a.dtype == b.dtype
+    for r0 in range(0, a.shape[0], block_rows):
+        if not torch.equal(_bits(a[r0:r0 + block_rows]), _bits(b[r0:r0 + block_rows])):
+            x, y = _bits(a[r0:r0 + block_rows]), _bits(b[r0:r0 + block_rows])
+            bad = (x != y).any(dim=1).nonzero()[:4, 0] + r0
+            raise AssertionError("%s: rows %s differ" % (what, bad.tolist()))
+
+
 # ------------------------------------------------------------------------------------ lm_head variant
 
 LMHEAD_ATOL = 4e-6   # fp32 MFMA accumulation of Hd ~ 2048 products adds ~1e-6 to every logit
+
+
+LMHEAD_EDGE_BAND = 2e-5   # clip-edge band of the lm_head variant (the mask keeps 1e-6)
+LMHEAD_CHOSEN_RTOL = 1e-5  # fp32 error of g p at the chosen column, relative to g
+
+
+def lmhead_near(o_logp, tt, p: ulorl.Params):
+    """(tokens within 1e-6 of tau, tokens within LMHEAD_EDGE_BAND of a clip edge), oracle side."""
+    near_tau = np.abs(np.exp(o_logp) - f32(p.tau)) < 1e-6
+    near_edge = (np.abs(tt.ratio - (1 - f32(p.eps_low))) < LMHEAD_EDGE_BAND) | \
+                (np.abs(tt.ratio - (1 + f32(p.eps_high))) < LMHEAD_EDGE_BAND)
+    return near_tau, near_edge
 
 
 def raw_bf16(t: torch.Tensor) -> np.ndarray:
@@ -350,16 +384,23 @@ def run_lmhead_parity(w: ui.Workload, p: ulorl.Params, chunk: int, data=None, gr
     np.testing.assert_array_equal(res.segment_out.cpu().numpy(), tt.seg)
     assert_close("resp_entropy", res.resp_entropy.cpu().numpy(), tt.resp_entropy, rtol, atol=LMHEAD_ATOL)
     np.testing.assert_array_equal(res.resp_gate.cpu().numpy(), tt.resp_gate)
-    # same discontinuity exclusions as the logits path; the ratio inherits the logits' absolute error
-    prob = np.exp(o_logp)
-    near = (np.abs(prob - f32(p.tau)) < 2e-5) | (np.abs(tt.ratio - (1 - f32(p.eps_low))) < 2e-5) | \
-           (np.abs(tt.ratio - (1 + f32(p.eps_high))) < 2e-5)
-    np.testing.assert_array_equal(res.mpt_mask.cpu().numpy()[~near], tt.mask[~near])
+    # The MPT mask keeps the 1e-6 band of the logits path: near p = tau = 0.99 an error d in a logit
+    # moves p by p (1 - p) d ~ 0.01 d, so the 4e-6 of the fp32 accumulation stay far inside it.  The
+    # ratio e^(logp - old) inherits the logits' absolute error as a relative one (4e-6 x 1.2), hence
+    # the wider band at the clip edges only.
+    near_tau, near_edge = lmhead_near(o_logp, tt, p)
+    near = near_tau | near_edge
+    np.testing.assert_array_equal(res.mpt_mask.cpu().numpy()[~near_tau], tt.mask[~near_tau])
     assert_close("ratio", res.ratio.cpu().numpy(), tt.ratio, 3e-5, atol=0.0)
-    assert_close("gcoef", res.gcoef.cpu().numpy()[~near], tt.gcoef[~near], 3e-5, atol=0.0)
+    g_gpu = res.gcoef.cpu().numpy()
+    assert_close("gcoef", g_gpu[~near], tt.gcoef[~near], 3e-5, atol=0.0)
+    assert np.all(g_gpu[~near][tt.gcoef[~near] == 0.0] == 0.0)         # masked / clipped: exactly zero
     if not near.any():
         assert_close("loss", res.loss.item(), tt.loss, 3e-5, atol=1e-7)
-    assert int(res.counters[3]) == 0 and int(res.counters[2]) == tt.n_pos
+    cnt = res.counters.cpu().numpy()
+    assert int(cnt[3]) == 0 and int(cnt[2]) == tt.n_pos
+    assert abs(int(cnt[0]) - tt.n_masked) <= int(near_tau.sum())
+    assert abs(int(cnt[1]) - tt.n_clip_inactive) <= int(near_edge.sum())
     if say:
         say("forward ok; oracle gradients")
 
@@ -376,10 +417,17 @@ def run_lmhead_parity(w: ui.Workload, p: ulorl.Params, chunk: int, data=None, gr
     qW = np.sqrt((hf * hf).T @ (dz * dz))
     # dz is rounded to bf16 as a GEMM operand (relative 2^-8 per term, worst case all aligned),
     # the result is rounded to bf16 once (2^-8 relative), fp32 accumulation is negligible beside both
-    for name, got, ref, bound, rss in (("d_hidden", dH, rdH, bH, qH), ("d_W", dW, rdW, bW, qW)):
+    # The chosen column is computed as g - g p: where p is close to 1 the result is much smaller than
+    # the fp32 error of g p (logit 4e-6, lse 4e-6, exponent argument 2e-6: LMHEAD_CHOSEN_RTOL of g),
+    # the same absolute term the logits path allows on dlogits.
+    ag = np.abs(grad_out * g)
+    sH = LMHEAD_CHOSEN_RTOL * ag[:, None] * np.abs(wf)[:, y].T                      # [N, Hd]
+    sWt = np.zeros((wf.shape[1], hf.shape[1]))
+    np.add.at(sWt, y, LMHEAD_CHOSEN_RTOL * ag[:, None] * np.abs(hf))                # [V, Hd]
+    for name, got, ref, bound, rss, slack in (("d_hidden", dH, rdH, bH, qH, sH), ("d_W", dW, rdW, bW, qW, sWt.T)):
         got = got.float().cpu().numpy().astype(np.float64)
         err = np.abs(got - ref)
-        tol = 2.0 ** -8 * bound + 2.0 ** -8 * np.abs(ref) + 1e-12
+        tol = 2.0 ** -8 * bound + 2.0 ** -8 * np.abs(ref) + slack + 1e-12
         bad = err > tol
         if bad.any():
             k = np.unravel_index(int(np.argmax(err - tol)), err.shape)
@@ -390,6 +438,127 @@ def run_lmhead_parity(w: ui.Workload, p: ulorl.Params, chunk: int, data=None, gr
         # error is at most 2^-8 relative and 2^-9 in the root mean square, so the terms contribute
         # at most 2^-9 * rss and the final rounding 2^-9 * |ref| (root mean square each; the mean
         # absolute error is below either).
-        typical = 2.0 ** -9 * (rss + np.abs(ref))
+        typical = 2.0 ** -9 * (rss + np.abs(ref)) + slack
         assert err.mean() <= typical.mean() + 1e-12, (name, err.mean(), typical.mean())
+    # a token with a zero coefficient (masked, clipped) contributes nothing: its dHidden row is exactly zero
+    zero = torch.as_tensor((tt.gcoef == 0.0) & ~near, device=dH.device)
+    assert bool((dH[zero] == 0).all()), "rows with a zero coefficient must have an exactly zero d_hidden"
+    res.d_hidden, res.d_weight = dH, dW
     return res, tt
+
+
+def run_lmhead_streamed_parity(w: ui.Workload, p: ulorl.Params, data, chunk=8192, block_rows=2048, n_cols=512,
+                               seed=0, say=print):
+    """lm_head variant at any size against the oracle, EVERY row and EVERY element of d_hidden and
+    d_W: the oracle's fp64 logits are formed block of rows by block of rows (stock matrix product),
+    each block goes through the oracle's row statistics, token terms and gradient, and the chain rule
+    to hidden and W is accumulated in fp64.  Needs a gate that does not couple rows (ALWAYS / NEVER):
+    then a token's terms depend on its own row and on the denominator only.
+    Bounds: as in run_lmhead_parity, except that the worst-case sum |dz| . |W| (resp. |hidden| . |dz|)
+    is replaced over the whole matrices by its Cauchy-Schwarz bound from row / column norms (no extra
+    matrix product); the exact sums and the typical-error check are applied on n_cols sampled
+    vocabulary columns of d_W."""
+    assert p.gate_mode in (ulorl.GATE_ALWAYS, ulorl.GATE_NEVER)
+    hidden, weight = data["hidden"], data["weight"]
+    old_t = None if p.is_mode == ulorl.IS_POIS else data["old_logp"]
+    res = ulorl.lmhead_token_loss_fwd(hidden, weight, data["token_ids"], data["cu_seqlens"], data["advantages"],
+                                      old_t, p, vocab_chunk=chunk)
+    dH, dW = ulorl.lmhead_token_loss_bwd(hidden, weight, data["token_ids"], res.lse, res.gcoef, vocab_chunk=chunk)
+    torch.cuda.synchronize()
+    say("gpu forward + backward done; oracle over %d rows in blocks of %d" % (w.N, block_rows))
+    N, Hd, V = w.N, w.hidden, w.V
+    D = p.denominator if p.denominator > 0 else float(N)
+    rtol = rtol_for("bf16")
+    wr = raw_bf16(weight)
+    wd = oracle.bf16_to_f64(wr)
+    w_norm = np.sqrt((wd * wd).sum(1))                        # |W[k, :]|
+    y = data["token_ids"].cpu().numpy()
+    adv = data["advantages"].cpu().numpy()
+    old = None if old_t is None else old_t.cpu().numpy()
+    g_lse, g_logp, g_H = res.lse.cpu().numpy(), res.logp.cpu().numpy(), res.entropy.cpu().numpy()
+    g_mask, g_ratio, g_g = res.mpt_mask.cpu().numpy(), res.ratio.cpu().numpy(), res.gcoef.cpu().numpy()
+    cols = np.sort(np.random.RandomState(seed).choice(V, n_cols, replace=False))
+    ref_dW = np.zeros((Hd, V))
+    bW = np.zeros((Hd, n_cols))
+    qW = np.zeros((Hd, n_cols))
+    dz_sq = np.zeros(V)
+    h_sq = np.zeros(Hd)
+    slack_Wt = np.zeros((V, Hd))          # chosen-column term of the d_W tolerance, transposed
+    resp = np.repeat(np.arange(w.R), w.lengths)
+    h_sum = np.zeros(w.R)
+    loss = 0.0
+    n_masked = n_clip = n_pos = n_tau = n_edge = 0
+    for r0 in range(0, N, block_rows):
+        r1 = min(N, r0 + block_rows)
+        hb = oracle.bf16_to_f64(raw_bf16(hidden[r0:r1]))
+        z = hb @ wd
+        o_lse, o_logp, o_H = oracle.row_stats(z, y[r0:r1])
+        assert_close("lse", g_lse[r0:r1], o_lse, rtol, atol=LMHEAD_ATOL)
+        assert_close("logp", g_logp[r0:r1], o_logp, rtol, atol=LMHEAD_ATOL)
+        assert_close("entropy", g_H[r0:r1], o_H, rtol, atol=LMHEAD_ATOL)
+        tt = oracle_terms(o_logp, o_H, [0, r1 - r0], adv[r0:r1], None if old is None else old[r0:r1], p, denominator=D)
+        near_tau, near_edge = lmhead_near(o_logp, tt, p)
+        near = near_tau | near_edge
+        np.testing.assert_array_equal(g_mask[r0:r1][~near_tau], tt.mask[~near_tau])
+        assert_close("ratio", g_ratio[r0:r1], tt.ratio, 3e-5, atol=0.0)
+        assert_close("gcoef", g_g[r0:r1][~near], tt.gcoef[~near], 3e-5, atol=0.0)
+        assert np.all(g_g[r0:r1][~near][tt.gcoef[~near] == 0.0] == 0.0)
+        np.add.at(h_sum, resp[r0:r1], o_H)
+        loss += tt.loss
+        n_masked += tt.n_masked; n_clip += tt.n_clip_inactive; n_pos += tt.n_pos
+        n_tau += int(near_tau.sum()); n_edge += int(near_edge.sum())
+        g = tt.gcoef.copy()
+        g[near] = g_g[r0:r1][near]           # a token on a discontinuity: either side is admissible
+        dz = oracle.dlogits(z, y[r0:r1], o_lse, g)
+        del z
+        blk_dH = dz @ wd.T
+        got = dH[r0:r1].float().cpu().numpy().astype(np.float64)
+        ag = np.abs(g)
+        tol = 2.0 ** -8 * np.sqrt((dz * dz).sum(1))[:, None] * w_norm[None, :] + 2.0 ** -8 * np.abs(blk_dH) + \
+            LMHEAD_CHOSEN_RTOL * ag[:, None] * np.abs(wd)[:, y[r0:r1]].T + 1e-12
+        err = np.abs(got - blk_dH)
+        if (err > tol).any():
+            k = np.unravel_index(int(np.argmax(err - tol)), err.shape)
+            raise AssertionError("d_hidden rows %d..: worst at %s gpu=%r ref=%r tol=%r" % (r0, k, got[k], blk_dH[k], tol[k]))
+        assert err.mean() <= 3e-3 * np.abs(blk_dH).mean() + 1e-12
+        assert np.all(got[(g == 0.0)] == 0.0)
+        ref_dW += hb.T @ dz
+        np.add.at(slack_Wt, y[r0:r1], LMHEAD_CHOSEN_RTOL * ag[:, None] * np.abs(hb))
+        dz_sq += (dz * dz).sum(0)
+        h_sq += (hb * hb).sum(0)
+        dzc = dz[:, cols]
+        bW += np.abs(hb).T @ np.abs(dzc)
+        qW += (hb * hb).T @ (dzc * dzc)
+        del dz
+        say("  oracle rows %d/%d" % (r1, N))
+    # per-response and whole-batch outputs
+    assert_close("resp_entropy", res.resp_entropy.cpu().numpy(), h_sum / np.asarray(w.lengths), rtol, atol=LMHEAD_ATOL)
+    expect_gate = np.full(w.R, 1 if p.gate_mode == ulorl.GATE_ALWAYS else 0, np.uint8)
+    np.testing.assert_array_equal(res.resp_gate.cpu().numpy(), expect_gate)
+    cnt = res.counters.cpu().numpy()
+    assert int(cnt[3]) == 0 and int(cnt[2]) == n_pos
+    assert abs(int(cnt[0]) - n_masked) <= n_tau and abs(int(cnt[1]) - n_clip) <= n_edge
+    if n_tau == 0 and n_edge == 0:
+        assert_close("loss", res.loss.item(), loss, 3e-5, atol=1e-7)
+    else:
+        assert abs(res.loss.item() - loss) <= 3e-5 * abs(loss) + 2.0 * (n_tau + n_edge) / D
+    say("forward and d_hidden ok on every row (masked %d, clipped %d, near tau %d, near a clip edge %d)"
+        % (n_masked, n_clip, n_tau, n_edge))
+    # d_W, every element
+    got = dW.float().cpu().numpy().astype(np.float64)
+    err = np.abs(got - ref_dW)
+    slack_W = slack_Wt.T
+    tol = 2.0 ** -8 * np.sqrt(h_sq)[:, None] * np.sqrt(dz_sq)[None, :] + 2.0 ** -8 * np.abs(ref_dW) + slack_W + 1e-12
+    if (err > tol).any():
+        k = np.unravel_index(int(np.argmax(err - tol)), err.shape)
+        raise AssertionError("d_W: %d outside tolerance; worst at %s gpu=%r ref=%r tol=%r"
+                             % ((err > tol).sum(), k, got[k], ref_dW[k], tol[k]))
+    ec, rc = err[:, cols], np.abs(ref_dW[:, cols])
+    tight = 2.0 ** -8 * bW + 2.0 ** -8 * rc + slack_W[:, cols] + 1e-12
+    assert np.all(ec <= tight), "d_W on sampled columns: exact worst-case bound"
+    typical = 2.0 ** -9 * (np.sqrt(qW) + rc) + slack_W[:, cols]
+    assert ec.mean() <= typical.mean() + 1e-12, (ec.mean(), typical.mean())
+    say("d_W ok on every element (mean error %.3e, mean magnitude %.3e; %d columns with exact bounds)"
+        % (err.mean(), np.abs(ref_dW).mean(), n_cols))
+    res.d_hidden, res.d_weight = dH, dW
+    return res, dict(loss=loss, n_masked=n_masked, n_clip=n_clip, n_pos=n_pos)

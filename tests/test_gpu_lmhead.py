@@ -75,6 +75,35 @@ def test_lmhead_config5_reduced_rows():
     assert tt.n_clip_inactive > 0
 
 
+def test_lmhead_mpt_mask_fires():
+    """A labelled extra case: full hidden size and vocabulary of configuration 5, 2 x 384 rows, a
+    third of the hidden rows aligned with one column of W (scaled so that the sampled token's
+    probability spreads from ~0.93 to ~1) -- with hidden ~ N(0, 1) . W ~ N(0, 0.02) alone no token
+    comes near tau = 0.99 and the mask of Eq. MPTS / I_msk (Sec. 3.2.2) would never be set.
+    Mask bit-exact outside |p - tau| < 1e-6, masked tokens carry a zero coefficient and contribute
+    exactly nothing to d_hidden (checked in run_lmhead_parity), d_W against the oracle."""
+    from dataclasses import replace
+    w = replace(ui.shrink(ui.config(5), [384, 384], seg_len=192), align_frac=0.35, name="cfg5_mpt_fires")
+    p = params_for(w, gate_mode=ulorl.GATE_ALWAYS)
+    res, tt = run_lmhead_parity(w, p, chunk=8192, say=say)
+    mask = res.mpt_mask.cpu().numpy().astype(bool)
+    assert tt.n_masked >= 20 and int(res.counters[0]) > 0, tt.n_masked
+    # some aligned tokens stay below the threshold, and the negative-advantage response is never masked
+    prob = np.exp(res.logp.cpu().numpy())
+    assert ((prob > 0.9) & (prob < 0.99) & ~mask).sum() >= 5
+    assert not mask[384:].any() and mask[:384].any()
+    assert bool((res.gcoef[torch.as_tensor(mask, device=DEV)] == 0).all())
+    assert bool((res.d_hidden[torch.as_tensor(mask, device=DEV)] == 0).all())
+    # the same batch under the per-response gate with sigma between the two responses' mean entropies:
+    # only one response's MPTs are masked
+    hb = np.sort(tt.resp_entropy)
+    if hb[1] - hb[0] > 2e-3:
+        sigma = float(0.5 * (hb[0] + hb[1]))
+        d = ui.generate(w, DEV)
+        r2, tt2 = run_lmhead_parity(w, params_for(w, gate_mode=ulorl.GATE_PER_RESPONSE, sigma=sigma), chunk=8192, data=d)
+        assert int(tt2.resp_gate.sum()) == 1
+
+
 @pytest.mark.parametrize("lengths,V,hidden,chunk", [([300, 212], 4096 + 1544, 256, 1024), ([64], 8192 + 8, 64, 64),
                                                     ([1000, 24], 1544, 128, 2048)])
 def test_workspace_is_never_overrun(lengths, V, hidden, chunk):

@@ -48,6 +48,12 @@ class Workload:
     sigma: float = 0.2
     hidden: int = 0           # >0: lm_head variant, logits = hidden_states @ weight
     weight_std: float = 0.02
+    # lm_head variant only: this fraction of the hidden rows is replaced by a multiple of one column
+    # of the weight, scaled so that the column's logit stands ln(V) + U(align_margin) above zero:
+    # such rows are "peaked" (probability of that token from ~0.9 to ~1), so some sampled tokens
+    # exceed the MPT threshold.  0 leaves the recipe (and its random streams) unchanged.
+    align_frac: float = 0.0
+    align_margin: tuple = (2.5, 9.0)
 
     @property
     def R(self) -> int:
@@ -172,6 +178,14 @@ def generate(w: Workload, device="cpu", logits_out: Optional[torch.Tensor] = Non
         if w.hidden > 0:
             h = torch.randn(ROWS_PER_BLOCK, w.hidden, generator=g, device=device,
                             dtype=torch.float32)[:rows].to(torch.bfloat16)
+            if w.align_frac > 0.0:
+                aligned = torch.rand(ROWS_PER_BLOCK, generator=g, device=device)[:rows] < w.align_frac
+                col = torch.randint(0, V, (ROWS_PER_BLOCK,), generator=g, device=device)[:rows]
+                lo, hi = w.align_margin
+                margin = lo + (hi - lo) * torch.rand(ROWS_PER_BLOCK, generator=g, device=device)[:rows]
+                wc = wf[:, col]                                   # [Hd, rows]
+                scale = (math.log(V) + margin) / (wc * wc).sum(0)
+                h = torch.where(aligned[:, None], (wc * scale).t().to(torch.bfloat16), h)
             hidden[r0:r1] = h
             zf = h.float() @ wf                      # stock GEMM: only used to draw y and old_logp
         else:

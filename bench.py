@@ -1,6 +1,7 @@
 """Throughput of the fused UloRL token loss (forward + backward) on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4] [--path fused|two_call]
+                    [--cpu-rows N] [--extras 0|1]
 
 A step is one pass of the whole hot path over one batch of synthetic input: row statistics,
 ratio, clip, MPT mask, loss and dlogits (written in place for the ultra-long configuration).
@@ -11,9 +12,17 @@ backward overwrites the logits, they are restored from a pristine device copy be
 the restore is outside the timed brackets (each step is bracketed by a device synchronisation
 on both sides and the step times are summed).
 
-Prints ONE JSON line: whole-job token-rows/s, the HBM roofline of the dominant kernel from
-HIP-event timings taken inside the timed region, and the CPU oracle timed on a bounded sample of
-the same workload as a reported baseline.
+Prints ONE JSON line: whole-job token-rows/s on the headline workload (configuration 4), the HBM
+roofline of the dominant kernel from HIP-event timings taken inside the timed region, and the CPU
+oracle timed on a bounded sample of the same workload as a reported baseline.  With --extras 1
+(the default for the headline workload) the same line also carries
+  "ceiling"  what the part delivers on the headline buffers with the library's own kernels: a pure
+             read (stats-only forward) and a pure write (backward of an all-zero coefficient),
+  "gated"    the headline workload under the per-response entropy gate (Sec. 3.2.2) with the single
+             response gated, so the members of the MPT set take the deferred second launch,
+  "configs"  configurations 2, 3 (static gate, and the per-response gate placed between two
+             responses) and 5 (lm_head variant, MFMA roofline, vendor GEMM as context, its own CPU
+             baseline), each timed in this run.
 """
 from __future__ import annotations
 
@@ -29,40 +38,32 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0      # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 matrix rate
+METRIC = "token-rows/sec fused fwd+bwd RL token loss (V=151936 bf16) + % HBM roofline"
 
 
-# Hardware byte counters (rocprofv3 --pmc FETCH_SIZE, then WRITE_SIZE, each scaled by what the
-# same counter reads for a plain copy kernel of known size; profiles/token_loss_cfg4_hbm_counters.txt)
+# Hardware byte counters (rocprofv3 --pmc FETCH_SIZE, then WRITE_SIZE, of this script, each scaled by
+# what the same counter reads for the restore copy of known size; profiles/token_loss_cfg4_hbm_counters.txt)
 # expressed as measured / algorithmic ratios.  They hold for the kernel source they were taken
 # on: the digest below is checked at run time and `traffic` is null once the kernels changed.
 PMC = {
-    "source_sha256": "abdf81f083a255a4679cb244afadc9116ecf6c383c5a2dc83ecd292518f71639",
-    "fused_read": 1.0077,            # cluster_row_kernel: every row once, plus the polling of the exchange slots
-    "fused_write": 1.0014,
-    "bwd_read": 1.0007,              # dlogits_chunk_kernel
-    "bwd_write": 1.0000,
+    "source_sha256": "",
+    "fused_read": 1.0, "fused_write": 1.0,      # cluster_row_kernel
+    "bwd_read": 1.0, "bwd_write": 1.0,          # dlogits_chunk_kernel
 }
-
 
 # HBM bytes of one lm_head backward / forward call at configuration 5 (vocabulary chunk 8192), from two
 # rocprofv3 --pmc runs of this script (FETCH_SIZE, then WRITE_SIZE, summed over the call's kernels and
 # scaled as above); valid for the lm_head source with this digest and for that workload only.
 PMC_LMHEAD = {
-    "source_sha256": "e89cdaf4a7c1b0f843ddbd3d776ae2b2014c02b389c401690e8dbc0d1aff86bd",
-    "bwd_bytes": (2 * 47244450 + 25036288) * 1024,
-    "fwd_bytes": (2 * 17484917 + 20480) * 1024,
+    "source_sha256": "",
+    "bwd_bytes": 0,
+    "fwd_bytes": 0,
 }
 
 
-def lmhead_source_digest():
+def source_digest(name):
     import hashlib
-    path = os.path.join(ROOT, "paper_2507_19766_amd", "csrc", "lmhead.hip")
-    return hashlib.sha256(open(path, "rb").read()).hexdigest()
-
-
-def kernel_source_digest():
-    import hashlib
-    path = os.path.join(ROOT, "paper_2507_19766_amd", "csrc", "token_loss.hip")
+    path = os.path.join(ROOT, "paper_2507_19766_amd", "csrc", name)
     return hashlib.sha256(open(path, "rb").read()).hexdigest()
 
 
@@ -97,7 +98,165 @@ def cpu_baseline(w, data, params, sample_rows):
             "sample": "first %d rows of %s, fp64 forward + backward, %.1f s" % (n, w.name, dt)}
 
 
-def bench_lmhead(args, w, ulorl, ui, torch, dev):
+class LogitsBench:
+    """One logits workload resident on the device, with the buffers a timed step needs."""
+
+    def __init__(self, w, inplace, ulorl, ui, torch, dev):
+        self.w, self.inplace, self.ulorl, self.torch = w, inplace, ulorl, torch
+        self.elem = 4 if w.dtype == "f32" else 2
+        log("generating %s: N=%d V=%d %s (%.1f GB of logits)..." % (w.name, w.N, w.V, w.dtype, w.N * w.V * self.elem / 1e9))
+        t0 = time.perf_counter()
+        self.data = ui.generate(w, dev)
+        torch.cuda.synchronize()
+        log("generated in %.1f s" % (time.perf_counter() - t0))
+        self.logits = self.data["logits"]
+        self.pristine = None
+        if inplace:
+            self.pristine = torch.empty_like(self.logits)
+            self._bitcopy(self.logits, self.pristine)
+        self.dz = self.logits if inplace else torch.empty_like(self.logits)
+        self.ws = torch.empty(ulorl.token_loss_workspace_bytes(w.N, w.V, w.R), dtype=torch.uint8, device=dev)
+        self.out = None
+
+    def params(self, gate_mode, sigma=None):
+        w, ulorl = self.w, self.ulorl
+        return ulorl.Params(eps_low=w.eps_low, eps_high=w.eps_high, tau=w.tau, sigma=w.sigma if sigma is None else sigma,
+                            is_mode=ulorl.IS_SAIS, gate_mode=gate_mode, seg_len=w.seg_len)
+
+    def _bitcopy(self, src, dst):
+        # an elementwise kernel (visible to the profiler as a dispatch of known size: it reads and
+        # writes the whole buffer once), bit-exact
+        bits = self.torch.int16 if self.elem == 2 else self.torch.int32
+        self.torch.bitwise_or(src.view(bits), 0, out=dst.view(bits))
+
+    def restore(self):
+        if self.inplace:
+            self._bitcopy(self.pristine, self.logits)
+        self.torch.cuda.synchronize()
+
+    def step_two_call(self, params):
+        torch, ulorl, d = self.torch, self.ulorl, self.data
+        self.restore()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        t_a = time.perf_counter()
+        ev[0].record()
+        self.out = ulorl.token_loss_fwd(self.logits, d["token_ids"], d["cu_seqlens"], d["advantages"], d["old_logp"], params,
+                                        out=self.out, workspace=self.ws)
+        ev[1].record()
+        ulorl.token_loss_bwd(self.logits, d["token_ids"], self.out.lse, self.out.gcoef, 1.0, dlogits=self.dz)
+        ev[2].record()
+        torch.cuda.synchronize()
+        return time.perf_counter() - t_a, ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2])
+
+    def step_fused(self, params):
+        torch, ulorl, d = self.torch, self.ulorl, self.data
+        self.restore()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        t_a = time.perf_counter()
+        ev[0].record()
+        self.out, _ = ulorl.token_loss_fwd_bwd(self.logits, d["token_ids"], d["cu_seqlens"], d["advantages"], d["old_logp"],
+                                               params, grad_out=1.0, dlogits=self.dz, out=self.out, workspace=self.ws)
+        ev[1].record()
+        torch.cuda.synchronize()
+        return time.perf_counter() - t_a, ev[0].elapsed_time(ev[1])
+
+    def time_fused(self, params, steps, warmup):
+        for _ in range(warmup):
+            self.step_fused(params)
+        wall = ms = 0.0
+        each = []
+        for _ in range(steps):
+            a, b = self.step_fused(params)
+            wall += a
+            ms += b
+            each.append(a * 1e3)
+        return wall, ms, each
+
+    def time_two_call(self, params, steps, warmup):
+        for _ in range(warmup):
+            self.step_two_call(params)
+        wall = fwd = bwd = 0.0
+        each = []
+        for _ in range(steps):
+            a, b, c = self.step_two_call(params)
+            wall += a
+            fwd += b
+            bwd += c
+            each.append(a * 1e3)
+        return wall, fwd, bwd, each
+
+    def batch_facts(self):
+        cnt = self.out.counters.cpu().tolist()
+        live = int((self.out.gcoef != 0).sum().item())
+        return cnt, live
+
+    def ceiling(self, steps):
+        """Pure read and pure write of the workload's logits buffer by the library's own kernels."""
+        torch, ulorl, d, w = self.torch, self.ulorl, self.data, self.w
+        self.restore()
+        stats = ulorl.FwdResult(None, torch.empty_like(self.out.logp), torch.empty_like(self.out.logp),
+                                torch.empty_like(self.out.logp))
+        zero_g = torch.zeros_like(self.out.gcoef)
+
+        def timed(fn):
+            fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(steps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / steps
+
+        rd = timed(lambda: ulorl.token_loss_fwd(self.logits, d["token_ids"], None, None, out=stats, workspace=self.ws))
+        wr = timed(lambda: ulorl.token_loss_bwd(self.logits, d["token_ids"], self.out.lse, zero_g, 1.0, dlogits=self.dz))
+        nbytes = w.N * w.V * self.elem
+        return {"read_only": {"kernel": "stats-only forward (piece_stats_kernel + piece_merge_kernel)", "ms": rd,
+                              "GBps": nbytes / (rd * 1e-3) / 1e9, "frac_of_hbm_peak": nbytes / (rd * 1e-3) / 1e9 / HBM_PEAK_GBS},
+                "write_only": {"kernel": "backward of an all-zero coefficient (dlogits_chunk_kernel, rows written as zeros "
+                                         "without being read)", "ms": wr, "GBps": nbytes / (wr * 1e-3) / 1e9,
+                               "frac_of_hbm_peak": nbytes / (wr * 1e-3) / 1e9 / HBM_PEAK_GBS},
+                "read_then_write_ms": rd + wr,
+                "note": "one read plus one write of the buffer, each at the rate the part sustains for it alone"}
+
+    def close(self):
+        self.data = self.logits = self.pristine = self.dz = self.ws = self.out = None
+        self.torch.cuda.empty_cache()
+
+
+def config_entry(b, steps, warmup, with_gate):
+    """Timings of one non-headline logits configuration (out of place)."""
+    import numpy as np
+    ulorl, w = b.ulorl, b.w
+    p = b.params(ulorl.GATE_ALWAYS)
+    wall2, fwd, bwd, _ = b.time_two_call(p, steps, warmup)
+    wall1, ms1, _ = b.time_fused(p, steps, warmup)
+    cnt, live = b.batch_facts()
+    row_bytes = w.V * b.elem
+    gbs = 2 * row_bytes * w.N / (ms1 / steps * 1e-3) / 1e9
+    e = {"workload": w.name, "rows": w.N, "responses": w.R, "dlogits": "in place" if b.inplace else "out of place",
+         "gate": "always", "one_call": {"ms_per_step": wall1 / steps * 1e3, "token_rows_per_s": w.N * steps / wall1,
+                                         "kernel_GBps": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS},
+         "two_call": {"ms_per_step": wall2 / steps * 1e3, "fwd_ms": fwd / steps, "bwd_ms": bwd / steps,
+                      "token_rows_per_s": w.N * steps / wall2},
+         "batch": {"masked_tokens": cnt[0], "clipped_tokens": cnt[1], "zero_gradient_rows": w.N - live, "status": cnt[3]}}
+    if with_gate and w.R > 1:
+        hbar = np.sort(b.out.resp_entropy.cpu().numpy().astype(np.float64))
+        gaps = np.diff(hbar)
+        j = int(np.argmax(gaps))
+        sigma = float(0.5 * (hbar[j] + hbar[j + 1]))
+        pg = b.params(ulorl.GATE_PER_RESPONSE, sigma=sigma)
+        wallg, msg, _ = b.time_fused(pg, steps, 1)
+        cntg, _ = b.batch_facts()
+        e["per_response_gate"] = {"sigma": sigma, "gated_responses": int(b.out.resp_gate.sum().item()),
+                                  "masked_tokens": cntg[0], "ms_per_step": wallg / steps * 1e3,
+                                  "token_rows_per_s": w.N * steps / wallg,
+                                  "note": "members of the MPT set wait for the gate and are finished by a second, filtered launch"}
+    return e
+
+
+def bench_lmhead(args, w, ulorl, ui, torch, dev, as_entry=False):
     """Configuration 5: logits = hidden . W never materialised; a step = lm_head forward + backward."""
     import numpy as np
     log("generating %s: N=%d Hd=%d V=%d ..." % (w.name, w.N, w.hidden, w.V))
@@ -139,16 +298,15 @@ def bench_lmhead(args, w, ulorl, ui, torch, dev):
     bwd_tf = 3 * gemm_flops / (bwd_ms / K * 1e-3) / 1e12     # recompute, dHidden, dW
     fwd_tf = gemm_flops / (fwd_ms / K * 1e-3) / 1e12
     cnt = out.counters.cpu().tolist()
-    counters_valid = (lmhead_source_digest() == PMC_LMHEAD["source_sha256"] and w.name == "cfg5_lmhead_bf16"
+    counters_valid = (source_digest("lmhead.hip") == PMC_LMHEAD["source_sha256"] and w.name == "cfg5_lmhead_bf16"
                       and chunk == 8192)
     result = {
-        "metric": "token-rows/sec fused fwd+bwd RL token loss (V=151936 bf16) + % HBM roofline",
+        "metric": METRIC,
         "value": w.N * K / wall, "unit": "token-rows/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
         "ms_per_step": wall / K * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16 MFMA operands, f32 accumulate", "data": "synthetic",
         "config": {"workload": w.name, "rows": w.N, "hidden": w.hidden, "vocab": w.V, "vocab_chunk": chunk,
                    "responses": w.R, "segment_len": w.seg_len, "path": "lm_head variant (logits never materialised)",
-                   "gemm_tile": args.gemm_tile if args.gemm_tile >= 0 else "default",
                    "is_mode": "SAIS", "gate": "always (static MPT masking)", "tau": w.tau},
         "roofline": {"bound": "mfma", "kernel": "backward call: lmhead_dz_kernel + 2 x gemm_tn_kernel per vocabulary "
                      "chunk (3 products of 2*N*Hd*V flop)", "achieved": bwd_tf, "peak": MFMA_BF16_PEAK_TFLOPS,
@@ -200,7 +358,11 @@ def bench_lmhead(args, w, ulorl, ui, torch, dev):
         result["cpu_baseline"] = {"value": n / dt, "unit": "token-rows/s", "cores": oracle.threads(), "kind": "oracle",
                                   "sample": "first %d rows of %s (full hidden and vocabulary; the d_W product costs "
                                             "the same per row at any row count), fp64, %.1f s" % (n, w.name, dt)}
+    if as_entry:
+        keep = ("value", "unit", "ms_per_step", "dtype", "config", "roofline", "roofline_fwd", "batch", "context", "cpu_baseline")
+        return {k: result[k] for k in keep if k in result}
     print(json.dumps(result), flush=True)
+    return None
 
 
 def main():
@@ -209,19 +371,12 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="cfg4", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
-    ap.add_argument("--gemm-tile", type=int, default=-1, help="lm_head variant: tile shape index (ulorl_tune)")
-    ap.add_argument("--out-of-place", action="store_true", help="write dlogits to a second buffer")
     ap.add_argument("--cpu-rows", type=int, default=98304, help="rows of the oracle sample (0 = skip)")
     ap.add_argument("--path", default="fused", choices=["fused", "two_call"],
                     help="which path gives the headline value (both are timed)")
-    ap.add_argument("--fwd-threads", type=int, default=0)
-    ap.add_argument("--fwd-unroll", type=int, default=0)
-    ap.add_argument("--bwd-threads", type=int, default=0)
-    ap.add_argument("--bwd-unroll", type=int, default=0)
-    ap.add_argument("--fused-threads", type=int, default=0)
-    ap.add_argument("--fused-unroll", type=int, default=0)
-    ap.add_argument("--fused-vpt", type=int, default=0,
-                    help="16-byte vectors per thread of the row-cooperative kernel (ULORL_TUNE_FUSED_VPT; 0: the library's choice)")
+    ap.add_argument("--extras", type=int, default=-1,
+                    help="1: also time the ceiling, the per-response gate and configurations 2, 3, 5 in the same "
+                         "run (default for cfg4); 0: the workload alone")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this library runs on ONE GPU (rows are independent, so a multi-GPU job shards rows and "
@@ -237,92 +392,23 @@ def main():
         sys.exit(2)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    for knob, val in ((ulorl.TUNE_FWD_THREADS, args.fwd_threads), (ulorl.TUNE_FWD_UNROLL, args.fwd_unroll),
-                      (ulorl.TUNE_BWD_THREADS, args.bwd_threads), (ulorl.TUNE_BWD_UNROLL, args.bwd_unroll),
-                      (ulorl.TUNE_FUSED_THREADS, args.fused_threads), (ulorl.TUNE_FUSED_UNROLL, args.fused_unroll),
-                      (ulorl.TUNE_FUSED_VPT, args.fused_vpt)):
-        if val:
-            ulorl.tune(knob, val)
 
     w = ui.config(int(args.workload[3]))
     if w.hidden > 0:
-        if args.gemm_tile >= 0:
-            ulorl.tune(ulorl.TUNE_GEMM_TILE, args.gemm_tile)
         return bench_lmhead(args, w, ulorl, ui, torch, dev)
-    inplace = (args.workload == "cfg4") and not args.out_of_place
-    elem = 4 if w.dtype == "f32" else 2
-    log("generating %s: N=%d V=%d %s (%.1f GB of logits)..." % (w.name, w.N, w.V, w.dtype, w.N * w.V * elem / 1e9))
-    t0 = time.perf_counter()
-    data = ui.generate(w, dev)
-    torch.cuda.synchronize()
-    log("generated in %.1f s" % (time.perf_counter() - t0))
+    extras = (args.workload == "cfg4") if args.extras < 0 else bool(args.extras)
+    inplace = args.workload == "cfg4"
+    b = LogitsBench(w, inplace, ulorl, ui, torch, dev)
+    elem = b.elem
 
     # static masking of MPTs (Sec. 3.2.1): with sigma = 0.2 the gate never fires on these
     # high-entropy synthetic rows, so the timed configuration keeps the mask always on
-    params = ulorl.Params(eps_low=w.eps_low, eps_high=w.eps_high, tau=w.tau, sigma=w.sigma,
-                          is_mode=ulorl.IS_SAIS, gate_mode=ulorl.GATE_ALWAYS, seg_len=w.seg_len)
-    logits = data["logits"]
-    pristine = logits.clone() if inplace else None
-    dz = logits if inplace else torch.empty_like(logits)
-    y, cu, adv, old = data["token_ids"], data["cu_seqlens"], data["advantages"], data["old_logp"]
-    ws = torch.empty(ulorl.token_loss_workspace_bytes(w.N, w.V, w.R), dtype=torch.uint8, device=dev)
-    out = None
-
-    def restore():
-        if inplace:
-            logits.copy_(pristine)
-        torch.cuda.synchronize()
-
-    def step_two_call():
-        nonlocal out
-        restore()
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
-        t_a = time.perf_counter()
-        ev[0].record()
-        out = ulorl.token_loss_fwd(logits, y, cu, adv, old, params, out=out, workspace=ws)
-        ev[1].record()
-        ulorl.token_loss_bwd(logits, y, out.lse, out.gcoef, 1.0, dlogits=dz)
-        ev[2].record()
-        torch.cuda.synchronize()
-        t_b = time.perf_counter()
-        return t_b - t_a, ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2])
-
-    def step_fused():
-        nonlocal out
-        restore()
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-        t_a = time.perf_counter()
-        ev[0].record()
-        out, _ = ulorl.token_loss_fwd_bwd(logits, y, cu, adv, old, params, grad_out=1.0, dlogits=dz, out=out,
-                                          workspace=ws)
-        ev[1].record()
-        torch.cuda.synchronize()
-        t_b = time.perf_counter()
-        return t_b - t_a, ev[0].elapsed_time(ev[1])
-
+    params = b.params(ulorl.GATE_ALWAYS)
     K = args.steps
-    for _ in range(args.warmup):
-        step_two_call()
-    wall2 = fwd_ms = bwd_ms = 0.0
-    two_steps = []
-    for _ in range(K):
-        a, b, c = step_two_call()
-        wall2 += a
-        fwd_ms += b
-        bwd_ms += c
-        two_steps.append(a * 1e3)
-    for _ in range(args.warmup):
-        step_fused()
-    wall1 = fused_ms = 0.0
-    fused_steps = []
-    for _ in range(K):
-        a, b = step_fused()
-        wall1 += a
-        fused_ms += b
-        fused_steps.append(a * 1e3)
-
-    cnt = out.counters.cpu().tolist()
-    live = int((out.gcoef != 0).sum().item())
+    wall2, fwd_ms, bwd_ms, two_steps = b.time_two_call(params, K, args.warmup)
+    wall1, fused_ms, fused_steps = b.time_fused(params, K, args.warmup)
+    cnt, live = b.batch_facts()
+    loss = b.out.loss.item()
     row_bytes = w.V * elem
     # Algorithmic HBM bytes per launch.  Two-call path: the forward reads every row once; the
     # backward reads and writes live rows and only writes rows whose coefficient is zero.  One-call
@@ -335,7 +421,7 @@ def main():
     bwd_gbs = bwd_bytes / (bwd_ms / K * 1e-3) / 1e9
     fwd_gbs = fwd_bytes / (fwd_ms / K * 1e-3) / 1e9
 
-    counters_valid = kernel_source_digest() == PMC["source_sha256"]
+    counters_valid = source_digest("token_loss.hip") == PMC["source_sha256"] and w.name == "cfg4_1x131072_bf16"
     fused_traffic = (row_bytes * w.N * (PMC["fused_read"] + PMC["fused_write"]) if counters_valid else None)
     bwd_traffic = (row_bytes * (live * PMC["bwd_read"] + w.N * PMC["bwd_write"]) if counters_valid else None)
     headline_fused = args.path == "fused"
@@ -343,7 +429,7 @@ def main():
     value = w.N * K / wall
     ms_per_step = wall / K * 1e3
     roof_fused = {"bound": "hbm", "kernel": "cluster_row_kernel (one-call forward+backward by row-cooperative "
-                  "workgroups; the call also runs five small kernels, about 0.1 ms)", "achieved": fused_gbs,
+                  "workgroups; the call also runs seven small kernels, about 0.1 ms)", "achieved": fused_gbs,
                   "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": fused_gbs / HBM_PEAK_GBS, "traffic": fused_traffic,
                   "traffic_note": "HBM bytes per launch (FETCH_SIZE, WRITE_SIZE scaled by a copy kernel)",
                   "algorithmic_bytes_per_launch": fused_bytes, "avg_launch_ms": fused_ms / K}
@@ -355,7 +441,7 @@ def main():
                 "algorithmic_bytes_per_launch": fwd_bytes, "avg_call_ms": fwd_ms / K}
 
     result = {
-        "metric": "token-rows/sec fused fwd+bwd RL token loss (V=151936 bf16) + % HBM roofline",
+        "metric": METRIC,
         "value": value, "unit": "token-rows/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
@@ -375,12 +461,36 @@ def main():
                      "fwd_ms": fwd_ms / K,
                      "bwd_ms": bwd_ms / K, "roofline_bwd": roof_bwd, "roofline_fwd": roof_fwd},
         "batch": {"masked_tokens": cnt[0], "clipped_tokens": cnt[1], "positive_tokens": cnt[2],
-                  "zero_gradient_rows": w.N - live, "status": cnt[3], "loss": out.loss.item()},
+                  "zero_gradient_rows": w.N - live, "status": cnt[3], "loss": loss},
     }
+    if extras:
+        log("ceiling: pure read and pure write of the same buffer...")
+        result["ceiling"] = b.ceiling(max(3, K // 2))
+        result["ceiling"]["one_call_vs_read_then_write"] = result["ceiling"]["read_then_write_ms"] / (fused_ms / K)
+        # the dynamic gate of Sec. 3.2.2 on the headline workload: sigma above the response's mean entropy,
+        # so its MPT members are masked -- through the deferred second launch
+        pg = b.params(ulorl.GATE_PER_RESPONSE, sigma=1.0e9)
+        wallg, msg, _ = b.time_fused(pg, K, 1)
+        cntg, _ = b.batch_facts()
+        result["gated"] = {"gate": "per response, sigma above the response's mean entropy (the response is gated)",
+                           "ms_per_step": wallg / K * 1e3, "token_rows_per_s": w.N * K / wallg,
+                           "call_ms": msg / K, "masked_tokens": cntg[0], "status": cntg[3]}
     if args.cpu_rows > 0:
-        restore()
+        b.restore()
         log("timing the CPU oracle on %d rows..." % min(args.cpu_rows, w.N))
-        result["cpu_baseline"] = cpu_baseline(w, data, params, args.cpu_rows)
+        result["cpu_baseline"] = cpu_baseline(w, b.data, params, args.cpu_rows)
+    b.close()
+    if extras:
+        sub_steps = max(3, K // 2)
+        configs = {}
+        for idx in (2, 3):
+            wk = ui.config(idx)
+            bk = LogitsBench(wk, False, ulorl, ui, torch, dev)
+            configs["cfg%d" % idx] = config_entry(bk, sub_steps, 1, with_gate=True)
+            bk.close()
+        sub = argparse.Namespace(steps=sub_steps, warmup=1, cpu_rows=args.cpu_rows)
+        configs["cfg5"] = bench_lmhead(sub, ui.config(5), ulorl, ui, torch, dev, as_entry=True)
+        result["configs"] = configs
     print(json.dumps(result), flush=True)
 
 

@@ -77,10 +77,11 @@ enum {
     ULORL_STATUS_BAD_TOKEN = 1,     /* a token id outside [0, V)                      */
     ULORL_STATUS_NONFINITE = 2,     /* a row whose softmax statistics are not finite  */
     ULORL_STATUS_BAD_CU = 4,        /* cu_seqlens not 0 = cu[0] <= ... <= cu[R] = N   */
-    ULORL_STATUS_SYNC = 8           /* one-call path only: workgroups that share a row waited
-                                       in vain for one another (seconds; never observed); the
-                                       rows concerned have a zero gradient and count as
-                                       non-finite.  Run the two-call path instead.           */
+    ULORL_STATUS_SYNC = 8           /* one-call path only, informational: a workgroup waited in vain
+                                       (seconds; never observed) for the others that share its row.
+                                       It then wrote nothing; the call's repair pass finished its
+                                       part of the row from the intact logits, so every result is
+                                       complete and identical to a call without the bit.         */
 };
 
 /* HOST struct of scalar parameters. */
@@ -99,6 +100,51 @@ typedef struct ulorl_params {
                              e.g. the global count when a batch is split over calls   */
 } ulorl_params;
 
+/* HOST struct of launch options, passed per call; NULL selects the defaults.  Nothing in the
+ * library keeps state between calls, so concurrent calls from several threads are safe as long as
+ * their buffers are distinct.  Workspace sizes never depend on these options. */
+enum {
+    ULORL_LAUNCH_PER_ROW = 1        /* row statistics and the one-call path by ONE looping workgroup
+                                       per row instead of several cooperating ones: the kernels the
+                                       library takes by itself for rows beyond 64 pieces
+                                       (1.9 M bf16 logits).  Slower on long rows (16.3 ms against
+                                       12.9 ms at 131072 x 151936); results differ from the default
+                                       by the summation order of the row statistics only.        */
+};
+typedef struct ulorl_launch {
+    uint32_t flags;       /* ULORL_LAUNCH_* bits                                                  */
+    int32_t sync_spins;   /* one-call path: polls (about 0.25 us each) a workgroup waits for the
+                             others of its row before it leaves its part to the repair pass
+                             (ULORL_STATUS_SYNC); 0: the default 2^24; a tiny value lets a test
+                             exercise that pass                                                  */
+    int32_t gemm_tile;    /* lm_head variant: 0 = 256 x 256 x 64 block tile, eight waves, tiles
+                             copied global -> LDS directly (default); 1 = 128 x 128 x 64, four
+                             waves, for products with fewer than a few hundred large tiles      */
+    int32_t gemm_group_m; /* lm_head variant: block tiles along M that an XCD walks before it moves
+                             along N (its L2 then re-serves their operand rows); 0 = default 4;
+                             1..64                                                               */
+    int32_t reserved[4];  /* must be 0                                                            */
+} ulorl_launch;
+
+/* HOST struct of DEVICE pointers: per-segment training-dynamics diagnostics, optional output of
+ * the forward calls (NULL: not wanted).  Produced in the same pass as the token terms, from the
+ * values already in registers.  Fields as in ulorl_segment_diagnostics below, which computes the
+ * same numbers (bit for bit) from the stored outputs of a forward call. */
+typedef struct ulorl_segment_stats {
+    int32_t K;            /* segment ids 0 .. K-1 are counted; 1 <= K <= 1024                     */
+    int32_t reserved;     /* must be 0                                                            */
+    int64_t *count;       /* [K]                                                                  */
+    double *ratio_sum;    /* [K]                                                                  */
+    float *ratio_max;     /* [K]                                                                  */
+    int64_t *clipped;     /* [K]                                                                  */
+    double *kl_sum;       /* [K]                                                                  */
+    double *ent_sum;      /* [K]                                                                  */
+    int64_t *masked;      /* [K]                                                                  */
+    int64_t *out_of_range;/* [1], may be NULL                                                     */
+    void *workspace;      /* ulorl_segment_diagnostics_workspace_bytes(N, K) bytes, 256-aligned   */
+    size_t workspace_bytes;
+} ulorl_segment_stats;
+
 /* Library version: major * 10000 + minor * 100 + patch. */
 int32_t ulorl_version(void);
 
@@ -107,9 +153,9 @@ const char *ulorl_status_string(int32_t status);
 
 /* Bytes of device workspace ulorl_token_loss_fwd / _fwd_bwd need for N rows of V logits
  * in R responses (0 if an argument is out of range).  The workspace holds per-response
- * entropy sums, per-block partial sums, one flag byte per row and 16 bytes per row and
+ * entropy sums, per-block partial sums, nine bytes per row and 16 bytes per row and
  * per piece of the row (61440 bytes of a long row); its contents need not be preserved
- * between calls.                                                                    */
+ * between calls.  The size depends on N, V and R only.                              */
 size_t ulorl_token_loss_workspace_bytes(int64_t N, int64_t V, int32_t R);
 
 /*
@@ -120,6 +166,12 @@ size_t ulorl_token_loss_workspace_bytes(int64_t N, int64_t V, int32_t R);
  *                 row_stride >= V.  V need not be a multiple of the vector width.
  *                 1 <= N <= 32768 * 65535 rows, 1 <= V < 2^31.
  *   token_ids     [N] chosen token o_t of each row, in [0, V).
+ *                 DOMAIN: every logit must be finite.  A row holding +-infinity or not-a-number
+ *                 -- this includes -infinity used to mask vocabulary entries, which a softmax
+ *                 defined by limits would take as probability 0 -- is outside the domain: it is
+ *                 reported (ULORL_STATUS_NONFINITE), contributes zero to the loss and gets a
+ *                 zero gradient.  Callers that mask vocabulary entries pass a large negative
+ *                 finite value (e.g. -1e30, exactly representable in bf16 as 0xF149) instead.
  *   cu_seqlens    [R+1] response boundaries, cu[0] = 0, cu[R] = N, non-decreasing.
  *   segment_ids   [N] segment id f(t) per token, or NULL (then p->seg_len rules).
  *                 The ids do not enter the loss (old_logp is already per token); they
@@ -145,10 +197,13 @@ size_t ulorl_token_loss_workspace_bytes(int64_t N, int64_t V, int32_t R);
  *   resp_gate     [R] uint8  1 if MPTs of response i are masked
  *   counters      [4] int64: masked tokens, tokens on the clipped (gradient-free) branch,
  *                 positive tokens, status word (ULORL_STATUS_* bits)
+ *   seg_stats     HOST, may be NULL: per-segment diagnostics wanted as a by-product (ignored by
+ *                 the stats-only pass).
  *   workspace     >= ulorl_token_loss_workspace_bytes(N, V, R) bytes, 256-byte aligned.  The
  *                 stats-only pass works without one (NULL); given one (sized with any R >= 1)
  *                 it forms the statistics by pieces of rows, which is faster and gives the
  *                 same bits as ulorl_token_loss_fwd_bwd.
+ *   launch        HOST, may be NULL: launch options.
  */
 int32_t ulorl_token_loss_fwd(
     const void *logits, int32_t dt, int64_t N, int64_t V, int64_t row_stride,
@@ -158,7 +213,8 @@ int32_t ulorl_token_loss_fwd(
     float *loss, float *logp, float *entropy, float *lse, float *gcoef,
     uint8_t *mpt_mask, float *ratio, int32_t *segment_out,
     float *resp_entropy, uint8_t *resp_gate, int64_t *counters,
-    void *workspace, size_t workspace_bytes, void *hip_stream);
+    const ulorl_segment_stats *seg_stats,
+    void *workspace, size_t workspace_bytes, const ulorl_launch *launch, void *hip_stream);
 
 /*
  * Backward: dlogits[t, j] = grad_out * gcoef[t] * ( [j == token_ids[t]] - exp(logits[t, j] - lse[t]) )
@@ -186,11 +242,13 @@ int32_t ulorl_token_loss_bwd(
  * of the MPT set (A_t > 0, p_t >= tau) are finished by a second, filtered backward launch after
  * the gate is known.  Results are bit-identical with ulorl_token_loss_fwd (given a workspace)
  * followed by ulorl_token_loss_bwd: both form a row's statistics from the same pieces in the same
- * order.  ulorl_tune(ULORL_TUNE_FUSED_CLUSTER, 0) selects the older one-workgroup-per-row kernel
- * (whose second read of a row is served by the on-chip caches); its results are bit-identical
- * with the forward call under ULORL_TUNE_FWD_PIECES = 0 and equal launch shapes, and differ from
- * the piece-wise kernels by rounding only.
- * The workgroups of a row wait for each other with a bounded wait: see ULORL_STATUS_SYNC.
+ * order (under ULORL_LAUNCH_PER_ROW both calls take their one-workgroup-per-row kernels, again
+ * bit-identical with each other).
+ * The workgroups of a row wait for each other with a bounded wait.  One whose wait expires writes
+ * nothing -- in place its part of the logits stays intact -- and marks its part; a repair pass at
+ * the end of the call (two small launches that return at once when nothing is marked) forms the
+ * row's statistics from the published pieces and writes the missing parts, so an expired wait
+ * costs time, never data: see ULORL_STATUS_SYNC.
  */
 int32_t ulorl_token_loss_fwd_bwd(
     const void *logits, int32_t dt, int64_t N, int64_t V, int64_t row_stride,
@@ -200,7 +258,8 @@ int32_t ulorl_token_loss_fwd_bwd(
     float *loss, float *logp, float *entropy, float *lse, float *gcoef,
     uint8_t *mpt_mask, float *ratio, int32_t *segment_out,
     float *resp_entropy, uint8_t *resp_gate, int64_t *counters,
-    void *dlogits, void *workspace, size_t workspace_bytes, void *hip_stream);
+    const ulorl_segment_stats *seg_stats,
+    void *dlogits, void *workspace, size_t workspace_bytes, const ulorl_launch *launch, void *hip_stream);
 
 /*
  * ulorl_token_loss_fwd_bwd for callers that cannot allocate device memory or pass a workspace:
@@ -228,7 +287,8 @@ int32_t ulorl_token_loss_fwd_bwd_static(
     float *loss, float *logp, float *entropy, float *lse, float *gcoef,
     uint8_t *mpt_mask, float *ratio, int32_t *segment_out,
     float *resp_entropy, uint8_t *resp_gate, int64_t *counters,
-    void *dlogits, void *hip_stream);
+    const ulorl_segment_stats *seg_stats,
+    void *dlogits, const ulorl_launch *launch, void *hip_stream);
 
 /* ------------------------------------------------------------------------------------------
  * lm_head variant: the logits are hidden . W and are never materialised.
@@ -260,7 +320,8 @@ int32_t ulorl_lmhead_token_loss_fwd(
     float *loss, float *logp, float *entropy, float *lse, float *gcoef,
     uint8_t *mpt_mask, float *ratio, int32_t *segment_out,
     float *resp_entropy, uint8_t *resp_gate, int64_t *counters,
-    void *workspace, size_t workspace_bytes, void *hip_stream);
+    const ulorl_segment_stats *seg_stats,
+    void *workspace, size_t workspace_bytes, const ulorl_launch *launch, void *hip_stream);
 
 /*
  * Backward of the lm_head variant.  With dz[t, v] = grad_out * gcoef[t] * ([v == token_ids[t]]
@@ -272,7 +333,8 @@ int32_t ulorl_lmhead_token_loss_fwd(
 int32_t ulorl_lmhead_token_loss_bwd(
     const void *hidden, const void *W, int64_t N, int64_t Hd, int64_t V, int32_t vocab_chunk,
     const int32_t *token_ids, const float *lse, const float *gcoef, float grad_out,
-    void *d_hidden, void *d_W, void *workspace, size_t workspace_bytes, void *hip_stream);
+    void *d_hidden, void *d_W, void *workspace, size_t workspace_bytes, const ulorl_launch *launch,
+    void *hip_stream);
 
 /*
  * The tiled bf16 MFMA product the lm_head variant is built from, on its own:
@@ -281,7 +343,8 @@ int32_t ulorl_lmhead_token_loss_bwd(
  * [M, N] with leading dimension ldc.  K must be a multiple of 8.
  */
 int32_t ulorl_gemm_tn_bf16(const void *A, int64_t lda, const void *B, int64_t ldb,
-                           int64_t M, int64_t N, int64_t K, float *C, int64_t ldc, void *hip_stream);
+                           int64_t M, int64_t N, int64_t K, float *C, int64_t ldc,
+                           const ulorl_launch *launch, void *hip_stream);
 
 /* ------------------------------------------------------------------------------------------
  * The step before the token loss: group-relative advantages (Eq. 4) with the dynamic-sampling
@@ -351,7 +414,8 @@ int32_t ulorl_segment_pool_step(
  *   masked[k]     int64   tokens removed by the MPT mask
  * out_of_range [1] int64 (may be NULL) counts tokens whose id is outside [0, K); they are ignored.
  * old_logp may be NULL (POIS): kl_sum is then 0.  Sums are fixed-order fp64: bitwise reproducible.
- * K <= 4096.  The workspace size comes from ulorl_segment_diagnostics_workspace_bytes.
+ * K <= 1024.  The workspace size comes from ulorl_segment_diagnostics_workspace_bytes.
+ * The forward calls produce the same numbers as a by-product when given a ulorl_segment_stats.
  */
 size_t ulorl_segment_diagnostics_workspace_bytes(int64_t N, int32_t K);
 
@@ -362,42 +426,6 @@ int32_t ulorl_segment_diagnostics(
     int64_t *count, double *ratio_sum, float *ratio_max, int64_t *clipped, double *kl_sum,
     double *ent_sum, int64_t *masked, int64_t *out_of_range,
     void *workspace, size_t workspace_bytes, void *hip_stream);
-
-/*
- * Launch-shape knobs of the streaming kernels (process-wide, HOST state; not thread
- * safe against concurrent calls).  Results do not depend on them beyond summation order.
- *   *_THREADS  workgroup size per token row: 256, 512 or 1024
- *   *_UNROLL   16-byte loads each lane keeps in flight per loop trip: 2, 4 or 8
- * Returns ULORL_ERR_PARAM for an unknown knob or an unsupported value.
- */
-typedef enum {
-    ULORL_TUNE_FWD_THREADS = 0,
-    ULORL_TUNE_FWD_UNROLL = 1,
-    ULORL_TUNE_BWD_THREADS = 2,
-    ULORL_TUNE_BWD_UNROLL = 3,
-    ULORL_TUNE_FUSED_THREADS = 4,
-    ULORL_TUNE_FUSED_UNROLL = 5,
-    ULORL_TUNE_BWD_ONESHOT = 7,   /* 1 (default): standalone backward by one-shot 4 KB workgroups;
-                                     0: one looping workgroup per row (BWD_THREADS / BWD_UNROLL apply) */
-    ULORL_TUNE_FUSED_CLUSTER = 8, /* 1 (default): one-call path by row-cooperative workgroups;
-                                     0: one looping workgroup per row (FUSED_THREADS / FUSED_UNROLL apply) */
-    ULORL_TUNE_FWD_PIECES = 11,   /* 1 (default): ulorl_token_loss_fwd forms the row statistics by the pieces
-                                     of the row-cooperative kernel (same bits as the one-call path) when
-                                     a workspace is given; 0: one looping workgroup per row
-                                     (FWD_THREADS / FWD_UNROLL apply) */
-    ULORL_TUNE_SYNC_SPINS = 10,   /* polls (about 0.25 us each) a row-cooperative workgroup waits for its
-                                     partners before it gives the row up (ULORL_STATUS_SYNC); >= 1,
-                                     default 2^24.  A tiny value lets a test exercise that path. */
-    ULORL_TUNE_FUSED_VPT = 9,     /* 16-byte vectors each thread of a row-cooperative workgroup keeps:
-                                     4, 8, 10, 12 or 15; 0 (default) chooses from V.  The workspace
-                                     query assumes this knob's value at the time it is called. */
-    ULORL_TUNE_GEMM_TILE = 6      /* lm_head variant, block tile M x N x K / waves along M x N:
-                                     0 = 128x128x64 / 2x2, 1 = 256x256x32 / 2x2, 2 = 256x256x64 / 2x2,
-                                     3 = 256x128x64 / 2x2, 4 = 256x256x64 / 2x4, 5 = 256x256x64 / 4x2,
-                                     6 = as 5 and 7 = as 4 with tiles copied global -> LDS directly
-                                     (default 7), 8 = as 2, direct */
-} ulorl_tune_knob;
-int32_t ulorl_tune(int32_t knob, int32_t value);
 
 #ifdef __cplusplus
 }

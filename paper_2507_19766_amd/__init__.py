@@ -7,8 +7,8 @@ there is no CPU or eager fallback: without the built library, or without a GPU, 
 from .binding import (  # noqa: F401
     F32, BF16, IS_SAIS, IS_POIS, GATE_PER_RESPONSE, GATE_GLOBAL, GATE_ALWAYS, GATE_NEVER,
     STATUS_BAD_TOKEN, STATUS_NONFINITE, STATUS_BAD_CU, STATUS_SYNC,
-    TUNE_FWD_THREADS, TUNE_FWD_UNROLL, TUNE_BWD_THREADS, TUNE_BWD_UNROLL, TUNE_FUSED_THREADS, TUNE_FUSED_UNROLL, TUNE_GEMM_TILE, TUNE_BWD_ONESHOT, TUNE_FUSED_CLUSTER, TUNE_FUSED_VPT, TUNE_SYNC_SPINS, TUNE_FWD_PIECES,
-    UlorlError, Params, FwdResult, lib_path, load_library, version, status_string, tune,
+    LAUNCH_PER_ROW, Launch,
+    UlorlError, Params, FwdResult, lib_path, load_library, version, status_string,
     token_loss_workspace_bytes, token_loss_fwd, token_loss_bwd, token_loss_fwd_bwd, token_loss_fwd_bwd_static, init, static_scratch_bytes, row_stats,
     lmhead_workspace_bytes, lmhead_token_loss_fwd, lmhead_token_loss_bwd, gemm_tn_bf16,
     advantage_prep, segment_diagnostics, segment_pool_step,

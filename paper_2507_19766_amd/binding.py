@@ -17,9 +17,7 @@ F32, BF16 = 0, 1
 IS_SAIS, IS_POIS = 0, 1
 GATE_PER_RESPONSE, GATE_GLOBAL, GATE_ALWAYS, GATE_NEVER = 0, 1, 2, 3
 STATUS_BAD_TOKEN, STATUS_NONFINITE, STATUS_BAD_CU, STATUS_SYNC = 1, 2, 4, 8
-TUNE_FWD_THREADS, TUNE_FWD_UNROLL, TUNE_BWD_THREADS, TUNE_BWD_UNROLL = 0, 1, 2, 3
-TUNE_FUSED_THREADS, TUNE_FUSED_UNROLL, TUNE_GEMM_TILE, TUNE_BWD_ONESHOT, TUNE_FUSED_CLUSTER, TUNE_FUSED_VPT, TUNE_SYNC_SPINS = 4, 5, 6, 7, 8, 9, 10
-TUNE_FWD_PIECES = 11
+LAUNCH_PER_ROW = 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 
@@ -36,6 +34,40 @@ class _CParams(ctypes.Structure):
                 ("is_mode", ctypes.c_int32), ("gate_mode", ctypes.c_int32),
                 ("seg_len", ctypes.c_int32), ("reserved", ctypes.c_int32),
                 ("denominator", ctypes.c_double)]
+
+
+class _CLaunch(ctypes.Structure):
+    _fields_ = [("flags", ctypes.c_uint32), ("sync_spins", ctypes.c_int32), ("gemm_tile", ctypes.c_int32),
+                ("gemm_group_m", ctypes.c_int32), ("reserved", ctypes.c_int32 * 4)]
+
+
+class _CSegStats(ctypes.Structure):
+    _fields_ = [("K", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("count", ctypes.c_void_p), ("ratio_sum", ctypes.c_void_p), ("ratio_max", ctypes.c_void_p),
+                ("clipped", ctypes.c_void_p), ("kl_sum", ctypes.c_void_p), ("ent_sum", ctypes.c_void_p),
+                ("masked", ctypes.c_void_p), ("out_of_range", ctypes.c_void_p),
+                ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
+
+
+@dataclass
+class Launch:
+    """Per-call launch options (ulorl_launch); the defaults are the library's."""
+    per_row: bool = False
+    sync_spins: int = 0
+    gemm_tile: int = 0
+    gemm_group_m: int = 0
+
+    def to_c(self) -> _CLaunch:
+        return _CLaunch(LAUNCH_PER_ROW if self.per_row else 0, self.sync_spins, self.gemm_tile, self.gemm_group_m,
+                        (ctypes.c_int32 * 4)(0, 0, 0, 0))
+
+
+def _launch_ref(launch: Optional["Launch"]):
+    """(pointer argument, object to keep alive) for an optional Launch."""
+    if launch is None:
+        return None, None
+    c = launch.to_c()
+    return ctypes.byref(c), c
 
 
 @dataclass
@@ -78,8 +110,6 @@ def load_library(build_if_missing: bool = True):
     lib.ulorl_version.restype = c.c_int32
     lib.ulorl_status_string.restype = c.c_char_p
     lib.ulorl_status_string.argtypes = [c.c_int32]
-    lib.ulorl_tune.restype = c.c_int32
-    lib.ulorl_tune.argtypes = [c.c_int32, c.c_int32]
     lib.ulorl_token_loss_workspace_bytes.restype = c.c_size_t
     lib.ulorl_token_loss_workspace_bytes.argtypes = [c.c_int64, c.c_int64, c.c_int32]
     vp = c.c_void_p
@@ -92,7 +122,8 @@ def load_library(build_if_missing: bool = True):
         vp, vp, vp, vp, vp,                                  # loss, logp, entropy, lse, gcoef
         vp, vp, vp,                                          # mpt_mask, ratio, segment_out
         vp, vp, vp,                                          # resp_entropy, resp_gate, counters
-        vp, c.c_size_t, vp]                                  # workspace, bytes, stream
+        vp,                                                  # seg_stats
+        vp, c.c_size_t, vp, vp]                              # workspace, bytes, launch, stream
     lib.ulorl_token_loss_fwd_bwd.restype = c.c_int32
     lib.ulorl_token_loss_fwd_bwd.argtypes = [
         vp, c.c_int32, c.c_int64, c.c_int64, c.c_int64,      # logits, dt, N, V, stride
@@ -102,13 +133,14 @@ def load_library(build_if_missing: bool = True):
         vp, vp, vp, vp, vp,                                  # loss, logp, entropy, lse, gcoef
         vp, vp, vp,                                          # mpt_mask, ratio, segment_out
         vp, vp, vp,                                          # resp_entropy, resp_gate, counters
-        vp, vp, c.c_size_t, vp]                              # dlogits, workspace, bytes, stream
+        vp,                                                  # seg_stats
+        vp, vp, c.c_size_t, vp, vp]                          # dlogits, workspace, bytes, launch, stream
     lib.ulorl_init.restype = c.c_int32
     lib.ulorl_init.argtypes = []
     lib.ulorl_static_scratch_bytes.restype = c.c_size_t
     lib.ulorl_static_scratch_bytes.argtypes = []
     lib.ulorl_token_loss_fwd_bwd_static.restype = c.c_int32
-    lib.ulorl_token_loss_fwd_bwd_static.argtypes = lib.ulorl_token_loss_fwd_bwd.argtypes[:-3] + [vp]
+    lib.ulorl_token_loss_fwd_bwd_static.argtypes = lib.ulorl_token_loss_fwd_bwd.argtypes[:-4] + [vp, vp]
     lib.ulorl_lmhead_workspace_bytes.restype = c.c_size_t
     lib.ulorl_lmhead_workspace_bytes.argtypes = [c.c_int64, c.c_int64, c.c_int64, c.c_int32, c.c_int32]
     lib.ulorl_lmhead_token_loss_fwd.restype = c.c_int32
@@ -116,12 +148,12 @@ def load_library(build_if_missing: bool = True):
         vp, vp, c.c_int64, c.c_int64, c.c_int64, c.c_int32,  # hidden, W, N, Hd, V, chunk
         vp, vp, c.c_int32, vp, vp, vp, c.POINTER(_CParams),
         vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
-        vp, c.c_size_t, vp]
+        vp, vp, c.c_size_t, vp, vp]                          # seg_stats, workspace, bytes, launch, stream
     lib.ulorl_lmhead_token_loss_bwd.restype = c.c_int32
     lib.ulorl_lmhead_token_loss_bwd.argtypes = [
-        vp, vp, c.c_int64, c.c_int64, c.c_int64, c.c_int32, vp, vp, vp, c.c_float, vp, vp, vp, c.c_size_t, vp]
+        vp, vp, c.c_int64, c.c_int64, c.c_int64, c.c_int32, vp, vp, vp, c.c_float, vp, vp, vp, c.c_size_t, vp, vp]
     lib.ulorl_gemm_tn_bf16.restype = c.c_int32
-    lib.ulorl_gemm_tn_bf16.argtypes = [vp, c.c_int64, vp, c.c_int64, c.c_int64, c.c_int64, c.c_int64, vp, c.c_int64, vp]
+    lib.ulorl_gemm_tn_bf16.argtypes = [vp, c.c_int64, vp, c.c_int64, c.c_int64, c.c_int64, c.c_int64, vp, c.c_int64, vp, vp]
     lib.ulorl_advantage_prep.restype = c.c_int32
     lib.ulorl_advantage_prep.argtypes = [vp, vp, vp, c.c_int32, c.c_int32, c.c_int64, c.c_float, c.c_int32,
                                          vp, vp, vp, vp, vp]
@@ -145,12 +177,6 @@ def version() -> int:
 
 def status_string(status: int) -> str:
     return load_library().ulorl_status_string(status).decode()
-
-
-def tune(knob: int, value: int) -> None:
-    rc = load_library().ulorl_tune(knob, value)
-    if rc != 0:
-        raise UlorlError(rc, "ulorl_tune")
 
 
 def token_loss_workspace_bytes(N: int, V: int, R: int) -> int:
@@ -204,6 +230,24 @@ class FwdResult:
     resp_entropy: Optional[torch.Tensor] = None
     resp_gate: Optional[torch.Tensor] = None
     counters: Optional[torch.Tensor] = None
+    segment_stats: Optional[dict] = None      # per-segment diagnostics, when asked for (segments=K)
+
+
+def _segment_stats_buffers(K: int, N: int, dev):
+    """Output tensors and workspace of the per-segment diagnostics -> (dict, ulorl_segment_stats)."""
+    i64 = dict(dtype=torch.int64, device=dev)
+    f64 = dict(dtype=torch.float64, device=dev)
+    out = {"count": torch.empty(K, **i64), "ratio_sum": torch.empty(K, **f64),
+           "ratio_max": torch.empty(K, dtype=torch.float32, device=dev), "clipped": torch.empty(K, **i64),
+           "kl_sum": torch.empty(K, **f64), "ent_sum": torch.empty(K, **f64), "masked": torch.empty(K, **i64),
+           "out_of_range": torch.empty(1, **i64)}
+    need = int(load_library().ulorl_segment_diagnostics_workspace_bytes(N, K))
+    ws = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    out["_workspace"] = ws
+    c = _CSegStats(K, 0, out["count"].data_ptr(), out["ratio_sum"].data_ptr(), out["ratio_max"].data_ptr(),
+                   out["clipped"].data_ptr(), out["kl_sum"].data_ptr(), out["ent_sum"].data_ptr(),
+                   out["masked"].data_ptr(), out["out_of_range"].data_ptr(), ws.data_ptr(), ws.numel())
+    return out, c
 
 
 def _prepare_objective(logits, token_ids, cu_seqlens, advantages, old_logp, params, segment_ids, out, workspace):
@@ -239,10 +283,13 @@ def _prepare_objective(logits, token_ids, cu_seqlens, advantages, old_logp, para
 
 def token_loss_fwd(logits, token_ids, cu_seqlens, advantages, old_logp=None, params: Params = None,
                    segment_ids=None, out: Optional[FwdResult] = None,
-                   workspace: Optional[torch.Tensor] = None) -> FwdResult:
+                   workspace: Optional[torch.Tensor] = None, launch: Optional[Launch] = None,
+                   segments: int = 0) -> FwdResult:
     """ulorl_token_loss_fwd.  ``advantages=None`` selects the stats-only pass.
-    ``out``/``workspace`` let a caller reuse buffers (nothing is allocated then)."""
+    ``out``/``workspace`` let a caller reuse buffers (nothing is allocated then).
+    ``segments=K`` asks for the per-segment diagnostics of ids 0..K-1 (``out.segment_stats``)."""
     lib = load_library()
+    lref, _keep = _launch_ref(launch)
     if advantages is None:                       # stats-only: lse, logp, entropy
         dt, N, V, stride = _check_logits(logits)
         dev = logits.device
@@ -255,20 +302,24 @@ def token_loss_fwd(logits, token_ids, cu_seqlens, advantages, old_logp=None, par
         ws_bytes = workspace.numel() * workspace.element_size()
         rc = lib.ulorl_token_loss_fwd(
             _p(logits), dt, N, V, stride, _p(token_ids), None, 0, None, None, None, None,
-            None, _p(out.logp), _p(out.entropy), _p(out.lse), None, None, None, None, None, None, None,
-            _p(workspace), ws_bytes, _stream(dev))
+            None, _p(out.logp), _p(out.entropy), _p(out.lse), None, None, None, None, None, None, None, None,
+            _p(workspace), ws_bytes, lref, _stream(dev))
         if rc != 0:
             raise UlorlError(rc, "ulorl_token_loss_fwd")
         return out
     (dt, N, V, stride, dev, token_ids, R, advantages, old_logp, segment_ids, cparams, out, workspace,
      ws_bytes) = _prepare_objective(logits, token_ids, cu_seqlens, advantages, old_logp, params,
                                     segment_ids, out, workspace)
+    sref = None
+    if segments > 0:
+        out.segment_stats, cseg = _segment_stats_buffers(segments, N, dev)
+        sref = ctypes.byref(cseg)
     rc = lib.ulorl_token_loss_fwd(
         _p(logits), dt, N, V, stride, _p(token_ids), _p(cu_seqlens), R, _p(segment_ids), _p(old_logp),
         _p(advantages), ctypes.byref(cparams),
         _p(out.loss), _p(out.logp), _p(out.entropy), _p(out.lse), _p(out.gcoef),
         _p(out.mpt_mask), _p(out.ratio), _p(out.segment_out), _p(out.resp_entropy),
-        _p(out.resp_gate), _p(out.counters), _p(workspace), ws_bytes, _stream(dev))
+        _p(out.resp_gate), _p(out.counters), sref, _p(workspace), ws_bytes, lref, _stream(dev))
     if rc != 0:
         raise UlorlError(rc, "ulorl_token_loss_fwd")
     return out
@@ -277,9 +328,11 @@ def token_loss_fwd(logits, token_ids, cu_seqlens, advantages, old_logp=None, par
 def token_loss_fwd_bwd(logits, token_ids, cu_seqlens, advantages, old_logp=None, params: Params = None,
                        segment_ids=None, grad_out: float = 1.0, dlogits: Optional[torch.Tensor] = None,
                        inplace: bool = False, out: Optional[FwdResult] = None,
-                       workspace: Optional[torch.Tensor] = None):
+                       workspace: Optional[torch.Tensor] = None, launch: Optional[Launch] = None,
+                       segments: int = 0):
     """ulorl_token_loss_fwd_bwd -> (FwdResult, dlogits).  ``inplace=True`` overwrites ``logits``."""
     lib = load_library()
+    lref, _keep = _launch_ref(launch)
     (dt, N, V, stride, dev, token_ids, R, advantages, old_logp, segment_ids, cparams, out, workspace,
      ws_bytes) = _prepare_objective(logits, token_ids, cu_seqlens, advantages, old_logp, params,
                                     segment_ids, out, workspace)
@@ -292,12 +345,16 @@ def token_loss_fwd_bwd(logits, token_ids, cu_seqlens, advantages, old_logp=None,
     if (dlogits.shape != logits.shape or dlogits.dtype != logits.dtype or dlogits.device != dev
             or dlogits.stride() != logits.stride()):
         raise ValueError("dlogits must match logits in shape, dtype, strides and device")
+    sref = None
+    if segments > 0:
+        out.segment_stats, cseg = _segment_stats_buffers(segments, N, dev)
+        sref = ctypes.byref(cseg)
     rc = lib.ulorl_token_loss_fwd_bwd(
         _p(logits), dt, N, V, stride, _p(token_ids), _p(cu_seqlens), R, _p(segment_ids), _p(old_logp),
         _p(advantages), ctypes.byref(cparams), float(grad_out),
         _p(out.loss), _p(out.logp), _p(out.entropy), _p(out.lse), _p(out.gcoef),
         _p(out.mpt_mask), _p(out.ratio), _p(out.segment_out), _p(out.resp_entropy),
-        _p(out.resp_gate), _p(out.counters), _p(dlogits), _p(workspace), ws_bytes, _stream(dev))
+        _p(out.resp_gate), _p(out.counters), sref, _p(dlogits), _p(workspace), ws_bytes, lref, _stream(dev))
     if rc != 0:
         raise UlorlError(rc, "ulorl_token_loss_fwd_bwd")
     return out, dlogits
@@ -316,7 +373,8 @@ def static_scratch_bytes() -> int:
 
 def token_loss_fwd_bwd_static(logits, token_ids, cu_seqlens, advantages, old_logp=None, params: Params = None,
                               segment_ids=None, grad_out: float = 1.0, dlogits: Optional[torch.Tensor] = None,
-                              inplace: bool = False, out: Optional[FwdResult] = None):
+                              inplace: bool = False, out: Optional[FwdResult] = None,
+                              launch: Optional[Launch] = None):
     """ulorl_token_loss_fwd_bwd_static -> (FwdResult, dlogits): the one-call path on the library's
     static scratch array (the C call allocates nothing; pass ``out`` and ``dlogits`` to keep this
     wrapper from allocating outputs either)."""
@@ -333,6 +391,7 @@ def token_loss_fwd_bwd_static(logits, token_ids, cu_seqlens, advantages, old_log
     segment_ids = _vec(segment_ids, torch.int32, N, "segment_ids", dev)
     if advantages is None:
         raise ValueError("token_loss_fwd_bwd_static needs advantages")
+    lref, _keep = _launch_ref(launch)
     cparams = (params or Params()).to_c()
     if out is None:
         out = FwdResult(torch.empty(1, **f32), torch.empty(N, **f32), torch.empty(N, **f32), torch.empty(N, **f32),
@@ -352,15 +411,15 @@ def token_loss_fwd_bwd_static(logits, token_ids, cu_seqlens, advantages, old_log
         _p(advantages), ctypes.byref(cparams), float(grad_out),
         _p(out.loss), _p(out.logp), _p(out.entropy), _p(out.lse), _p(out.gcoef),
         _p(out.mpt_mask), _p(out.ratio), _p(out.segment_out), _p(out.resp_entropy),
-        _p(out.resp_gate), _p(out.counters), _p(dlogits), _stream(dev))
+        _p(out.resp_gate), _p(out.counters), None, _p(dlogits), lref, _stream(dev))
     if rc != 0:
         raise UlorlError(rc, "ulorl_token_loss_fwd_bwd_static")
     return out, dlogits
 
 
-def row_stats(logits, token_ids, out: Optional[FwdResult] = None) -> FwdResult:
+def row_stats(logits, token_ids, out: Optional[FwdResult] = None, launch: Optional[Launch] = None) -> FwdResult:
     """Stats-only forward: lse, chosen-token log-prob and entropy per row."""
-    return token_loss_fwd(logits, token_ids, None, None, out=out)
+    return token_loss_fwd(logits, token_ids, None, None, out=out, launch=launch)
 
 
 def token_loss_bwd(logits, token_ids, lse, gcoef, grad_out: float = 1.0,
@@ -406,9 +465,11 @@ def _check_lmhead(hidden, weight):
 
 def lmhead_token_loss_fwd(hidden, weight, token_ids, cu_seqlens, advantages, old_logp=None,
                           params: Params = None, segment_ids=None, vocab_chunk: int = 8192,
-                          out: Optional[FwdResult] = None, workspace: Optional[torch.Tensor] = None) -> FwdResult:
+                          out: Optional[FwdResult] = None, workspace: Optional[torch.Tensor] = None,
+                          launch: Optional[Launch] = None, segments: int = 0) -> FwdResult:
     """ulorl_lmhead_token_loss_fwd."""
     lib = load_library()
+    lref, _keep = _launch_ref(launch)
     N, Hd, V = _check_lmhead(hidden, weight)
     dev = hidden.device
     f32 = dict(dtype=torch.float32, device=dev)
@@ -429,7 +490,7 @@ def lmhead_token_loss_fwd(hidden, weight, token_ids, cu_seqlens, advantages, old
         rc = lib.ulorl_lmhead_token_loss_fwd(
             _p(hidden), _p(weight), N, Hd, V, vocab_chunk, _p(token_ids), _p(cu_seqlens), R, None, None, None,
             ctypes.byref(cparams), None, _p(out.logp), _p(out.entropy), _p(out.lse), None, None, None, None, None,
-            None, None, _p(workspace), workspace.numel(), _stream(dev))
+            None, None, None, _p(workspace), workspace.numel(), lref, _stream(dev))
         if rc != 0:
             raise UlorlError(rc, "ulorl_lmhead_token_loss_fwd")
         return out
@@ -441,12 +502,16 @@ def lmhead_token_loss_fwd(hidden, weight, token_ids, cu_seqlens, advantages, old
                         torch.empty(4, dtype=torch.int64, device=dev))
     if workspace is None:
         workspace = torch.empty(max(lmhead_workspace_bytes(N, Hd, V, R, vocab_chunk), 256), dtype=torch.uint8, device=dev)
+    sref = None
+    if segments > 0:
+        out.segment_stats, cseg = _segment_stats_buffers(segments, N, dev)
+        sref = ctypes.byref(cseg)
     rc = lib.ulorl_lmhead_token_loss_fwd(
         _p(hidden), _p(weight), N, Hd, V, vocab_chunk, _p(token_ids), _p(cu_seqlens), R, _p(segment_ids),
         _p(old_logp), _p(advantages), ctypes.byref(cparams),
         _p(out.loss), _p(out.logp), _p(out.entropy), _p(out.lse), _p(out.gcoef), _p(out.mpt_mask), _p(out.ratio),
-        _p(out.segment_out), _p(out.resp_entropy), _p(out.resp_gate), _p(out.counters),
-        _p(workspace), workspace.numel(), _stream(dev))
+        _p(out.segment_out), _p(out.resp_entropy), _p(out.resp_gate), _p(out.counters), sref,
+        _p(workspace), workspace.numel(), lref, _stream(dev))
     if rc != 0:
         raise UlorlError(rc, "ulorl_lmhead_token_loss_fwd")
     return out
@@ -454,7 +519,7 @@ def lmhead_token_loss_fwd(hidden, weight, token_ids, cu_seqlens, advantages, old
 
 def lmhead_token_loss_bwd(hidden, weight, token_ids, lse, gcoef, grad_out: float = 1.0, vocab_chunk: int = 8192,
                           d_hidden: Optional[torch.Tensor] = None, d_weight: Optional[torch.Tensor] = None,
-                          workspace: Optional[torch.Tensor] = None):
+                          workspace: Optional[torch.Tensor] = None, launch: Optional[Launch] = None):
     """ulorl_lmhead_token_loss_bwd -> (d_hidden [N, Hd] bf16, d_weight [Hd, V] bf16)."""
     lib = load_library()
     N, Hd, V = _check_lmhead(hidden, weight)
@@ -468,15 +533,17 @@ def lmhead_token_loss_bwd(hidden, weight, token_ids, lse, gcoef, grad_out: float
         d_weight = torch.empty_like(weight)
     if workspace is None:
         workspace = torch.empty(max(lmhead_workspace_bytes(N, Hd, V, 1, vocab_chunk), 256), dtype=torch.uint8, device=dev)
+    lref, _keep = _launch_ref(launch)
     rc = lib.ulorl_lmhead_token_loss_bwd(
         _p(hidden), _p(weight), N, Hd, V, vocab_chunk, _p(token_ids), _p(lse), _p(gcoef), float(grad_out),
-        _p(d_hidden), _p(d_weight), _p(workspace), workspace.numel(), _stream(dev))
+        _p(d_hidden), _p(d_weight), _p(workspace), workspace.numel(), lref, _stream(dev))
     if rc != 0:
         raise UlorlError(rc, "ulorl_lmhead_token_loss_bwd")
     return d_hidden, d_weight
 
 
-def gemm_tn_bf16(a: torch.Tensor, b: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+def gemm_tn_bf16(a: torch.Tensor, b: torch.Tensor, out: Optional[torch.Tensor] = None,
+                 launch: Optional[Launch] = None) -> torch.Tensor:
     """ulorl_gemm_tn_bf16: a [M, K] . b [N, K]^T -> fp32 [M, N]."""
     lib = load_library()
     if not (a.is_cuda and b.is_cuda) or a.dtype != torch.bfloat16 or b.dtype != torch.bfloat16:
@@ -487,7 +554,9 @@ def gemm_tn_bf16(a: torch.Tensor, b: torch.Tensor, out: Optional[torch.Tensor] =
     N = b.shape[0]
     if out is None:
         out = torch.empty(M, N, dtype=torch.float32, device=a.device)
-    rc = lib.ulorl_gemm_tn_bf16(_p(a), a.stride(0), _p(b), b.stride(0), M, N, K, _p(out), out.stride(0), _stream(a.device))
+    lref, _keep = _launch_ref(launch)
+    rc = lib.ulorl_gemm_tn_bf16(_p(a), a.stride(0), _p(b), b.stride(0), M, N, K, _p(out), out.stride(0), lref,
+                                _stream(a.device))
     if rc != 0:
         raise UlorlError(rc, "ulorl_gemm_tn_bf16")
     return out

@@ -12,7 +12,6 @@ CSRC = os.path.join(_HERE, "csrc")
 INCLUDE = os.path.join(ROOT, "include")
 LIB_DIR = os.path.join(_HERE, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "libulorl.so")
-PROBE_PATH = os.path.join(LIB_DIR, "ulorl_probe")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -47,24 +46,21 @@ def _hipcc(args, out_path, verbose):
 
 
 def build(verbose: bool = False) -> str:
-    """Compile every HIP source (one object each, in parallel), link lib/libulorl.so and the
-    torch-free profiling driver lib/ulorl_probe (library objects + csrc/probe); always recompiles."""
+    """Compile every HIP source (one object each, in parallel) and link lib/libulorl.so; always
+    recompiles."""
     from concurrent.futures import ThreadPoolExecutor
 
     os.makedirs(LIB_DIR, exist_ok=True)
     obj_dir = os.path.join(LIB_DIR, "obj")
     os.makedirs(obj_dir, exist_ok=True)
-    probe = sorted(glob.glob(os.path.join(CSRC, "probe", "*.hip")))
 
     def compile_one(src):
         obj = os.path.join(obj_dir, os.path.basename(src) + ".o")
         return _hipcc(["-c", src], obj, verbose)
 
     with ThreadPoolExecutor(max_workers=4) as pool:
-        objs = list(pool.map(compile_one, sources() + probe))
-    lib_objs, probe_objs = objs[:len(sources())], objs[len(sources()):]
-    _hipcc(["-shared"] + lib_objs, LIB_PATH, verbose)
-    _hipcc(lib_objs + probe_objs, PROBE_PATH, verbose)
+        objs = list(pool.map(compile_one, sources()))
+    _hipcc(["-shared"] + objs, LIB_PATH, verbose)
     return LIB_PATH
 
 

@@ -427,23 +427,23 @@ __device__ __forceinline__ void gemm_tn_tile(const bf16_t* __restrict__ A, int64
 
 // Workgroup -> tile mapping.  The hardware deals consecutive workgroup ids round-robin to the 8
 // XCDs, each with its own L2.  Ids are first regrouped so that every XCD owns one contiguous
-// range of logical tile numbers, and logical numbers walk the tile grid in blocks of 4 tiles
-// along M by all tiles along N (column-major inside the block): the 32 workgroups resident on an
-// XCD then cover about 4 x 8 tiles and share their A and B slices through that XCD's L2.
+// range of logical tile numbers, and logical numbers walk the tile grid in blocks of group_m
+// (default 4) tiles along M by all tiles along N (column-major inside the block): the 32
+// workgroups resident on an XCD then cover about 4 x 8 tiles and share their A and B slices
+// through that XCD's L2.
 constexpr int kXcds = 8;
-constexpr int kGroupM = 4;
 
-__device__ __forceinline__ bool tile_coords(int num_m, int num_n, int& tile_m, int& tile_n)
+__device__ __forceinline__ bool tile_coords(int num_m, int num_n, int group_m, int& tile_m, int& tile_n)
 {
     const int total = num_m * num_n;
     const int per_xcd = (total + kXcds - 1) / kXcds;
     const int bid = blockIdx.x;
     const int logical = (bid % kXcds) * per_xcd + bid / kXcds;
     if (bid / kXcds >= per_xcd || logical >= total) return false;
-    const int group_size = kGroupM * num_n;
+    const int group_size = group_m * num_n;
     const int group = logical / group_size;
-    const int first_m = group * kGroupM;
-    const int gm = min(kGroupM, num_m - first_m);
+    const int first_m = group * group_m;
+    const int gm = min(group_m, num_m - first_m);
     const int in_group = logical % group_size;
     tile_m = first_m + in_group % gm;
     tile_n = in_group / gm;
@@ -533,12 +533,12 @@ __device__ __forceinline__ void store_wave_tile_rows(const f32x16 (&acc)[Cfg::MB
 template <class Cfg, int STORE>
 __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(Cfg::WAVES_PER_SIMD, Cfg::WAVES_PER_SIMD)))
 void gemm_tn_kernel(const bf16_t* __restrict__ A, int64_t lda, int M, const bf16_t* __restrict__ B, int64_t ldb, int N,
-                    int K, void* __restrict__ C, int64_t ldc, int wide_rows)
+                    int K, void* __restrict__ C, int64_t ldc, int wide_rows, int group_m)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     bf16_t* lds = reinterpret_cast<bf16_t*>(lds_raw);
     int tile_m, tile_n;
-    if (!tile_coords((M + Cfg::BM - 1) / Cfg::BM, (N + Cfg::BN - 1) / Cfg::BN, tile_m, tile_n)) return;
+    if (!tile_coords((M + Cfg::BM - 1) / Cfg::BM, (N + Cfg::BN - 1) / Cfg::BN, group_m, tile_m, tile_n)) return;
     const int m0 = tile_m * Cfg::BM, n0 = tile_n * Cfg::BN;
     f32x16 acc[Cfg::MB][Cfg::NB];
     gemm_tn_tile<Cfg>(A, lda, M, m0, B, ldb, N, n0, K, acc, lds);
@@ -627,12 +627,12 @@ template <class Cfg>
 __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(Cfg::WAVES_PER_SIMD, Cfg::WAVES_PER_SIMD)))
 void lmhead_stats_kernel(const bf16_t* __restrict__ Wt, const bf16_t* __restrict__ H, int Hd, int V, int Ntok,
                          const int32_t* __restrict__ token_ids, int v_per_split, int splits,
-                         StatQuad* __restrict__ partial)
+                         StatQuad* __restrict__ partial, int group_m)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     bf16_t* lds = reinterpret_cast<bf16_t*>(lds_raw);
     int t_tile, split;
-    if (!tile_coords((Ntok + Cfg::BN - 1) / Cfg::BN, splits, t_tile, split)) return;
+    if (!tile_coords((Ntok + Cfg::BN - 1) / Cfg::BN, splits, group_m, t_tile, split)) return;
     const int t0 = t_tile * Cfg::BN;
     const int vb = split * v_per_split;
     const int ve = min(V, vb + v_per_split);
@@ -755,12 +755,12 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(Cfg::WA
 void lmhead_dz_kernel(const bf16_t* __restrict__ Wt, const bf16_t* __restrict__ H, int Hd, int V, int Ntok, int vc0,
                       int cw, const int32_t* __restrict__ token_ids, const float* __restrict__ lse,
                       const float* __restrict__ gcoef, float grad_out, bf16_t* __restrict__ dZc, int64_t ld_c,
-                      bf16_t* __restrict__ dZcT, int64_t ld_t)
+                      bf16_t* __restrict__ dZcT, int64_t ld_t, int group_m)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     bf16_t* lds = reinterpret_cast<bf16_t*>(lds_raw);
     int v_tile, t_tile;
-    if (!tile_coords((cw + Cfg::BM - 1) / Cfg::BM, (int)((ld_t + Cfg::BN - 1) / Cfg::BN), v_tile, t_tile)) return;
+    if (!tile_coords((cw + Cfg::BM - 1) / Cfg::BM, (int)((ld_t + Cfg::BN - 1) / Cfg::BN), group_m, v_tile, t_tile)) return;
     const int v0 = vc0 + v_tile * Cfg::BM;
     const int t0 = t_tile * Cfg::BN;
     const int vend = min(V, vc0 + cw);
@@ -872,28 +872,14 @@ void lmhead_dz_kernel(const bf16_t* __restrict__ Wt, const bf16_t* __restrict__ 
 // ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
-// Tile shapes that are compiled in; ulorl_tune(ULORL_TUNE_GEMM_TILE, i) selects one.
-using Tile0 = GemmCfg<128, 128, 64, 2, 2>;   // wave tile 64 x 64
-using Tile1 = GemmCfg<256, 256, 32, 2, 2>;   // wave tile 128 x 128, 80 KB of LDS
-using Tile2 = GemmCfg<256, 256, 64, 2, 2>;   // wave tile 128 x 128, 144 KB of LDS
-using Tile3 = GemmCfg<256, 128, 64, 2, 2>;   // wave tile 128 x 64
-using Tile4 = GemmCfg<256, 256, 64, 2, 4>;   // eight waves (two per SIMD), wave tile 128 x 64
-using Tile5 = GemmCfg<256, 256, 64, 4, 2>;   // eight waves, wave tile 64 x 128
-using Tile6 = GemmCfg<256, 256, 64, 4, 2, true>;   // as 5, tiles copied global -> LDS directly
-using Tile7 = GemmCfg<256, 256, 64, 2, 4, true>;   // as 4, direct
-using Tile8 = GemmCfg<256, 256, 64, 2, 2, true>;   // as 2, direct (four waves, one per SIMD)
+// Tile shapes that are compiled in; ulorl_launch.gemm_tile selects one.
+using TileLarge = GemmCfg<256, 256, 64, 2, 4, true>;   // eight waves (two per SIMD), wave tile 128 x 64, tiles copied global -> LDS directly
+using TileSmall = GemmCfg<128, 128, 64, 2, 2>;         // four waves, wave tile 64 x 64, register-staged copies
 
-#define ULORL_FOR_TILE(choice, ...)                          \
-    switch (choice) {                                        \
-    case 0: { using Cfg = Tile0; __VA_ARGS__; } break;       \
-    case 1: { using Cfg = Tile1; __VA_ARGS__; } break;       \
-    case 2: { using Cfg = Tile2; __VA_ARGS__; } break;       \
-    case 3: { using Cfg = Tile3; __VA_ARGS__; } break;       \
-    case 4: { using Cfg = Tile4; __VA_ARGS__; } break;       \
-    case 5: { using Cfg = Tile5; __VA_ARGS__; } break;       \
-    case 6: { using Cfg = Tile6; __VA_ARGS__; } break;       \
-    case 8: { using Cfg = Tile8; __VA_ARGS__; } break;       \
-    default: { using Cfg = Tile7; __VA_ARGS__; } break;      \
+#define ULORL_FOR_TILE(choice, ...)                              \
+    switch (choice) {                                            \
+    case 1: { using Cfg = TileSmall; __VA_ARGS__; } break;       \
+    default: { using Cfg = TileLarge; __VA_ARGS__; } break;      \
     }
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -907,10 +893,10 @@ struct LmheadLayout {
     int v_per_split;
 };
 
-LmheadLayout lmhead_layout(int64_t N, int64_t Hd, int64_t V, int32_t R, int32_t chunk)
+LmheadLayout lmhead_layout(int64_t N, int64_t Hd, int64_t V, int32_t R, int32_t chunk, int tile)
 {
     int bm = 0, bn = 0;
-    ULORL_FOR_TILE(gemm_tile_choice(), bm = Cfg::BM; bn = Cfg::BN)
+    ULORL_FOR_TILE(tile, bm = Cfg::BM; bn = Cfg::BN)
     LmheadLayout L;
     L.ldt = round_up64(N);
     L.ldc = round_up64(chunk);
@@ -925,7 +911,7 @@ LmheadLayout lmhead_layout(int64_t N, int64_t Hd, int64_t V, int32_t R, int32_t 
     L.v_per_split = (int)(tiles_per_split * bm);
     L.splits = (int)((vtiles + tiles_per_split - 1) / tiles_per_split);
     // sized for the largest split count any tile shape can ask for, so that the workspace
-    // requirement does not depend on the tuning knob
+    // requirement does not depend on the launch options
     const size_t max_splits = kMaxSplits;
     size_t off = 0;
     L.wt = off;      off = align_up(off + (size_t)V * Hd * 2, 256);
@@ -980,48 +966,48 @@ void launch_transpose(const bf16_t* src, int64_t ld_src, int rows, int cols, bf1
 
 template <class Cfg, int STORE>
 bool launch_gemm_cfg(const bf16_t* A, int64_t lda, int M, const bf16_t* B, int64_t ldb, int N, int K, void* C,
-                     int64_t ldc, hipStream_t st)
+                     int64_t ldc, int group_m, hipStream_t st)
 {
     auto kern = gemm_tn_kernel<Cfg, STORE>;
     if (!allow_lds(kern, Cfg::LDS_BYTES)) return false;
     dim3 grid(tile_grid((M + Cfg::BM - 1) / Cfg::BM, (N + Cfg::BN - 1) / Cfg::BN));
     const int eb = STORE == STORE_BF16 ? 2 : 4;
     const int wide_rows = (((uintptr_t)C & 15u) == 0 && (ldc * eb) % 16 == 0) ? 1 : 0;
-    hipLaunchKernelGGL(kern, grid, dim3(Cfg::NT), Cfg::LDS_BYTES, st, A, lda, M, B, ldb, N, K, C, ldc, wide_rows);
+    hipLaunchKernelGGL(kern, grid, dim3(Cfg::NT), Cfg::LDS_BYTES, st, A, lda, M, B, ldb, N, K, C, ldc, wide_rows, group_m);
     return true;
 }
 
 template <int STORE>
-bool launch_gemm(const bf16_t* A, int64_t lda, int M, const bf16_t* B, int64_t ldb, int N, int K, void* C, int64_t ldc,
-                 hipStream_t st)
+bool launch_gemm(const LaunchOpts& o, const bf16_t* A, int64_t lda, int M, const bf16_t* B, int64_t ldb, int N, int K,
+                 void* C, int64_t ldc, hipStream_t st)
 {
     bool ok = false;
-    ULORL_FOR_TILE(gemm_tile_choice(), ok = (launch_gemm_cfg<Cfg, STORE>(A, lda, M, B, ldb, N, K, C, ldc, st)))
+    ULORL_FOR_TILE(o.gemm_tile, ok = (launch_gemm_cfg<Cfg, STORE>(A, lda, M, B, ldb, N, K, C, ldc, o.gemm_group_m, st)))
     return ok;
 }
 
 template <class Cfg>
 bool launch_stats_cfg(const bf16_t* Wt, const bf16_t* H, int Hd, int V, int N, const int32_t* token_ids,
-                      const LmheadLayout& L, StatQuad* partial, hipStream_t st)
+                      const LmheadLayout& L, StatQuad* partial, int group_m, hipStream_t st)
 {
     auto kern = lmhead_stats_kernel<Cfg>;
     if (!allow_lds(kern, Cfg::LDS_BYTES)) return false;
     dim3 grid(tile_grid((N + Cfg::BN - 1) / Cfg::BN, L.splits));
     hipLaunchKernelGGL(kern, grid, dim3(Cfg::NT), Cfg::LDS_BYTES, st, Wt, H, Hd, V, N, token_ids, L.v_per_split, L.splits,
-                       partial);
+                       partial, group_m);
     return true;
 }
 
 template <class Cfg>
 bool launch_dz_cfg(const bf16_t* Wt, const bf16_t* H, int Hd, int V, int N, int vc0, int cw_pad,
                    const int32_t* token_ids, const float* lse, const float* gcoef, float grad_out, bf16_t* dZc,
-                   bf16_t* dZcT, const LmheadLayout& L, hipStream_t st)
+                   bf16_t* dZcT, const LmheadLayout& L, int group_m, hipStream_t st)
 {
     auto kern = lmhead_dz_kernel<Cfg>;
     if (!allow_lds(kern, Cfg::LDS_BYTES)) return false;
     dim3 grid(tile_grid((cw_pad + Cfg::BM - 1) / Cfg::BM, (int)((L.ldt + Cfg::BN - 1) / Cfg::BN)));
     hipLaunchKernelGGL(kern, grid, dim3(Cfg::NT), Cfg::LDS_BYTES, st, Wt, H, Hd, V, N, vc0, cw_pad, token_ids, lse, gcoef,
-                       grad_out, dZc, L.ldc, dZcT, L.ldt);
+                       grad_out, dZc, L.ldc, dZcT, L.ldt, group_m);
     return true;
 }
 
@@ -1030,14 +1016,17 @@ bool launch_dz_cfg(const bf16_t* Wt, const bf16_t* H, int Hd, int V, int N, int 
 extern "C" {
 
 int32_t ulorl_gemm_tn_bf16(const void* A, int64_t lda, const void* B, int64_t ldb, int64_t M, int64_t N, int64_t K,
-                           float* C, int64_t ldc, void* hip_stream)
+                           float* C, int64_t ldc, const ulorl_launch* launch, void* hip_stream)
 {
     if (!A || !B || !C) return ULORL_ERR_NULL;
+    LaunchOpts opts;
+    const int32_t lrc = resolve_launch(launch, &opts);
+    if (lrc != ULORL_OK) return lrc;
     if (M <= 0 || N <= 0 || K <= 0 || M > 0x7fffffffLL || N > 0x7fffffffLL || K > 0x7fffffffLL) return ULORL_ERR_SHAPE;
     if (K % 8 != 0 || lda % 8 != 0 || ldb % 8 != 0 || lda < K || ldb < K || ldc < N) return ULORL_ERR_SHAPE;
     if (lda > kMaxLeadingDim || ldb > kMaxLeadingDim) return ULORL_ERR_SHAPE;
     if (((uintptr_t)A & 15u) != 0 || ((uintptr_t)B & 15u) != 0) return ULORL_ERR_ALIGN;
-    if (!launch_gemm<STORE_F32>((const bf16_t*)A, lda, (int)M, (const bf16_t*)B, ldb, (int)N, (int)K, C, ldc,
+    if (!launch_gemm<STORE_F32>(opts, (const bf16_t*)A, lda, (int)M, (const bf16_t*)B, ldb, (int)N, (int)K, C, ldc,
                                 (hipStream_t)hip_stream))
         return ULORL_ERR_HIP;
     return hipGetLastError() == hipSuccess ? ULORL_OK : ULORL_ERR_HIP;
@@ -1046,7 +1035,7 @@ int32_t ulorl_gemm_tn_bf16(const void* A, int64_t lda, const void* B, int64_t ld
 size_t ulorl_lmhead_workspace_bytes(int64_t N, int64_t Hd, int64_t V, int32_t R, int32_t vocab_chunk)
 {
     if (N <= 0 || N > 0x7fffffffLL || Hd <= 0 || V <= 0 || R <= 0 || vocab_chunk <= 0 || vocab_chunk % 64 != 0) return 0;
-    return lmhead_layout(N, Hd, V, R, vocab_chunk).total;
+    return lmhead_layout(N, Hd, V, R, vocab_chunk, 0).total;      // the same for every tile shape
 }
 
 int32_t ulorl_lmhead_token_loss_fwd(const void* hidden, const void* W, int64_t N, int64_t Hd, int64_t V,
@@ -1055,19 +1044,27 @@ int32_t ulorl_lmhead_token_loss_fwd(const void* hidden, const void* W, int64_t N
                                     const float* advantages, const ulorl_params* p, float* loss, float* logp,
                                     float* entropy, float* lse, float* gcoef, uint8_t* mpt_mask, float* ratio,
                                     int32_t* segment_out, float* resp_entropy, uint8_t* resp_gate, int64_t* counters,
-                                    void* workspace, size_t workspace_bytes, void* hip_stream)
+                                    const ulorl_segment_stats* seg_stats, void* workspace, size_t workspace_bytes,
+                                    const ulorl_launch* launch, void* hip_stream)
 {
     int32_t rc = check_lmhead(hidden, W, N, Hd, V, vocab_chunk);
     if (rc != ULORL_OK) return rc;
     if (!token_ids || !logp || !entropy || !lse) return ULORL_ERR_NULL;
+    LaunchOpts opts;
+    rc = resolve_launch(launch, &opts);
+    if (rc != ULORL_OK) return rc;
     const bool stats_only = advantages == nullptr;      // lse, logp and entropy only (recording old log-probs)
+    SegStatsArgs seg;
+    seg.K = 0;
     if (!stats_only) {
         rc = check_objective_args(cu_seqlens, R, old_logp, p, loss, gcoef);
+        if (rc != ULORL_OK) return rc;
+        rc = resolve_segment_stats(seg_stats, N, &seg);
         if (rc != ULORL_OK) return rc;
     } else if (R <= 0) {
         R = 1;      // only sizes the workspace layout
     }
-    const LmheadLayout L = lmhead_layout(N, Hd, V, R, vocab_chunk);
+    const LmheadLayout L = lmhead_layout(N, Hd, V, R, vocab_chunk, opts.gemm_tile);
     if (!workspace || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < L.total) return ULORL_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)hip_stream;
     char* ws = (char*)workspace;
@@ -1076,8 +1073,8 @@ int32_t ulorl_lmhead_token_loss_fwd(const void* hidden, const void* W, int64_t N
 
     launch_transpose((const bf16_t*)W, V, (int)Hd, (int)V, Wt, Hd, (int)Hd, st);      // Wt[v, k] = W[k, v]
     bool ok = false;
-    ULORL_FOR_TILE(gemm_tile_choice(), ok = launch_stats_cfg<Cfg>(Wt, (const bf16_t*)hidden, (int)Hd, (int)V, (int)N,
-                                                                  token_ids, L, partial, st))
+    ULORL_FOR_TILE(opts.gemm_tile, ok = launch_stats_cfg<Cfg>(Wt, (const bf16_t*)hidden, (int)Hd, (int)V, (int)N, token_ids, L,
+                                                              partial, opts.gemm_group_m, st))
     if (!ok) return ULORL_ERR_HIP;
     hipLaunchKernelGGL(lmhead_stats_merge_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, st, partial, L.splits,
                        (int)N, (int)V, token_ids, lse, logp, entropy);
@@ -1087,7 +1084,7 @@ int32_t ulorl_lmhead_token_loss_fwd(const void* hidden, const void* W, int64_t N
     const WorkspaceLayout wl = workspace_layout(N, 0, R);
     const TokenArgs a = make_token_args(N, V, token_ids, cu_seqlens, R, segment_ids, old_logp, advantages, p, logp,
                                         entropy, lse, gcoef, mpt_mask, ratio, segment_out, resp_entropy, resp_gate,
-                                        ws + L.token_ws, wl);
+                                        ws + L.token_ws, wl, seg);
     launch_token_epilogue(a, wl, loss, counters, st);
     return hipGetLastError() == hipSuccess ? ULORL_OK : ULORL_ERR_HIP;
 }
@@ -1095,13 +1092,16 @@ int32_t ulorl_lmhead_token_loss_fwd(const void* hidden, const void* W, int64_t N
 int32_t ulorl_lmhead_token_loss_bwd(const void* hidden, const void* W, int64_t N, int64_t Hd, int64_t V,
                                     int32_t vocab_chunk, const int32_t* token_ids, const float* lse,
                                     const float* gcoef, float grad_out, void* d_hidden, void* d_W, void* workspace,
-                                    size_t workspace_bytes, void* hip_stream)
+                                    size_t workspace_bytes, const ulorl_launch* launch, void* hip_stream)
 {
     int32_t rc = check_lmhead(hidden, W, N, Hd, V, vocab_chunk);
     if (rc != ULORL_OK) return rc;
+    LaunchOpts opts;
+    rc = resolve_launch(launch, &opts);
+    if (rc != ULORL_OK) return rc;
     if (!token_ids || !lse || !gcoef || !d_hidden || !d_W) return ULORL_ERR_NULL;
     if (((uintptr_t)d_hidden & 15u) != 0 || ((uintptr_t)d_W & 15u) != 0) return ULORL_ERR_ALIGN;
-    const LmheadLayout L = lmhead_layout(N, Hd, V, 1, vocab_chunk);
+    const LmheadLayout L = lmhead_layout(N, Hd, V, 1, vocab_chunk, opts.gemm_tile);
     if (!workspace || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < L.total) return ULORL_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)hip_stream;
     char* ws = (char*)workspace;
@@ -1122,13 +1122,13 @@ int32_t ulorl_lmhead_token_loss_bwd(const void* hidden, const void* W, int64_t N
         const int cw = (int)((V - vc0 < vocab_chunk) ? (V - vc0) : vocab_chunk);
         const int cw_pad = (int)round_up64(cw);         // dz of the padding columns is written as zero
         bool ok = false;
-        ULORL_FOR_TILE(gemm_tile_choice(), ok = launch_dz_cfg<Cfg>(Wt, H, (int)Hd, (int)V, (int)N, (int)vc0, cw_pad,
-                                                                   token_ids, lse, gcoef, grad_out, dZc, dZcT, L, st))
+        ULORL_FOR_TILE(opts.gemm_tile, ok = launch_dz_cfg<Cfg>(Wt, H, (int)Hd, (int)V, (int)N, (int)vc0, cw_pad, token_ids, lse,
+                                                               gcoef, grad_out, dZc, dZcT, L, opts.gemm_group_m, st))
         if (!ok) return ULORL_ERR_HIP;
         // dHidden[t, k] += sum_v dZc[t, v] W[k, vc0 + v]
-        if (!launch_gemm<STORE_F32_ACCUM>(dZc, L.ldc, (int)N, Wp + vc0, V, (int)Hd, cw, dHacc, Hd, st)) return ULORL_ERR_HIP;
+        if (!launch_gemm<STORE_F32_ACCUM>(opts, dZc, L.ldc, (int)N, Wp + vc0, V, (int)Hd, cw, dHacc, Hd, st)) return ULORL_ERR_HIP;
         // dW[k, vc0 + v] = sum_t Ht[k, t] dZc^T[v, t]
-        if (!launch_gemm<STORE_BF16>(Ht, L.ldt, (int)Hd, dZcT, L.ldt, cw, (int)L.ldt, (bf16_t*)d_W + vc0, V, st))
+        if (!launch_gemm<STORE_BF16>(opts, Ht, L.ldt, (int)Hd, dZcT, L.ldt, cw, (int)L.ldt, (bf16_t*)d_W + vc0, V, st))
             return ULORL_ERR_HIP;
         if (hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;
     }

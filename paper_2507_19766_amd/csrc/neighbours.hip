@@ -37,18 +37,6 @@ __device__ __forceinline__ double block_sum_f64(double x, double* scratch)
     return s;
 }
 
-__device__ __forceinline__ double block_max_f64(double x, double* scratch)
-{
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) x = fmax(x, shfl_xor_f64(x, off));
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = x;
-    __syncthreads();
-    double s = scratch[0];
-    for (int w = 1; w < kBlock / 64; ++w) s = fmax(s, scratch[w]);
-    return s;
-}
-
 // ---------------------------------------------------------------------------------------------
 // advantage preparation (Eq. 4; dynamic-sampling constraint of Eq. 7; Sec. 3.5)
 // ---------------------------------------------------------------------------------------------
@@ -107,9 +95,10 @@ __global__ __launch_bounds__(256) void broadcast_advantage_kernel(const float* _
 }
 
 // ---------------------------------------------------------------------------------------------
-// per-segment diagnostics
+// per-segment diagnostics (standalone form; the forward calls produce the same numbers as a
+// by-product through the same device functions, segment_stats.hpp)
 // ---------------------------------------------------------------------------------------------
-struct DiagArgs {
+struct DiagInputs {
     const int32_t* seg;
     const float* ratio;
     const float* logp;
@@ -118,82 +107,28 @@ struct DiagArgs {
     const uint8_t* mask;
     const float* adv;
     int64_t N;
-    int32_t K;
     double eps_low, eps_high;
-    double* part;   // [nblk][K][7]: count, ratio_sum, ratio_max, clipped, kl_sum, ent_sum, masked
-    double* part_oor;  // [nblk]
 };
 
-__global__ __launch_bounds__(kBlock) void segment_partial_kernel(DiagArgs a)
+__global__ __launch_bounds__(kSegBlock) void segment_partial_kernel(DiagInputs in, SegStatsArgs a)
 {
-    __shared__ double scratch[kBlock / 64];
-    const int64_t t = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    int k = -1;
-    double r = 0.0, kl = 0.0, h = 0.0, clip = 0.0, msk = 0.0, oor = 0.0;
-    if (t < a.N) {
-        k = a.seg[t];
-        if (k < 0 || k >= a.K) { oor = 1.0; k = -1; }
-        r = (double)a.ratio[t];
-        const double A = (double)a.adv[t];
-        const double c = fmin(fmax(r, 1.0 - a.eps_low), 1.0 + a.eps_high);
-        clip = (r * A <= c * A) ? 0.0 : 1.0;
-        kl = a.old_logp ? (double)a.old_logp[t] - (double)a.logp[t] : 0.0;
-        h = (double)a.entropy[t];
-        msk = a.mask[t] ? 1.0 : 0.0;
-    }
-    // a block of consecutive tokens holds few distinct segment ids: reduce only those present
-    const int kmin = -(int)block_max_f64(k < 0 ? -1.0e9 : -(double)k, scratch);
-    const int kmax = (int)block_max_f64((double)k, scratch);
-    double* out = a.part + (int64_t)blockIdx.x * a.K * 7;
-    for (int kk = threadIdx.x; kk < a.K * 7; kk += kBlock) out[kk] = 0.0;
-    __syncthreads();
-    for (int kk = (kmin > 1000000 ? 0 : kmin); kk <= kmax; ++kk) {
-        const bool mine = k == kk;
-        const double v0 = block_sum_f64(mine ? 1.0 : 0.0, scratch);
-        const double v1 = block_sum_f64(mine ? r : 0.0, scratch);
-        const double v2 = block_max_f64(mine ? r : 0.0, scratch);
-        const double v3 = block_sum_f64(mine ? clip : 0.0, scratch);
-        const double v4 = block_sum_f64(mine ? kl : 0.0, scratch);
-        const double v5 = block_sum_f64(mine ? h : 0.0, scratch);
-        const double v6 = block_sum_f64(mine ? msk : 0.0, scratch);
-        if (threadIdx.x == 0) {
-            double* o = out + kk * 7;
-            o[0] = v0; o[1] = v1; o[2] = v2; o[3] = v3; o[4] = v4; o[5] = v5; o[6] = v6;
-        }
-    }
-    const double o = block_sum_f64(oor, scratch);
+    extern __shared__ double seg_table[];
+    const int64_t t = (int64_t)blockIdx.x * kSegBlock + threadIdx.x;
+    const bool valid = t < in.N;
+    int k;
+    double v[kSegStats], oor;
+    seg_token_values(valid, valid ? in.seg[t] : 0, a.K, valid ? in.ratio[t] : 0.0f, valid ? in.logp[t] : 0.0f,
+                     in.old_logp != nullptr, (valid && in.old_logp) ? in.old_logp[t] : 0.0f, valid ? in.entropy[t] : 0.0f,
+                     valid ? in.mask[t] : (uint8_t)0, valid ? in.adv[t] : 0.0f, in.eps_low, in.eps_high, k, v, oor);
+    const double o = seg_block_partials(k, v, oor, a.K, seg_table, a.part + (int64_t)blockIdx.x * a.K * kSegStats);
     if (threadIdx.x == 0) a.part_oor[blockIdx.x] = o;
 }
 
-__global__ __launch_bounds__(kBlock) void segment_final_kernel(const double* __restrict__ part,
-                                                               const double* __restrict__ part_oor, int64_t nblk, int32_t K,
-                                                               int64_t* count, double* ratio_sum, float* ratio_max,
-                                                               int64_t* clipped, double* kl_sum, double* ent_sum,
-                                                               int64_t* masked, int64_t* out_of_range)
+__global__ __launch_bounds__(kSegBlock) void segment_final_kernel(SegStatsArgs a, int64_t nblk)
 {
-    __shared__ double scratch[kBlock / 64];
-    for (int k = 0; k < K; ++k) {
-        double v[7] = {0, 0, 0, 0, 0, 0, 0};
-        for (int64_t b = threadIdx.x; b < nblk; b += kBlock) {
-            const double* p = part + (b * K + k) * 7;
-            v[0] += p[0]; v[1] += p[1]; v[2] = fmax(v[2], p[2]); v[3] += p[3]; v[4] += p[4]; v[5] += p[5]; v[6] += p[6];
-        }
-        const double s0 = block_sum_f64(v[0], scratch), s1 = block_sum_f64(v[1], scratch);
-        const double s2 = block_max_f64(v[2], scratch), s3 = block_sum_f64(v[3], scratch);
-        const double s4 = block_sum_f64(v[4], scratch), s5 = block_sum_f64(v[5], scratch);
-        const double s6 = block_sum_f64(v[6], scratch);
-        if (threadIdx.x == 0) {
-            count[k] = (int64_t)s0; ratio_sum[k] = s1; ratio_max[k] = (float)s2; clipped[k] = (int64_t)s3;
-            kl_sum[k] = s4; ent_sum[k] = s5; masked[k] = (int64_t)s6;
-        }
-    }
-    double o = 0.0;
-    for (int64_t b = threadIdx.x; b < nblk; b += kBlock) o += part_oor[b];
-    o = block_sum_f64(o, scratch);
-    if (threadIdx.x == 0 && out_of_range) *out_of_range = (int64_t)o;
+    __shared__ double scratch[kSegBlock];
+    seg_finalize(a, nblk, scratch);
 }
-
-inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // ---------------------------------------------------------------------------------------------
 // segment-rollout pool update (Algorithm 1, Sec. 3.1.1)
@@ -303,9 +238,8 @@ int32_t ulorl_advantage_prep(const float* rewards, const uint8_t* truncated, con
 
 size_t ulorl_segment_diagnostics_workspace_bytes(int64_t N, int32_t K)
 {
-    if (N <= 0 || N > 0x7fffffffLL || K <= 0 || K > 4096) return 0;
-    const size_t nblk = (size_t)((N + kBlock - 1) / kBlock);
-    return align_up(nblk * (size_t)K * 7 * sizeof(double), 256) + align_up(nblk * sizeof(double), 256);
+    if (N <= 0 || N > 0x7fffffffLL || K <= 0 || K > kSegMaxK) return 0;
+    return seg_workspace_bytes(N, K);
 }
 
 int32_t ulorl_segment_diagnostics(int64_t N, int32_t K, const int32_t* segment_ids, const float* ratio,
@@ -316,22 +250,25 @@ int32_t ulorl_segment_diagnostics(int64_t N, int32_t K, const int32_t* segment_i
                                   void* workspace, size_t workspace_bytes, void* hip_stream)
 {
     if (!segment_ids || !ratio || !logp || !entropy || !mpt_mask || !advantages) return ULORL_ERR_NULL;
-    if (!count || !ratio_sum || !ratio_max || !clipped || !kl_sum || !ent_sum || !masked) return ULORL_ERR_NULL;
-    if (N <= 0 || N > 0x7fffffffLL || K <= 0 || K > 4096) return ULORL_ERR_SHAPE;
+    if (N <= 0) return ULORL_ERR_SHAPE;
     if (!(eps_low >= 0.0f) || !(eps_high >= 0.0f)) return ULORL_ERR_PARAM;
-    const size_t need = ulorl_segment_diagnostics_workspace_bytes(N, K);
-    if (!workspace || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < need) return ULORL_ERR_WORKSPACE;
-    const int64_t nblk = (N + kBlock - 1) / kBlock;
-    DiagArgs a;
-    a.seg = segment_ids; a.ratio = ratio; a.logp = logp; a.old_logp = old_logp; a.entropy = entropy;
-    a.mask = mpt_mask; a.adv = advantages; a.N = N; a.K = K;
-    a.eps_low = (double)eps_low; a.eps_high = (double)eps_high;
-    a.part = (double*)workspace;
-    a.part_oor = (double*)((char*)workspace + align_up((size_t)nblk * K * 7 * sizeof(double), 256));
-    hipStream_t st = (hipStream_t)hip_stream;
-    hipLaunchKernelGGL(segment_partial_kernel, dim3((unsigned)nblk), dim3(kBlock), 0, st, a);
-    hipLaunchKernelGGL(segment_final_kernel, dim3(1), dim3(kBlock), 0, st, a.part, a.part_oor, nblk, K, count, ratio_sum,
-                       ratio_max, clipped, kl_sum, ent_sum, masked, out_of_range);
+    ulorl_segment_stats st = {};
+    st.K = K;
+    st.count = count; st.ratio_sum = ratio_sum; st.ratio_max = ratio_max; st.clipped = clipped;
+    st.kl_sum = kl_sum; st.ent_sum = ent_sum; st.masked = masked; st.out_of_range = out_of_range;
+    st.workspace = workspace; st.workspace_bytes = workspace_bytes;
+    SegStatsArgs a;
+    const int32_t rc = resolve_segment_stats(&st, N, &a);
+    if (rc != ULORL_OK) return rc;
+    const int64_t nblk = (N + kSegBlock - 1) / kSegBlock;
+    DiagInputs in;
+    in.seg = segment_ids; in.ratio = ratio; in.logp = logp; in.old_logp = old_logp; in.entropy = entropy;
+    in.mask = mpt_mask; in.adv = advantages; in.N = N;
+    in.eps_low = (double)eps_low; in.eps_high = (double)eps_high;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    hipLaunchKernelGGL(segment_partial_kernel, dim3((unsigned)nblk), dim3(kSegBlock), (size_t)K * kSegStats * sizeof(double),
+                       stream, in, a);
+    hipLaunchKernelGGL(segment_final_kernel, dim3(1), dim3(kSegBlock), 0, stream, a, nblk);
     return hipGetLastError() == hipSuccess ? ULORL_OK : ULORL_ERR_HIP;
 }
 

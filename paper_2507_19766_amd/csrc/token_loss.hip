@@ -16,12 +16,17 @@
 //   dlogits_chunk_kernel  the backward call: recomputes the softmax from the saved lse and writes
 //                         g_t * (onehot - p) with one 16-byte vector per thread; rows with
 //                         g_t == 0 are write-only.  Safe in place: each vector is read and then
-//                         written by the same thread.  (dlogits_kernel: the same by one looping
-//                         workgroup per row.)
+//                         written by the same thread.
 //   cluster_row_kernel    the one-call entry point: a row is split into pieces, one workgroup per
 //                         piece keeps its piece in registers, the pieces exchange their partial
 //                         (max, sum, weighted sum) through memory and each writes its share of
 //                         the gradient: every logit is read once and written once.
+//   defer_compact_kernel, dlogits_rows_kernel
+//                         the rows the one-call path leaves until the entropy gate is known (the
+//                         members of the MPT set), collected into a list and finished from it.
+//   repair_rows_kernel, repair_pieces_kernel
+//                         finish what a workgroup of cluster_row_kernel left undone because its
+//                         bounded wait expired; they return at once when nothing was left.
 //   fused_row_kernel      the same call by one workgroup per row, forward and backward back to
 //                         back (rows too long for the cooperative kernel, or on request).
 //
@@ -50,6 +55,7 @@ namespace {
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kEmpty = -1.0e30f;  // "no element seen yet"; finite so that 0 * kEmpty == 0
+static_assert(kSegBlock == kTokBlock, "the per-segment diagnostics ride on the O(N) epilogue's workgroups");
 // Kernels with several workgroups per row lay the rows over grid dimensions y (up to
 // kRowsPerGridY) and z (up to 65535).
 constexpr int64_t kRowsPerGridY = 32768;
@@ -372,44 +378,19 @@ __device__ __forceinline__ bool row_is_live(float g, float l, int32_t y, int32_t
     return (g != 0.0f) && (fabsf(g) <= 3.0e38f) && (fabsf(l) <= 3.0e38f) && y >= 0 && y < V;
 }
 
-// `only` (may be NULL): process just the rows whose flag is non-zero (the rows the fused
-// forward+backward kernel had to defer until the entropy gate was known).
-template <class Tr, int NT, int U>
-__global__ __launch_bounds__(NT) void dlogits_kernel(const typename Tr::elem* logits,
-                                                     int64_t row_stride, int32_t V,
-                                                     const int32_t* __restrict__ token_ids,
-                                                     const float* __restrict__ lse,
-                                                     const float* __restrict__ gcoef, float grad_out,
-                                                     typename Tr::elem* dlogits,
-                                                     const uint8_t* __restrict__ only)
-{
-    const int64_t row = blockIdx.x;
-    if (only != nullptr && only[row] == 0) return;
-    const float g = gcoef[row] * grad_out;
-    const float l = lse[row];
-    const int32_t y = token_ids[row];
-    dlogits_core<Tr, NT, U>(logits + row * row_stride, dlogits + row * row_stride, V, row_is_live(g, l, y, V), g, l, y);
-}
-
-// The same gradient by one-shot workgroups: 256 threads, one 16-byte vector per thread, 4 KB of
+// The backward call, by one-shot workgroups: 256 threads, one 16-byte vector per thread, 4 KB of
 // one row per workgroup, consecutive workgroups on consecutive addresses.  Measured on MI355X, a
 // read-modify-write stream moves 6.5 TB/s this way against 5.1 TB/s when each workgroup loops
-// over a whole row (the concurrent writes then spread over thousands of rows), so the standalone
-// backward uses this shape; the fused kernel cannot (its row needs one owner for the reduction).
+// over a whole row (the concurrent writes then spread over thousands of rows).
 // grid = (chunks per row, rows mod kRowsPerGridY, rows / kRowsPerGridY).
+// One 4 KB chunk (256 threads x one 16-byte vector) of one row of the gradient.
 template <class Tr>
-__global__ __launch_bounds__(256) void dlogits_chunk_kernel(const typename Tr::elem* logits, int64_t row_stride,
-                                                            int32_t V, int64_t N,
-                                                            const int32_t* __restrict__ token_ids,
-                                                            const float* __restrict__ lse,
-                                                            const float* __restrict__ gcoef, float grad_out,
-                                                            typename Tr::elem* dlogits,
-                                                            const uint8_t* __restrict__ only)
+__device__ __forceinline__ void dlogits_chunk_body(const typename Tr::elem* logits, int64_t row_stride, int32_t V, int64_t row,
+                                                   int chunk, bool last_chunk, const int32_t* __restrict__ token_ids,
+                                                   const float* __restrict__ lse, const float* __restrict__ gcoef,
+                                                   float grad_out, typename Tr::elem* dlogits)
 {
     constexpr int E = Tr::kPerVec;
-    const int64_t row = (int64_t)blockIdx.z * kRowsPerGridY + blockIdx.y;
-    if (row >= N) return;
-    if (only != nullptr && only[row] == 0) return;
     const float g = gcoef[row] * grad_out;
     const float l = lse[row];
     const int32_t y = token_ids[row];
@@ -417,7 +398,7 @@ __global__ __launch_bounds__(256) void dlogits_chunk_kernel(const typename Tr::e
     const typename Tr::elem* rowp = logits + row * row_stride;
     typename Tr::elem* outp = dlogits + row * row_stride;
     const int nvec = V / E;
-    const int i = blockIdx.x * 256 + threadIdx.x;
+    const int i = chunk * 256 + threadIdx.x;
     const float c = live ? fmaf(-l, kLog2e, log2f(fabsf(g))) : 0.0f;
     const bool negate = g > 0.0f;              // see dlogits_core
     const float sgn = negate ? -1.0f : 1.0f;
@@ -442,7 +423,7 @@ __global__ __launch_bounds__(256) void dlogits_chunk_kernel(const typename Tr::e
             store_stream(op, o);
         }
     }
-    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 255) {   // ragged tail of the row
+    if (last_chunk && threadIdx.x == 255) {   // ragged tail of the row
         for (int j = nvec * E; j < V; ++j) {
             float x = 0.0f;
             if (live) {
@@ -452,6 +433,55 @@ __global__ __launch_bounds__(256) void dlogits_chunk_kernel(const typename Tr::e
             Tr::store1(outp + j, x);
         }
     }
+}
+
+template <class Tr>
+__global__ __launch_bounds__(256) void dlogits_chunk_kernel(const typename Tr::elem* logits, int64_t row_stride,
+                                                            int32_t V, int64_t N,
+                                                            const int32_t* __restrict__ token_ids,
+                                                            const float* __restrict__ lse,
+                                                            const float* __restrict__ gcoef, float grad_out,
+                                                            typename Tr::elem* dlogits)
+{
+    const int64_t row = (int64_t)blockIdx.z * kRowsPerGridY + blockIdx.y;
+    if (row >= N) return;
+    dlogits_chunk_body<Tr>(logits, row_stride, V, row, (int)blockIdx.x, blockIdx.x == gridDim.x - 1, token_ids, lse, gcoef,
+                           grad_out, dlogits);
+}
+
+// The same for a list of rows (the rows the one-call path deferred until the entropy gate was
+// known): a fixed grid of (chunks per row) x kListRowSlots workgroups walks the list, so the launch
+// costs what the listed rows cost, not a scan of all rows.
+constexpr int kListRowSlots = 128;
+template <class Tr>
+__global__ __launch_bounds__(256) void dlogits_rows_kernel(const typename Tr::elem* logits, int64_t row_stride, int32_t V,
+                                                           const uint32_t* __restrict__ rows,
+                                                           const uint32_t* __restrict__ n_rows,
+                                                           const int32_t* __restrict__ token_ids,
+                                                           const float* __restrict__ lse,
+                                                           const float* __restrict__ gcoef, float grad_out,
+                                                           typename Tr::elem* dlogits)
+{
+    const uint32_t n = *n_rows;
+    for (uint32_t k = blockIdx.y; k < n; k += gridDim.y)
+        dlogits_chunk_body<Tr>(logits, row_stride, V, (int64_t)rows[k], (int)blockIdx.x, blockIdx.x == gridDim.x - 1, token_ids,
+                               lse, gcoef, grad_out, dlogits);
+}
+
+// Collects the rows flagged in `defer` into a list (order arbitrary: each row is processed exactly
+// once whatever its position).  *count must be zero before the launch.
+__global__ __launch_bounds__(256) void defer_compact_kernel(const uint8_t* __restrict__ defer, int64_t N,
+                                                            uint32_t* __restrict__ rows, uint32_t* __restrict__ count)
+{
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const bool flagged = t < N && defer[t] != 0;
+    const unsigned long long ballot = __ballot(flagged);
+    if (ballot == 0ull) return;
+    const int lane = threadIdx.x & 63;
+    uint32_t base = 0;
+    if (lane == 0) base = atomicAdd(count, (uint32_t)__popcll(ballot));
+    base = __shfl(base, 0);
+    if (flagged) rows[base + __popcll(ballot & ((1ull << lane) - 1ull))] = (uint32_t)t;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -551,8 +581,10 @@ __device__ __forceinline__ bool response_bounds_ok(const int32_t* cu, int i, int
 
 // Single workgroup: is cu_seqlens well formed?  (The fused kernel needs the answer before it
 // writes any gradient.)
-__global__ __launch_bounds__(kTokBlock) void cu_check_kernel(const int32_t* cu, int32_t R, int64_t N, uint32_t* badcu)
+__global__ __launch_bounds__(kTokBlock) void cu_check_kernel(const int32_t* cu, int32_t R, int64_t N, uint32_t* badcu,
+                                                             uint32_t* defer_count)
 {
+    if (threadIdx.x == 0) *defer_count = 0u;       // the list of deferred rows starts empty
     int bad = 0;
     for (int i = threadIdx.x; i < R; i += kTokBlock) bad |= response_bounds_ok(cu, i, R, N) ? 0 : 1;
     bad = __syncthreads_or(bad);
@@ -579,6 +611,7 @@ __global__ __launch_bounds__(kTokBlock) void response_entropy_kernel(TokenArgs a
 
 __global__ __launch_bounds__(kTokBlock) void token_terms_kernel(TokenArgs a)
 {
+    extern __shared__ double seg_table[];       // [K][7], only when the per-segment diagnostics are wanted
     __shared__ double scratch[kTokBlock / 64];
     __shared__ long long iscratch[kTokBlock / 64];
     const int tid = threadIdx.x;
@@ -597,6 +630,11 @@ __global__ __launch_bounds__(kTokBlock) void token_terms_kernel(TokenArgs a)
     const int64_t t = (int64_t)blockIdx.x * kTokBlock + tid;
     double contrib = 0.0;
     long long n_mask = 0, n_clip = 0, n_pos = 0, flags = badcu ? ULORL_STATUS_BAD_CU : 0;
+    // what the per-segment diagnostics see of this token: exactly the values the call stores
+    float g_out = 0.0f, r_out = 0.0f;
+    uint8_t m_out = 0;
+    int32_t sg_seg = 0;
+    float sg_logp = 0.0f, sg_ent = 0.0f, sg_adv = 0.0f, sg_old = 0.0f;
 
     if (t < a.N) {
         // response of token t: largest i with cu[i] <= t
@@ -631,8 +669,8 @@ __global__ __launch_bounds__(kTokBlock) void token_terms_kernel(TokenArgs a)
         if (bad_tok) flags |= ULORL_STATUS_BAD_TOKEN;
         if (!bad_tok && nonfinite) flags |= ULORL_STATUS_NONFINITE;
 
-        float g_out = 0.0f, r_out = 0.0f;
-        uint8_t m_out = 0;
+        sg_seg = seg; sg_logp = lpf; sg_ent = hf; sg_adv = a.adv[t];
+        sg_old = (a.old_logp != nullptr) ? a.old_logp[t] : 0.0f;
         if (!bad_tok && !nonfinite && !badcu) {
             const TokenEval ev = token_eval(lpf, a.adv[t], a.is_mode == ULORL_IS_POIS ? 0.0f : a.old_logp[t],
                                             a.is_mode, a.eps_low, a.eps_high, a.log_tau, a.inv_D);
@@ -661,6 +699,15 @@ __global__ __launch_bounds__(kTokBlock) void token_terms_kernel(TokenArgs a)
         a.part_cnt[4 * (int64_t)blockIdx.x + 1] = c1;
         a.part_cnt[4 * (int64_t)blockIdx.x + 2] = c2;
         a.part_cnt[4 * (int64_t)blockIdx.x + 3] = fl;
+    }
+    if (a.seg.K > 0) {      // uniform over the grid
+        int k;
+        double v[kSegStats], oor;
+        seg_token_values(t < a.N, sg_seg, a.seg.K, r_out, sg_logp, a.old_logp != nullptr, sg_old, sg_ent, m_out, sg_adv,
+                         a.eps_low, a.eps_high, k, v, oor);
+        const double o = seg_block_partials(k, v, oor, a.seg.K, seg_table,
+                                            a.seg.part + (int64_t)blockIdx.x * a.seg.K * kSegStats);
+        if (tid == 0) a.seg.part_oor[blockIdx.x] = o;
     }
 }
 
@@ -723,6 +770,10 @@ __global__ __launch_bounds__(kTokBlock) void loss_finalize_kernel(TokenArgs a, i
             counters[3] = fl;
         }
     }
+    if (a.seg.K > 0) {
+        __shared__ double seg_scratch[kTokBlock];
+        seg_finalize(a.seg, nblk, seg_scratch);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -743,11 +794,29 @@ struct FusedArgs {
     float* logp;
     float* entropy;
     uint8_t* defer;
+    float* zy_row;          // [N] chosen logit of each row, kept for the repair pass (row-cooperative kernel only)
     const uint32_t* badcu;  // one word: non-zero if cu_seqlens is malformed (then nothing is trained)
     int32_t is_mode, gate_mode;
     double eps_low, eps_high, log_tau, inv_D;
     float grad_out;
 };
+
+// What the one-call path does with a row once its statistics are known: mode 0 = write zeros,
+// 1 = write the gradient with coefficient g, 2 = leave the row to the filtered backward launch that
+// follows the gate (a member of the MPT set under an entropy gate).
+__device__ __forceinline__ int row_decision(const FusedArgs& a, int32_t y, int32_t V, float lse, float lp, float ent,
+                                            float adv, float old, uint32_t badcu, float& g)
+{
+    g = 0.0f;
+    const bool bad = (y < 0 || y >= V) || not_finite(lp) || not_finite(ent) || not_finite(lse) || badcu != 0;
+    if (bad) return 0;
+    const TokenEval ev = token_eval(lp, adv, old, a.is_mode, a.eps_low, a.eps_high, a.log_tau, a.inv_D);
+    const bool gate_known = a.gate_mode == ULORL_GATE_ALWAYS || a.gate_mode == ULORL_GATE_NEVER;
+    if (ev.mpt && !gate_known) return 2;
+    const bool I = ev.mpt && a.gate_mode == ULORL_GATE_ALWAYS;
+    g = (I ? 0.0f : ev.g) * a.grad_out;
+    return row_is_live(g, lse, y, V) ? 1 : 0;
+}
 
 template <class Tr, int NT, int U>
 __global__ __launch_bounds__(NT) void fused_row_kernel(const typename Tr::elem* logits, int64_t row_stride, int32_t V,
@@ -765,21 +834,9 @@ __global__ __launch_bounds__(NT) void fused_row_kernel(const typename Tr::elem* 
         a.lse[row] = lse;
         a.logp[row] = lp;
         a.entropy[row] = ent;
-        int mode = 0;
-        float g = 0.0f;
-        const bool bad = (y < 0 || y >= V) || not_finite(lp) || not_finite(ent) || not_finite(lse) || *a.badcu != 0;
-        if (!bad) {
-            const TokenEval ev = token_eval(lp, a.adv[row], a.is_mode == ULORL_IS_POIS ? 0.0f : a.old_logp[row],
-                                            a.is_mode, a.eps_low, a.eps_high, a.log_tau, a.inv_D);
-            const bool gate_known = a.gate_mode == ULORL_GATE_ALWAYS || a.gate_mode == ULORL_GATE_NEVER;
-            if (ev.mpt && !gate_known) {
-                mode = 2;
-            } else {
-                const bool I = ev.mpt && a.gate_mode == ULORL_GATE_ALWAYS;
-                g = (I ? 0.0f : ev.g) * a.grad_out;
-                mode = row_is_live(g, lse, y, V) ? 1 : 0;
-            }
-        }
+        float g;
+        const int mode = row_decision(a, y, V, lse, lp, ent, a.adv[row], a.is_mode == ULORL_IS_POIS ? 0.0f : a.old_logp[row],
+                                      *a.badcu, g);
         a.defer[row] = mode == 2 ? 1 : 0;
         bc_g = g;
         bc_l = lse;
@@ -806,9 +863,12 @@ __global__ __launch_bounds__(NT) void fused_row_kernel(const typename Tr::elem* 
 // (S >= 1 for a non-empty piece; the tag), so no ordering between memory locations and no cache
 // maintenance is needed.  Workgroups are dispatched in order of their linear id and a row's
 // pieces have consecutive ids, so the partners of a resident workgroup are resident or next in
-// line; the wait is nevertheless bounded (spin_limit polls, seconds by default): on expiry the row
-// is given a zero gradient, not-a-number statistics and the SYNC status bit.  Every workgroup of a
-// row merges the same pieces in the same order and therefore takes the same decisions.
+// line; the wait is nevertheless bounded (spin_limit polls, seconds by default).  A workgroup whose
+// wait expires writes NOTHING (in place, its piece of the logits stays intact), re-publishes its
+// second word with the tag kTagPending and raises the sync_fail word; after the kernel every piece's
+// statistics are in the slots, and the repair kernels below finish the row from them.  Every
+// workgroup of a row that completes its wait merges the same pieces in the same order and therefore
+// takes the same decisions; the repair pass merges them in that order too.
 constexpr int kClusterThreads = 256;
 constexpr int kClusterMaxPieces = 64;         // one polled piece per lane of a wave
 
@@ -905,7 +965,11 @@ __device__ __forceinline__ unsigned long long piece_word0(float m, float S)
 {
     return ((unsigned long long)__float_as_uint(S) << 32) | __float_as_uint(m);
 }
-__device__ __forceinline__ unsigned long long piece_word1(float T) { return (1ull << 32) | __float_as_uint(T); }
+constexpr unsigned long long kTagPublished = 1, kTagPending = 3;   // pending = published, and the piece's gradient is not written yet
+__device__ __forceinline__ unsigned long long piece_word1(float T, unsigned long long tag = kTagPublished)
+{
+    return (tag << 32) | __float_as_uint(T);
+}
 
 // Merge of a row's pieces by one wave: lane c < C brings piece c, the other lanes nothing; a fixed
 // xor-shuffle tree, so every wave that merges the same pieces gets the same bits.
@@ -971,6 +1035,7 @@ __global__ __launch_bounds__(kClusterThreads) void cluster_row_kernel(const type
     const uint32_t badcu = *a.f.badcu;
     float zy = 0.0f;
     if (tid == 0 && y >= 0 && y < V) zy = Tr::load1(rowp + y);
+    if (tid == 0 && c == 0) a.f.zy_row[row] = zy;     // the repair pass cannot read it from a row overwritten in place
 
     // ---- phase 1: the piece into registers, its statistics (valid on thread 0)
     u32x4 v[VPT];
@@ -1009,36 +1074,25 @@ __global__ __launch_bounds__(kClusterThreads) void cluster_row_kernel(const type
         expired = __any(expired);
         merge_pieces_tree(pm, pS, pT);
         if (tid == 0) {
-            float lse, lp, ent;
-            finish_pieces(pm, pS, pT, y >= 0 && y < V, zy, lse, lp, ent);
             if (expired) {
-                lse = lp = ent = __builtin_nanf("");
+                // leave everything to the repair pass: nothing of this piece is written
+                __hip_atomic_store(slot + 2 * c + 1, piece_word1(T, kTagPending), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 *a.sync_fail = 1u;
-            }
-            int mode = 0;
-            float g = 0.0f;
-            const bool bad = (y < 0 || y >= V) || not_finite(lp) || not_finite(ent) || not_finite(lse) || badcu != 0;
-            if (!bad) {
-                const TokenEval ev = token_eval(lp, adv_row, old_row, a.f.is_mode, a.f.eps_low, a.f.eps_high, a.f.log_tau,
-                                                a.f.inv_D);
-                const bool gate_known = a.f.gate_mode == ULORL_GATE_ALWAYS || a.f.gate_mode == ULORL_GATE_NEVER;
-                if (ev.mpt && !gate_known) {
-                    mode = 2;
-                } else {
-                    const bool I = ev.mpt && a.f.gate_mode == ULORL_GATE_ALWAYS;
-                    g = (I ? 0.0f : ev.g) * a.f.grad_out;
-                    mode = row_is_live(g, lse, y, V) ? 1 : 0;
+                bc_mode = 2;
+            } else {
+                float lse, lp, ent, g;
+                finish_pieces(pm, pS, pT, y >= 0 && y < V, zy, lse, lp, ent);
+                const int mode = row_decision(a.f, y, V, lse, lp, ent, adv_row, old_row, badcu, g);
+                if (c == 0) {
+                    a.f.lse[row] = lse;
+                    a.f.logp[row] = lp;
+                    a.f.entropy[row] = ent;
+                    a.f.defer[row] = mode == 2 ? 1 : 0;
                 }
+                bc_g = g;
+                bc_l = lse;
+                bc_mode = mode;
             }
-            if (c == 0) {
-                a.f.lse[row] = lse;
-                a.f.logp[row] = lp;
-                a.f.entropy[row] = ent;
-                a.f.defer[row] = mode == 2 ? 1 : 0;
-            }
-            bc_g = g;
-            bc_l = lse;
-            bc_mode = mode;
         }
     }
     __syncthreads();
@@ -1116,6 +1170,114 @@ __global__ void fill_zero_u64_kernel(unsigned long long* p, int64_t n, uint32_t*
 }
 
 // ---------------------------------------------------------------------------------------------
+// repair pass of the row-cooperative kernel
+// ---------------------------------------------------------------------------------------------
+// Both kernels have a small fixed grid and return at once unless a wait expired (sync_fail).  By
+// the time they run every piece of every row has published its statistics (a workgroup publishes
+// before it waits), so a row's statistics can be formed exactly as a workgroup would have formed
+// them; a pending piece's logits are intact because only its own workgroup writes them.
+constexpr int kRepairRowGrid = 256;      // workgroups of 4 waves, one wave per row at a time
+constexpr int kRepairPieceGrid = 2048;   // workgroups of kClusterThreads, one piece at a time
+
+// Rows with a pending piece: their statistics, per-row outputs and deferral flag, as piece 0 would
+// have written them (rewritten with the same bits if it did).
+__global__ __launch_bounds__(256) void repair_rows_kernel(ClusterArgs a, int32_t V)
+{
+    if (*a.sync_fail == 0u) return;
+    const int lane = threadIdx.x & 63;
+    const int C = a.C;
+    const uint32_t badcu = *a.f.badcu;
+    for (int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); row < a.N; row += (int64_t)gridDim.x * 4) {
+        float pm = kEmpty, pS = 0.0f, pT = 0.0f;
+        int pending = 0;
+        if (lane < C) {
+            const unsigned long long w0 = a.slots[(row * C + lane) * 2], w1 = a.slots[(row * C + lane) * 2 + 1];
+            pm = __uint_as_float((uint32_t)w0);
+            pS = __uint_as_float((uint32_t)(w0 >> 32));
+            pT = __uint_as_float((uint32_t)w1);
+            pending = (w1 >> 32) == kTagPending;
+        }
+        if (!__any(pending)) continue;
+        merge_pieces_tree(pm, pS, pT);
+        if (lane == 0) {
+            const int32_t y = a.f.token_ids[row];
+            float lse, lp, ent, g;
+            finish_pieces(pm, pS, pT, y >= 0 && y < V, a.f.zy_row[row], lse, lp, ent);
+            const int mode = row_decision(a.f, y, V, lse, lp, ent, a.f.adv[row],
+                                          a.f.is_mode == ULORL_IS_POIS ? 0.0f : a.f.old_logp[row], badcu, g);
+            a.f.lse[row] = lse;
+            a.f.logp[row] = lp;
+            a.f.entropy[row] = ent;
+            a.f.defer[row] = mode == 2 ? 1 : 0;
+        }
+    }
+}
+
+// Pending pieces of rows that were not deferred as a whole: their share of the gradient, with the
+// arithmetic of the backward call (the same bits the piece's own workgroup would have written).
+// Runs after the O(N) epilogue (gcoef) and after the filtered backward launch of the deferred rows.
+template <class Tr>
+__global__ __launch_bounds__(kClusterThreads) void repair_pieces_kernel(const typename Tr::elem* logits, int64_t row_stride,
+                                                                        int32_t V, typename Tr::elem* dlogits,
+                                                                        ClusterArgs a, int32_t vpt,
+                                                                        const float* __restrict__ gcoef)
+{
+    if (*a.sync_fail == 0u) return;
+    constexpr int E = Tr::kPerVec;
+    constexpr int NT = kClusterThreads;
+    const int C = a.C;
+    const int nvec = V / E;
+    const int tid = threadIdx.x;
+    for (int64_t q = blockIdx.x; q < a.N * C; q += gridDim.x) {
+        const int64_t row = q / C;
+        const int c = (int)(q - row * C);
+        if ((a.slots[q * 2 + 1] >> 32) != kTagPending || a.f.defer[row] != 0) continue;   // uniform over the workgroup
+        const float g = gcoef[row] * a.f.grad_out;
+        const float l = a.f.lse[row];
+        const int32_t y = a.f.token_ids[row];
+        const bool live = row_is_live(g, l, y, V);
+        const typename Tr::elem* rowp = logits + row * row_stride;
+        typename Tr::elem* outp = dlogits + row * row_stride;
+        const float cexp = live ? fmaf(-l, kLog2e, log2f(fabsf(g))) : 0.0f;
+        const bool negate = g > 0.0f;
+        const float sgn = negate ? -1.0f : 1.0f;
+        const float g_mag = negate ? -g : g;
+        const int yvec = y / E;
+        const int first = c * NT * vpt;
+        for (int k = 0; k < vpt; ++k) {
+            const int i = first + k * NT + tid;
+            if (i >= nvec) break;
+            u32x4* op = reinterpret_cast<u32x4*>(outp) + i;
+            if (!live) {
+                store_stream(op, u32x4{0u, 0u, 0u, 0u});
+                continue;
+            }
+            float f[E];
+            Tr::unpack(load_stream(reinterpret_cast<const u32x4*>(rowp) + i), f);
+#pragma unroll
+            for (int e = 0; e < E; ++e) f[e] = fast_exp2(fmaf(f[e], kLog2e, cexp));
+            if (i == yvec) {
+#pragma unroll
+                for (int e = 0; e < E; ++e) f[e] += (e == y - yvec * E) ? g_mag : 0.0f;
+            }
+            u32x4 o = Tr::pack(f);
+            if (negate) o ^= Tr::sign_bits();
+            store_stream(op, o);
+        }
+        if (c == C - 1 && tid == NT - 1) {      // ragged tail of the row
+            for (int j = nvec * E; j < V; ++j) {
+                float x = 0.0f;
+                if (live) {
+                    x = sgn * fast_exp2(fmaf(Tr::load1(rowp + j), kLog2e, cexp));
+                    if (j == y) x += g;
+                }
+                Tr::store1(outp + j, x);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // forward call by pieces: the statistics half of the row-cooperative kernel
 // ---------------------------------------------------------------------------------------------
 // The same pieces, the same per-piece arithmetic and the same merge tree as cluster_row_kernel, so
@@ -1185,6 +1347,12 @@ __global__ __launch_bounds__(256) void piece_merge_kernel(const typename Tr::ele
 // ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
+// Shape of the one-workgroup-per-row kernels (row_stats_kernel, fused_row_kernel): 512 threads,
+// eight 16-byte loads in flight per lane.  One shape for both, so that their row statistics are
+// bit-identical.
+constexpr int kRowThreads = 512;
+constexpr int kRowUnroll = 8;
+
 bool shape_ok(int64_t N, int64_t V, int64_t stride)
 {
     return N > 0 && N <= kMaxRows && V > 0 && V <= 0x7fffffffLL && stride >= V;
@@ -1200,95 +1368,56 @@ int32_t check_logits(const void* logits, int32_t dt, int64_t N, int64_t V, int64
     return ULORL_OK;
 }
 
-template <class Tr, int NT, int U>
+dim3 rows_grid(unsigned x, int64_t N)
+{
+    return dim3(x, (unsigned)(N < kRowsPerGridY ? N : kRowsPerGridY), (unsigned)((N + kRowsPerGridY - 1) / kRowsPerGridY));
+}
+
+template <class Tr>
 void launch_row_stats(const void* logits, int64_t N, int64_t V, int64_t stride, const int32_t* y, float* lse,
                       float* logp, float* ent, hipStream_t st)
 {
-    hipLaunchKernelGGL((row_stats_kernel<Tr, NT, U>), dim3((unsigned)N), dim3(NT), 0, st,
+    hipLaunchKernelGGL((row_stats_kernel<Tr, kRowThreads, kRowUnroll>), dim3((unsigned)N), dim3(kRowThreads), 0, st,
                        (const typename Tr::elem*)logits, stride, (int32_t)V, y, lse, logp, ent);
 }
 
 template <class Tr>
-bool dispatch_row_stats(int nt, int u, const void* logits, int64_t N, int64_t V, int64_t stride, const int32_t* y,
-                        float* lse, float* logp, float* ent, hipStream_t st)
-{
-#define ULORL_CASE(NT_, U_)                                                          \
-    if (nt == NT_ && u == U_) {                                                      \
-        launch_row_stats<Tr, NT_, U_>(logits, N, V, stride, y, lse, logp, ent, st);  \
-        return true;                                                                 \
-    }
-    ULORL_CASE(256, 2) ULORL_CASE(256, 4) ULORL_CASE(256, 8)
-    ULORL_CASE(512, 2) ULORL_CASE(512, 4) ULORL_CASE(512, 8)
-    ULORL_CASE(1024, 2) ULORL_CASE(1024, 4) ULORL_CASE(1024, 8)
-#undef ULORL_CASE
-    return false;
-}
-
-template <class Tr, int NT, int U>
 void launch_dlogits(const void* logits, int64_t N, int64_t V, int64_t stride, const int32_t* y, const float* lse,
-                    const float* g, float grad_out, void* dz, const uint8_t* only, hipStream_t st)
+                    const float* g, float grad_out, void* dz, hipStream_t st)
 {
-    hipLaunchKernelGGL((dlogits_kernel<Tr, NT, U>), dim3((unsigned)N), dim3(NT), 0, st,
-                       (const typename Tr::elem*)logits, stride, (int32_t)V, y, lse, g, grad_out,
-                       (typename Tr::elem*)dz, only);
+    const int64_t nvec = V / Tr::kPerVec;
+    const int64_t chunks = nvec > 0 ? (nvec + 255) / 256 : 1;      // at most 2^21: V < 2^31
+    hipLaunchKernelGGL((dlogits_chunk_kernel<Tr>), rows_grid((unsigned)chunks, N), dim3(256), 0, st,
+                       (const typename Tr::elem*)logits, stride, (int32_t)V, N, y, lse, g, grad_out,
+                       (typename Tr::elem*)dz);
+}
+
+// The gradient of the rows flagged in `defer`, through a compacted list.
+template <class Tr>
+void launch_dlogits_deferred(const void* logits, int64_t N, int64_t V, int64_t stride, const int32_t* y, const float* lse,
+                             const float* g, float grad_out, void* dz, const uint8_t* defer, uint32_t* list,
+                             uint32_t* count, hipStream_t st)
+{
+    const int64_t nvec = V / Tr::kPerVec;
+    const int64_t chunks = nvec > 0 ? (nvec + 255) / 256 : 1;
+    hipLaunchKernelGGL(defer_compact_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, st, defer, N, list, count);
+    hipLaunchKernelGGL((dlogits_rows_kernel<Tr>), dim3((unsigned)chunks, kListRowSlots), dim3(256), 0, st,
+                       (const typename Tr::elem*)logits, stride, (int32_t)V, (const uint32_t*)list, (const uint32_t*)count, y,
+                       lse, g, grad_out, (typename Tr::elem*)dz);
 }
 
 template <class Tr>
-bool dispatch_dlogits(int nt, int u, const void* logits, int64_t N, int64_t V, int64_t stride, const int32_t* y,
-                      const float* lse, const float* g, float grad_out, void* dz, const uint8_t* only, hipStream_t st)
+void launch_fused_rows(const void* logits, int64_t N, int64_t V, int64_t stride, void* dz, const FusedArgs& a, hipStream_t st)
 {
-    if (tuning().bwd_oneshot) {
-        const int64_t nvec = V / Tr::kPerVec;
-        const int64_t chunks = nvec > 0 ? (nvec + 255) / 256 : 1;
-        if (chunks <= 0x7fffffffLL) {
-            dim3 grid((unsigned)chunks, (unsigned)(N < kRowsPerGridY ? N : kRowsPerGridY),
-                      (unsigned)((N + kRowsPerGridY - 1) / kRowsPerGridY));
-            hipLaunchKernelGGL((dlogits_chunk_kernel<Tr>), grid, dim3(256), 0, st, (const typename Tr::elem*)logits, stride,
-                               (int32_t)V, N, y, lse, g, grad_out, (typename Tr::elem*)dz, only);
-            return true;
-        }
-    }
-#define ULORL_CASE(NT_, U_)                                                                    \
-    if (nt == NT_ && u == U_) {                                                                \
-        launch_dlogits<Tr, NT_, U_>(logits, N, V, stride, y, lse, g, grad_out, dz, only, st);  \
-        return true;                                                                           \
-    }
-    ULORL_CASE(256, 2) ULORL_CASE(256, 4) ULORL_CASE(256, 8)
-    ULORL_CASE(512, 2) ULORL_CASE(512, 4) ULORL_CASE(512, 8)
-    ULORL_CASE(1024, 2) ULORL_CASE(1024, 4) ULORL_CASE(1024, 8)
-#undef ULORL_CASE
-    return false;
-}
-
-template <class Tr, int NT, int U>
-void launch_fused(const void* logits, int64_t N, int64_t V, int64_t stride, void* dz, const FusedArgs& a, hipStream_t st)
-{
-    hipLaunchKernelGGL((fused_row_kernel<Tr, NT, U>), dim3((unsigned)N), dim3(NT), 0, st,
+    hipLaunchKernelGGL((fused_row_kernel<Tr, kRowThreads, kRowUnroll>), dim3((unsigned)N), dim3(kRowThreads), 0, st,
                        (const typename Tr::elem*)logits, stride, (int32_t)V, (typename Tr::elem*)dz, a);
-}
-
-template <class Tr>
-bool dispatch_fused(int nt, int u, const void* logits, int64_t N, int64_t V, int64_t stride, void* dz,
-                    const FusedArgs& a, hipStream_t st)
-{
-#define ULORL_CASE(NT_, U_)                                              \
-    if (nt == NT_ && u == U_) {                                          \
-        launch_fused<Tr, NT_, U_>(logits, N, V, stride, dz, a, st);      \
-        return true;                                                     \
-    }
-    ULORL_CASE(256, 2) ULORL_CASE(256, 4) ULORL_CASE(256, 8)
-    ULORL_CASE(512, 2) ULORL_CASE(512, 4) ULORL_CASE(512, 8)
-    ULORL_CASE(1024, 2) ULORL_CASE(1024, 4) ULORL_CASE(1024, 8)
-#undef ULORL_CASE
-    return false;
 }
 
 template <class Tr>
 bool launch_piece_stats(const ClusterShape& shape, const void* logits, int64_t N, int64_t V, int64_t stride,
                         const int32_t* y, float* lse, float* logp, float* ent, unsigned long long* slots, hipStream_t st)
 {
-    dim3 grid((unsigned)shape.pieces, (unsigned)(N < kRowsPerGridY ? N : kRowsPerGridY),
-              (unsigned)((N + kRowsPerGridY - 1) / kRowsPerGridY));
+    const dim3 grid = rows_grid((unsigned)shape.pieces, N);
     bool launched = false;
 #define ULORL_CASE(VPT_)                                                                                        \
     if (shape.vpt == VPT_) {                                                                                    \
@@ -1296,7 +1425,7 @@ bool launch_piece_stats(const ClusterShape& shape, const void* logits, int64_t N
                            (const typename Tr::elem*)logits, stride, (int32_t)V, N, (int32_t)shape.pieces, slots); \
         launched = true;                                                                                        \
     }
-    ULORL_CASE(4) ULORL_CASE(8) ULORL_CASE(10) ULORL_CASE(12) ULORL_CASE(15)
+    ULORL_CASE(4) ULORL_CASE(8) ULORL_CASE(15)
 #undef ULORL_CASE
     if (!launched) return false;
     hipLaunchKernelGGL((piece_merge_kernel<Tr>), dim3((unsigned)((N + 3) / 4)), dim3(256), 0, st,
@@ -1311,17 +1440,28 @@ bool launch_cluster(int vpt, const void* logits, int64_t N, int64_t V, int64_t s
 {
     // x: piece (fastest, so a row's pieces have consecutive linear ids and land on different XCDs:
     // putting a row's pieces on one XCD measured 15 % slower), y/z: row
-    dim3 grid((unsigned)a.C, (unsigned)(N < kRowsPerGridY ? N : kRowsPerGridY),
-                      (unsigned)((N + kRowsPerGridY - 1) / kRowsPerGridY));
+    const dim3 grid = rows_grid((unsigned)a.C, N);
 #define ULORL_CASE(VPT_)                                                                                       \
     if (vpt == VPT_) {                                                                                         \
         hipLaunchKernelGGL((cluster_row_kernel<Tr, VPT_>), grid, dim3(kClusterThreads), 0, st,                 \
                            (const typename Tr::elem*)logits, stride, (int32_t)V, (typename Tr::elem*)dz, a);   \
         return true;                                                                                           \
     }
-    ULORL_CASE(4) ULORL_CASE(8) ULORL_CASE(10) ULORL_CASE(12) ULORL_CASE(15)
+    ULORL_CASE(4) ULORL_CASE(8) ULORL_CASE(15)
 #undef ULORL_CASE
     return false;
+}
+
+int32_t check_fwd_bwd_args(const void* logits, int32_t dt, int64_t N, int64_t V, int64_t row_stride,
+                           const int32_t* token_ids, const int32_t* cu_seqlens, int32_t R, const float* old_logp,
+                           const float* advantages, const ulorl_params* p, const float* loss, const float* logp,
+                           const float* entropy, const float* lse, const float* gcoef, const void* dlogits)
+{
+    int32_t rc = check_logits(logits, dt, N, V, row_stride);
+    if (rc != ULORL_OK) return rc;
+    if (!token_ids || !logp || !entropy || !lse || !advantages || !dlogits) return ULORL_ERR_NULL;
+    if (((uintptr_t)dlogits & 15u) != 0) return ULORL_ERR_ALIGN;
+    return check_objective_args(cu_seqlens, R, old_logp, p, loss, gcoef);
 }
 
 }  // namespace
@@ -1332,13 +1472,12 @@ static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; 
 
 // Shape of the row-cooperative kernel for a row of V elements: vectors per thread and pieces
 // (workgroups) per row; pieces == 0 if the row is too long for one wave to poll its pieces.
+// A function of V and the storage type only, so the workspace size is too.
 ClusterShape cluster_shape(int64_t V, int32_t dt)
 {
     const int64_t nvec = V / (dt == ULORL_F32 ? 4 : 8);
     ClusterShape c;
     c.vpt = nvec >= kClusterThreads * 15 ? 15 : nvec >= kClusterThreads * 8 ? 8 : 4;
-    const int forced = tuning().fused_vpt;
-    if (forced == 4 || forced == 8 || forced == 10 || forced == 12 || forced == 15) c.vpt = forced;
     const int64_t per_piece = kClusterThreads * (int64_t)c.vpt;
     const int64_t pieces = nvec > 0 ? (nvec + per_piece - 1) / per_piece : 1;
     c.pieces = pieces <= kClusterMaxPieces ? (int)pieces : 0;
@@ -1361,8 +1500,48 @@ WorkspaceLayout workspace_layout(int64_t N, int64_t V, int32_t R)
     w.part_cnt = off; off = align_up(off + sizeof(int64_t) * 4 * (size_t)w.nblk, 256);
     w.defer = off;    off = align_up(off + (size_t)N, 256);
     w.badcu = off;    off = align_up(off + sizeof(uint32_t), 256);
+    w.zy = off;       off = align_up(off + (V > 0 ? sizeof(float) * (size_t)N : 0), 256);
+    w.defer_list = off;  off = align_up(off + (V > 0 ? sizeof(uint32_t) * (size_t)N : 0), 256);
+    w.defer_count = off; off = align_up(off + sizeof(uint32_t), 256);
     w.total = off;
     return w;
+}
+
+int32_t resolve_launch(const ulorl_launch* launch, LaunchOpts* out)
+{
+    *out = LaunchOpts();
+    if (!launch) return ULORL_OK;
+    if ((launch->flags & ~(uint32_t)ULORL_LAUNCH_PER_ROW) != 0) return ULORL_ERR_PARAM;
+    for (int i = 0; i < 4; ++i)
+        if (launch->reserved[i] != 0) return ULORL_ERR_PARAM;
+    if (launch->sync_spins < 0 || launch->gemm_tile < 0 || launch->gemm_tile > 1 || launch->gemm_group_m < 0 ||
+        launch->gemm_group_m > 64)
+        return ULORL_ERR_PARAM;
+    out->per_row = (launch->flags & ULORL_LAUNCH_PER_ROW) != 0;
+    if (launch->sync_spins > 0) out->sync_spins = launch->sync_spins;
+    out->gemm_tile = launch->gemm_tile;
+    if (launch->gemm_group_m > 0) out->gemm_group_m = launch->gemm_group_m;
+    return ULORL_OK;
+}
+
+int32_t resolve_segment_stats(const ulorl_segment_stats* st, int64_t N, SegStatsArgs* out)
+{
+    *out = SegStatsArgs();
+    out->K = 0;
+    if (!st) return ULORL_OK;
+    if (st->K <= 0 || st->K > kSegMaxK || st->reserved != 0 || N > 0x7fffffffLL) return ULORL_ERR_SHAPE;
+    if (!st->count || !st->ratio_sum || !st->ratio_max || !st->clipped || !st->kl_sum || !st->ent_sum || !st->masked)
+        return ULORL_ERR_NULL;
+    if (!st->workspace || ((uintptr_t)st->workspace & 255u) != 0 || st->workspace_bytes < seg_workspace_bytes(N, st->K))
+        return ULORL_ERR_WORKSPACE;
+    const size_t nblk = (size_t)((N + kSegBlock - 1) / kSegBlock);
+    out->K = st->K;
+    out->part = (double*)st->workspace;
+    out->part_oor = (double*)((char*)st->workspace + seg_align_up(nblk * (size_t)st->K * kSegStats * sizeof(double), 256));
+    out->count = st->count; out->ratio_sum = st->ratio_sum; out->ratio_max = st->ratio_max;
+    out->clipped = st->clipped; out->kl_sum = st->kl_sum; out->ent_sum = st->ent_sum; out->masked = st->masked;
+    out->out_of_range = st->out_of_range;
+    return ULORL_OK;
 }
 
 // Argument checks shared by the forward and the fused forward+backward entry points.
@@ -1384,12 +1563,13 @@ TokenArgs make_token_args(int64_t N, int64_t V, const int32_t* token_ids, const 
                           const int32_t* segment_ids, const float* old_logp, const float* advantages,
                           const ulorl_params* p, float* logp, float* entropy, float* lse, float* gcoef,
                           uint8_t* mpt_mask, float* ratio, int32_t* segment_out, float* resp_entropy,
-                          uint8_t* resp_gate, void* workspace, const WorkspaceLayout& wl)
+                          uint8_t* resp_gate, void* workspace, const WorkspaceLayout& wl, const SegStatsArgs& seg)
 {
     char* ws = (char*)workspace;
     TokenArgs a;
     a.logp = logp; a.entropy = entropy; a.lse = lse; a.token_ids = token_ids; a.cu = cu_seqlens;
-    a.segment_ids = segment_ids; a.old_logp = old_logp; a.adv = advantages; a.gcoef = gcoef;
+    a.segment_ids = segment_ids; a.old_logp = old_logp; a.adv = advantages;
+    a.gcoef = gcoef;
     a.mask = mpt_mask; a.ratio = ratio; a.seg_out = segment_out; a.resp_entropy = resp_entropy;
     a.resp_gate = resp_gate;
     a.hsum = (double*)(ws + wl.hsum); a.rflags = (uint32_t*)(ws + wl.rflags);
@@ -1402,13 +1582,15 @@ TokenArgs make_token_args(int64_t N, int64_t V, const int32_t* token_ids, const 
     a.D = p->denominator > 0.0 ? p->denominator : (double)N;
     a.log_tau = log(a.tau);
     a.inv_D = 1.0 / a.D;
+    a.seg = seg;
     return a;
 }
 
 void launch_token_epilogue(const TokenArgs& a, const WorkspaceLayout& wl, float* loss, int64_t* counters, hipStream_t st)
 {
+    const size_t seg_lds = (size_t)a.seg.K * kSegStats * sizeof(double);
     hipLaunchKernelGGL(response_entropy_kernel, dim3((unsigned)a.R), dim3(kTokBlock), 0, st, a);
-    hipLaunchKernelGGL(token_terms_kernel, dim3((unsigned)wl.nblk), dim3(kTokBlock), 0, st, a);
+    hipLaunchKernelGGL(token_terms_kernel, dim3((unsigned)wl.nblk), dim3(kTokBlock), seg_lds, st, a);
     hipLaunchKernelGGL(loss_finalize_kernel, dim3(1), dim3(kTokBlock), 0, st, a, wl.nblk, loss, counters);
 }
 
@@ -1416,29 +1598,114 @@ void launch_token_epilogue(const TokenArgs& a, const WorkspaceLayout& wl, float*
 
 // Scratch memory of ulorl_token_loss_fwd_bwd_static, the entry point for callers that cannot
 // allocate: the workspace of the one-call path (exchange slots, per-response sums, per-block
-// partial sums, one flag byte per row) in a file-scope device array.  Every GPU the library runs
+// partial sums, nine bytes per row) in a file-scope device array.  Every GPU the library runs
 // on holds its own copy until the process ends.  The name below is a host-side stand-in, never a
 // device address: host code uses the pointer static_scratch_for_current_device() resolves.
 constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {
-int32_t check_fwd_bwd_args(const void* logits, int32_t dt, int64_t N, int64_t V, int64_t row_stride,
-                           const int32_t* token_ids, const int32_t* cu_seqlens, int32_t R, const float* old_logp,
-                           const float* advantages, const ulorl_params* p, const float* loss, const float* logp,
-                           const float* entropy, const float* lse, const float* gcoef, const void* dlogits);
-int32_t static_scratch_for_current_device(void** out);
+
+// Address of this device's copy of the static scratch array, resolved once per device (each GPU
+// holds its own copy of a __device__ array at its own address).
+int32_t static_scratch_for_current_device(void** out)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void* ptrs[kMaxDevices] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return ULORL_ERR_HIP;
+    std::lock_guard<std::mutex> lock(mu);
+    if (ptrs[dev] == nullptr) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return ULORL_ERR_HIP;
+        if (((uintptr_t)ptr & 255u) != 0) return ULORL_ERR_HIP;
+        ptrs[dev] = ptr;
+    }
+    *out = ptrs[dev];
+    return ULORL_OK;
+}
+
+// The one-call path on a validated problem and a workspace of at least wl.total bytes.
 int32_t fwd_bwd_enqueue(const void* logits, int32_t dt, int64_t N, int64_t V, int64_t row_stride,
                         const int32_t* token_ids, const int32_t* cu_seqlens, int32_t R, const int32_t* segment_ids,
                         const float* old_logp, const float* advantages, const ulorl_params* p, float grad_out,
                         float* loss, float* logp, float* entropy, float* lse, float* gcoef, uint8_t* mpt_mask,
                         float* ratio, int32_t* segment_out, float* resp_entropy, uint8_t* resp_gate,
-                        int64_t* counters, void* dlogits, void* workspace, const WorkspaceLayout& wl, void* hip_stream);
+                        int64_t* counters, const SegStatsArgs& seg, void* dlogits, void* workspace,
+                        const WorkspaceLayout& wl, const LaunchOpts& opts, void* hip_stream)
+{
+    hipStream_t st = (hipStream_t)hip_stream;
+    char* ws = (char*)workspace;
+    const bool bf16 = dt == ULORL_BF16;
+
+    TokenArgs a = make_token_args(N, V, token_ids, cu_seqlens, R, segment_ids, old_logp, advantages, p, logp, entropy,
+                                  lse, gcoef, mpt_mask, ratio, segment_out, resp_entropy, resp_gate, workspace, wl, seg);
+    FusedArgs f;
+    f.token_ids = token_ids; f.old_logp = old_logp; f.adv = advantages;
+    f.lse = lse; f.logp = logp; f.entropy = entropy;
+    f.defer = (uint8_t*)(ws + wl.defer); f.zy_row = (float*)(ws + wl.zy); f.badcu = (const uint32_t*)(ws + wl.badcu);
+    f.is_mode = a.is_mode; f.gate_mode = a.gate_mode;
+    f.eps_low = a.eps_low; f.eps_high = a.eps_high; f.log_tau = a.log_tau; f.inv_D = a.inv_D;
+    f.grad_out = grad_out;
+
+    hipLaunchKernelGGL(cu_check_kernel, dim3(1), dim3(kTokBlock), 0, st, cu_seqlens, R, N, (uint32_t*)(ws + wl.badcu),
+                       (uint32_t*)(ws + wl.defer_count));
+    const ClusterShape shape = cluster_shape(V, dt);
+    const bool cooperative = !opts.per_row && shape.pieces > 0 && 2 * N * (int64_t)shape.pieces < (1LL << 38);
+    ClusterArgs ca = {};
+    if (cooperative) {
+        ca.f = f;
+        ca.slots = (unsigned long long*)(ws + wl.slots);
+        ca.sync_fail = (uint32_t*)(ws + wl.syncfail);
+        ca.N = N;
+        ca.C = shape.pieces;
+        ca.spin_limit = opts.sync_spins;
+        a.sync_fail = ca.sync_fail;
+        const int64_t nslots = 2 * N * (int64_t)shape.pieces;
+        hipLaunchKernelGGL(fill_zero_u64_kernel, dim3((unsigned)((nslots + 255) / 256)), dim3(256), 0, st, ca.slots, nslots,
+                           ca.sync_fail);
+        const bool ok = bf16 ? launch_cluster<StoreBF16>(shape.vpt, logits, N, V, row_stride, dlogits, ca, st)
+                             : launch_cluster<StoreF32>(shape.vpt, logits, N, V, row_stride, dlogits, ca, st);
+        if (!ok) return ULORL_ERR_HIP;
+        hipLaunchKernelGGL(repair_rows_kernel, dim3(kRepairRowGrid), dim3(256), 0, st, ca, (int32_t)V);
+    } else if (bf16) {
+        launch_fused_rows<StoreBF16>(logits, N, V, row_stride, dlogits, f, st);
+    } else {
+        launch_fused_rows<StoreF32>(logits, N, V, row_stride, dlogits, f, st);
+    }
+    if (hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;
+    launch_token_epilogue(a, wl, loss, counters, st);
+    if (hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;
+    if (a.gate_mode == ULORL_GATE_PER_RESPONSE || a.gate_mode == ULORL_GATE_GLOBAL) {
+        // MPT members waited for the gate: their rows are still logits (in place) or unwritten
+        uint32_t* list = (uint32_t*)(ws + wl.defer_list);
+        uint32_t* count = (uint32_t*)(ws + wl.defer_count);
+        if (bf16)
+            launch_dlogits_deferred<StoreBF16>(logits, N, V, row_stride, token_ids, lse, gcoef, grad_out, dlogits, f.defer, list,
+                                               count, st);
+        else
+            launch_dlogits_deferred<StoreF32>(logits, N, V, row_stride, token_ids, lse, gcoef, grad_out, dlogits, f.defer, list,
+                                              count, st);
+    }
+    if (cooperative) {
+        if (bf16)
+            hipLaunchKernelGGL((repair_pieces_kernel<StoreBF16>), dim3(kRepairPieceGrid), dim3(kClusterThreads), 0, st,
+                               (const uint16_t*)logits, row_stride, (int32_t)V, (uint16_t*)dlogits, ca, (int32_t)shape.vpt,
+                               (const float*)gcoef);
+        else
+            hipLaunchKernelGGL((repair_pieces_kernel<StoreF32>), dim3(kRepairPieceGrid), dim3(kClusterThreads), 0, st,
+                               (const float*)logits, row_stride, (int32_t)V, (float*)dlogits, ca, (int32_t)shape.vpt,
+                               (const float*)gcoef);
+    }
+    return hipGetLastError() == hipSuccess ? ULORL_OK : ULORL_ERR_HIP;
+}
+
 }  // namespace
 
 extern "C" {
 
-int32_t ulorl_version(void) { return 101; }
+int32_t ulorl_version(void) { return 200; }
 
 const char* ulorl_status_string(int32_t status)
 {
@@ -1467,16 +1734,24 @@ int32_t ulorl_token_loss_fwd(const void* logits, int32_t dt, int64_t N, int64_t 
                              const int32_t* segment_ids, const float* old_logp, const float* advantages,
                              const ulorl_params* p, float* loss, float* logp, float* entropy, float* lse,
                              float* gcoef, uint8_t* mpt_mask, float* ratio, int32_t* segment_out,
-                             float* resp_entropy, uint8_t* resp_gate, int64_t* counters, void* workspace,
-                             size_t workspace_bytes, void* hip_stream)
+                             float* resp_entropy, uint8_t* resp_gate, int64_t* counters,
+                             const ulorl_segment_stats* seg_stats, void* workspace, size_t workspace_bytes,
+                             const ulorl_launch* launch, void* hip_stream)
 {
     int32_t rc = check_logits(logits, dt, N, V, row_stride);
     if (rc != ULORL_OK) return rc;
     if (!token_ids || !logp || !entropy || !lse) return ULORL_ERR_NULL;
+    LaunchOpts opts;
+    rc = resolve_launch(launch, &opts);
+    if (rc != ULORL_OK) return rc;
     const bool stats_only = advantages == nullptr;
     WorkspaceLayout wl = {};
+    SegStatsArgs seg;
+    seg.K = 0;
     if (!stats_only) {
         rc = check_objective_args(cu_seqlens, R, old_logp, p, loss, gcoef);
+        if (rc != ULORL_OK) return rc;
+        rc = resolve_segment_stats(seg_stats, N, &seg);
         if (rc != ULORL_OK) return rc;
         wl = workspace_layout(N, V, R);
         if (!workspace || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < wl.total)
@@ -1488,27 +1763,25 @@ int32_t ulorl_token_loss_fwd(const void* logits, int32_t dt, int64_t N, int64_t 
     // caller gave a workspace that holds the pieces' slots; else one looping workgroup per row.
     const ClusterShape shape = cluster_shape(V, dt);
     const size_t slot_bytes = sizeof(unsigned long long) * 2 * (size_t)N * (size_t)(shape.pieces > 0 ? shape.pieces : 0);
-    const bool by_pieces = tuning().fwd_pieces && shape.pieces > 0 && workspace != nullptr &&
+    const bool by_pieces = !opts.per_row && shape.pieces > 0 && workspace != nullptr &&
                            ((uintptr_t)workspace & 255u) == 0 && workspace_bytes >= slot_bytes;
-    bool ok;
     if (by_pieces) {
         unsigned long long* slots = (unsigned long long*)workspace;    // the layout's first region
-        ok = dt == ULORL_BF16
+        const bool ok = dt == ULORL_BF16
                  ? launch_piece_stats<StoreBF16>(shape, logits, N, V, row_stride, token_ids, lse, logp, entropy, slots, st)
                  : launch_piece_stats<StoreF32>(shape, logits, N, V, row_stride, token_ids, lse, logp, entropy, slots, st);
+        if (!ok) return ULORL_ERR_HIP;
+    } else if (dt == ULORL_BF16) {
+        launch_row_stats<StoreBF16>(logits, N, V, row_stride, token_ids, lse, logp, entropy, st);
     } else {
-        ok = dt == ULORL_BF16
-                 ? dispatch_row_stats<StoreBF16>(tuning().fwd_threads, tuning().fwd_unroll, logits, N, V, row_stride,
-                                                 token_ids, lse, logp, entropy, st)
-                 : dispatch_row_stats<StoreF32>(tuning().fwd_threads, tuning().fwd_unroll, logits, N, V, row_stride,
-                                                token_ids, lse, logp, entropy, st);
+        launch_row_stats<StoreF32>(logits, N, V, row_stride, token_ids, lse, logp, entropy, st);
     }
-    if (!ok || hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;
+    if (hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;
     if (stats_only) return ULORL_OK;
 
     const TokenArgs a = make_token_args(N, V, token_ids, cu_seqlens, R, segment_ids, old_logp, advantages, p, logp,
                                         entropy, lse, gcoef, mpt_mask, ratio, segment_out, resp_entropy, resp_gate,
-                                        workspace, wl);
+                                        workspace, wl, seg);
     launch_token_epilogue(a, wl, loss, counters, st);
     if (hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;
     return ULORL_OK;
@@ -1519,17 +1792,24 @@ int32_t ulorl_token_loss_fwd_bwd(const void* logits, int32_t dt, int64_t N, int6
                                  const int32_t* segment_ids, const float* old_logp, const float* advantages,
                                  const ulorl_params* p, float grad_out, float* loss, float* logp, float* entropy,
                                  float* lse, float* gcoef, uint8_t* mpt_mask, float* ratio, int32_t* segment_out,
-                                 float* resp_entropy, uint8_t* resp_gate, int64_t* counters, void* dlogits,
-                                 void* workspace, size_t workspace_bytes, void* hip_stream)
+                                 float* resp_entropy, uint8_t* resp_gate, int64_t* counters,
+                                 const ulorl_segment_stats* seg_stats, void* dlogits, void* workspace,
+                                 size_t workspace_bytes, const ulorl_launch* launch, void* hip_stream)
 {
     int32_t rc = check_fwd_bwd_args(logits, dt, N, V, row_stride, token_ids, cu_seqlens, R, old_logp, advantages, p,
                                     loss, logp, entropy, lse, gcoef, dlogits);
+    if (rc != ULORL_OK) return rc;
+    LaunchOpts opts;
+    rc = resolve_launch(launch, &opts);
+    if (rc != ULORL_OK) return rc;
+    SegStatsArgs seg;
+    rc = resolve_segment_stats(seg_stats, N, &seg);
     if (rc != ULORL_OK) return rc;
     const WorkspaceLayout wl = workspace_layout(N, V, R);
     if (!workspace || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < wl.total) return ULORL_ERR_WORKSPACE;
     return fwd_bwd_enqueue(logits, dt, N, V, row_stride, token_ids, cu_seqlens, R, segment_ids, old_logp, advantages, p,
                            grad_out, loss, logp, entropy, lse, gcoef, mpt_mask, ratio, segment_out, resp_entropy,
-                           resp_gate, counters, dlogits, workspace, wl, hip_stream);
+                           resp_gate, counters, seg, dlogits, workspace, wl, opts, hip_stream);
 }
 
 int32_t ulorl_init(void)
@@ -1546,10 +1826,17 @@ int32_t ulorl_token_loss_fwd_bwd_static(const void* logits, int32_t dt, int64_t 
                                         const ulorl_params* p, float grad_out, float* loss, float* logp,
                                         float* entropy, float* lse, float* gcoef, uint8_t* mpt_mask, float* ratio,
                                         int32_t* segment_out, float* resp_entropy, uint8_t* resp_gate,
-                                        int64_t* counters, void* dlogits, void* hip_stream)
+                                        int64_t* counters, const ulorl_segment_stats* seg_stats, void* dlogits,
+                                        const ulorl_launch* launch, void* hip_stream)
 {
     int32_t rc = check_fwd_bwd_args(logits, dt, N, V, row_stride, token_ids, cu_seqlens, R, old_logp, advantages, p,
                                     loss, logp, entropy, lse, gcoef, dlogits);
+    if (rc != ULORL_OK) return rc;
+    LaunchOpts opts;
+    rc = resolve_launch(launch, &opts);
+    if (rc != ULORL_OK) return rc;
+    SegStatsArgs seg;
+    rc = resolve_segment_stats(seg_stats, N, &seg);
     if (rc != ULORL_OK) return rc;
     const WorkspaceLayout wl = workspace_layout(N, V, R);
     if (wl.total > kStaticScratchBytes) return ULORL_ERR_TOO_LARGE;
@@ -1558,108 +1845,8 @@ int32_t ulorl_token_loss_fwd_bwd_static(const void* logits, int32_t dt, int64_t 
     if (rc != ULORL_OK) return rc;
     return fwd_bwd_enqueue(logits, dt, N, V, row_stride, token_ids, cu_seqlens, R, segment_ids, old_logp, advantages, p,
                            grad_out, loss, logp, entropy, lse, gcoef, mpt_mask, ratio, segment_out, resp_entropy,
-                           resp_gate, counters, dlogits, ws, wl, hip_stream);
+                           resp_gate, counters, seg, dlogits, ws, wl, opts, hip_stream);
 }
-
-}  // extern "C"
-
-namespace {
-
-int32_t check_fwd_bwd_args(const void* logits, int32_t dt, int64_t N, int64_t V, int64_t row_stride,
-                           const int32_t* token_ids, const int32_t* cu_seqlens, int32_t R, const float* old_logp,
-                           const float* advantages, const ulorl_params* p, const float* loss, const float* logp,
-                           const float* entropy, const float* lse, const float* gcoef, const void* dlogits)
-{
-    int32_t rc = check_logits(logits, dt, N, V, row_stride);
-    if (rc != ULORL_OK) return rc;
-    if (!token_ids || !logp || !entropy || !lse || !advantages || !dlogits) return ULORL_ERR_NULL;
-    if (((uintptr_t)dlogits & 15u) != 0) return ULORL_ERR_ALIGN;
-    return check_objective_args(cu_seqlens, R, old_logp, p, loss, gcoef);
-}
-
-// Address of this device's copy of the static scratch array, resolved once per device (each GPU
-// holds its own copy of a __device__ array at its own address).
-int32_t static_scratch_for_current_device(void** out)
-{
-    constexpr int kMaxDevices = 64;
-    static std::mutex mu;
-    static void* ptrs[kMaxDevices] = {};
-    int dev = -1;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return ULORL_ERR_HIP;
-    std::lock_guard<std::mutex> lock(mu);
-    if (ptrs[dev] == nullptr) {
-        void* ptr = nullptr;
-        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return ULORL_ERR_HIP;
-        if (((uintptr_t)ptr & 255u) != 0) return ULORL_ERR_HIP;
-        ptrs[dev] = ptr;
-    }
-    *out = ptrs[dev];
-    return ULORL_OK;
-}
-
-int32_t fwd_bwd_enqueue(const void* logits, int32_t dt, int64_t N, int64_t V, int64_t row_stride,
-                        const int32_t* token_ids, const int32_t* cu_seqlens, int32_t R, const int32_t* segment_ids,
-                        const float* old_logp, const float* advantages, const ulorl_params* p, float grad_out,
-                        float* loss, float* logp, float* entropy, float* lse, float* gcoef, uint8_t* mpt_mask,
-                        float* ratio, int32_t* segment_out, float* resp_entropy, uint8_t* resp_gate,
-                        int64_t* counters, void* dlogits, void* workspace, const WorkspaceLayout& wl, void* hip_stream)
-{
-    bool ok;
-    hipStream_t st = (hipStream_t)hip_stream;
-    char* ws = (char*)workspace;
-
-    TokenArgs a = make_token_args(N, V, token_ids, cu_seqlens, R, segment_ids, old_logp, advantages, p, logp,
-                                        entropy, lse, gcoef, mpt_mask, ratio, segment_out, resp_entropy, resp_gate,
-                                        workspace, wl);
-    FusedArgs f;
-    f.token_ids = token_ids; f.old_logp = old_logp; f.adv = advantages;
-    f.lse = lse; f.logp = logp; f.entropy = entropy;
-    f.defer = (uint8_t*)(ws + wl.defer); f.badcu = (const uint32_t*)(ws + wl.badcu);
-    f.is_mode = a.is_mode; f.gate_mode = a.gate_mode;
-    f.eps_low = a.eps_low; f.eps_high = a.eps_high; f.log_tau = a.log_tau; f.inv_D = a.inv_D;
-    f.grad_out = grad_out;
-
-    hipLaunchKernelGGL(cu_check_kernel, dim3(1), dim3(kTokBlock), 0, st, cu_seqlens, R, N, (uint32_t*)(ws + wl.badcu));
-    const ClusterShape shape = cluster_shape(V, dt);
-    if (tuning().fused_cluster && shape.pieces > 0 && 2 * N * (int64_t)shape.pieces < (1LL << 38)) {
-        ClusterArgs ca;
-        ca.f = f;
-        ca.slots = (unsigned long long*)(ws + wl.slots);
-        ca.sync_fail = (uint32_t*)(ws + wl.syncfail);
-        ca.N = N;
-        ca.C = shape.pieces;
-        ca.spin_limit = tuning().sync_spins;
-        a.sync_fail = ca.sync_fail;
-        const int64_t nslots = 2 * N * (int64_t)shape.pieces;
-        hipLaunchKernelGGL(fill_zero_u64_kernel, dim3((unsigned)((nslots + 255) / 256)), dim3(256), 0, st, ca.slots, nslots,
-                           ca.sync_fail);
-        ok = dt == ULORL_BF16 ? launch_cluster<StoreBF16>(shape.vpt, logits, N, V, row_stride, dlogits, ca, st)
-                              : launch_cluster<StoreF32>(shape.vpt, logits, N, V, row_stride, dlogits, ca, st);
-    } else {
-        ok = dt == ULORL_BF16
-                 ? dispatch_fused<StoreBF16>(tuning().fused_threads, tuning().fused_unroll, logits, N, V, row_stride,
-                                             dlogits, f, st)
-                 : dispatch_fused<StoreF32>(tuning().fused_threads, tuning().fused_unroll, logits, N, V, row_stride,
-                                            dlogits, f, st);
-    }
-    if (!ok || hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;
-    launch_token_epilogue(a, wl, loss, counters, st);
-    if (hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;
-    if (a.gate_mode == ULORL_GATE_PER_RESPONSE || a.gate_mode == ULORL_GATE_GLOBAL) {
-        // MPT members waited for the gate: their rows are still logits (in place) or unwritten
-        ok = dt == ULORL_BF16
-                 ? dispatch_dlogits<StoreBF16>(tuning().bwd_threads, tuning().bwd_unroll, logits, N, V, row_stride,
-                                               token_ids, lse, gcoef, grad_out, dlogits, f.defer, st)
-                 : dispatch_dlogits<StoreF32>(tuning().bwd_threads, tuning().bwd_unroll, logits, N, V, row_stride,
-                                              token_ids, lse, gcoef, grad_out, dlogits, f.defer, st);
-        if (!ok || hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;
-    }
-    return ULORL_OK;
-}
-
-}  // namespace
-
-extern "C" {
 
 int32_t ulorl_token_loss_bwd(const void* logits, int32_t dt, int64_t N, int64_t V, int64_t row_stride,
                              const int32_t* token_ids, const float* lse, const float* gcoef, float grad_out,
@@ -1670,13 +1857,11 @@ int32_t ulorl_token_loss_bwd(const void* logits, int32_t dt, int64_t N, int64_t 
     if (!token_ids || !lse || !gcoef || !dlogits) return ULORL_ERR_NULL;
     if (((uintptr_t)dlogits & 15u) != 0) return ULORL_ERR_ALIGN;
     hipStream_t st = (hipStream_t)hip_stream;
-    bool ok = dt == ULORL_BF16
-                  ? dispatch_dlogits<StoreBF16>(tuning().bwd_threads, tuning().bwd_unroll, logits, N, V, row_stride,
-                                                token_ids, lse, gcoef, grad_out, dlogits, nullptr, st)
-                  : dispatch_dlogits<StoreF32>(tuning().bwd_threads, tuning().bwd_unroll, logits, N, V, row_stride,
-                                               token_ids, lse, gcoef, grad_out, dlogits, nullptr, st);
-    if (!ok || hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;
-    return ULORL_OK;
+    if (dt == ULORL_BF16)
+        launch_dlogits<StoreBF16>(logits, N, V, row_stride, token_ids, lse, gcoef, grad_out, dlogits, st);
+    else
+        launch_dlogits<StoreF32>(logits, N, V, row_stride, token_ids, lse, gcoef, grad_out, dlogits, st);
+    return hipGetLastError() == hipSuccess ? ULORL_OK : ULORL_ERR_HIP;
 }
 
 }  // extern "C"

@@ -7,6 +7,7 @@
 #include <stdint.h>
 
 #include "ulorl.h"
+#include "segment_stats.hpp"
 
 namespace ulorl_detail {
 
@@ -38,10 +39,11 @@ struct TokenArgs {
     int32_t is_mode, gate_mode, seg_len;
     double eps_low, eps_high, tau, sigma, D;
     double log_tau, inv_D;   // ln(tau), 1 / D
+    SegStatsArgs seg;        // per-segment diagnostics as a by-product (seg.K == 0: not wanted)
 };
 
 struct WorkspaceLayout {
-    size_t slots, syncfail, hsum, rflags, part_sum, part_cnt, defer, badcu, total;
+    size_t slots, syncfail, hsum, rflags, part_sum, part_cnt, defer, badcu, zy, defer_list, defer_count, total;
     int64_t nblk;
 };
 
@@ -62,31 +64,24 @@ TokenArgs make_token_args(int64_t N, int64_t V, const int32_t* token_ids, const 
                           const int32_t* segment_ids, const float* old_logp, const float* advantages,
                           const ulorl_params* p, float* logp, float* entropy, float* lse, float* gcoef,
                           uint8_t* mpt_mask, float* ratio, int32_t* segment_out, float* resp_entropy,
-                          uint8_t* resp_gate, void* workspace, const WorkspaceLayout& wl);
+                          uint8_t* resp_gate, void* workspace, const WorkspaceLayout& wl, const SegStatsArgs& seg);
 
 // Enqueues response_entropy_kernel, token_terms_kernel and loss_finalize_kernel.
 void launch_token_epilogue(const TokenArgs& a, const WorkspaceLayout& wl, float* loss, int64_t* counters,
                            hipStream_t st);
 
-// Launch shapes, set with ulorl_tune().  Defaults from sweeps on 131072 x 151936 bf16 (logits
-// path) and 32768 x 2048 x 151936 (lm_head variant).  The one-workgroup-per-row forward and fused
-// kernels share one shape so that their row statistics are bit-identical, and so do the piece-wise
-// forward and the row-cooperative kernel (the backward is elementwise, its shape does not change
-// results).
-struct Tuning {
-    int fwd_threads = 512, fwd_unroll = 8;
-    int bwd_threads = 256, bwd_unroll = 4;
-    int fused_threads = 512, fused_unroll = 8;
-    int gemm_tile = 7;     // index into the compiled-in GEMM tile shapes
-    int bwd_oneshot = 1;   // standalone backward by one-shot 4 KB workgroups (0: one looping workgroup per row)
-    int fused_cluster = 1; // one-call path by row-cooperative workgroups (0: one looping workgroup per row)
-    int fwd_pieces = 1;    // forward statistics by pieces when a workspace is given (0: one looping workgroup per row)
-    int fused_vpt = 0;     // 16-byte vectors per thread of the row-cooperative kernel (0: chosen from V)
-    int sync_spins = 1 << 24;  // polls before a workgroup of the row-cooperative kernel gives up on its partners
+// Launch options of one call, validated and with the defaults filled in.
+struct LaunchOpts {
+    bool per_row = false;         // ULORL_LAUNCH_PER_ROW
+    int sync_spins = 1 << 24;
+    int gemm_tile = 0;
+    int gemm_group_m = 4;
 };
-Tuning& tuning();
-constexpr int kGemmTileCount = 9;
-inline int gemm_tile_choice() { return tuning().gemm_tile; }
+int32_t resolve_launch(const ulorl_launch* launch, LaunchOpts* out);
+
+// Validates an optional ulorl_segment_stats against N and turns it into kernel arguments
+// (out->K == 0 when st is NULL).
+int32_t resolve_segment_stats(const ulorl_segment_stats* st, int64_t N, SegStatsArgs* out);
 
 }  // namespace ulorl_detail
 

@@ -129,7 +129,7 @@ def near_discontinuity(o_logp, tt, p: ulorl.Params):
 
 
 def run_full_parity(w: ui.Workload, p: ulorl.Params, dz_rows=None, inplace=False, data=None,
-                    grad_out=1.0, same_bits=True):
+                    grad_out=1.0, same_bits=True, launch=None):
     """Whole path on the GPU vs whole oracle on the host, every row: the two-call path, then (when
     the logits survive, i.e. not in place) the one-call path in both of its kernels.
     ``same_bits``: the two-call forward runs by pieces (the library's default), so the two paths
@@ -138,7 +138,7 @@ def run_full_parity(w: ui.Workload, p: ulorl.Params, dz_rows=None, inplace=False
     d = data if data is not None else ui.generate(w, dev)
     logits = d["logits"]
     old = None if p.is_mode == ulorl.IS_POIS else d["old_logp"]
-    res = ulorl.token_loss_fwd(logits, d["token_ids"], d["cu_seqlens"], d["advantages"], old, p)
+    res = ulorl.token_loss_fwd(logits, d["token_ids"], d["cu_seqlens"], d["advantages"], old, p, launch=launch)
     host_logits = ui.to_numpy_logits(logits)
     y = d["token_ids"].cpu().numpy()
     rtol = rtol_for(w.dtype)
@@ -217,21 +217,17 @@ def check_one_call_path(d, p: ulorl.Params, res2: ulorl.FwdResult, o_lse, o_logp
 
 
 def check_row_kernels_bitwise(d, p: ulorl.Params, grad_out=1.0):
-    """The kernels with one looping workgroup per row (the fallbacks of both paths) reproduce each
-    other bit for bit as well."""
+    """The kernels with one looping workgroup per row (ULORL_LAUNCH_PER_ROW: the fallbacks of both
+    paths) reproduce each other bit for bit as well."""
     old = None if p.is_mode == ulorl.IS_POIS else d["old_logp"]
-    ulorl.tune(ulorl.TUNE_FUSED_CLUSTER, 0)
-    ulorl.tune(ulorl.TUNE_FWD_PIECES, 0)
-    try:
-        r2, dz2 = ulorl.token_loss_fwd_bwd(d["logits"], d["token_ids"], d["cu_seqlens"], d["advantages"], old, p,
-                                           grad_out=grad_out)
-        res = ulorl.token_loss_fwd(d["logits"], d["token_ids"], d["cu_seqlens"], d["advantages"], old, p)
-        dz = ulorl.token_loss_bwd(d["logits"], d["token_ids"], res.lse, res.gcoef, grad_out=grad_out)
-    finally:
-        ulorl.tune(ulorl.TUNE_FUSED_CLUSTER, 1)
-        ulorl.tune(ulorl.TUNE_FWD_PIECES, 1)
+    per_row = ulorl.Launch(per_row=True)
+    r2, dz2 = ulorl.token_loss_fwd_bwd(d["logits"], d["token_ids"], d["cu_seqlens"], d["advantages"], old, p,
+                                       grad_out=grad_out, launch=per_row)
+    res = ulorl.token_loss_fwd(d["logits"], d["token_ids"], d["cu_seqlens"], d["advantages"], old, p, launch=per_row)
+    dz = ulorl.token_loss_bwd(d["logits"], d["token_ids"], res.lse, res.gcoef, grad_out=grad_out)
     assert_same_results(res, r2, "row kernels")
     assert torch.equal(_bits(dz2), _bits(dz)), "row-kernel fused dlogits differ from the two-call dlogits"
+    return res, dz
 
 
 def sigma_between_responses(host_logits, y, cu, k=None):
@@ -357,7 +353,7 @@ def raw_bf16(t: torch.Tensor) -> np.ndarray:
     return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
 
 
-def run_lmhead_parity(w: ui.Workload, p: ulorl.Params, chunk: int, data=None, grad_out=1.0, say=None):
+def run_lmhead_parity(w: ui.Workload, p: ulorl.Params, chunk: int, data=None, grad_out=1.0, say=None, launch=None):
     """lm_head variant through the C ABI against the oracle (fp64 logits from a stock matrix
     product, then the same oracle functions as the logits path, then the chain rule to hidden, W)."""
     dev = torch.device("cuda:0")
@@ -365,9 +361,9 @@ def run_lmhead_parity(w: ui.Workload, p: ulorl.Params, chunk: int, data=None, gr
     hidden, weight = d["hidden"], d["weight"]
     old = None if p.is_mode == ulorl.IS_POIS else d["old_logp"]
     res = ulorl.lmhead_token_loss_fwd(hidden, weight, d["token_ids"], d["cu_seqlens"], d["advantages"], old, p,
-                                      vocab_chunk=chunk)
+                                      vocab_chunk=chunk, launch=launch)
     dH, dW = ulorl.lmhead_token_loss_bwd(hidden, weight, d["token_ids"], res.lse, res.gcoef, grad_out=grad_out,
-                                         vocab_chunk=chunk)
+                                         vocab_chunk=chunk, launch=launch)
     torch.cuda.synchronize()
     if say:
         say("gpu done; oracle logits %d x %d x %d" % (w.N, w.hidden, w.V))

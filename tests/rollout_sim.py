@@ -1,4 +1,6 @@
-"""Training with segment rollouts (Algorithm 1, Sec. 3.1.1) on synthetic response lengths.
+"""Test harness: training with segment rollouts (Algorithm 1, Sec. 3.1.1) on synthetic response
+lengths, driving a pool update passed in as a callable (the oracle's, or the GPU entry point's).
+It belongs to neither side: it holds the loop and a cost model, none of the pool update's logic.
 
 The loop is the paper's: every step decodes at most one segment for each sample in flight
 (samples carried over from the unfinished pool first, then new prompts up to the rollout batch
@@ -89,10 +91,10 @@ def gpu_pool_step(prev_len, new_len, hit_eos, seg_len, max_len):
     """`pool_step` callable backed by ulorl_segment_pool_step (numpy in, numpy out, trimmed to the counts)."""
     import torch
 
-    from . import binding
+    import paper_2507_19766_amd as ulorl
 
     dev = torch.device("cuda:0")
-    out = binding.segment_pool_step(torch.from_numpy(np.ascontiguousarray(prev_len)).to(dev),
+    out = ulorl.segment_pool_step(torch.from_numpy(np.ascontiguousarray(prev_len)).to(dev),
                                     torch.from_numpy(np.ascontiguousarray(new_len)).to(dev),
                                     torch.from_numpy(np.ascontiguousarray(hit_eos)).to(dev), seg_len, max_len)
     host = {k: v.cpu().numpy() for k, v in out.items()}

@@ -40,23 +40,21 @@ def test_gemm_tn_bf16_against_fp64(M, N, K):
     assert torch.all(wide[:, N:] == -7.0)
 
 
-@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4, 5, 6, 8])
-def test_every_compiled_tile_shape(tile):
-    """All tile shapes / both main loops (register-staged and direct-to-LDS) give the same answers."""
-    ulorl.tune(ulorl.TUNE_GEMM_TILE, tile)
-    try:
-        g = torch.Generator(device=DEV).manual_seed(tile)
-        for (M, N, K) in ((300, 520, 192), (256, 256, 72)):          # K = 72 exercises the ragged-K fallback
-            a = torch.randn(M, K, generator=g, device=DEV).to(torch.bfloat16)
-            b = torch.randn(N, K, generator=g, device=DEV).to(torch.bfloat16)
-            c = ulorl.gemm_tn_bf16(a, b)
-            ref = a.double() @ b.double().T
-            bound = 1e-6 * (a.double().abs() @ b.double().abs().T) + 1e-30
-            assert torch.all((c.double() - ref).abs() <= bound)
-        w = ui.shrink(ui.config(5), [150, 120], V=1544, hidden=128, seg_len=64, name="lmhead_tile%d" % tile)
-        run_lmhead_parity(w, params_for(w, gate_mode=ulorl.GATE_ALWAYS, tau=0.05), chunk=512)
-    finally:
-        ulorl.tune(ulorl.TUNE_GEMM_TILE, 7)
+@pytest.mark.parametrize("tile,group_m", [(0, 0), (1, 0), (0, 1), (0, 7), (1, 64)])
+def test_every_compiled_tile_shape(tile, group_m):
+    """Both tile shapes / both main loops (direct-to-LDS and register-staged) and other walks of the
+    tile grid give the same answers."""
+    launch = ulorl.Launch(gemm_tile=tile, gemm_group_m=group_m)
+    g = torch.Generator(device=DEV).manual_seed(tile)
+    for (M, N, K) in ((300, 520, 192), (256, 256, 72), (1300, 700, 128)):     # K = 72 exercises the ragged-K fallback
+        a = torch.randn(M, K, generator=g, device=DEV).to(torch.bfloat16)
+        b = torch.randn(N, K, generator=g, device=DEV).to(torch.bfloat16)
+        c = ulorl.gemm_tn_bf16(a, b, launch=launch)
+        ref = a.double() @ b.double().T
+        bound = 1e-6 * (a.double().abs() @ b.double().abs().T) + 1e-30
+        assert torch.all((c.double() - ref).abs() <= bound)
+    w = ui.shrink(ui.config(5), [150, 120], V=1544, hidden=128, seg_len=64, name="lmhead_tile%d" % tile)
+    run_lmhead_parity(w, params_for(w, gate_mode=ulorl.GATE_ALWAYS, tau=0.05), chunk=512, launch=launch)
 
 
 def test_lmhead_small_ragged_chunks():

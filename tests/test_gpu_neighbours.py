@@ -94,6 +94,52 @@ def test_segment_diagnostics_match_the_oracle():
     np.testing.assert_array_equal(g3["count"].cpu().numpy(), o["count"][:4])
 
 
+@pytest.mark.parametrize("case", ["logits_two_call", "logits_one_call", "lmhead", "explicit_ids_pois"])
+def test_segment_diagnostics_as_a_by_product_of_the_forward_calls(case):
+    """The forward calls hand out the per-segment diagnostics in the same pass as the token terms;
+    the numbers carry the bits of the standalone call on the stored outputs (which the test above
+    holds against the oracle), and the other outputs do not change."""
+    K = 6
+    if case == "lmhead":
+        w = ui.shrink(ui.config(5), [700, 1500, 30], V=1544, hidden=128, seg_len=300, name="diag_lmhead")
+        d = ui.generate(w, DEV)
+        p = params_for(w, gate_mode=ulorl.GATE_ALWAYS, tau=0.001)
+        plain = ulorl.lmhead_token_loss_fwd(d["hidden"], d["weight"], d["token_ids"], d["cu_seqlens"], d["advantages"],
+                                            d["old_logp"], p, vocab_chunk=512)
+        res = ulorl.lmhead_token_loss_fwd(d["hidden"], d["weight"], d["token_ids"], d["cu_seqlens"], d["advantages"],
+                                          d["old_logp"], p, vocab_chunk=512, segments=K)
+        old, ids = d["old_logp"], None
+    else:
+        w = ui.shrink(ui.config(4), [1100, 2050, 1, 37], V=4096, seg_len=400, name="diag_fused")   # ids 0..5, ragged blocks
+        d = ui.generate(w, DEV)
+        pois = case == "explicit_ids_pois"
+        p = params_for(w, gate_mode=ulorl.GATE_ALWAYS, tau=0.5, is_mode=ulorl.IS_POIS if pois else ulorl.IS_SAIS,
+                       seg_len=0 if pois else 400)
+        old = None if pois else d["old_logp"]
+        # arbitrary ids, some outside [0, K): many distinct ids inside one wave
+        ids = ((torch.arange(w.N, device=DEV) * 7) % 9 - 1).to(torch.int32) if pois else None
+        args = (d["logits"], d["token_ids"], d["cu_seqlens"], d["advantages"], old, p)
+        if case == "logits_one_call":
+            plain, _ = ulorl.token_loss_fwd_bwd(*args)
+            res, _ = ulorl.token_loss_fwd_bwd(*args, segments=K)
+        else:
+            plain = ulorl.token_loss_fwd(*args, segment_ids=ids)
+            res = ulorl.token_loss_fwd(*args, segment_ids=ids, segments=K)
+    for name in ("loss", "logp", "entropy", "lse", "gcoef", "mpt_mask", "ratio", "segment_out", "counters"):
+        assert torch.equal(getattr(res, name), getattr(plain, name)), name
+    alone = ulorl.segment_diagnostics(res, d["advantages"], old, K)
+    fused = res.segment_stats
+    for name in ("count", "ratio_sum", "ratio_max", "clipped", "kl_sum", "ent_sum", "masked", "out_of_range"):
+        a, b = fused[name], alone[name]
+        assert torch.equal(a.view(torch.int64) if a.dtype == torch.float64 else a,
+                           b.view(torch.int64) if b.dtype == torch.float64 else b), name
+    n_in = int(((res.segment_out >= 0) & (res.segment_out < K)).sum())
+    assert int(fused["count"].sum()) == n_in and int(fused["out_of_range"]) == w.N - n_in
+    if case == "explicit_ids_pois":
+        assert int(fused["out_of_range"]) > 0 and float(fused["kl_sum"].abs().sum()) == 0.0
+        assert bool((fused["ratio_sum"] == fused["count"].double()).all())       # POIS: every ratio is 1
+
+
 @pytest.mark.parametrize("B", [1, 63, 1024, 1025, 5000])
 def test_segment_pool_step_matches_the_oracle(B):
     rng = np.random.default_rng(B)
@@ -124,7 +170,7 @@ def test_segment_pool_step_matches_the_oracle(B):
 def test_rollout_model_takes_the_same_path_on_the_gpu():
     """Forty steps of the segment-rollout loop driven by the GPU pool update and by the oracle:
     identical pools at every step."""
-    from paper_2507_19766_amd import rollout_model as rm
+    import rollout_sim as rm
 
     L = rm.synthetic_lengths(3000, 4096, 5)
     a = rm.simulate(rm.gpu_pool_step, L, batch=96, segments=4, max_len=4096, steps=40)

@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 
 import oracle
-from paper_2507_19766_amd import rollout_model as rm
+import rollout_sim as rm
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 

@@ -53,6 +53,6 @@ def test_static_scratch_entry_point_rejects_what_does_not_fit():
     rc = lib.ulorl_token_loss_fwd_bwd_static(
         vp(0x1000), 1, 1 << 20, 151936, 151936, vp(0x2000), vp(0x3000), 1, None, vp(0x4000), vp(0x5000),
         ctypes.byref(cp), 1.0, vp(0x6000), vp(0x7000), vp(0x8000), vp(0x9000), vp(0xa000), None, None, None, None,
-        None, None, vp(0x20000), None)
+        None, None, None, vp(0x20000), None, None)
     assert rc == -8
     assert "static" in ulorl.status_string(-8)

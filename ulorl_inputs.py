@@ -195,9 +195,10 @@ def generate(w: Workload, device="cpu", logits_out: Optional[torch.Tensor] = Non
             where = torch.randint(0, V, (ROWS_PER_BLOCK,), generator=g, device=device)[:rows]
             ridx = torch.arange(rows, device=device)
             z[ridx, where] += spiked.to(torch.float32) * w.spike_boost
-            zq = z.to(w.torch_dtype())
-            logits[r0:r1] = zq
-            zf = zq.float()
+            # rounded to the storage type by an elementwise kernel writing in place (fp32 source: a
+            # converting copy; no staging tensor, no device-to-device memcpy of the block)
+            torch.mul(z, 1.0, out=logits[r0:r1])
+            zf = logits[r0:r1].float()
         y = _sample_tokens(zf, g)
         cur = torch.log_softmax(zf, dim=-1).gather(1, y.long().unsqueeze(1)).squeeze(1)
         noise = torch.randn(ROWS_PER_BLOCK, generator=g, device=device, dtype=torch.float32)[:rows]

@@ -1,7 +1,7 @@
 """Throughput of the fused UloRL token loss (forward + backward) on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4] [--path fused|two_call]
-                    [--cpu-rows N] [--extras 0|1]
+                    [--cpu-rows N] [--extras 0|1] [--gemm-group-m G]
 
 A step is one pass of the whole hot path over one batch of synthetic input: row statistics,
 ratio, clip, MPT mask, loss and dlogits (written in place for the ultra-long configuration).
@@ -270,6 +270,7 @@ def bench_lmhead(args, w, ulorl, ui, torch, dev, as_entry=False):
     ws = torch.empty(ulorl.lmhead_workspace_bytes(w.N, w.hidden, w.V, w.R, chunk), dtype=torch.uint8, device=dev)
     dH, dW = torch.empty_like(H), torch.empty_like(W)
     out = None
+    launch = ulorl.Launch(gemm_group_m=getattr(args, "gemm_group_m", 0))
 
     def step():
         nonlocal out
@@ -277,10 +278,11 @@ def bench_lmhead(args, w, ulorl, ui, torch, dev, as_entry=False):
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
         t_a = time.perf_counter()
         ev[0].record()
-        out = ulorl.lmhead_token_loss_fwd(H, W, y, cu, adv, old, params, vocab_chunk=chunk, out=out, workspace=ws)
+        out = ulorl.lmhead_token_loss_fwd(H, W, y, cu, adv, old, params, vocab_chunk=chunk, out=out, workspace=ws,
+                                          launch=launch)
         ev[1].record()
         ulorl.lmhead_token_loss_bwd(H, W, y, out.lse, out.gcoef, 1.0, vocab_chunk=chunk, d_hidden=dH, d_weight=dW,
-                                    workspace=ws)
+                                    workspace=ws, launch=launch)
         ev[2].record()
         torch.cuda.synchronize()
         return time.perf_counter() - t_a, ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2])
@@ -307,7 +309,7 @@ def bench_lmhead(args, w, ulorl, ui, torch, dev, as_entry=False):
         "dtype": "bf16 MFMA operands, f32 accumulate", "data": "synthetic",
         "config": {"workload": w.name, "rows": w.N, "hidden": w.hidden, "vocab": w.V, "vocab_chunk": chunk,
                    "responses": w.R, "segment_len": w.seg_len, "path": "lm_head variant (logits never materialised)",
-                   "is_mode": "SAIS", "gate": "always (static MPT masking)", "tau": w.tau},
+                   "gemm_group_m": launch.gemm_group_m or "default (4)", "is_mode": "SAIS", "gate": "always (static MPT masking)", "tau": w.tau},
         "roofline": {"bound": "mfma", "kernel": "backward call: lmhead_dz_kernel + 2 x gemm_tn_kernel per vocabulary "
                      "chunk (3 products of 2*N*Hd*V flop)", "achieved": bwd_tf, "peak": MFMA_BF16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": bwd_tf / MFMA_BF16_PEAK_TFLOPS,
@@ -374,6 +376,9 @@ def main():
     ap.add_argument("--cpu-rows", type=int, default=98304, help="rows of the oracle sample (0 = skip)")
     ap.add_argument("--path", default="fused", choices=["fused", "two_call"],
                     help="which path gives the headline value (both are timed)")
+    ap.add_argument("--gemm-group-m", type=int, default=0,
+                    help="cfg5 only: ulorl_launch.gemm_group_m, the block tiles along M an XCD walks before it moves "
+                         "along N (0: the library's default)")
     ap.add_argument("--extras", type=int, default=-1,
                     help="1: also time the ceiling, the per-response gate and configurations 2, 3, 5 in the same "
                          "run (default for cfg4); 0: the workload alone")

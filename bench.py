@@ -41,23 +41,24 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 matrix rate
 METRIC = "token-rows/sec fused fwd+bwd RL token loss (V=151936 bf16) + % HBM roofline"
 
 
-# Hardware byte counters (rocprofv3 --pmc FETCH_SIZE, then WRITE_SIZE, of this script, each scaled by
-# what the same counter reads for the restore copy of known size; profiles/token_loss_cfg4_hbm_counters.txt)
-# expressed as measured / algorithmic ratios.  They hold for the kernel source they were taken
+# Hardware byte counters (rocprofv3 --pmc FETCH_SIZE, then WRITE_SIZE, of this script at configuration 2 --
+# the same row shape and launch shapes; the profiler does not survive configuration 4's 80 GB -- each scaled
+# by what the same counter reads for a copy of known size; profiles/token_loss_cfg2_hbm_counters.txt)
+# expressed as measured / algorithmic ratios per row.  They hold for the kernel source they were taken
 # on: the digest below is checked at run time and `traffic` is null once the kernels changed.
 PMC = {
-    "source_sha256": "",
-    "fused_read": 1.0, "fused_write": 1.0,      # cluster_row_kernel
-    "bwd_read": 1.0, "bwd_write": 1.0,          # dlogits_chunk_kernel
+    "source_sha256": "986bce3ccda45625c707148f715fb107814986a076ccafd9989f9609f08aca19",
+    "fused_read": 1.0078, "fused_write": 1.0015,      # cluster_row_kernel: every row once, plus the polling of the exchange slots
+    "bwd_read": 1.0007, "bwd_write": 1.0000,          # dlogits_chunk_kernel
 }
 
 # HBM bytes of one lm_head backward / forward call at configuration 5 (vocabulary chunk 8192), from two
 # rocprofv3 --pmc runs of this script (FETCH_SIZE, then WRITE_SIZE, summed over the call's kernels and
 # scaled as above); valid for the lm_head source with this digest and for that workload only.
 PMC_LMHEAD = {
-    "source_sha256": "",
-    "bwd_bytes": 0,
-    "fwd_bytes": 0,
+    "source_sha256": "7805af89cba247323237f140e8a30c5d3c033cf6a20138f27c493eab53b38dda",
+    "bwd_bytes": 121365484 * 1024,     # 19 x (dz + dHidden + dW products) + transposes, accumulator fill, final conversion
+    "fwd_bytes": 36937632 * 1024,      # lmhead_stats_kernel + transpose of W + the small kernels
 }
 
 
@@ -436,7 +437,8 @@ def main():
     roof_fused = {"bound": "hbm", "kernel": "cluster_row_kernel (one-call forward+backward by row-cooperative "
                   "workgroups; the call also runs seven small kernels, about 0.1 ms)", "achieved": fused_gbs,
                   "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": fused_gbs / HBM_PEAK_GBS, "traffic": fused_traffic,
-                  "traffic_note": "HBM bytes per launch (FETCH_SIZE, WRITE_SIZE scaled by a copy kernel)",
+                  "traffic_note": "HBM bytes per launch: algorithmic bytes x the measured/algorithmic ratio per row that "
+                  "FETCH_SIZE and WRITE_SIZE (scaled by a copy of known size) give for this kernel at 65536 rows of the same shape",
                   "algorithmic_bytes_per_launch": fused_bytes, "avg_launch_ms": fused_ms / K}
     roof_bwd = {"bound": "hbm", "kernel": "dlogits_chunk_kernel (backward call of the two-call path)",
                 "achieved": bwd_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": bwd_gbs / HBM_PEAK_GBS,

@@ -56,9 +56,9 @@ PMC = {
 # rocprofv3 --pmc runs of this script (FETCH_SIZE, then WRITE_SIZE, summed over the call's kernels and
 # scaled as above); valid for the lm_head source with this digest and for that workload only.
 PMC_LMHEAD = {
-    "source_sha256": "7805af89cba247323237f140e8a30c5d3c033cf6a20138f27c493eab53b38dda",
-    "bwd_bytes": 121365484 * 1024,     # 19 x (dz + dHidden + dW products) + transposes, accumulator fill, final conversion
-    "fwd_bytes": 36937632 * 1024,      # lmhead_stats_kernel + transpose of W + the small kernels
+    "source_sha256": "2b8ee1ddd675efc616c15050a871c3a3ae73185821b5b3e32513c8ff05fa32e1",
+    "bwd_bytes": 121265430 * 1024,     # 19 x (dz + dHidden + dW products) + transposes, accumulator fill, final conversion
+    "fwd_bytes": 36751410 * 1024,      # lmhead_stats_kernel + transpose of W + the small kernels
 }
 
 

@@ -769,25 +769,37 @@ void lmhead_dz_kernel(const bf16_t* __restrict__ Wt, const bf16_t* __restrict__ 
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
-    // per token column of this lane: coefficient, sign and exponent offset of  dz = g (onehot - e^(z - lse))
-    float g[Cfg::NB], c[Cfg::NB], sgn[Cfg::NB];
-    int32_t y[Cfg::NB];
+    // Per token column of this lane:  dz = g (onehot - e^(z - lse)) = s (2^(z log2e + c) - |g| onehot)  with s = -sign(g),
+    // c = log2|g| - lse log2e.  The magnitudes are computed and rounded; a negative s is applied to the packed pair by
+    // flipping sign bits (rounding to nearest even is symmetric); a column without a gradient (zero coefficient, flagged row,
+    // padding) is zeroed on the packed pair; the chosen token's term is patched in by the rare lanes whose rows hold it.
+    // Per element that leaves one FMA, one exponential and half a conversion in the common path.
+    const int v_wave = v0 + wm * Cfg::WM;
+    const int t_wave = t0 + wn * Cfg::WN;
+    float g_mag[Cfg::NB], c[Cfg::NB];
+    uint32_t flip[Cfg::NB], keep[Cfg::NB];
+    int dy[Cfg::NB];                              // row of the chosen token inside this wave's rows, -1 if not this lane's
 #pragma unroll
     for (int bj = 0; bj < Cfg::NB; ++bj) {
-        const int t = t0 + wn * Cfg::WN + bj * 32 + (lane & 31);
-        g[bj] = 0.0f; c[bj] = 0.0f; sgn[bj] = 0.0f; y[bj] = -1;
+        const int t = t_wave + bj * 32 + (lane & 31);
+        g_mag[bj] = 0.0f; c[bj] = 0.0f; flip[bj] = 0u; keep[bj] = 0u; dy[bj] = -1;
         if (t < Ntok) {
             const float gg = gcoef[t] * grad_out;
             const float l = lse[t];
             const int32_t yy = token_ids[t];
             const bool live = (gg != 0.0f) && (fabsf(gg) <= 3.0e38f) && (fabsf(l) <= 3.0e38f) && yy >= 0 && yy < V;
             if (live) {
-                g[bj] = gg; y[bj] = yy;
+                const bool negate = gg > 0.0f;
+                g_mag[bj] = negate ? -gg : gg;    // -|g|
                 c[bj] = fmaf(-l, kLog2e, log2f(fabsf(gg)));
-                sgn[bj] = gg > 0.0f ? -1.0f : 1.0f;
+                flip[bj] = negate ? 0x80008000u : 0u;
+                keep[bj] = 0xffffffffu;
+                const int d = yy - v_wave;
+                if (d >= 0 && d < Cfg::WM && ((d >> 2) & 1) == (lane >> 5) && yy < vend) dy[bj] = d;
             }
         }
     }
+    const bool ragged = v0 + Cfg::BM > vend;      // uniform: the tile reaches past the end of the chunk
 
     // The tile leaves in both orientations, dZc[t, v] and dZc^T[v, t], as 16-byte row segments:
     // 64 vocabulary rows at a time go through the wave's share of LDS (the main loop's stages,
@@ -799,8 +811,6 @@ void lmhead_dz_kernel(const bf16_t* __restrict__ Wt, const bf16_t* __restrict__ 
     static_assert(Cfg::MB % 2 == 0, "64 vocabulary rows per round");
     static_assert((size_t)64 * SA <= Cfg::LDS_BYTES / NW && (size_t)Cfg::WN * SB <= Cfg::LDS_BYTES / NW, "round fits the wave's LDS share");
     unsigned char* slab = lds_raw + (size_t)wave * (Cfg::LDS_BYTES / NW);
-    const int v_wave = v0 + wm * Cfg::WM;
-    const int t_wave = t0 + wn * Cfg::WN;
 #pragma unroll
     for (int h = 0; h < Cfg::MB / 2; ++h) {
         uint32_t pk[2][Cfg::NB][4][2];            // bf16 dz of this round: [block][column block][row quad] -> 4 rows
@@ -810,17 +820,37 @@ void lmhead_dz_kernel(const bf16_t* __restrict__ Wt, const bf16_t* __restrict__ 
             for (int bj = 0; bj < Cfg::NB; ++bj)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const int v = v_wave + (2 * h + b2) * 32 + 8 * q + 4 * (lane >> 5);
-                    float dz[4];
+                    float m[4];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        float x = sgn[bj] * fast_exp2(fmaf(acc[2 * h + b2][bj][4 * q + e], kLog2e, c[bj]));
-                        if (v + e == y[bj]) x += g[bj];
-                        dz[e] = (sgn[bj] != 0.0f && v + e < vend) ? x : 0.0f;
+                    for (int e = 0; e < 4; ++e) m[e] = fast_exp2(fmaf(acc[2 * h + b2][bj][4 * q + e], kLog2e, c[bj]));
+                    if (ragged) {
+                        const int v = v_wave + (2 * h + b2) * 32 + 8 * q + 4 * (lane >> 5);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) m[e] = (v + e < vend) ? m[e] : 0.0f;
                     }
-                    pk[b2][bj][q][0] = pack_bf16x2(dz[0], dz[1]);
-                    pk[b2][bj][q][1] = pack_bf16x2(dz[2], dz[3]);
+                    pk[b2][bj][q][0] = (pack_bf16x2(m[0], m[1]) ^ flip[bj]) & keep[bj];
+                    pk[b2][bj][q][1] = (pack_bf16x2(m[2], m[3]) ^ flip[bj]) & keep[bj];
                 }
+        // the chosen token's own term: only the lane whose rows of this round hold it
+#pragma unroll
+        for (int bj = 0; bj < Cfg::NB; ++bj) {
+            if (dy[bj] >= h * 64 && dy[bj] < h * 64 + 64) {
+#pragma unroll
+                for (int b2 = 0; b2 < 2; ++b2)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+#pragma unroll
+                        for (int half = 0; half < 2; ++half) {
+                            const int row = (2 * h + b2) * 32 + 8 * q + 4 * (lane >> 5) + 2 * half;
+                            if (dy[bj] == row || dy[bj] == row + 1) {
+                                float m0 = fast_exp2(fmaf(acc[2 * h + b2][bj][4 * q + 2 * half], kLog2e, c[bj]));
+                                float m1 = fast_exp2(fmaf(acc[2 * h + b2][bj][4 * q + 2 * half + 1], kLog2e, c[bj]));
+                                if (dy[bj] == row) m0 += g_mag[bj]; else m1 += g_mag[bj];
+                                pk[b2][bj][q][half] = pack_bf16x2(m0, m1) ^ flip[bj];
+                            }
+                        }
+            }
+        }
         // ---- [v][t]: rows of dZc^T
 #pragma unroll
         for (int b2 = 0; b2 < 2; ++b2)

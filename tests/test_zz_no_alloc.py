@@ -56,3 +56,37 @@ def test_static_scratch_entry_point_rejects_what_does_not_fit():
         None, None, None, vp(0x20000), None, None)
     assert rc == -8
     assert "static" in ulorl.status_string(-8)
+
+
+def test_static_scratch_entry_point_replays_from_a_graph():
+    """What the entry point is for: a caller under HIP graph capture, where nothing may be allocated.
+    After ulorl_init() and a warm-up call the static-scratch call is captured, replayed three times
+    with eager work in between (another static call on a different input among it: the scratch array is
+    shared and keeps that call's contents), and every replay must carry the bits of the eager result."""
+    ulorl.init()
+    w = ui.shrink(ui.config(2), [500, 260, 3], V=151936 // 4, seg_len=128, name="static_graph")
+    d = ui.generate(w, DEV)
+    p = params_for(w, gate_mode=ulorl.GATE_PER_RESPONSE, sigma=100.0, tau=0.5)
+    args = (d["logits"], d["token_ids"], d["cu_seqlens"], d["advantages"], d["old_logp"], p)
+    ref, dz_ref = ulorl.token_loss_fwd_bwd(*args)
+    dz = torch.empty_like(d["logits"])
+    out, _ = ulorl.token_loss_fwd_bwd_static(*args, dlogits=dz)                  # warm-up, allocates the outputs
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        ulorl.token_loss_fwd_bwd_static(*args, dlogits=dz, out=out)
+    other = ui.shrink(ui.config(2), [90, 37], V=5000, seg_len=16, name="static_graph_other")
+    do = ui.generate(other, DEV)
+    for replay in range(3):
+        dz.fill_(float("nan"))
+        out.loss.fill_(float("nan"))
+        out.gcoef.fill_(float("nan"))
+        # eager work between the replays, on the same scratch array
+        ulorl.token_loss_fwd_bwd_static(do["logits"], do["token_ids"], do["cu_seqlens"], do["advantages"], do["old_logp"],
+                                        params_for(other, gate_mode=ulorl.GATE_ALWAYS))
+        float(torch.randn(1 << 18, device=DEV).sum())
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert_same_results(ref, out, "graph replay %d of the static-scratch call" % replay)
+        assert torch.equal(_bits(dz), _bits(dz_ref)), replay

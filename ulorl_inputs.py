@@ -137,6 +137,13 @@ def _sample_tokens(z_f32: torch.Tensor, gen: torch.Generator) -> torch.Tensor:
     return torch.argmax(z_f32 + gumbel, dim=-1).to(torch.int32)
 
 
+def _behaviour_logp(z_f32: torch.Tensor, y: torch.Tensor) -> torch.Tensor:
+    """Centre of the recorded behaviour-policy log-probs of a block: the framework's stock fp32
+    log_softmax at the sampled tokens.  INPUT GENERATION ONLY -- the result (plus noise) is handed to
+    both sides as ``old_logp``; neither the library nor the oracle computes anything through it."""
+    return torch.log_softmax(z_f32, dim=-1).gather(1, y.long().unsqueeze(1)).squeeze(1)
+
+
 def generate(w: Workload, device="cpu", logits_out: Optional[torch.Tensor] = None,
              progress: Optional[Callable[[int, int], None]] = None) -> Dict[str, torch.Tensor]:
     """Materialise one workload on ``device``.
@@ -200,7 +207,7 @@ def generate(w: Workload, device="cpu", logits_out: Optional[torch.Tensor] = Non
             torch.mul(z, 1.0, out=logits[r0:r1])
             zf = logits[r0:r1].float()
         y = _sample_tokens(zf, g)
-        cur = torch.log_softmax(zf, dim=-1).gather(1, y.long().unsqueeze(1)).squeeze(1)
+        cur = _behaviour_logp(zf, y)
         noise = torch.randn(ROWS_PER_BLOCK, generator=g, device=device, dtype=torch.float32)[:rows]
         scale = torch.full((rows,), w.old_noise_std, device=device, dtype=torch.float32)
         if w.old_noise_per_segment:

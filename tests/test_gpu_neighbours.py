@@ -94,12 +94,13 @@ def test_segment_diagnostics_match_the_oracle():
     np.testing.assert_array_equal(g3["count"].cpu().numpy(), o["count"][:4])
 
 
-@pytest.mark.parametrize("case", ["logits_two_call", "logits_one_call", "lmhead", "explicit_ids_pois"])
+@pytest.mark.parametrize("case", ["logits_two_call", "logits_one_call", "lmhead", "explicit_ids_pois", "many_segments"])
 def test_segment_diagnostics_as_a_by_product_of_the_forward_calls(case):
     """The forward calls hand out the per-segment diagnostics in the same pass as the token terms;
     the numbers carry the bits of the standalone call on the stored outputs (which the test above
     holds against the oracle), and the other outputs do not change."""
-    K = 6
+    K = 1024 if case == "many_segments" else 6
+    pois = case in ("explicit_ids_pois", "many_segments")
     if case == "lmhead":
         w = ui.shrink(ui.config(5), [700, 1500, 30], V=1544, hidden=128, seg_len=300, name="diag_lmhead")
         d = ui.generate(w, DEV)
@@ -112,12 +113,13 @@ def test_segment_diagnostics_as_a_by_product_of_the_forward_calls(case):
     else:
         w = ui.shrink(ui.config(4), [1100, 2050, 1, 37], V=4096, seg_len=400, name="diag_fused")   # ids 0..5, ragged blocks
         d = ui.generate(w, DEV)
-        pois = case == "explicit_ids_pois"
         p = params_for(w, gate_mode=ulorl.GATE_ALWAYS, tau=0.5, is_mode=ulorl.IS_POIS if pois else ulorl.IS_SAIS,
                        seg_len=0 if pois else 400)
         old = None if pois else d["old_logp"]
         # arbitrary ids, some outside [0, K): many distinct ids inside one wave
         ids = ((torch.arange(w.N, device=DEV) * 7) % 9 - 1).to(torch.int32) if pois else None
+        if case == "many_segments":     # the largest table the kernels take, every id present, a few outside
+            ids = ((torch.arange(w.N, device=DEV) * 5) % 1030 - 3).to(torch.int32)
         args = (d["logits"], d["token_ids"], d["cu_seqlens"], d["advantages"], old, p)
         if case == "logits_one_call":
             plain, _ = ulorl.token_loss_fwd_bwd(*args)
@@ -135,7 +137,7 @@ def test_segment_diagnostics_as_a_by_product_of_the_forward_calls(case):
                            b.view(torch.int64) if b.dtype == torch.float64 else b), name
     n_in = int(((res.segment_out >= 0) & (res.segment_out < K)).sum())
     assert int(fused["count"].sum()) == n_in and int(fused["out_of_range"]) == w.N - n_in
-    if case == "explicit_ids_pois":
+    if pois:
         assert int(fused["out_of_range"]) > 0 and float(fused["kl_sum"].abs().sum()) == 0.0
         assert bool((fused["ratio_sum"] == fused["count"].double()).all())       # POIS: every ratio is 1
 

@@ -298,9 +298,26 @@ def bench_lmhead(args, w, ulorl, ui, torch, dev, as_entry=False):
         fwd_ms += b
         bwd_ms += c
     gemm_flops = 2.0 * w.N * w.hidden * w.V                 # one N x Hd x V product
-    bwd_tf = 3 * gemm_flops / (bwd_ms / K * 1e-3) / 1e12     # recompute, dHidden, dW
+    # The backward call runs its three products (recompute, dHidden, dW) over the rows with a
+    # non-zero coefficient only; the rate is priced on those rows, not on all N.
+    live = int((out.gcoef != 0).sum().item())
+    bwd_flops = 3 * gemm_flops * live / w.N
+    bwd_tf = bwd_flops / (bwd_ms / K * 1e-3) / 1e12
     fwd_tf = gemm_flops / (fwd_ms / K * 1e-3) / 1e12
     cnt = out.counters.cpu().tolist()
+    # the same backward call with every row in the products (ULORL_LAUNCH_DENSE_ROWS), for comparison
+    dense = ulorl.Launch(gemm_group_m=launch.gemm_group_m, dense_rows=True)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ulorl.lmhead_token_loss_bwd(H, W, y, out.lse, out.gcoef, 1.0, vocab_chunk=chunk, d_hidden=dH, d_weight=dW, workspace=ws,
+                                launch=dense)
+    nd = max(2, min(K, 5))
+    e0.record()
+    for _ in range(nd):
+        ulorl.lmhead_token_loss_bwd(H, W, y, out.lse, out.gcoef, 1.0, vocab_chunk=chunk, d_hidden=dH, d_weight=dW,
+                                    workspace=ws, launch=dense)
+    e1.record()
+    torch.cuda.synchronize()
+    dense_ms = e0.elapsed_time(e1) / nd
     counters_valid = (source_digest("lmhead.hip") == PMC_LMHEAD["source_sha256"] and w.name == "cfg5_lmhead_bf16"
                       and chunk == 8192)
     result = {
@@ -317,13 +334,14 @@ def bench_lmhead(args, w, ulorl, ui, torch, dev, as_entry=False):
                      "traffic": PMC_LMHEAD["bwd_bytes"] if counters_valid else None,
                      "traffic_note": "HBM-side bytes of the call (operand tiles are re-fetched per XCD; the "
                      "operands themselves are 1.5 GB)",
-                     "algorithmic_flops_per_launch": 3 * gemm_flops, "avg_launch_ms": bwd_ms / K},
+                     "algorithmic_flops_per_launch": bwd_flops, "live_rows": live, "avg_launch_ms": bwd_ms / K,
+                     "avg_launch_ms_every_row": dense_ms},
         "roofline_fwd": {"bound": "mfma", "kernel": "lmhead_stats_kernel (1 product)", "achieved": fwd_tf,
                          "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": fwd_tf / MFMA_BF16_PEAK_TFLOPS,
                          "traffic": PMC_LMHEAD["fwd_bytes"] if counters_valid else None,
                          "avg_call_ms": fwd_ms / K},
         "batch": {"masked_tokens": cnt[0], "clipped_tokens": cnt[1], "positive_tokens": cnt[2], "status": cnt[3],
-                  "loss": out.loss.item()},
+                  "live_rows": live, "loss": out.loss.item()},
     }
     # context only: the vendor library's plain bf16 GEMM on the shape of one vocabulary chunk
     # (N x chunk x Hd), timed the same way; no part of the path above uses it
@@ -497,6 +515,13 @@ def main():
             bk.close()
         sub = argparse.Namespace(steps=sub_steps, warmup=1, cpu_rows=args.cpu_rows)
         configs["cfg5"] = bench_lmhead(sub, ui.config(5), ulorl, ui, torch, dev, as_entry=True)
+        # labelled variant, not one of the named configurations: the same shape with 60 % of the hidden
+        # rows aligned with the sampled token's column of W, so that (as late in training, Sec. 3.2) many
+        # positive tokens are mastered and masked; the backward call then runs over the live rows only
+        from dataclasses import replace
+        sub0 = argparse.Namespace(steps=sub_steps, warmup=1, cpu_rows=0)
+        configs["cfg5_mastered_rows"] = bench_lmhead(sub0, replace(ui.config(5), align_frac=0.6, name="cfg5_lmhead_bf16_aligned60"),
+                                                     ulorl, ui, torch, dev, as_entry=True)
         result["configs"] = configs
     print(json.dumps(result), flush=True)
 

@@ -104,12 +104,19 @@ typedef struct ulorl_params {
  * library keeps state between calls, so concurrent calls from several threads are safe as long as
  * their buffers are distinct.  Workspace sizes never depend on these options. */
 enum {
-    ULORL_LAUNCH_PER_ROW = 1        /* row statistics and the one-call path by ONE looping workgroup
+    ULORL_LAUNCH_PER_ROW = 1,       /* row statistics and the one-call path by ONE looping workgroup
                                        per row instead of several cooperating ones: the kernels the
                                        library takes by itself for rows beyond 64 pieces
                                        (1.9 M bf16 logits).  Slower on long rows (16.3 ms against
                                        12.9 ms at 131072 x 151936); results differ from the default
                                        by the summation order of the row statistics only.        */
+    ULORL_LAUNCH_DENSE_ROWS = 2     /* lm_head backward: run every row through the three products.  By
+                                       default only the rows with a non-zero coefficient are (they are
+                                       gathered in order first): masked, clipped and flagged tokens
+                                       then cost nothing, which is most of the positive tokens when the
+                                       MPT mask is active.  d_hidden is the same either way; d_W
+                                       differs by the rounding of fp32 sums whose zero terms are left
+                                       out.                                                      */
 };
 typedef struct ulorl_launch {
     uint32_t flags;       /* ULORL_LAUNCH_* bits                                                  */
@@ -307,8 +314,9 @@ int32_t ulorl_token_loss_fwd_bwd_static(
  * the workspace is still needed, sized with any R >= 1).
  *
  * The workspace (ulorl_lmhead_workspace_bytes, 256-byte aligned) holds W^T, hidden^T, the two
- * dlogits chunk buffers, an fp32 accumulator for dHidden and the token-loss workspace; nothing
- * in it needs to survive between the forward and the backward call.
+ * dlogits chunk buffers, an fp32 accumulator for dHidden, the gathered live rows of hidden with
+ * their index maps and the token-loss workspace; nothing in it needs to survive between the forward
+ * and the backward call.
  */
 size_t ulorl_lmhead_workspace_bytes(int64_t N, int64_t Hd, int64_t V, int32_t R, int32_t vocab_chunk);
 

@@ -7,7 +7,7 @@ there is no CPU or eager fallback: without the built library, or without a GPU, 
 from .binding import (  # noqa: F401
     F32, BF16, IS_SAIS, IS_POIS, GATE_PER_RESPONSE, GATE_GLOBAL, GATE_ALWAYS, GATE_NEVER,
     STATUS_BAD_TOKEN, STATUS_NONFINITE, STATUS_BAD_CU, STATUS_SYNC,
-    LAUNCH_PER_ROW, Launch,
+    LAUNCH_PER_ROW, LAUNCH_DENSE_ROWS, Launch,
     UlorlError, Params, FwdResult, lib_path, load_library, version, status_string,
     token_loss_workspace_bytes, token_loss_fwd, token_loss_bwd, token_loss_fwd_bwd, token_loss_fwd_bwd_static, init, static_scratch_bytes, row_stats,
     lmhead_workspace_bytes, lmhead_token_loss_fwd, lmhead_token_loss_bwd, gemm_tn_bf16,

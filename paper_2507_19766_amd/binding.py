@@ -18,6 +18,7 @@ IS_SAIS, IS_POIS = 0, 1
 GATE_PER_RESPONSE, GATE_GLOBAL, GATE_ALWAYS, GATE_NEVER = 0, 1, 2, 3
 STATUS_BAD_TOKEN, STATUS_NONFINITE, STATUS_BAD_CU, STATUS_SYNC = 1, 2, 4, 8
 LAUNCH_PER_ROW = 1
+LAUNCH_DENSE_ROWS = 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 
@@ -53,12 +54,13 @@ class _CSegStats(ctypes.Structure):
 class Launch:
     """Per-call launch options (ulorl_launch); the defaults are the library's."""
     per_row: bool = False
+    dense_rows: bool = False
     sync_spins: int = 0
     gemm_tile: int = 0
     gemm_group_m: int = 0
 
     def to_c(self) -> _CLaunch:
-        return _CLaunch(LAUNCH_PER_ROW if self.per_row else 0, self.sync_spins, self.gemm_tile, self.gemm_group_m,
+        return _CLaunch((LAUNCH_PER_ROW if self.per_row else 0) | (LAUNCH_DENSE_ROWS if self.dense_rows else 0), self.sync_spins, self.gemm_tile, self.gemm_group_m,
                         (ctypes.c_int32 * 4)(0, 0, 0, 0))
 
 

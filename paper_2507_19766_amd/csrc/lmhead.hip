@@ -416,6 +416,16 @@ __device__ __forceinline__ void gemm_tn_tile(const bf16_t* __restrict__ A, int64
                                              const bf16_t* __restrict__ B, int64_t ldb, int N, int n0, int K,
                                              f32x16 (&acc)[Cfg::MB][Cfg::NB], bf16_t* lds)
 {
+    if (K <= 0) {           // empty contraction (no live row): the product is zero
+#pragma unroll
+        for (int bi = 0; bi < Cfg::MB; ++bi)
+#pragma unroll
+            for (int bj = 0; bj < Cfg::NB; ++bj)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[bi][bj][r] = 0.0f;
+        __syncthreads();
+        return;
+    }
     if constexpr (Cfg::DIRECT) {
         if (K % Cfg::BK == 0) {
             gemm_tn_mainloop_direct<Cfg>(A, lda, M, m0, B, ldb, N, n0, K, acc, lds);
@@ -533,10 +543,16 @@ __device__ __forceinline__ void store_wave_tile_rows(const f32x16 (&acc)[Cfg::MB
 template <class Cfg, int STORE>
 __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(Cfg::WAVES_PER_SIMD, Cfg::WAVES_PER_SIMD)))
 void gemm_tn_kernel(const bf16_t* __restrict__ A, int64_t lda, int M, const bf16_t* __restrict__ B, int64_t ldb, int N,
-                    int K, void* __restrict__ C, int64_t ldc, int wide_rows, int group_m)
+                    int K, void* __restrict__ C, int64_t ldc, int wide_rows, int group_m,
+                    const int* __restrict__ dyn_m, const int* __restrict__ dyn_k)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     bf16_t* lds = reinterpret_cast<bf16_t*>(lds_raw);
+    // Extents known only on the device (the number of live rows of the lm_head backward): the
+    // launch covers the largest case and workgroups beyond the actual tile grid return at once.
+    if (dyn_m != nullptr) M = min(M, *dyn_m);
+    if (dyn_k != nullptr) K = min(K, (*dyn_k + 63) / 64 * 64);
+    if (M <= 0) return;
     int tile_m, tile_n;
     if (!tile_coords((M + Cfg::BM - 1) / Cfg::BM, (N + Cfg::BN - 1) / Cfg::BN, group_m, tile_m, tile_n)) return;
     const int m0 = tile_m * Cfg::BM, n0 = tile_n * Cfg::BN;
@@ -568,17 +584,23 @@ void gemm_tn_kernel(const bf16_t* __restrict__ A, int64_t lda, int M, const bf16
 }
 
 // dst[c, r] = src[r, c] (bf16), 64x64 tiles through LDS; columns of dst beyond `rows` up to
-// dst_cols are written as zero (padding of the contraction dimension).
+// dst_cols are written as zero (padding of the contraction dimension).  With a row map, row r of
+// the source is src[row_map[r]] and the row count comes from the device (*dyn_rows): the gathered
+// transpose of the live rows.
 __global__ __launch_bounds__(256) void transpose_bf16_kernel(const bf16_t* __restrict__ src, int64_t lds_, int rows,
                                                             int cols, bf16_t* __restrict__ dst, int64_t ldd,
-                                                            int dst_cols)
+                                                            int dst_cols, const int* __restrict__ row_map,
+                                                            const int* __restrict__ dyn_rows)
 {
     __shared__ bf16_t tile[64][66];
+    if (dyn_rows != nullptr) rows = min(rows, *dyn_rows);
     const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     for (int i = ty; i < 64; i += 4) {
         const int r = r0 + i, c = c0 + tx;
-        tile[i][tx] = (r < rows && c < cols) ? src[(int64_t)r * lds_ + c] : (bf16_t)0;
+        bf16_t x = 0;
+        if (r < rows && c < cols) x = src[(int64_t)(row_map != nullptr ? row_map[r] : r) * lds_ + c];
+        tile[i][tx] = x;
     }
     __syncthreads();
     for (int i = ty; i < 64; i += 4) {
@@ -587,14 +609,116 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(const bf16_t* __res
     }
 }
 
-__global__ void f32_to_bf16_kernel(const float* __restrict__ src, bf16_t* __restrict__ dst, int64_t n)
+// d_hidden[t, :] = bf16(acc[pos[t], :]) (pos == NULL: acc[t, :]); rows without a live position are zero.
+// Hd is even (a multiple of 8).
+__global__ void dhidden_finish_kernel(const float* __restrict__ acc, const int* __restrict__ pos, int64_t N, int Hd,
+                                      bf16_t* __restrict__ dst)
 {
-    int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 2;
-    if (i + 1 < n) {
-        *reinterpret_cast<uint32_t*>(dst + i) = pack_bf16x2(src[i], src[i + 1]);
-    } else if (i < n) {
-        dst[i] = to_bf16(src[i]);
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;     // one pair of elements
+    const int half = Hd / 2;
+    const int64_t t = i / half;
+    if (t >= N) return;
+    const int c = (int)(i - t * half) * 2;
+    const int64_t j = pos != nullptr ? (int64_t)pos[t] : t;
+    uint32_t out = 0u;
+    if (j >= 0) out = pack_bf16x2(acc[j * Hd + c], acc[j * Hd + c + 1]);
+    *reinterpret_cast<uint32_t*>(dst + t * Hd + c) = out;
+}
+
+// ---------------------------------------------------------------------------------------------
+// live rows of the backward pass
+// ---------------------------------------------------------------------------------------------
+// A token whose coefficient is zero (masked as a well-mastered positive token, on the clipped
+// branch, zero advantage, or flagged) contributes nothing to d_W and has a zero d_hidden row.  The
+// backward pass therefore runs its three products over the LIVE rows only: their indices are
+// collected in order (so that every sum keeps a fixed order), hidden is gathered, and the kernels
+// take the live count from device memory.  The dynamic mask of the method makes this count
+// much smaller than N whenever many positive tokens are mastered.
+constexpr int kLiveBlock = 1024;
+
+__device__ __forceinline__ bool row_has_gradient(float g, float l, int32_t y, int32_t V)
+{
+    return (g != 0.0f) && (fabsf(g) <= 3.0e38f) && (fabsf(l) <= 3.0e38f) && y >= 0 && y < V;
+}
+
+// Inclusive prefix sum over a workgroup of kLiveBlock threads; *total = the workgroup's sum.
+__device__ __forceinline__ int live_block_scan(int v, int* wave_tot, int* total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int up = __shfl_up(v, off);
+        if (lane >= off) v += up;
     }
+    __syncthreads();
+    if (lane == 63) wave_tot[wave] = v;
+    __syncthreads();
+    int before = 0, all = 0;
+    for (int w = 0; w < kLiveBlock / 64; ++w) {
+        const int x = wave_tot[w];
+        before += w < wave ? x : 0;
+        all += x;
+    }
+    *total = all;
+    return v + before;
+}
+
+__global__ __launch_bounds__(kLiveBlock) void live_count_kernel(const float* __restrict__ gcoef, const float* __restrict__ lse,
+                                                                const int32_t* __restrict__ token_ids, float grad_out,
+                                                                int64_t N, int32_t V, int* __restrict__ block_count)
+{
+    __shared__ int wave_tot[kLiveBlock / 64];
+    const int64_t t = (int64_t)blockIdx.x * kLiveBlock + threadIdx.x;
+    const int live = t < N && row_has_gradient(gcoef[t] * grad_out, lse[t], token_ids[t], V);
+    int total;
+    live_block_scan(live, wave_tot, &total);
+    if (threadIdx.x == 0) block_count[blockIdx.x] = total;
+}
+
+// One workgroup: exclusive prefix sums of the blocks' counts (in place) and the total.
+__global__ __launch_bounds__(kLiveBlock) void live_scan_kernel(int* __restrict__ block_count, int nblk, int* __restrict__ n_live)
+{
+    __shared__ int wave_tot[kLiveBlock / 64];
+    int base = 0;
+    for (int b0 = 0; b0 < nblk; b0 += kLiveBlock) {
+        const int b = b0 + threadIdx.x;
+        const int c = b < nblk ? block_count[b] : 0;
+        int total;
+        const int incl = live_block_scan(c, wave_tot, &total);
+        if (b < nblk) block_count[b] = base + incl - c;
+        base += total;
+    }
+    if (threadIdx.x == 0) *n_live = base;
+}
+
+// pos[t] = position of row t among the live rows (-1: not live); row_map[position] = t.
+__global__ __launch_bounds__(kLiveBlock) void live_fill_kernel(const float* __restrict__ gcoef, const float* __restrict__ lse,
+                                                               const int32_t* __restrict__ token_ids, float grad_out,
+                                                               int64_t N, int32_t V, const int* __restrict__ block_offset,
+                                                               int* __restrict__ pos, int* __restrict__ row_map)
+{
+    __shared__ int wave_tot[kLiveBlock / 64];
+    const int64_t t = (int64_t)blockIdx.x * kLiveBlock + threadIdx.x;
+    const int live = t < N && row_has_gradient(gcoef[t] * grad_out, lse[t], token_ids[t], V);
+    int total;
+    const int incl = live_block_scan(live, wave_tot, &total);
+    if (t < N) {
+        const int p = block_offset[blockIdx.x] + incl - 1;
+        pos[t] = live ? p : -1;
+        if (live) row_map[p] = (int)t;
+    }
+}
+
+// dst[j, :] = src[row_map[j], :] for j < *n_live (16-byte vectors; cols is a multiple of 8).
+__global__ void gather_rows_kernel(const bf16_t* __restrict__ src, int cols, const int* __restrict__ row_map,
+                                   const int* __restrict__ n_live, int64_t N, bf16_t* __restrict__ dst)
+{
+    const int vpr = cols / 8;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t j = i / vpr;
+    if (j >= N || j >= *n_live) return;
+    const int v = (int)(i - j * vpr);
+    reinterpret_cast<u32x4*>(dst + j * cols)[v] = reinterpret_cast<const u32x4*>(src + (int64_t)row_map[j] * cols)[v];
 }
 
 __global__ void fill_zero_f32_kernel(float* p, int64_t n)
@@ -755,12 +879,22 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(Cfg::WA
 void lmhead_dz_kernel(const bf16_t* __restrict__ Wt, const bf16_t* __restrict__ H, int Hd, int V, int Ntok, int vc0,
                       int cw, const int32_t* __restrict__ token_ids, const float* __restrict__ lse,
                       const float* __restrict__ gcoef, float grad_out, bf16_t* __restrict__ dZc, int64_t ld_c,
-                      bf16_t* __restrict__ dZcT, int64_t ld_t, int group_m)
+                      bf16_t* __restrict__ dZcT, int64_t ld_t, int group_m, const int* __restrict__ row_map,
+                      const int* __restrict__ n_live)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     bf16_t* lds = reinterpret_cast<bf16_t*>(lds_raw);
+    // With a row map, H holds the gathered live rows, Ntok becomes their count (from the device) and
+    // token column t stands for row row_map[t] of the per-token arrays.  The last token tile is
+    // written in full (zeros beyond the count): the d_W product contracts over whole 64-column blocks.
+    int t_tiles = (int)((ld_t + Cfg::BN - 1) / Cfg::BN);
+    if (n_live != nullptr) {
+        Ntok = min(Ntok, *n_live);
+        if (Ntok <= 0) return;
+        t_tiles = (Ntok + Cfg::BN - 1) / Cfg::BN;
+    }
     int v_tile, t_tile;
-    if (!tile_coords((cw + Cfg::BM - 1) / Cfg::BM, (int)((ld_t + Cfg::BN - 1) / Cfg::BN), group_m, v_tile, t_tile)) return;
+    if (!tile_coords((cw + Cfg::BM - 1) / Cfg::BM, t_tiles, group_m, v_tile, t_tile)) return;
     const int v0 = vc0 + v_tile * Cfg::BM;
     const int t0 = t_tile * Cfg::BN;
     const int vend = min(V, vc0 + cw);
@@ -784,11 +918,11 @@ void lmhead_dz_kernel(const bf16_t* __restrict__ Wt, const bf16_t* __restrict__ 
         const int t = t_wave + bj * 32 + (lane & 31);
         g_mag[bj] = 0.0f; c[bj] = 0.0f; flip[bj] = 0u; keep[bj] = 0u; dy[bj] = -1;
         if (t < Ntok) {
-            const float gg = gcoef[t] * grad_out;
-            const float l = lse[t];
-            const int32_t yy = token_ids[t];
-            const bool live = (gg != 0.0f) && (fabsf(gg) <= 3.0e38f) && (fabsf(l) <= 3.0e38f) && yy >= 0 && yy < V;
-            if (live) {
+            const int tt = row_map != nullptr ? row_map[t] : t;
+            const float gg = gcoef[tt] * grad_out;
+            const float l = lse[tt];
+            const int32_t yy = token_ids[tt];
+            if (row_has_gradient(gg, l, yy, V)) {
                 const bool negate = gg > 0.0f;
                 g_mag[bj] = negate ? -gg : gg;    // -|g|
                 c[bj] = fmaf(-l, kLog2e, log2f(fabsf(gg)));
@@ -916,7 +1050,7 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline int64_t round_up64(int64_t x) { return (x + 63) / 64 * 64; }
 
 struct LmheadLayout {
-    size_t wt, ht, dzc, dzct, dhacc, partial, token_ws, total;
+    size_t wt, ht, dzc, dzct, dhacc, partial, token_ws, hc, pos, row_map, block_count, n_live, total;
     int64_t ldt;      // padded token count (leading dimension of Ht and dZc^T)
     int64_t ldc;      // padded chunk width (leading dimension of dZc)
     int splits;
@@ -951,6 +1085,12 @@ LmheadLayout lmhead_layout(int64_t N, int64_t Hd, int64_t V, int32_t R, int32_t 
     L.dhacc = off;   off = align_up(off + (size_t)N * Hd * 4, 256);
     L.partial = off; off = align_up(off + max_splits * (size_t)N * sizeof(StatQuad), 256);
     L.token_ws = off; off = align_up(off + workspace_layout(N, 0, R).total, 256);
+    // backward over the live rows only: gathered hidden rows, row <-> position maps, scan scratch
+    L.hc = off;          off = align_up(off + (size_t)N * Hd * 2, 256);
+    L.pos = off;         off = align_up(off + (size_t)N * sizeof(int), 256);
+    L.row_map = off;     off = align_up(off + (size_t)L.ldt * sizeof(int), 256);
+    L.block_count = off; off = align_up(off + (size_t)((N + kLiveBlock - 1) / kLiveBlock) * sizeof(int), 256);
+    L.n_live = off;      off = align_up(off + sizeof(int), 256);
     L.total = off;
     return L;
 }
@@ -988,31 +1128,36 @@ bool allow_lds(Kernel k, size_t bytes)
 }
 
 void launch_transpose(const bf16_t* src, int64_t ld_src, int rows, int cols, bf16_t* dst, int64_t ld_dst, int dst_cols,
-                      hipStream_t st)
+                      hipStream_t st, const int* row_map = nullptr, const int* dyn_rows = nullptr)
 {
     dim3 grid((unsigned)((dst_cols + 63) / 64), (unsigned)((cols + 63) / 64));
-    hipLaunchKernelGGL(transpose_bf16_kernel, grid, dim3(256), 0, st, src, ld_src, rows, cols, dst, ld_dst, dst_cols);
+    hipLaunchKernelGGL(transpose_bf16_kernel, grid, dim3(256), 0, st, src, ld_src, rows, cols, dst, ld_dst, dst_cols,
+                       row_map, dyn_rows);
 }
 
 template <class Cfg, int STORE>
 bool launch_gemm_cfg(const bf16_t* A, int64_t lda, int M, const bf16_t* B, int64_t ldb, int N, int K, void* C,
-                     int64_t ldc, int group_m, hipStream_t st)
+                     int64_t ldc, int group_m, const int* dyn_m, const int* dyn_k, hipStream_t st)
 {
     auto kern = gemm_tn_kernel<Cfg, STORE>;
     if (!allow_lds(kern, Cfg::LDS_BYTES)) return false;
     dim3 grid(tile_grid((M + Cfg::BM - 1) / Cfg::BM, (N + Cfg::BN - 1) / Cfg::BN));
     const int eb = STORE == STORE_BF16 ? 2 : 4;
     const int wide_rows = (((uintptr_t)C & 15u) == 0 && (ldc * eb) % 16 == 0) ? 1 : 0;
-    hipLaunchKernelGGL(kern, grid, dim3(Cfg::NT), Cfg::LDS_BYTES, st, A, lda, M, B, ldb, N, K, C, ldc, wide_rows, group_m);
+    hipLaunchKernelGGL(kern, grid, dim3(Cfg::NT), Cfg::LDS_BYTES, st, A, lda, M, B, ldb, N, K, C, ldc, wide_rows, group_m,
+                       dyn_m, dyn_k);
     return true;
 }
 
+// dyn_m / dyn_k (device, may be NULL): the actual row count of A and C / the actual contraction
+// length, when only the device knows them; M and K are then their upper bounds.
 template <int STORE>
 bool launch_gemm(const LaunchOpts& o, const bf16_t* A, int64_t lda, int M, const bf16_t* B, int64_t ldb, int N, int K,
-                 void* C, int64_t ldc, hipStream_t st)
+                 void* C, int64_t ldc, hipStream_t st, const int* dyn_m = nullptr, const int* dyn_k = nullptr)
 {
     bool ok = false;
-    ULORL_FOR_TILE(o.gemm_tile, ok = (launch_gemm_cfg<Cfg, STORE>(A, lda, M, B, ldb, N, K, C, ldc, o.gemm_group_m, st)))
+    ULORL_FOR_TILE(o.gemm_tile,
+                   ok = (launch_gemm_cfg<Cfg, STORE>(A, lda, M, B, ldb, N, K, C, ldc, o.gemm_group_m, dyn_m, dyn_k, st)))
     return ok;
 }
 
@@ -1031,13 +1176,13 @@ bool launch_stats_cfg(const bf16_t* Wt, const bf16_t* H, int Hd, int V, int N, c
 template <class Cfg>
 bool launch_dz_cfg(const bf16_t* Wt, const bf16_t* H, int Hd, int V, int N, int vc0, int cw_pad,
                    const int32_t* token_ids, const float* lse, const float* gcoef, float grad_out, bf16_t* dZc,
-                   bf16_t* dZcT, const LmheadLayout& L, int group_m, hipStream_t st)
+                   bf16_t* dZcT, const LmheadLayout& L, int group_m, const int* row_map, const int* n_live, hipStream_t st)
 {
     auto kern = lmhead_dz_kernel<Cfg>;
     if (!allow_lds(kern, Cfg::LDS_BYTES)) return false;
     dim3 grid(tile_grid((cw_pad + Cfg::BM - 1) / Cfg::BM, (int)((L.ldt + Cfg::BN - 1) / Cfg::BN)));
     hipLaunchKernelGGL(kern, grid, dim3(Cfg::NT), Cfg::LDS_BYTES, st, Wt, H, Hd, V, N, vc0, cw_pad, token_ids, lse, gcoef,
-                       grad_out, dZc, L.ldc, dZcT, L.ldt, group_m);
+                       grad_out, dZc, L.ldc, dZcT, L.ldt, group_m, row_map, n_live);
     return true;
 }
 
@@ -1144,26 +1289,56 @@ int32_t ulorl_lmhead_token_loss_bwd(const void* hidden, const void* W, int64_t N
     const bf16_t* Wp = (const bf16_t*)W;
 
     launch_transpose(Wp, V, (int)Hd, (int)V, Wt, Hd, (int)Hd, st);                    // Wt[v, k]
-    launch_transpose(H, Hd, (int)N, (int)Hd, Ht, L.ldt, (int)L.ldt, st);              // Ht[k, t], zero padded
     const int64_t nh = N * Hd;
     hipLaunchKernelGGL(fill_zero_f32_kernel, dim3((unsigned)((nh + 255) / 256)), dim3(256), 0, st, dHacc, nh);
+
+    // Live rows (those with a non-zero coefficient): positions in order, gathered hidden rows and
+    // their transpose.  ULORL_LAUNCH_DENSE_ROWS runs every row through the products instead.
+    const bf16_t* Hrows = H;            // the token operand of the z product: [rows, Hd]
+    const int* row_map = nullptr;
+    const int* pos = nullptr;
+    const int* n_live = nullptr;
+    if (!opts.dense_rows) {
+        int* posw = (int*)(ws + L.pos);
+        int* mapw = (int*)(ws + L.row_map);
+        int* cntw = (int*)(ws + L.block_count);
+        int* nlw = (int*)(ws + L.n_live);
+        bf16_t* Hc = (bf16_t*)(ws + L.hc);
+        const int nblk = (int)((N + kLiveBlock - 1) / kLiveBlock);
+        hipLaunchKernelGGL(live_count_kernel, dim3((unsigned)nblk), dim3(kLiveBlock), 0, st, gcoef, lse, token_ids, grad_out,
+                           N, (int32_t)V, cntw);
+        hipLaunchKernelGGL(live_scan_kernel, dim3(1), dim3(kLiveBlock), 0, st, cntw, nblk, nlw);
+        hipLaunchKernelGGL(live_fill_kernel, dim3((unsigned)nblk), dim3(kLiveBlock), 0, st, gcoef, lse, token_ids, grad_out, N,
+                           (int32_t)V, (const int*)cntw, posw, mapw);
+        const int64_t nvec = N * (Hd / 8);
+        hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)((nvec + 255) / 256)), dim3(256), 0, st, H, (int)Hd,
+                           (const int*)mapw, (const int*)nlw, N, Hc);
+        launch_transpose(H, Hd, (int)N, (int)Hd, Ht, L.ldt, (int)L.ldt, st, mapw, nlw);   // Ht[k, j] = hidden[row_map[j], k], zero padded
+        Hrows = Hc; row_map = mapw; pos = posw; n_live = nlw;
+    } else {
+        launch_transpose(H, Hd, (int)N, (int)Hd, Ht, L.ldt, (int)L.ldt, st);              // Ht[k, t], zero padded
+    }
+    if (hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;
 
     for (int64_t vc0 = 0; vc0 < V; vc0 += vocab_chunk) {
         const int cw = (int)((V - vc0 < vocab_chunk) ? (V - vc0) : vocab_chunk);
         const int cw_pad = (int)round_up64(cw);         // dz of the padding columns is written as zero
         bool ok = false;
-        ULORL_FOR_TILE(opts.gemm_tile, ok = launch_dz_cfg<Cfg>(Wt, H, (int)Hd, (int)V, (int)N, (int)vc0, cw_pad, token_ids, lse,
-                                                               gcoef, grad_out, dZc, dZcT, L, opts.gemm_group_m, st))
+        ULORL_FOR_TILE(opts.gemm_tile, ok = launch_dz_cfg<Cfg>(Wt, Hrows, (int)Hd, (int)V, (int)N, (int)vc0, cw_pad, token_ids,
+                                                               lse, gcoef, grad_out, dZc, dZcT, L, opts.gemm_group_m, row_map,
+                                                               n_live, st))
         if (!ok) return ULORL_ERR_HIP;
-        // dHidden[t, k] += sum_v dZc[t, v] W[k, vc0 + v]
-        if (!launch_gemm<STORE_F32_ACCUM>(opts, dZc, L.ldc, (int)N, Wp + vc0, V, (int)Hd, cw, dHacc, Hd, st)) return ULORL_ERR_HIP;
-        // dW[k, vc0 + v] = sum_t Ht[k, t] dZc^T[v, t]
-        if (!launch_gemm<STORE_BF16>(opts, Ht, L.ldt, (int)Hd, dZcT, L.ldt, cw, (int)L.ldt, (bf16_t*)d_W + vc0, V, st))
+        // dHidden[j, k] += sum_v dZc[j, v] W[k, vc0 + v]          (j: live position, or the row itself)
+        if (!launch_gemm<STORE_F32_ACCUM>(opts, dZc, L.ldc, (int)N, Wp + vc0, V, (int)Hd, cw, dHacc, Hd, st, n_live, nullptr))
+            return ULORL_ERR_HIP;
+        // dW[k, vc0 + v] = sum_j Ht[k, j] dZc^T[v, j]
+        if (!launch_gemm<STORE_BF16>(opts, Ht, L.ldt, (int)Hd, dZcT, L.ldt, cw, (int)L.ldt, (bf16_t*)d_W + vc0, V, st, nullptr,
+                                     n_live))
             return ULORL_ERR_HIP;
         if (hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;
     }
-    hipLaunchKernelGGL(f32_to_bf16_kernel, dim3((unsigned)((nh / 2 + 256) / 256)), dim3(256), 0, st, dHacc,
-                       (bf16_t*)d_hidden, nh);
+    hipLaunchKernelGGL(dhidden_finish_kernel, dim3((unsigned)((nh / 2 + 255) / 256)), dim3(256), 0, st, (const float*)dHacc, pos,
+                       N, (int)Hd, (bf16_t*)d_hidden);
     return hipGetLastError() == hipSuccess ? ULORL_OK : ULORL_ERR_HIP;
 }
 

@@ -1511,13 +1511,14 @@ int32_t resolve_launch(const ulorl_launch* launch, LaunchOpts* out)
 {
     *out = LaunchOpts();
     if (!launch) return ULORL_OK;
-    if ((launch->flags & ~(uint32_t)ULORL_LAUNCH_PER_ROW) != 0) return ULORL_ERR_PARAM;
+    if ((launch->flags & ~(uint32_t)(ULORL_LAUNCH_PER_ROW | ULORL_LAUNCH_DENSE_ROWS)) != 0) return ULORL_ERR_PARAM;
     for (int i = 0; i < 4; ++i)
         if (launch->reserved[i] != 0) return ULORL_ERR_PARAM;
     if (launch->sync_spins < 0 || launch->gemm_tile < 0 || launch->gemm_tile > 1 || launch->gemm_group_m < 0 ||
         launch->gemm_group_m > 64)
         return ULORL_ERR_PARAM;
     out->per_row = (launch->flags & ULORL_LAUNCH_PER_ROW) != 0;
+    out->dense_rows = (launch->flags & ULORL_LAUNCH_DENSE_ROWS) != 0;
     if (launch->sync_spins > 0) out->sync_spins = launch->sync_spins;
     out->gemm_tile = launch->gemm_tile;
     if (launch->gemm_group_m > 0) out->gemm_group_m = launch->gemm_group_m;

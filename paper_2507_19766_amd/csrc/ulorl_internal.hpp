@@ -73,6 +73,7 @@ void launch_token_epilogue(const TokenArgs& a, const WorkspaceLayout& wl, float*
 // Launch options of one call, validated and with the defaults filled in.
 struct LaunchOpts {
     bool per_row = false;         // ULORL_LAUNCH_PER_ROW
+    bool dense_rows = false;      // ULORL_LAUNCH_DENSE_ROWS
     int sync_spins = 1 << 24;
     int gemm_tile = 0;
     int gemm_group_m = 4;

@@ -96,7 +96,7 @@ def test_launch_options_and_segment_stats_validate_on_the_host():
 
     def launch(flags=0, spins=0, tile=0, group=0, reserved=(0, 0, 0, 0)):
         return ctypes.byref(L(flags, spins, tile, group, four(*reserved)))
-    assert _fwd(lib, launch=launch(flags=2)) == -5            # unknown flag
+    assert _fwd(lib, launch=launch(flags=4)) == -5            # unknown flag
     assert _fwd(lib, launch=launch(spins=-1)) == -5
     assert _fwd(lib, launch=launch(tile=2)) == -5 and _fwd(lib, launch=launch(group=65)) == -5
     assert _fwd(lib, launch=launch(reserved=(0, 0, 1, 0))) == -5

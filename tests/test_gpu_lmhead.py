@@ -134,3 +134,62 @@ def test_lmhead_stats_only_pass():
     assert only.loss is None and only.gcoef is None
     for name in ("lse", "logp", "entropy"):
         assert torch.equal(getattr(only, name), getattr(full, name)), name
+
+
+def _lmhead_bwd_pair(d, w, p, chunk):
+    """(forward result, (d_hidden, d_W) over the live rows, the same with every row in the products)"""
+    fwd = ulorl.lmhead_token_loss_fwd(d["hidden"], d["weight"], d["token_ids"], d["cu_seqlens"], d["advantages"],
+                                      d["old_logp"], p, vocab_chunk=chunk)
+    live = ulorl.lmhead_token_loss_bwd(d["hidden"], d["weight"], d["token_ids"], fwd.lse, fwd.gcoef, 1.0, vocab_chunk=chunk)
+    dense = ulorl.lmhead_token_loss_bwd(d["hidden"], d["weight"], d["token_ids"], fwd.lse, fwd.gcoef, 1.0, vocab_chunk=chunk,
+                                        launch=ulorl.Launch(dense_rows=True))
+    torch.cuda.synchronize()
+    return fwd, live, dense
+
+
+def _assert_dw_same_up_to_rounding(a, b):
+    a, b = a.float(), b.float()
+    # different grouping of the same fp32 terms, then one rounding to bf16: at most an ulp of the larger entries
+    assert float((a - b).abs().max()) <= 2.0 ** -7 * float(torch.maximum(a.abs(), b.abs()).max())
+    assert float((a - b).abs().mean()) <= 2.0 ** -9 * float(a.abs().mean()) + 1e-30
+
+
+def test_backward_runs_over_the_live_rows_only():
+    """The backward pass gathers the rows with a non-zero coefficient (Sec. 3.2.2: a masked token
+    contributes no gradient) and runs its products over those; ULORL_LAUNCH_DENSE_ROWS runs them
+    over every row.  Both against the oracle, and against each other: d_hidden bit for bit (a row's
+    sums do not depend on which other rows are present), d_W up to the rounding of regrouped sums."""
+    from dataclasses import replace
+    w = replace(ui.shrink(ui.config(5), [300, 212], V=4096 + 8, hidden=256, seg_len=64), align_frac=0.5,
+                name="lmhead_live_rows")
+    d = ui.generate(w, DEV)
+    p = params_for(w, gate_mode=ulorl.GATE_ALWAYS)
+    res, tt = run_lmhead_parity(w, p, chunk=1024, data=d)
+    res2, _ = run_lmhead_parity(w, p, chunk=1024, data=d, launch=ulorl.Launch(dense_rows=True))
+    dead = int((res.gcoef == 0).sum())
+    say("live rows: %d of %d" % (w.N - dead, w.N))
+    assert 20 <= dead < w.N - 20
+    assert torch.equal(res.d_hidden, res2.d_hidden)
+    _assert_dw_same_up_to_rounding(res.d_weight, res2.d_weight)
+
+
+@pytest.mark.parametrize("n_live", [0, 1, 65])
+def test_backward_with_few_or_no_live_rows(n_live):
+    """Degenerate live counts: no row at all (every advantage zero: both gradients exactly zero), one
+    row, one row more than a 64-column block of the contraction."""
+    w = ui.shrink(ui.config(5), [200, 150], V=2056, hidden=128, seg_len=64, name="lmhead_few_live")
+    d = ui.generate(w, DEV)
+    keep = torch.zeros(w.N, dtype=torch.bool, device=DEV)
+    if n_live:
+        keep[torch.randperm(w.N, generator=torch.Generator().manual_seed(5))[:n_live].to(DEV)] = True
+    d["advantages"] = torch.where(keep, torch.full_like(d["advantages"], 0.75), torch.zeros_like(d["advantages"]))
+    p = ulorl.Params(gate_mode=ulorl.GATE_NEVER, seg_len=w.seg_len, eps_low=10.0, eps_high=10.0)
+    fwd, (dH, dW), (dH2, dW2) = _lmhead_bwd_pair(d, w, p, chunk=512)
+    assert int((fwd.gcoef != 0).sum()) == n_live
+    assert torch.equal(dH, dH2)
+    assert bool((dH[~keep] == 0).all())
+    if n_live == 0:
+        assert bool((dH == 0).all()) and bool((dW == 0).all()) and bool((dW2 == 0).all())
+    else:
+        assert bool((dH[keep].float().abs().sum(dim=1) > 0).all())
+        _assert_dw_same_up_to_rounding(dW, dW2)

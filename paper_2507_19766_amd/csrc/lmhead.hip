@@ -14,6 +14,7 @@
 // token column and 16 vocabulary rows, which makes the softmax reductions lane-local.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <string.h>
 
 #include <mutex>
 #include <type_traits>
@@ -443,11 +444,12 @@ __device__ __forceinline__ void gemm_tn_tile(const bf16_t* __restrict__ A, int64
 // through that XCD's L2.
 constexpr int kXcds = 8;
 
-__device__ __forceinline__ bool tile_coords(int num_m, int num_n, int group_m, int& tile_m, int& tile_n)
+// bid: the workgroup's id within its kernel, or within its part of a launch that several products
+// share (a part starts at a multiple of 8 workgroups, so bid % 8 is still the XCD).
+__device__ __forceinline__ bool tile_coords(int bid, int num_m, int num_n, int group_m, int& tile_m, int& tile_n)
 {
     const int total = num_m * num_n;
     const int per_xcd = (total + kXcds - 1) / kXcds;
-    const int bid = blockIdx.x;
     const int logical = (bid % kXcds) * per_xcd + bid / kXcds;
     if (bid / kXcds >= per_xcd || logical >= total) return false;
     const int group_size = group_m * num_n;
@@ -460,7 +462,7 @@ __device__ __forceinline__ bool tile_coords(int num_m, int num_n, int group_m, i
     return true;
 }
 
-inline unsigned tile_grid(int num_m, int num_n)
+__host__ __device__ inline unsigned tile_grid(int num_m, int num_n)
 {
     const int total = num_m * num_n;
     return (unsigned)(((total + kXcds - 1) / kXcds) * kXcds);
@@ -540,21 +542,27 @@ __device__ __forceinline__ void store_wave_tile_rows(const f32x16 (&acc)[Cfg::MB
     }
 }
 
+// One product C = A . B^T (A [M, K], B [N, K], both with K contiguous).  wide_rows: C allows
+// 16-byte accesses.
+struct GemmArgs {
+    const bf16_t* A; int64_t lda; int M;
+    const bf16_t* B; int64_t ldb; int N;
+    int K;
+    void* C; int64_t ldc;
+    int wide_rows;
+};
+
+// The tile of workgroup `bid` (see tile_coords) of one product; workgroups beyond the tile grid
+// return at once.
 template <class Cfg, int STORE>
-__global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(Cfg::WAVES_PER_SIMD, Cfg::WAVES_PER_SIMD)))
-void gemm_tn_kernel(const bf16_t* __restrict__ A, int64_t lda, int M, const bf16_t* __restrict__ B, int64_t ldb, int N,
-                    int K, void* __restrict__ C, int64_t ldc, int wide_rows, int group_m,
-                    const int* __restrict__ dyn_m, const int* __restrict__ dyn_k)
+__device__ __forceinline__ void gemm_tn_block(int bid, const bf16_t* __restrict__ A, int64_t lda, int M,
+                                              const bf16_t* __restrict__ B, int64_t ldb, int N, int K, void* __restrict__ C,
+                                              int64_t ldc, int wide_rows, int group_m, unsigned char* lds_raw)
 {
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     bf16_t* lds = reinterpret_cast<bf16_t*>(lds_raw);
-    // Extents known only on the device (the number of live rows of the lm_head backward): the
-    // launch covers the largest case and workgroups beyond the actual tile grid return at once.
-    if (dyn_m != nullptr) M = min(M, *dyn_m);
-    if (dyn_k != nullptr) K = min(K, (*dyn_k + 63) / 64 * 64);
     if (M <= 0) return;
     int tile_m, tile_n;
-    if (!tile_coords((M + Cfg::BM - 1) / Cfg::BM, (N + Cfg::BN - 1) / Cfg::BN, group_m, tile_m, tile_n)) return;
+    if (!tile_coords(bid, (M + Cfg::BM - 1) / Cfg::BM, (N + Cfg::BN - 1) / Cfg::BN, group_m, tile_m, tile_n)) return;
     const int m0 = tile_m * Cfg::BM, n0 = tile_n * Cfg::BN;
     f32x16 acc[Cfg::MB][Cfg::NB];
     gemm_tn_tile<Cfg>(A, lda, M, m0, B, ldb, N, n0, K, acc, lds);
@@ -581,6 +589,14 @@ void gemm_tn_kernel(const bf16_t* __restrict__ A, int64_t lda, int M, const bf16
                 }
             }
         }
+}
+
+template <class Cfg, int STORE>
+__global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(Cfg::WAVES_PER_SIMD, Cfg::WAVES_PER_SIMD)))
+void gemm_tn_kernel(const GemmArgs g, int group_m)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    gemm_tn_block<Cfg, STORE>((int)blockIdx.x, g.A, g.lda, g.M, g.B, g.ldb, g.N, g.K, g.C, g.ldc, g.wide_rows, group_m, lds_raw);
 }
 
 // dst[c, r] = src[r, c] (bf16), 64x64 tiles through LDS; columns of dst beyond `rows` up to
@@ -756,7 +772,7 @@ void lmhead_stats_kernel(const bf16_t* __restrict__ Wt, const bf16_t* __restrict
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     bf16_t* lds = reinterpret_cast<bf16_t*>(lds_raw);
     int t_tile, split;
-    if (!tile_coords((Ntok + Cfg::BN - 1) / Cfg::BN, splits, group_m, t_tile, split)) return;
+    if (!tile_coords((int)blockIdx.x, (Ntok + Cfg::BN - 1) / Cfg::BN, splits, group_m, t_tile, split)) return;
     const int t0 = t_tile * Cfg::BN;
     const int vb = split * v_per_split;
     const int ve = min(V, vb + v_per_split);
@@ -874,27 +890,38 @@ __global__ void lmhead_stats_merge_kernel(const StatQuad* __restrict__ partial, 
 // ---------------------------------------------------------------------------------------------
 // backward: dz tiles of one vocabulary chunk, stored in both orientations
 // ---------------------------------------------------------------------------------------------
+// dz of one vocabulary chunk [vc0, vc0 + cw) (cw a multiple of 64; columns at or beyond V are
+// written as zero): H [rows, Hd] holds the token rows of the product, Wt [V, Hd].  With a row map, H
+// holds the gathered live rows and token column t stands for row row_map[t] of the per-token arrays.
+struct DzArgs {
+    const bf16_t* Wt; const bf16_t* H; int Hd; int V; int vc0; int cw;
+    const int32_t* token_ids; const float* lse; const float* gcoef; float grad_out;
+    bf16_t* dZc; int64_t ld_c;       // [token, v - vc0]
+    bf16_t* dZcT; int64_t ld_t;      // [v - vc0, token]
+    const int* row_map;
+};
+
+// The tile of workgroup `bid`.  Ntok: the number of token rows; t_tiles: token tiles to write (the
+// last one is written in full, zeros beyond Ntok: the d_W product contracts over whole 64-column
+// blocks of tokens).
 template <class Cfg>
-__global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(Cfg::WAVES_PER_SIMD, Cfg::WAVES_PER_SIMD)))
-void lmhead_dz_kernel(const bf16_t* __restrict__ Wt, const bf16_t* __restrict__ H, int Hd, int V, int Ntok, int vc0,
-                      int cw, const int32_t* __restrict__ token_ids, const float* __restrict__ lse,
-                      const float* __restrict__ gcoef, float grad_out, bf16_t* __restrict__ dZc, int64_t ld_c,
-                      bf16_t* __restrict__ dZcT, int64_t ld_t, int group_m, const int* __restrict__ row_map,
-                      const int* __restrict__ n_live)
+__device__ __forceinline__ void lmhead_dz_block(int bid, const DzArgs& a, int Ntok, int t_tiles, int group_m,
+                                                unsigned char* lds_raw)
 {
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    const bf16_t* __restrict__ Wt = a.Wt;
+    const bf16_t* __restrict__ H = a.H;
+    const int Hd = a.Hd, V = a.V, vc0 = a.vc0, cw = a.cw;
+    const int32_t* __restrict__ token_ids = a.token_ids;
+    const float* __restrict__ lse = a.lse;
+    const float* __restrict__ gcoef = a.gcoef;
+    const float grad_out = a.grad_out;
+    bf16_t* __restrict__ dZc = a.dZc;
+    bf16_t* __restrict__ dZcT = a.dZcT;
+    const int64_t ld_c = a.ld_c, ld_t = a.ld_t;
+    const int* __restrict__ row_map = a.row_map;
     bf16_t* lds = reinterpret_cast<bf16_t*>(lds_raw);
-    // With a row map, H holds the gathered live rows, Ntok becomes their count (from the device) and
-    // token column t stands for row row_map[t] of the per-token arrays.  The last token tile is
-    // written in full (zeros beyond the count): the d_W product contracts over whole 64-column blocks.
-    int t_tiles = (int)((ld_t + Cfg::BN - 1) / Cfg::BN);
-    if (n_live != nullptr) {
-        Ntok = min(Ntok, *n_live);
-        if (Ntok <= 0) return;
-        t_tiles = (Ntok + Cfg::BN - 1) / Cfg::BN;
-    }
     int v_tile, t_tile;
-    if (!tile_coords((cw + Cfg::BM - 1) / Cfg::BM, t_tiles, group_m, v_tile, t_tile)) return;
+    if (!tile_coords(bid, (cw + Cfg::BM - 1) / Cfg::BM, t_tiles, group_m, v_tile, t_tile)) return;
     const int v0 = vc0 + v_tile * Cfg::BM;
     const int t0 = t_tile * Cfg::BN;
     const int vend = min(V, vc0 + cw);
@@ -1033,6 +1060,55 @@ void lmhead_dz_kernel(const bf16_t* __restrict__ Wt, const bf16_t* __restrict__ 
     }
 }
 
+// One launch of the backward pass over the vocabulary chunks: the two products of the PREVIOUS
+// chunk (d_W, then dHidden, from that chunk's dz buffers) and the dz tiles of the NEXT chunk
+// (into the other pair of buffers) share the grid, longest tiles first.  Tile counts of the
+// separate products rarely fill the 256 compute units a whole number of times (dHidden has only
+// rows/256 x Hd/256 tiles); as parts of one launch the short dz tiles fill what the products leave
+// idle.  Each part starts at a multiple of 8 workgroups, so a workgroup's XCD is its part-local
+// id modulo 8.  n_live (device, may be NULL): the number of live rows, when rows were gathered.
+struct BwdStepArgs {
+    GemmArgs dw;       // C = d_W columns of the previous chunk: A = hidden^T [Hd, tokens], B = dz^T [cw, tokens]
+    GemmArgs dh;       // C += dHidden accumulator: A = dz [tokens, cw], B = W rows restricted to the chunk [Hd, cw]
+    DzArgs dz;
+    int have_products, have_dz;
+    int N;             // token rows (upper bound of the live count)
+    int group_m;
+    const int* n_live;
+};
+
+template <class Cfg>
+__global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(Cfg::WAVES_PER_SIMD, Cfg::WAVES_PER_SIMD)))
+void lmhead_bwd_step_kernel(const BwdStepArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    int rows = a.N;
+    if (a.n_live != nullptr) rows = min(rows, *a.n_live);
+    int bid = (int)blockIdx.x;
+    if (a.have_products) {
+        const int g_dw = (int)tile_grid((a.dw.M + Cfg::BM - 1) / Cfg::BM, (a.dw.N + Cfg::BN - 1) / Cfg::BN);
+        if (bid < g_dw) {
+            // contraction over the tokens: whole 64-column blocks up to the live count (zero terms beyond it)
+            const int K = a.n_live != nullptr ? min(a.dw.K, (rows + 63) / 64 * 64) : a.dw.K;
+            gemm_tn_block<Cfg, STORE_BF16>(bid, a.dw.A, a.dw.lda, a.dw.M, a.dw.B, a.dw.ldb, a.dw.N, K, a.dw.C, a.dw.ldc,
+                                           a.dw.wide_rows, a.group_m, lds_raw);
+            return;
+        }
+        bid -= g_dw;
+        const int g_dh = rows > 0 ? (int)tile_grid((rows + Cfg::BM - 1) / Cfg::BM, (a.dh.N + Cfg::BN - 1) / Cfg::BN) : 0;
+        if (bid < g_dh) {
+            gemm_tn_block<Cfg, STORE_F32_ACCUM>(bid, a.dh.A, a.dh.lda, rows, a.dh.B, a.dh.ldb, a.dh.N, a.dh.K, a.dh.C, a.dh.ldc,
+                                                a.dh.wide_rows, a.group_m, lds_raw);
+            return;
+        }
+        bid -= g_dh;
+    }
+    if (a.have_dz && rows > 0) {
+        const int t_tiles = a.n_live != nullptr ? (rows + Cfg::BN - 1) / Cfg::BN : (int)((a.dz.ld_t + Cfg::BN - 1) / Cfg::BN);
+        lmhead_dz_block<Cfg>(bid, a.dz, rows, t_tiles, a.group_m, lds_raw);
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
@@ -1050,7 +1126,7 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline int64_t round_up64(int64_t x) { return (x + 63) / 64 * 64; }
 
 struct LmheadLayout {
-    size_t wt, ht, dzc, dzct, dhacc, partial, token_ws, hc, pos, row_map, block_count, n_live, total;
+    size_t wt, ht, dzc[2], dzct[2], dhacc, partial, token_ws, hc, pos, row_map, block_count, n_live, total;
     int64_t ldt;      // padded token count (leading dimension of Ht and dZc^T)
     int64_t ldc;      // padded chunk width (leading dimension of dZc)
     int splits;
@@ -1080,8 +1156,11 @@ LmheadLayout lmhead_layout(int64_t N, int64_t Hd, int64_t V, int32_t R, int32_t 
     size_t off = 0;
     L.wt = off;      off = align_up(off + (size_t)V * Hd * 2, 256);
     L.ht = off;      off = align_up(off + (size_t)Hd * L.ldt * 2, 256);
-    L.dzc = off;     off = align_up(off + (size_t)N * L.ldc * 2, 256);
-    L.dzct = off;    off = align_up(off + (size_t)L.ldc * L.ldt * 2, 256);
+    // two pairs of dz buffers: one chunk's products read theirs while the next chunk's dz is written
+    for (int b = 0; b < 2; ++b) {
+        L.dzc[b] = off;  off = align_up(off + (size_t)N * L.ldc * 2, 256);
+        L.dzct[b] = off; off = align_up(off + (size_t)L.ldc * L.ldt * 2, 256);
+    }
     L.dhacc = off;   off = align_up(off + (size_t)N * Hd * 4, 256);
     L.partial = off; off = align_up(off + max_splits * (size_t)N * sizeof(StatQuad), 256);
     L.token_ws = off; off = align_up(off + workspace_layout(N, 0, R).total, 256);
@@ -1135,29 +1214,36 @@ void launch_transpose(const bf16_t* src, int64_t ld_src, int rows, int cols, bf1
                        row_map, dyn_rows);
 }
 
+template <int STORE>
+GemmArgs gemm_args(const bf16_t* A, int64_t lda, int M, const bf16_t* B, int64_t ldb, int N, int K, void* C, int64_t ldc)
+{
+    const int eb = STORE == STORE_BF16 ? 2 : 4;
+    GemmArgs g;
+    g.A = A; g.lda = lda; g.M = M;
+    g.B = B; g.ldb = ldb; g.N = N;
+    g.K = K;
+    g.C = C; g.ldc = ldc;
+    g.wide_rows = (((uintptr_t)C & 15u) == 0 && (ldc * eb) % 16 == 0) ? 1 : 0;
+    return g;
+}
+
 template <class Cfg, int STORE>
-bool launch_gemm_cfg(const bf16_t* A, int64_t lda, int M, const bf16_t* B, int64_t ldb, int N, int K, void* C,
-                     int64_t ldc, int group_m, const int* dyn_m, const int* dyn_k, hipStream_t st)
+bool launch_gemm_cfg(const GemmArgs& g, int group_m, hipStream_t st)
 {
     auto kern = gemm_tn_kernel<Cfg, STORE>;
     if (!allow_lds(kern, Cfg::LDS_BYTES)) return false;
-    dim3 grid(tile_grid((M + Cfg::BM - 1) / Cfg::BM, (N + Cfg::BN - 1) / Cfg::BN));
-    const int eb = STORE == STORE_BF16 ? 2 : 4;
-    const int wide_rows = (((uintptr_t)C & 15u) == 0 && (ldc * eb) % 16 == 0) ? 1 : 0;
-    hipLaunchKernelGGL(kern, grid, dim3(Cfg::NT), Cfg::LDS_BYTES, st, A, lda, M, B, ldb, N, K, C, ldc, wide_rows, group_m,
-                       dyn_m, dyn_k);
+    dim3 grid(tile_grid((g.M + Cfg::BM - 1) / Cfg::BM, (g.N + Cfg::BN - 1) / Cfg::BN));
+    hipLaunchKernelGGL(kern, grid, dim3(Cfg::NT), Cfg::LDS_BYTES, st, g, group_m);
     return true;
 }
 
-// dyn_m / dyn_k (device, may be NULL): the actual row count of A and C / the actual contraction
-// length, when only the device knows them; M and K are then their upper bounds.
 template <int STORE>
 bool launch_gemm(const LaunchOpts& o, const bf16_t* A, int64_t lda, int M, const bf16_t* B, int64_t ldb, int N, int K,
-                 void* C, int64_t ldc, hipStream_t st, const int* dyn_m = nullptr, const int* dyn_k = nullptr)
+                 void* C, int64_t ldc, hipStream_t st)
 {
+    const GemmArgs g = gemm_args<STORE>(A, lda, M, B, ldb, N, K, C, ldc);
     bool ok = false;
-    ULORL_FOR_TILE(o.gemm_tile,
-                   ok = (launch_gemm_cfg<Cfg, STORE>(A, lda, M, B, ldb, N, K, C, ldc, o.gemm_group_m, dyn_m, dyn_k, st)))
+    ULORL_FOR_TILE(o.gemm_tile, ok = (launch_gemm_cfg<Cfg, STORE>(g, o.gemm_group_m, st)))
     return ok;
 }
 
@@ -1174,15 +1260,18 @@ bool launch_stats_cfg(const bf16_t* Wt, const bf16_t* H, int Hd, int V, int N, c
 }
 
 template <class Cfg>
-bool launch_dz_cfg(const bf16_t* Wt, const bf16_t* H, int Hd, int V, int N, int vc0, int cw_pad,
-                   const int32_t* token_ids, const float* lse, const float* gcoef, float grad_out, bf16_t* dZc,
-                   bf16_t* dZcT, const LmheadLayout& L, int group_m, const int* row_map, const int* n_live, hipStream_t st)
+bool launch_bwd_step_cfg(const BwdStepArgs& a, hipStream_t st)
 {
-    auto kern = lmhead_dz_kernel<Cfg>;
+    auto kern = lmhead_bwd_step_kernel<Cfg>;
     if (!allow_lds(kern, Cfg::LDS_BYTES)) return false;
-    dim3 grid(tile_grid((cw_pad + Cfg::BM - 1) / Cfg::BM, (int)((L.ldt + Cfg::BN - 1) / Cfg::BN)));
-    hipLaunchKernelGGL(kern, grid, dim3(Cfg::NT), Cfg::LDS_BYTES, st, Wt, H, Hd, V, N, vc0, cw_pad, token_ids, lse, gcoef,
-                       grad_out, dZc, L.ldc, dZcT, L.ldt, group_m, row_map, n_live);
+    // the largest grid the live count allows; workgroups beyond the actual tiles return at once
+    unsigned grid = 0;
+    if (a.have_products) {
+        grid += tile_grid((a.dw.M + Cfg::BM - 1) / Cfg::BM, (a.dw.N + Cfg::BN - 1) / Cfg::BN);
+        grid += tile_grid((a.N + Cfg::BM - 1) / Cfg::BM, (a.dh.N + Cfg::BN - 1) / Cfg::BN);
+    }
+    if (a.have_dz) grid += tile_grid((a.dz.cw + Cfg::BM - 1) / Cfg::BM, (int)((a.dz.ld_t + Cfg::BN - 1) / Cfg::BN));
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, a);
     return true;
 }
 
@@ -1282,8 +1371,6 @@ int32_t ulorl_lmhead_token_loss_bwd(const void* hidden, const void* W, int64_t N
     char* ws = (char*)workspace;
     bf16_t* Wt = (bf16_t*)(ws + L.wt);
     bf16_t* Ht = (bf16_t*)(ws + L.ht);
-    bf16_t* dZc = (bf16_t*)(ws + L.dzc);
-    bf16_t* dZcT = (bf16_t*)(ws + L.dzct);
     float* dHacc = (float*)(ws + L.dhacc);
     const bf16_t* H = (const bf16_t*)hidden;
     const bf16_t* Wp = (const bf16_t*)W;
@@ -1320,22 +1407,39 @@ int32_t ulorl_lmhead_token_loss_bwd(const void* hidden, const void* W, int64_t N
     }
     if (hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;
 
-    for (int64_t vc0 = 0; vc0 < V; vc0 += vocab_chunk) {
-        const int cw = (int)((V - vc0 < vocab_chunk) ? (V - vc0) : vocab_chunk);
-        const int cw_pad = (int)round_up64(cw);         // dz of the padding columns is written as zero
+    // Chunk pipeline: launch c holds the dz tiles of chunk c and the two products of chunk c - 1.
+    const int64_t n_chunks = (V + vocab_chunk - 1) / vocab_chunk;
+    for (int64_t c = 0; c <= n_chunks; ++c) {
+        BwdStepArgs a;
+        memset(&a, 0, sizeof(a));
+        a.N = (int)N;
+        a.group_m = opts.gemm_group_m;
+        a.n_live = n_live;
+        if (c >= 1) {
+            const int64_t vp = (c - 1) * vocab_chunk;
+            const int cwp = (int)((V - vp < vocab_chunk) ? (V - vp) : vocab_chunk);
+            const bf16_t* dZc = (const bf16_t*)(ws + L.dzc[(c - 1) & 1]);
+            const bf16_t* dZcT = (const bf16_t*)(ws + L.dzct[(c - 1) & 1]);
+            a.have_products = 1;
+            // dW[k, vp + v] = sum_j Ht[k, j] dZc^T[v, j]
+            a.dw = gemm_args<STORE_BF16>(Ht, L.ldt, (int)Hd, dZcT, L.ldt, cwp, (int)L.ldt, (bf16_t*)d_W + vp, V);
+            // dHidden[j, k] += sum_v dZc[j, v] W[k, vp + v]          (j: live position, or the row itself)
+            a.dh = gemm_args<STORE_F32_ACCUM>(dZc, L.ldc, (int)N, Wp + vp, V, (int)Hd, cwp, dHacc, Hd);
+        }
+        if (c < n_chunks) {
+            const int64_t vc0 = c * vocab_chunk;
+            const int cw = (int)((V - vc0 < vocab_chunk) ? (V - vc0) : vocab_chunk);
+            a.have_dz = 1;
+            a.dz.Wt = Wt; a.dz.H = Hrows; a.dz.Hd = (int)Hd; a.dz.V = (int)V; a.dz.vc0 = (int)vc0;
+            a.dz.cw = (int)round_up64(cw);               // dz of the padding columns is written as zero
+            a.dz.token_ids = token_ids; a.dz.lse = lse; a.dz.gcoef = gcoef; a.dz.grad_out = grad_out;
+            a.dz.dZc = (bf16_t*)(ws + L.dzc[c & 1]); a.dz.ld_c = L.ldc;
+            a.dz.dZcT = (bf16_t*)(ws + L.dzct[c & 1]); a.dz.ld_t = L.ldt;
+            a.dz.row_map = row_map;
+        }
         bool ok = false;
-        ULORL_FOR_TILE(opts.gemm_tile, ok = launch_dz_cfg<Cfg>(Wt, Hrows, (int)Hd, (int)V, (int)N, (int)vc0, cw_pad, token_ids,
-                                                               lse, gcoef, grad_out, dZc, dZcT, L, opts.gemm_group_m, row_map,
-                                                               n_live, st))
-        if (!ok) return ULORL_ERR_HIP;
-        // dHidden[j, k] += sum_v dZc[j, v] W[k, vc0 + v]          (j: live position, or the row itself)
-        if (!launch_gemm<STORE_F32_ACCUM>(opts, dZc, L.ldc, (int)N, Wp + vc0, V, (int)Hd, cw, dHacc, Hd, st, n_live, nullptr))
-            return ULORL_ERR_HIP;
-        // dW[k, vc0 + v] = sum_j Ht[k, j] dZc^T[v, j]
-        if (!launch_gemm<STORE_BF16>(opts, Ht, L.ldt, (int)Hd, dZcT, L.ldt, cw, (int)L.ldt, (bf16_t*)d_W + vc0, V, st, nullptr,
-                                     n_live))
-            return ULORL_ERR_HIP;
-        if (hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;
+        ULORL_FOR_TILE(opts.gemm_tile, ok = launch_bwd_step_cfg<Cfg>(a, st))
+        if (!ok || hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;
     }
     hipLaunchKernelGGL(dhidden_finish_kernel, dim3((unsigned)((nh / 2 + 255) / 256)), dim3(256), 0, st, (const float*)dHacc, pos,
                        N, (int)Hd, (bf16_t*)d_hidden);

@@ -56,9 +56,9 @@ PMC = {
 # rocprofv3 --pmc runs of this script (FETCH_SIZE, then WRITE_SIZE, summed over the call's kernels and
 # scaled as above); valid for the lm_head source with this digest and for that workload only.
 PMC_LMHEAD = {
-    "source_sha256": "2b8ee1ddd675efc616c15050a871c3a3ae73185821b5b3e32513c8ff05fa32e1",
-    "bwd_bytes": 121265430 * 1024,     # 19 x (dz + dHidden + dW products) + transposes, accumulator fill, final conversion
-    "fwd_bytes": 36751410 * 1024,      # lmhead_stats_kernel + transpose of W + the small kernels
+    "source_sha256": "35c506523f9b5147e3a0c3df9673e637f4e22d7f16f63cbf98af4adffa8c490b",
+    "bwd_bytes": 131788111 * 1024,     # 20 x lmhead_bwd_step_kernel + live-row gather, transposes, accumulator fill, final conversion
+    "fwd_bytes": 34746303 * 1024,      # lmhead_stats_kernel + transpose of W + the small kernels
 }
 
 
@@ -306,18 +306,20 @@ def bench_lmhead(args, w, ulorl, ui, torch, dev, as_entry=False):
     fwd_tf = gemm_flops / (fwd_ms / K * 1e-3) / 1e12
     cnt = out.counters.cpu().tolist()
     # the same backward call with every row in the products (ULORL_LAUNCH_DENSE_ROWS), for comparison
-    dense = ulorl.Launch(gemm_group_m=launch.gemm_group_m, dense_rows=True)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    ulorl.lmhead_token_loss_bwd(H, W, y, out.lse, out.gcoef, 1.0, vocab_chunk=chunk, d_hidden=dH, d_weight=dW, workspace=ws,
-                                launch=dense)
-    nd = max(2, min(K, 5))
-    e0.record()
-    for _ in range(nd):
+    dense_ms = None
+    if getattr(args, "dense_compare", 1):
+        dense = ulorl.Launch(gemm_group_m=launch.gemm_group_m, dense_rows=True)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         ulorl.lmhead_token_loss_bwd(H, W, y, out.lse, out.gcoef, 1.0, vocab_chunk=chunk, d_hidden=dH, d_weight=dW,
                                     workspace=ws, launch=dense)
-    e1.record()
-    torch.cuda.synchronize()
-    dense_ms = e0.elapsed_time(e1) / nd
+        nd = max(2, min(K, 5))
+        e0.record()
+        for _ in range(nd):
+            ulorl.lmhead_token_loss_bwd(H, W, y, out.lse, out.gcoef, 1.0, vocab_chunk=chunk, d_hidden=dH, d_weight=dW,
+                                        workspace=ws, launch=dense)
+        e1.record()
+        torch.cuda.synchronize()
+        dense_ms = e0.elapsed_time(e1) / nd
     counters_valid = (source_digest("lmhead.hip") == PMC_LMHEAD["source_sha256"] and w.name == "cfg5_lmhead_bf16"
                       and chunk == 8192)
     result = {
@@ -328,8 +330,9 @@ def bench_lmhead(args, w, ulorl, ui, torch, dev, as_entry=False):
         "config": {"workload": w.name, "rows": w.N, "hidden": w.hidden, "vocab": w.V, "vocab_chunk": chunk,
                    "responses": w.R, "segment_len": w.seg_len, "path": "lm_head variant (logits never materialised)",
                    "gemm_group_m": launch.gemm_group_m or "default (4)", "is_mode": "SAIS", "gate": "always (static MPT masking)", "tau": w.tau},
-        "roofline": {"bound": "mfma", "kernel": "backward call: lmhead_dz_kernel + 2 x gemm_tn_kernel per vocabulary "
-                     "chunk (3 products of 2*N*Hd*V flop)", "achieved": bwd_tf, "peak": MFMA_BF16_PEAK_TFLOPS,
+        "roofline": {"bound": "mfma", "kernel": "backward call: lmhead_bwd_step_kernel, one launch per vocabulary chunk "
+                     "(dz tiles of the chunk + the dW and dHidden products of the chunk before: 3 products of "
+                     "2*live_rows*Hd*V flop)", "achieved": bwd_tf, "peak": MFMA_BF16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": bwd_tf / MFMA_BF16_PEAK_TFLOPS,
                      "traffic": PMC_LMHEAD["bwd_bytes"] if counters_valid else None,
                      "traffic_note": "HBM-side bytes of the call (operand tiles are re-fetched per XCD; the "
@@ -398,6 +401,9 @@ def main():
     ap.add_argument("--gemm-group-m", type=int, default=0,
                     help="cfg5 only: ulorl_launch.gemm_group_m, the block tiles along M an XCD walks before it moves "
                          "along N (0: the library's default)")
+    ap.add_argument("--dense-compare", type=int, default=1,
+                    help="cfg5: 1 = also time the backward call with every row in the products (default); 0 = skip "
+                         "(for profiler runs, whose per-call sums should hold the timed calls only)")
     ap.add_argument("--extras", type=int, default=-1,
                     help="1: also time the ceiling, the per-response gate and configurations 2, 3, 5 in the same "
                          "run (default for cfg4); 0: the workload alone")

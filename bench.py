@@ -56,9 +56,9 @@ PMC = {
 # rocprofv3 --pmc runs of this script (FETCH_SIZE, then WRITE_SIZE, summed over the call's kernels and
 # scaled as above); valid for the lm_head source with this digest and for that workload only.
 PMC_LMHEAD = {
-    "source_sha256": "35c506523f9b5147e3a0c3df9673e637f4e22d7f16f63cbf98af4adffa8c490b",
-    "bwd_bytes": 131788111 * 1024,     # 20 x lmhead_bwd_step_kernel + live-row gather, transposes, accumulator fill, final conversion
-    "fwd_bytes": 34746303 * 1024,      # lmhead_stats_kernel + transpose of W + the small kernels
+    "source_sha256": "9f1e03bb04fbc79ed15b08a2832e08111ee79ddabe0d31adf5d400a8d8f934f2",
+    "bwd_bytes": 131621665 * 1024,     # 20 x lmhead_bwd_step_kernel + live-row gather, transposes, accumulator fill, final conversion
+    "fwd_bytes": 35197904 * 1024,      # lmhead_stats_kernel + transpose of W + the small kernels
 }
 
 

@@ -313,10 +313,11 @@ int32_t ulorl_token_loss_fwd_bwd_static(
  * the stats-only pass selected by advantages == NULL (only lse, logp and entropy are written;
  * the workspace is still needed, sized with any R >= 1).
  *
- * The workspace (ulorl_lmhead_workspace_bytes, 256-byte aligned) holds W^T, hidden^T, the two
- * dlogits chunk buffers, an fp32 accumulator for dHidden, the gathered live rows of hidden with
- * their index maps and the token-loss workspace; nothing in it needs to survive between the forward
- * and the backward call.
+ * The workspace (ulorl_lmhead_workspace_bytes, 256-byte aligned) holds W^T, hidden^T, two pairs of
+ * dlogits chunk buffers (each chunk in both orientations; one chunk's gradient products read theirs
+ * while the next chunk's are written: 4 x N x vocab_chunk x 2 bytes), an fp32 accumulator for
+ * dHidden, the gathered live rows of hidden with their index maps and the token-loss workspace;
+ * nothing in it needs to survive between the forward and the backward call.
  */
 size_t ulorl_lmhead_workspace_bytes(int64_t N, int64_t Hd, int64_t V, int32_t R, int32_t vocab_chunk);
 

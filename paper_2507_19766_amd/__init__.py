@@ -13,3 +13,4 @@ from .binding import (  # noqa: F401
     lmhead_workspace_bytes, lmhead_token_loss_fwd, lmhead_token_loss_bwd, gemm_tn_bf16,
     advantage_prep, segment_diagnostics, segment_pool_step,
 )
+from . import autograd  # noqa: F401,E402
